@@ -1,0 +1,291 @@
+"""Seeded synthetic inputs shaped like METok's workloads.
+
+This module only draws random numbers and lays them out; it holds none of the
+method's arithmetic (no similarity, score, selection, pooling or gather code).
+Both the CPU oracle's tests and the HIP path's tests/bench take their inputs
+from here, so the two sides see identical bits.
+
+Every draw uses ``numpy.random.Generator(PCG64(seed))`` with float32 normals in
+the order written below.  Tensors that the configs call bf16 are rounded once
+(round-to-nearest-even) and returned as float32 arrays whose values are exactly
+bf16-representable; ``to_torch`` turns them into real bf16 tensors losslessly.
+
+The recipes stand in for the paper's video benchmarks (MVBench, EgoSchema,
+MLVU, VideoMME) and model activations, none of which are available here: only
+shapes (frames, tokens per frame, widths, heads, layers, text length) and the
+piecewise-constant event structure are taken from those workloads.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+SEED_BASE = 250602850
+
+
+# --------------------------------------------------------------------------
+# bf16 helpers (format conversion of inputs only)
+# --------------------------------------------------------------------------
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """float32 -> float32 holding the nearest-even bf16 value of each element."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + (((u >> 16) & 1) + 0x7FFF)
+    u = (u >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(x))
+
+
+def maybe_bf16(x: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return bf16_round(x)
+    if dtype == "f32":
+        return np.ascontiguousarray(x, dtype=np.float32)
+    raise ValueError(f"dtype must be 'bf16' or 'f32', got {dtype!r}")
+
+
+def to_torch(x: np.ndarray, dtype: str, device="cpu"):
+    """numpy float32 (bf16-representable where dtype == 'bf16') -> torch tensor."""
+    import torch
+
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.to(device)
+
+
+# --------------------------------------------------------------------------
+# event structure
+# --------------------------------------------------------------------------
+def event_lengths(rng: np.random.Generator, total: int, n_events: int, lo: int, hi: int) -> np.ndarray:
+    """Random lengths in [lo, hi] summing to ``total`` (rejection sampling)."""
+    if not (n_events * lo <= total <= n_events * hi):
+        raise ValueError("no composition of total with these bounds")
+    for _ in range(100000):
+        lens = rng.integers(lo, hi + 1, size=n_events)
+        if int(lens.sum()) == total:
+            return lens.astype(np.int64)
+    raise RuntimeError("rejection sampling of event lengths did not converge")
+
+
+def starts_from_lengths(lens: Sequence[int]) -> np.ndarray:
+    out = np.zeros(len(lens) + 1, dtype=np.int32)
+    out[1:] = np.cumsum(np.asarray(lens, dtype=np.int64))
+    return out
+
+
+def unit_rows(rng: np.random.Generator, n: int, d: int) -> np.ndarray:
+    c = rng.standard_normal((n, d), dtype=np.float32)
+    c /= np.linalg.norm(c.astype(np.float64), axis=1, keepdims=True).astype(np.float32)
+    return c
+
+
+# --------------------------------------------------------------------------
+# stage 1: frame features with planted events
+# --------------------------------------------------------------------------
+@dataclass
+class Video:
+    feats: np.ndarray          # [T, N, d] float32 (bf16-representable if dtype == 'bf16')
+    text_emb: np.ndarray       # [d]
+    dtype: str
+    grid: Tuple[int, int]      # (grid_h, grid_w), N = grid_h * grid_w
+    n_events: int
+    event_start: np.ndarray    # planted [n_events + 1]
+    centroids: np.ndarray      # [n_events, d]
+    text_weights: np.ndarray   # [n_events] weight of each centroid inside text_emb
+    sigma: float
+
+
+def planted_video(seed: int, T: int, grid: Tuple[int, int], d: int, n_events: int,
+                  len_lo: int, len_hi: int, sigma: float, dtype: str) -> Video:
+    """Frames of one event share a unit-norm centroid; every token adds N(0, sigma^2) noise.
+
+    The text embedding is a normalised mix of the centroids with strictly
+    decreasing weights handed out to the events in a random order, so the
+    events have clearly separated text relevance.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    N = grid[0] * grid[1]
+    lens = event_lengths(rng, T, n_events, len_lo, len_hi)
+    starts = starts_from_lengths(lens)
+    cent = unit_rows(rng, n_events, d)
+    weights = np.linspace(1.0, 0.2, n_events).astype(np.float32)
+    weights = weights[rng.permutation(n_events)]
+    text = (weights[:, None] * cent).sum(axis=0)
+    text /= np.float32(np.linalg.norm(text.astype(np.float64)))
+    feats = np.empty((T, N, d), dtype=np.float32)
+    for e in range(n_events):
+        for t in range(int(starts[e]), int(starts[e + 1])):
+            feats[t] = cent[e][None, :] + np.float32(sigma) * rng.standard_normal((N, d), dtype=np.float32)
+    return Video(feats=maybe_bf16(feats, dtype), text_emb=maybe_bf16(text, dtype), dtype=dtype,
+                 grid=grid, n_events=n_events, event_start=starts, centroids=cent,
+                 text_weights=weights, sigma=sigma)
+
+
+# --------------------------------------------------------------------------
+# stage 2: LLM-side activations for one pruning layer
+# --------------------------------------------------------------------------
+@dataclass
+class PrefillLayer:
+    hidden: np.ndarray         # [S, D]
+    q_text: np.ndarray         # [Hq, Tq, dh]
+    k_all: np.ndarray          # [Hkv, S, dh]
+    dtype: str
+    vis_start: int
+    n_vis: int
+    n_text: int
+    token_event: np.ndarray    # [n_vis] int32 event id of each visual token
+    n_events: int
+    event_weight: np.ndarray   # [n_events] float32 in (0.5, 1.5)
+    event_is_key: np.ndarray   # [n_events] uint8, ceil(alpha k) of them set
+    target_event: int
+
+
+def token_events_for_frames(rng: np.random.Generator, n_frames: int, tokens_per_frame: int,
+                            n_events: int) -> np.ndarray:
+    lens = event_lengths(rng, n_frames, n_events, 1, n_frames)
+    starts = starts_from_lengths(lens)
+    frame_event = np.repeat(np.arange(n_events, dtype=np.int32), np.diff(starts))
+    return np.repeat(frame_event, tokens_per_frame).astype(np.int32)
+
+
+def prefill_layer(seed: int, token_event: np.ndarray, n_events: int, n_text: int, D: int,
+                  Hq: int, Hkv: int, dh: int, dtype: str, vis_start: int = 0,
+                  n_key_events: Optional[int] = None, with_hidden: bool = True) -> PrefillLayer:
+    """Keys of an event share a mean shift; the text queries lean towards one target event.
+
+    K_j = 0.5 mu_e(j) + N(0,1) for visual keys, N(0,1) for prefix and text keys;
+    Q_i = N(0,1) + 0.5 mu_target; hidden = N(0,1) + a per-event scalar shift.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n_vis = int(token_event.shape[0])
+    S = vis_start + n_vis + n_text
+    mu = rng.standard_normal((n_events, dh), dtype=np.float32)
+    target = int(rng.integers(0, n_events))
+    k_all = rng.standard_normal((Hkv, S, dh), dtype=np.float32)
+    k_all[:, vis_start:vis_start + n_vis, :] += 0.5 * mu[token_event][None, :, :]
+    q_text = rng.standard_normal((Hq, n_text, dh), dtype=np.float32) + 0.5 * mu[target][None, None, :]
+    weight = rng.uniform(0.5, 1.5, size=n_events).astype(np.float32)
+    if n_key_events is None:
+        n_key_events = (n_events + 1) // 2
+    is_key = np.zeros(n_events, dtype=np.uint8)
+    is_key[rng.permutation(n_events)[:n_key_events]] = 1
+    if with_hidden:
+        shift = rng.standard_normal(n_events, dtype=np.float32)
+        hidden = rng.standard_normal((S, D), dtype=np.float32)
+        hidden[vis_start:vis_start + n_vis] += shift[token_event][:, None]
+    else:
+        hidden = np.zeros((0, D), dtype=np.float32)
+    return PrefillLayer(hidden=maybe_bf16(hidden, dtype), q_text=maybe_bf16(q_text, dtype),
+                        k_all=maybe_bf16(k_all, dtype), dtype=dtype, vis_start=vis_start,
+                        n_vis=n_vis, n_text=n_text, token_event=token_event, n_events=n_events,
+                        event_weight=weight, event_is_key=is_key, target_event=target)
+
+
+# --------------------------------------------------------------------------
+# stage 3: KV cache contents and per-layer retained index lists
+# --------------------------------------------------------------------------
+def kv_pattern(layer: int, which: int, batch: int, head: int, rows, dh: int, xp=np):
+    """Deterministic, per-row-unique 16-bit payload of a KV cache row.
+
+    Returns int16 values of shape [len(rows), dh]; ``xp`` is numpy or torch so
+    the same integer formula fills a device cache and re-creates single rows
+    on the host.  The bits are used as opaque payload (copy correctness does
+    not depend on the value distribution).
+    """
+    slab = ((layer * 2 + which) * 64 + batch) * 64 + head
+    if xp is np:
+        r = np.asarray(rows, dtype=np.int64)[:, None]
+        c = np.arange(dh, dtype=np.int64)[None, :]
+        v = (r * 40503 + c * 9973 + slab * 30011 + ((r * c) >> 3)) & 0xFFFF
+        return v.astype(np.uint16).view(np.int16)
+    import torch
+
+    r = rows.to(torch.int64)[:, None]
+    c = torch.arange(dh, dtype=torch.int64, device=rows.device)[None, :]
+    v = (r * 40503 + c * 9973 + slab * 30011 + ((r * c) >> 3)) & 0xFFFF
+    v = torch.where(v >= 32768, v - 65536, v)
+    return v.to(torch.int16)
+
+
+def nested_keep_sets(seed: int, n_vis: int, counts: Sequence[int]) -> List[np.ndarray]:
+    """Nested random subsets of range(n_vis): set i has counts[i] members, ascending."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    cur = np.arange(n_vis, dtype=np.int64)
+    out = []
+    for c in counts:
+        pick = np.sort(rng.choice(cur.shape[0], size=int(c), replace=False))
+        cur = cur[pick]
+        out.append(cur.astype(np.int32))
+    return out
+
+
+def kv_layer_schedule(n_layers: int, L_H: Sequence[int], n_vis: int, n_text: int,
+                      level_sets: Sequence[np.ndarray], n_vis_now: Optional[Sequence[int]] = None):
+    """Per-layer index lists into a cache that holds n_vis visual then n_text text rows.
+
+    Layers below L_H[0] keep everything (None = identity); layers in
+    [L_H[i], L_H[i+1]) keep level_sets[i] followed by all text rows.
+    """
+    text_rows = np.arange(n_vis, n_vis + n_text, dtype=np.int32)
+    out: List[Optional[np.ndarray]] = []
+    for l in range(n_layers):
+        level = sum(1 for b in L_H if l >= b)
+        if level == 0:
+            out.append(None)
+        else:
+            out.append(np.concatenate([level_sets[level - 1], text_rows]).astype(np.int32))
+    return out
+
+
+# --------------------------------------------------------------------------
+# the five named configurations (shapes only; tensors are built on demand)
+# --------------------------------------------------------------------------
+@dataclass
+class Shapes:
+    name: str
+    T: int = 0
+    grid: Tuple[int, int] = (0, 0)
+    d: int = 0
+    dtype: str = "bf16"
+    n_events: int = 0
+    len_lo: int = 1
+    len_hi: int = 1
+    sigma: float = 0.0
+    tokens_per_frame: int = 0
+    n_text: int = 0
+    D: int = 0
+    Hq: int = 0
+    Hkv: int = 0
+    dh: int = 0
+    keep: Tuple[float, ...] = ()
+    n_layers: int = 0
+    L_H: Tuple[int, ...] = ()
+    batch: int = 1
+    extra: Dict[str, float] = field(default_factory=dict)
+
+    @property
+    def seed(self) -> int:
+        return SEED_BASE + int(self.extra.get("config", 0))
+
+
+TINY = Shapes("tiny", T=8, grid=(4, 4), d=64, dtype="f32", n_events=4, len_lo=1, len_hi=8, sigma=0.1,
+              tokens_per_frame=4, n_text=16, D=64, Hq=2, Hkv=2, dh=32, keep=(0.25,), n_layers=2,
+              L_H=(1,), batch=1, extra={"config": 1})
+ENCODER = Shapes("encoder", T=32, grid=(24, 24), d=1024, dtype="bf16", n_events=8, len_lo=2, len_hi=6,
+                 sigma=0.2, tokens_per_frame=144, extra={"config": 2})
+PREFILL = Shapes("prefill", T=128, tokens_per_frame=144, n_text=64, D=3584, Hq=28, Hkv=4, dh=128,
+                 dtype="bf16", n_events=13, keep=(0.25,), extra={"config": 3})
+HIERARCHICAL = Shapes("hierarchical", T=256, tokens_per_frame=144, n_text=64, D=3584, Hq=28, Hkv=4,
+                      dh=128, dtype="bf16", n_events=16, keep=(0.5, 0.5, 0.5), extra={"config": 4})
+KV_DECODE = Shapes("kv_decode", T=256, tokens_per_frame=144, n_text=128, Hkv=4, dh=128, dtype="bf16",
+                   n_layers=28, L_H=(3, 10, 19), keep=(0.5, 0.5, 0.5), batch=8, extra={"config": 5})
+# stage 1 at the frame count of the two 256-frame configs (not one of the five; used by the bench
+# so that the stage-1 kernels are measured against HBM rather than the last-level cache)
+ENCODER_256 = Shapes("encoder_256", T=256, grid=(24, 24), d=1024, dtype="bf16", n_events=16, len_lo=4,
+                     len_hi=40, sigma=0.2, tokens_per_frame=144, extra={"config": 6})
+
+
+def video_for(shapes: Shapes, seed_offset: int = 0) -> Video:
+    return planted_video(shapes.seed + 1000 * seed_offset, shapes.T, shapes.grid, shapes.d,
+                         shapes.n_events, shapes.len_lo, shapes.len_hi, shapes.sigma, shapes.dtype)

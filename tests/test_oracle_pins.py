@@ -1,0 +1,492 @@
+"""Pins for the CPU oracle: brute force on tiny inputs, closed forms, invariants, special cases
+that reduce to library routines, and numbers the paper prints.  None of these call the HIP path.
+
+Each test is meant to fail for a plausible mistake in the oracle (dropped term, wrong sign or
+index, transposed operand, wrong tie-break, wrong rounding)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import metok_oracle as O
+from paper_2506_02850_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_efficiency_tables.txt")
+
+
+def golden():
+    out = {}
+    with open(GOLDEN) as fh:
+        for line in fh:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                k, v = line.split()
+                out[k] = float(v)
+    return out
+
+
+# ---------------------------------------------------------------------------
+# P1: Eq. 4 and the boundary rule
+# ---------------------------------------------------------------------------
+def brute_adjacent_cosine(V):
+    T, N, d = V.shape
+    out = []
+    for i in range(T - 1):
+        dot = na = nb = 0.0
+        for n in range(N):
+            for c in range(d):
+                a, b = float(V[i, n, c]), float(V[i + 1, n, c])
+                dot += a * b
+                na += a * a
+                nb += b * b
+        den = math.sqrt(na) * math.sqrt(nb)
+        out.append(0.0 if den < 1e-12 else dot / den)
+    return out
+
+
+def test_eq4_brute_force_tiny():
+    v = synth.video_for(synth.TINY)
+    got = O.adjacent_frame_cosine(v.feats)
+    want = brute_adjacent_cosine(v.feats)
+    assert got.shape == (7,)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+
+
+def test_eq4_special_cases():
+    rng = np.random.default_rng(0)
+    a = rng.standard_normal((3, 5))
+    V = np.stack([a, a, -a, 2.5 * a])
+    np.testing.assert_allclose(O.adjacent_frame_cosine(V), [1.0, -1.0, -1.0], rtol=1e-14)
+    # orthogonal frames and a zero frame
+    e0 = np.zeros((2, 4)); e0[0, 0] = 1.0
+    e1 = np.zeros((2, 4)); e1[1, 3] = 1.0
+    V = np.stack([e0, e1, np.zeros((2, 4)), e1])
+    np.testing.assert_array_equal(O.adjacent_frame_cosine(V), [0.0, 0.0, 0.0])
+    # known value: <(1,2,3,4),(4,3,2,1)> / 30 = 20 / 30, frames laid out as 2 x 2
+    V = np.array([[[1.0, 2.0], [3.0, 4.0]], [[4.0, 3.0], [2.0, 1.0]]])
+    np.testing.assert_allclose(O.adjacent_frame_cosine(V), [2.0 / 3.0], rtol=1e-15)
+
+
+@pytest.mark.parametrize("shapes", [synth.TINY, synth.ENCODER])
+def test_planted_events_recovered_and_closed_form(shapes):
+    v = synth.video_for(shapes)
+    S = O.adjacent_frame_cosine(v.feats)
+    es, fe = O.event_boundaries(S, shapes.n_events)
+    np.testing.assert_array_equal(es, v.event_start)
+    # closed form for the generator: unit centroid + N(0, sigma^2) noise per entry gives a
+    # within-event cosine of 1 / (1 + sigma^2 d) and a cross-event cosine near 0
+    expect = 1.0 / (1.0 + shapes.sigma ** 2 * shapes.d)
+    boundary = set(int(b) - 1 for b in v.event_start[1:-1])
+    inside = [S[i] for i in range(len(S)) if i not in boundary]
+    across = [S[i] for i in boundary]
+    assert abs(np.mean(inside) - expect) < 0.08 * expect
+    assert max(abs(x) for x in across) < 0.5 * expect
+    # invariants: k events, strictly increasing starts covering [0, T), frame_event consistent
+    assert es[0] == 0 and es[-1] == shapes.T and np.all(np.diff(es) > 0)
+    assert fe.shape == (shapes.T,) and np.all(np.diff(fe) >= 0) and fe[-1] == shapes.n_events - 1
+    for e in range(shapes.n_events):
+        assert np.all(fe[es[e]:es[e + 1]] == e)
+
+
+def test_boundary_rule_by_hand_and_ties():
+    S = np.array([0.9, 0.1, 0.8, 0.1, 0.7, 0.1])
+    es, fe = O.event_boundaries(S, 3)          # two lowest: ties at 0.1 -> indices 1 and 3
+    np.testing.assert_array_equal(es, [0, 2, 4, 7])
+    np.testing.assert_array_equal(fe, [0, 0, 1, 1, 2, 2, 2])
+    es, _ = O.event_boundaries(S, 1)
+    np.testing.assert_array_equal(es, [0, 7])
+    es, _ = O.event_boundaries(S, 7)           # every frame its own event
+    np.testing.assert_array_equal(es, np.arange(8))
+    with pytest.raises(ValueError):
+        O.event_boundaries(S, 8)
+    # lowest, not highest: a mistake in the sign of the ordering picks index 0 here
+    es, _ = O.event_boundaries(np.array([0.9, 0.2, 0.5]), 2)
+    np.testing.assert_array_equal(es, [0, 2, 4])
+
+
+def test_boundaries_random_against_argsort():
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        T = int(rng.integers(2, 40))
+        k = int(rng.integers(1, T + 1))
+        S = np.round(rng.standard_normal(T - 1), 1)      # many exact ties
+        es, _ = O.event_boundaries(S, k)
+        cuts = np.sort(np.argsort(S, kind="stable")[:k - 1])
+        np.testing.assert_array_equal(es, np.concatenate([[0], cuts + 1, [T]]))
+
+
+# ---------------------------------------------------------------------------
+# P2: Eq. 5, key events, key frames
+# ---------------------------------------------------------------------------
+def brute_frame_text(V, t):
+    T, N, d = V.shape
+    tn = math.sqrt(sum(float(x) ** 2 for x in t))
+    out = []
+    for i in range(T):
+        acc = 0.0
+        for n in range(N):
+            dot = sum(float(V[i, n, c]) * float(t[c]) for c in range(d))
+            nn = math.sqrt(sum(float(V[i, n, c]) ** 2 for c in range(d)))
+            acc += 0.0 if nn * tn < 1e-12 else dot / (nn * tn)
+        out.append(acc / N)
+    return out
+
+
+def test_eq5_brute_force_tiny():
+    v = synth.video_for(synth.TINY)
+    np.testing.assert_allclose(O.frame_text_score(v.feats, v.text_emb), brute_frame_text(v.feats, v.text_emb),
+                               rtol=1e-12)
+
+
+def test_eq5_special_cases():
+    t = np.array([3.0, 4.0])
+    V = np.array([[[3.0, 4.0], [6.0, 8.0]],          # both tokens parallel to t -> 1
+                  [[-3.0, -4.0], [4.0, -3.0]],       # antiparallel and orthogonal -> (-1 + 0) / 2
+                  [[0.0, 0.0], [5.0, 0.0]]])         # zero token counts as 0; second: 15 / 25
+    np.testing.assert_allclose(O.frame_text_score(V, t), [1.0, -0.5, 0.3], rtol=1e-14)
+    # per-token normalisation, not per-frame: scaling one token must not change the score
+    V2 = V.copy(); V2[1, 1] *= 100.0
+    np.testing.assert_allclose(O.frame_text_score(V2, t), [1.0, -0.5, 0.3], rtol=1e-14)
+
+
+def test_text_equal_to_a_centroid_ranks_that_event_first():
+    v = synth.video_for(synth.ENCODER)
+    for e in (0, 3, 7):
+        f = O.frame_text_score(v.feats[:, ::16], v.centroids[e])     # a token subsample is enough
+        score, is_key, _ = O.key_events_and_frames(f, v.event_start, 1.0 / 8, 0.5)
+        assert int(np.argmax(score)) == e and is_key[e] == 1 and is_key.sum() == 1
+
+
+def test_key_selection_by_hand():
+    f = np.array([0.1, 0.5, 0.3, 0.3, 0.9, 0.2, 0.2, 0.2, 0.4])
+    es = np.array([0, 2, 5, 9], dtype=np.int32)
+    score, ek, fk = O.key_events_and_frames(f, es, 0.5, 0.45)
+    np.testing.assert_allclose(score, [0.3, 0.5, 0.25], rtol=1e-14)
+    np.testing.assert_array_equal(ek, [1, 1, 0])           # ceil(0.5 * 3) = 2 best means
+    # key frames: ceil(.45*2)=1 -> frame 1; ceil(.45*3)=2 -> frames 4 and 2 (tie 0.3: lower index);
+    # ceil(.45*4)=2 -> frame 8 then the first of the 0.2 ties (frame 5)
+    np.testing.assert_array_equal(fk, [0, 1, 1, 0, 1, 1, 0, 0, 1])
+    score_max, ek_max, _ = O.key_events_and_frames(f, es, 1.0 / 3, 0.45, O.EVENT_REDUCE_MAX)
+    np.testing.assert_allclose(score_max, [0.5, 0.9, 0.4])
+    np.testing.assert_array_equal(ek_max, [0, 1, 0])
+
+
+def test_key_counts_and_event_permutation():
+    rng = np.random.default_rng(5)
+    for _ in range(30):
+        k = int(rng.integers(1, 9))
+        lens = rng.integers(1, 7, size=k)
+        es = synth.starts_from_lengths(lens)
+        f = rng.standard_normal(int(es[-1]))
+        alpha, beta = float(rng.uniform(0.05, 1.0)), float(rng.uniform(0.05, 1.0))
+        score, ek, fk = O.key_events_and_frames(f, es, alpha, beta)
+        assert ek.sum() == math.ceil(alpha * k - 1e-9)
+        for j in range(k):
+            seg = slice(es[j], es[j + 1])
+            nk = fk[seg].sum()
+            assert nk == math.ceil(beta * lens[j] - 1e-9) and nk >= 1
+            assert f[seg][fk[seg] == 1].min() >= f[seg][fk[seg] == 0].max() if nk < lens[j] else True
+        if ek.sum() < k:
+            assert score[ek == 1].min() >= score[ek == 0].max()
+
+
+def test_ceil_ratio_is_a_guarded_ceiling():
+    assert O.ceil_ratio(0.5 * 13) == 7 and O.ceil_ratio(0.5 * 5) == 3        # paper's (alpha, k) pairs
+    assert O.ceil_ratio(0.55 * 20) == 11                                   # 11.000000000000002
+    assert O.ceil_ratio(0.4 * 5) == 2 and O.ceil_ratio(0.45 * 3) == 2 and O.ceil_ratio(2.0000001) == 3
+
+
+# ---------------------------------------------------------------------------
+# P3: adaptive pooling
+# ---------------------------------------------------------------------------
+def test_strides_follow_algorithm_1():
+    es = np.array([0, 2, 4], dtype=np.int32)
+    s = O.pooling_strides(es, np.array([1, 0]), np.array([1, 0, 1, 0]), 0.5, 2, 3, (24, 24))
+    np.testing.assert_array_equal(s, [2, 3, 4, 6])            # s1, s2, s1/alpha, s2/alpha
+    s = O.pooling_strides(es, np.array([1, 0]), np.array([1, 0, 1, 0]), 0.3, 2, 3, (24, 24))
+    np.testing.assert_array_equal(s, [2, 3, 7, 10])           # non-integer s/alpha rounds up
+    s = O.pooling_strides(es, np.array([0, 0]), np.array([1, 0, 1, 0]), 0.1, 2, 3, (4, 4))
+    np.testing.assert_array_equal(s, [4, 4, 4, 4])            # clamped to the grid
+
+
+def test_pool_identity_constant_and_counts():
+    rng = np.random.default_rng(1)
+    v = rng.standard_normal((24 * 24, 8))
+    np.testing.assert_array_equal(O.pool_frame(v, (24, 24), 1), v)
+    c = np.full((24 * 24, 3), 2.5)
+    for s, rows in ((2, 144), (3, 64), (4, 36), (6, 16)):     # strides of (s1,s2)=(2,3), alpha=.5 on 24x24
+        out = O.pool_frame(c, (24, 24), s)
+        assert out.shape == (rows, 3) and np.all(out == 2.5)
+        # every input cell lands in exactly one window: pooled mean of means equals the global mean
+        np.testing.assert_allclose(O.pool_frame(v, (24, 24), s).mean(axis=0), v.mean(axis=0), rtol=1e-12, atol=1e-15)
+    out = O.pool_frame(v, (24, 24), 24)
+    np.testing.assert_allclose(out, v.mean(axis=0, keepdims=True), rtol=1e-12)
+
+
+def test_pool_window_layout_by_hand():
+    # 4 x 4 grid, d = 1, token value = its row-major index; stride 2 windows are {0,1,4,5} ...
+    v = np.arange(16, dtype=np.float64).reshape(16, 1)
+    np.testing.assert_array_equal(O.pool_frame(v, (4, 4), 2).ravel(), [2.5, 4.5, 10.5, 12.5])
+    # non-square grid 2 x 4: windows {0,1,4,5} and {2,3,6,7}
+    v = np.arange(8, dtype=np.float64).reshape(8, 1)
+    np.testing.assert_array_equal(O.pool_frame(v, (2, 4), 2).ravel(), [2.5, 4.5])
+
+
+@pytest.mark.parametrize("grid,s", [((24, 24), 2), ((24, 24), 3), ((24, 24), 6), ((27, 27), 2), ((27, 27), 4),
+                                    ((6, 10), 4), ((5, 7), 3)])
+@pytest.mark.parametrize("edge", [O.POOL_FLOOR, O.POOL_CEIL])
+def test_pool_matches_library_avg_pool(grid, s, edge):
+    rng = np.random.default_rng(7)
+    d = 5
+    v = rng.standard_normal((grid[0] * grid[1], d))
+    x = torch.from_numpy(v.reshape(1, grid[0], grid[1], d)).permute(0, 3, 1, 2)
+    y = torch.nn.functional.avg_pool2d(x, kernel_size=s, stride=s, ceil_mode=(edge == O.POOL_CEIL),
+                                       count_include_pad=False)
+    want = y.permute(0, 2, 3, 1).reshape(-1, d).numpy()
+    got = O.pool_frame(v, grid, s, edge)
+    assert got.shape == want.shape
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+
+
+def test_floor_pooling_is_what_the_papers_base_kv_cache_implies():
+    """Table 3's base LLaVA-OneVision-7B cache (32 SigLIP frames of 27 x 27 patches, uniform stride 2,
+    cf. the Fig. 7 caption) only fits floor pooling: 13 x 13 = 169 tokens per frame."""
+    g = golden()
+    bytes_per_token = g["impl_layers_7b"] * 4 * 128 * 2 * 2          # layers x kv heads x dh x bf16 x (K,V)
+    tokens = g["t3_kv_base_mb"] * 2 ** 20 / bytes_per_token
+    frames = int(g["frames_ov"])
+    floor_rows = O.pool_frame(np.zeros((27 * 27, 1)), (27, 27), 2, O.POOL_FLOOR).shape[0]
+    ceil_rows = O.pool_frame(np.zeros((27 * 27, 1)), (27, 27), 2, O.POOL_CEIL).shape[0]
+    assert (floor_rows, ceil_rows) == (169, 196)
+    text = tokens - frames * floor_rows
+    assert 20 < text < 150                       # a plausible prompt length
+    assert tokens - frames * ceil_rows < 0       # ceil pooling would not even fit the printed cache
+
+
+def test_compress_concatenates_in_temporal_order():
+    v = synth.video_for(synth.TINY)
+    r = O.compress_encoder_tokens(v.feats, (4, 4), v.text_emb, v.event_start, 0.5, 0.5, 1, 2)
+    stride, off = r["frame_stride"], r["frame_offsets"]
+    assert set(stride.tolist()) <= {1, 2, 4}
+    assert off[0] == 0 and off[-1] == r["tokens"].shape[0] == r["token_event"].shape[0]
+    for i in range(8):
+        side = 4 // stride[i]
+        assert off[i + 1] - off[i] == side * side
+        np.testing.assert_array_equal(r["tokens"][off[i]:off[i + 1]], O.pool_frame(v.feats[i], (4, 4), int(stride[i])))
+        e = int(np.searchsorted(v.event_start, i, side="right") - 1)
+        assert np.all(r["token_event"][off[i]:off[i + 1]] == e)
+    # uniform setting of the configs: alpha = beta = 1, s1 = s2 = 2 keeps a quarter
+    r = O.compress_encoder_tokens(v.feats, (4, 4), v.text_emb, v.event_start, 1.0, 1.0, 2, 2)
+    assert r["tokens"].shape[0] == 8 * 4 and np.all(r["frame_stride"] == 2)
+
+
+def test_round_to_bf16():
+    x = np.array([1.0, 1.00390625, 1.005859375, 1.01171875, -3.1415926, 1e-3, 65504.0, 0.0])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(x), want)
+    rng = np.random.default_rng(11)
+    y = rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))
+    np.testing.assert_array_equal(O.round_to_bf16(y), torch.from_numpy(y).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+# ---------------------------------------------------------------------------
+# P4: text-to-visual attention
+# ---------------------------------------------------------------------------
+def brute_attention(q, k, vis_start, n_vis):
+    Hq, Tq, dh = q.shape
+    Hkv, S, _ = k.shape
+    a = [0.0] * n_vis
+    for h in range(Hq):
+        g = h // (Hq // Hkv)
+        for i in range(Tq):
+            p = S - Tq + i
+            logit = [sum(float(q[h, i, c]) * float(k[g, j, c]) for c in range(dh)) / math.sqrt(dh) for j in range(p + 1)]
+            m = max(logit)
+            w = [math.exp(x - m) for x in logit]
+            z = sum(w)
+            for j in range(n_vis):
+                a[j] += w[vis_start + j] / z
+    return [x / (Hq * Tq) for x in a]
+
+
+def test_attention_brute_force_small():
+    rng = np.random.default_rng(2)
+    q = rng.standard_normal((4, 3, 8))
+    k = rng.standard_normal((2, 2 + 9 + 3, 8))
+    got = O.text_to_visual_attention(q, k, 2, 9)
+    np.testing.assert_allclose(got, brute_attention(q, k, 2, 9), rtol=1e-12)
+
+
+def test_attention_rows_sum_to_one_and_uniform_keys():
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((6, 5, 16))
+    k = rng.standard_normal((3, 40, 16))
+    # all 35 non-query keys are visible to every query; the five text keys are visible causally.
+    # Calling the whole sequence "visual" must account for all probability mass.
+    a_all = O.text_to_visual_attention(q, k, 0, 40)
+    assert abs(a_all.sum() - 1.0) < 1e-12
+    a_vis = O.text_to_visual_attention(q, k, 3, 30)
+    np.testing.assert_allclose(a_vis, a_all[3:33], rtol=1e-13)
+    # identical keys: query at position p spreads 1/(p+1) on each visible key
+    k1 = np.broadcast_to(rng.standard_normal((3, 1, 16)), (3, 40, 16)).copy()
+    a = O.text_to_visual_attention(q, k1, 0, 35)
+    want = np.mean([1.0 / (35 + i + 1) for i in range(5)])
+    np.testing.assert_allclose(a, np.full(35, want), rtol=1e-12)
+
+
+def test_attention_matches_library_sdpa():
+    """With one-hot values the library attention routine returns the probabilities themselves."""
+    rng = np.random.default_rng(6)
+    Hq, Hkv, Tq, S, dh = 4, 2, 6, 50, 16
+    q = rng.standard_normal((Hq, Tq, dh))
+    k = rng.standard_normal((Hkv, S, dh))
+    kk = torch.from_numpy(k).repeat_interleave(Hq // Hkv, dim=0)
+    pos_q = torch.arange(S - Tq, S)[:, None]
+    mask = torch.arange(S)[None, :] <= pos_q
+    probs = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[None], kk[None],
+                                                             torch.eye(S, dtype=torch.float64).expand(1, Hq, S, S),
+                                                             attn_mask=mask)[0]
+    want = probs.mean(dim=(0, 1))[5:5 + 30].numpy()
+    np.testing.assert_allclose(O.text_to_visual_attention(q, k, 5, 30), want, rtol=1e-10)
+
+
+def test_attention_gqa_head_mapping():
+    # keys differ per kv head; query heads 0,1 must read kv head 0 and heads 2,3 kv head 1
+    rng = np.random.default_rng(8)
+    q = rng.standard_normal((4, 2, 8))
+    k = rng.standard_normal((2, 12, 8))
+    full = O.text_to_visual_attention(q, k, 0, 10)
+    parts = [O.text_to_visual_attention(q[h:h + 1], k[h // 2:h // 2 + 1], 0, 10) for h in range(4)]
+    np.testing.assert_allclose(full, np.mean(parts, axis=0), rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------
+# P5: quotas, per-segment top-k, compaction
+# ---------------------------------------------------------------------------
+def test_quota_arithmetic_by_hand():
+    assert O.ceil_ratio(0.25 * 32) == 8                               # Tiny
+    assert O.ceil_ratio(0.25 * 18432) == 4608                          # prefill config
+    n = 36864
+    for want in (18432, 9216, 4608):                                   # hierarchical config
+        n = O.ceil_ratio(0.5 * n)
+        assert n == want
+    g = golden()
+    r, alpha = g["impl_longva_r"], g["impl_alpha"]
+    assert O.retention_ratios(0, r, alpha) == (1.0, 1.0)
+    assert O.retention_ratios(1, r, alpha) == (0.55, 0.275)
+    np.testing.assert_allclose(O.retention_ratios(2, r, alpha), (0.3025, 0.0), rtol=1e-15)
+    assert O.retention_ratios(3, r, alpha) == (0.0, 0.0)
+    assert O.retention_quotas(1, r, alpha, 10000, 8432) == (5500, 2319)    # 0.275 * 8432 = 2318.8
+    assert O.retention_quotas(2, r, alpha, 10000, 8432) == (3025, 0)
+    assert O.retention_quotas(3, r, alpha, 10000, 8432) == (0, 0)
+    assert O.retention_quotas(0, r, alpha, 10000, 8432) == (10000, 8432)
+
+
+def test_topk_against_stable_argsort_and_invariants():
+    rng = np.random.default_rng(9)
+    for trial in range(40):
+        n = int(rng.integers(1, 200))
+        n_seg = int(rng.integers(1, 4))
+        seg = rng.integers(0, n_seg, size=n).astype(np.int32)
+        scores = np.round(rng.standard_normal(n), 1 if trial % 2 else 6)       # exact ties every other trial
+        quota = [int(rng.integers(0, (seg == s).sum() + 1)) for s in range(n_seg)]
+        kept = O.segmented_topk(scores, seg, quota)
+        assert np.all(np.diff(kept) > 0)
+        want = []
+        for s in range(n_seg):
+            members = np.nonzero(seg == s)[0]
+            order = np.argsort(-scores[members], kind="stable")
+            want.extend(members[order[:quota[s]]].tolist())
+            k_s = kept[seg[kept] == s]
+            assert len(k_s) == quota[s]
+            dropped = np.setdiff1d(members, k_s)
+            if len(k_s) and len(dropped):
+                assert scores[k_s].min() >= scores[dropped].max()
+        np.testing.assert_array_equal(kept, np.sort(want))
+
+
+def test_topk_all_equal_scores_keeps_first_indices():
+    kept = O.segmented_topk(np.full(10, 0.125), np.zeros(10, dtype=np.int32), [4])
+    np.testing.assert_array_equal(kept, [0, 1, 2, 3])
+    kept = O.segmented_topk(np.full(10, 0.125), np.array([0, 1] * 5, dtype=np.int32), [2, 3])
+    np.testing.assert_array_equal(kept, [0, 1, 2, 3, 5])
+
+
+def test_prefill_prune_layout_and_nesting():
+    rng = np.random.default_rng(10)
+    vis_start, n_vis, n_text, D = 2, 24, 3, 4
+    S = vis_start + n_vis + n_text
+    hidden = rng.standard_normal((S, D))
+    q = rng.standard_normal((2, n_text, 8))
+    k = rng.standard_normal((2, S, 8))
+    ev = np.repeat(np.arange(4), 6).astype(np.int32)
+    seg = (ev % 2).astype(np.int32)
+    w = np.array([1.0, 0.5, 2.0, 1.5])
+    out = O.prefill_prune(hidden, q, k, vis_start, n_vis, seg, ev, w, [6, 3])
+    kept = out["kept_idx"]
+    np.testing.assert_allclose(out["scores"], O.text_to_visual_attention(q, k, vis_start, n_vis) * w[ev], rtol=1e-14)
+    assert out["hidden_out"].shape == (vis_start + 9 + n_text, D)
+    np.testing.assert_array_equal(out["hidden_out"][:vis_start], hidden[:vis_start])
+    np.testing.assert_array_equal(out["hidden_out"][vis_start:vis_start + 9], hidden[vis_start + kept])
+    np.testing.assert_array_equal(out["hidden_out"][vis_start + 9:], hidden[vis_start + n_vis:])
+    np.testing.assert_array_equal(out["orig_idx_out"], kept)
+    np.testing.assert_array_equal(out["token_event_out"], ev[kept])
+    # second level selects among the survivors only: original indices are nested
+    h2 = out["hidden_out"]
+    S2 = h2.shape[0]
+    out2 = O.prefill_prune(h2, q, rng.standard_normal((2, S2, 8)), vis_start, 9, out["token_seg_out"],
+                           out["token_event_out"], w, [3, 0], orig_idx=out["orig_idx_out"])
+    assert set(out2["orig_idx_out"].tolist()) <= set(kept.tolist())
+    assert np.all(np.diff(out2["orig_idx_out"]) > 0) and np.all(out2["token_seg_out"] == 0)
+
+
+# ---------------------------------------------------------------------------
+# P6 / P7 / P8: KV compaction and the paper's cache accounting
+# ---------------------------------------------------------------------------
+def test_kv_compact_is_a_pure_row_copy():
+    rows = np.arange(50)
+    slab = synth.kv_pattern(3, 1, 2, 1, rows, 16)
+    idx = np.array([0, 1, 5, 7, 30, 49], dtype=np.int32)
+    out = O.kv_compact(slab, idx)
+    assert out.dtype == slab.dtype
+    for i, j in enumerate(idx):
+        assert out[i].tobytes() == slab[j].tobytes()
+    np.testing.assert_array_equal(O.kv_compact(slab, None), slab)
+    sched = O.kv_text_only_schedule(5, 2, 40, 10)
+    assert sched[0] is None and sched[1] is None
+    np.testing.assert_array_equal(sched[2], np.arange(40, 50))
+    assert O.kv_token_layers(5, 2, 40, 10) == 2 * 50 + 3 * 10 == sum(
+        50 if s is None else len(s) for s in sched)
+
+
+def test_stage3_reading_reproduces_table3():
+    """Table 3: with l_1 = 3 of 28 layers, 'layers below l_1 keep everything, the rest keep text only'
+    must turn the stage-1 cache (171.8 MB) into the stage-3 cache (22.3 MB) for a plausible prompt length."""
+    g = golden()
+    L, l1 = int(g["impl_layers_7b"]), int(g["impl_l1"])
+    per_token_layer = 4 * 128 * 2 * 2
+    total_tokens = g["t3_kv_stage1_mb"] * 2 ** 20 / (per_token_layer * L)            # visual + text after stage 1
+    token_layers = g["t3_kv_stage3_mb"] * 2 ** 20 / per_token_layer
+    n_text = (token_layers - l1 * total_tokens) / (L - l1)
+    assert 40 < n_text < 120
+    n_vis = round(total_tokens - n_text)
+    got_mb = O.kv_token_layers(L, l1, n_vis, round(n_text)) * per_token_layer / 2 ** 20
+    assert abs(got_mb - g["t3_kv_stage3_mb"]) < 0.1
+    # 1-based numbering of l_1 (two full layers) or dropping from layer 0 cannot give the printed value
+    for wrong_l1 in (0, 2, 4):
+        assert abs(O.kv_token_layers(L, wrong_l1, n_vis, round(n_text)) * per_token_layer / 2 ** 20
+                   - g["t3_kv_stage3_mb"]) > 5.0
+
+
+def test_headline_percentages_rederive():
+    g = golden()
+    assert round(100 * (1 - g["t2_longva_flops_metok"] / g["t2_longva_flops_base"]), 1) == g["abstract_longva_flops_reduction_pct"]
+    assert abs(100 * (1 - g["t2_longva_kv_metok_mb"] / g["t2_longva_kv_base_mb"]) - g["abstract_longva_kv_saving_pct"]) < 0.15
+    assert round(100 * (1 - g["t2_ov7b_flops_metok"] / g["t2_ov7b_flops_base"]), 1) == g["sec43_ov7b_flops_reduction_pct"]
+    assert round(100 * (1 - g["t2_ov7b_prefill_metok_ms"] / g["t2_ov7b_prefill_base_ms"]), 1) == g["sec43_ov7b_prefill_reduction_pct"]
+    assert round(100 * (1 - g["t2_ov7b_kv_metok_mb"] / g["t2_ov7b_kv_base_mb"]), 1) == g["sec43_ov7b_kv_reduction_pct"]
+    # LongVA's base cache is 128 frames x 144 tokens plus a prompt: 24 x 24 CLIP patches pooled with stride 2
+    tokens = g["t2_longva_kv_base_mb"] * 2 ** 20 / (g["impl_layers_7b"] * 4 * 128 * 2 * 2)
+    assert 20 < tokens - g["frames_longva"] * O.pool_frame(np.zeros((576, 1)), (24, 24), 2).shape[0] < 150
