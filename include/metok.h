@@ -1,0 +1,228 @@
+/*
+ * metok.h -- C ABI of the METok token-compression hot path for AMD MI355X (gfx950).
+ *
+ * METok (arXiv 2506.02850) removes visual tokens of a video LLM in three stages:
+ *   stage 1 (Sec. 3.2.1, Algorithm 1): split the frames into events at the lowest adjacent-frame
+ *           cosine similarities (Eq. 4), rank events and frames against a text embedding (Eq. 5)
+ *           and pool every frame's patch grid with a stride that depends on that ranking;
+ *   stage 2 (Sec. 3.2.2, Eq. 6-7): at chosen prefill layers keep only the visual tokens that
+ *           receive the most attention from the text, with per-class retention quotas, and
+ *           compact the hidden states;
+ *   stage 3 (Sec. 3.3): compact the KV cache to the retained rows.
+ *
+ * Conventions shared by every call
+ *   - Every pointer named "device" is GPU memory of the current HIP device; "host" is ordinary
+ *     host memory.  The library never allocates, frees or keeps a pointer: the caller owns all
+ *     buffers, including the scratch `workspace`, whose minimum size comes from the matching
+ *     *_workspace_bytes() query (called with the same shape arguments).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue
+ *     work on that stream; they never synchronise.  Results are deterministic: the same inputs
+ *     give bit-identical outputs (no floating-point atomics anywhere).
+ *   - Return value: METOK_OK or a negative METOK_ERR_* code.  On error nothing has been
+ *     enqueued (argument errors) or the launch failed (METOK_ERR_DEVICE); metok_last_error()
+ *     returns a thread-local description.
+ *   - dtype is METOK_F32 or METOK_BF16; tensors are dense, row-major, innermost dimension last,
+ *     16-byte aligned.  Indices and counts stored in memory are int32.
+ *   - Inputs must be finite.  NaN/Inf never cause out-of-bounds accesses but make the
+ *     selections unspecified.
+ *   - Ratios are turned into counts with ceil(x - 1e-9) evaluated in double precision, the
+ *     guarded form of the paper's ceil(alpha k) (Sec. 3.2.1); ties in every ranking go to the
+ *     lower index.
+ */
+#ifndef METOK_H
+#define METOK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define METOK_API __attribute__((visibility("default")))
+
+enum {
+    METOK_OK = 0,
+    METOK_ERR_INVALID_ARG = -1,  /* a shape, ratio, pointer or alignment is not acceptable */
+    METOK_ERR_UNSUPPORTED = -2,  /* valid request that this build has no kernel for */
+    METOK_ERR_WORKSPACE = -3,    /* workspace missing or smaller than *_workspace_bytes() */
+    METOK_ERR_CAPACITY = -4,     /* an output buffer is smaller than the worst case */
+    METOK_ERR_DEVICE = -5        /* the HIP runtime reported an error */
+};
+
+enum { METOK_F32 = 0, METOK_BF16 = 1 };
+enum { METOK_SIM_FLAT = 0 };                       /* Eq. 4 over all N*d entries of a frame */
+enum { METOK_EVENT_MEAN = 0, METOK_EVENT_MAX = 1 };/* event score: Sec. 3.2.1 text / Algorithm 1 */
+enum { METOK_POOL_FLOOR = 0, METOK_POOL_CEIL = 1 };/* output side floor(g/s) or ceil(g/s) */
+
+#define METOK_MAX_FRAMES 8192     /* T limit of the stage-1 calls */
+#define METOK_MAX_SEGMENTS 256    /* n_seg limit of metok_prefill_prune */
+#define METOK_MAX_LAYERS 128      /* L limit of metok_kv_compact */
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+METOK_API const char* metok_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+METOK_API int metok_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 1a -- temporal event segmentation (Sec. 3.2.1 "Temporal Event Segmentation", Eq. 4;
+ * first two lines of Algorithm 1), optionally fused with the frame-text relevance of Eq. 5 so
+ * that the frame features are streamed from HBM once.
+ *
+ *   feats        device, [T, N, d] of `dtype`: N patch tokens of width d for each of T frames.
+ *   text_emb     device, [d] of `dtype`, or NULL.  When given, frame_score is produced.
+ *   k            number of events, 1 <= k <= T.
+ *   sim_mode     METOK_SIM_FLAT: S_i = <v_i, v_{i+1}> / (|v_i| |v_{i+1}|) with the inner product
+ *                and norms over all N*d entries (a denominator below 1e-12 gives S_i = 0).
+ *   sim          device out, [T-1] float: S_i for the pair (i, i+1), i = 0..T-2.
+ *   event_start  device out, [k+1] int32: event e covers frames [event_start[e], event_start[e+1]);
+ *                event_start[0] = 0, event_start[k] = T, strictly increasing.  The k-1 lowest
+ *                S_i are the boundaries; a boundary at i makes frame i+1 open an event.
+ *   frame_event  device out, [T] int32: event id of every frame.
+ *   frame_score  device out, [T] float, or NULL: mean over the frame's N tokens of
+ *                cos(token, text_emb) (Eq. 5 read per token).  Requires text_emb.
+ *   Limits: 1 <= T <= METOK_MAX_FRAMES (T = 1: no similarities, one event); T * N < 2^31;
+ *   d a multiple of 8 (bf16) or 4 (f32) and at most 8192 (bf16) / 4096 (f32).
+ * ------------------------------------------------------------------------------------------- */
+METOK_API size_t metok_segment_events_workspace_bytes(int T, int N, int d, int dtype);
+
+METOK_API int metok_segment_events(const void* feats, int dtype, int T, int N, int d,
+                         const void* text_emb, int k, int sim_mode,
+                         float* sim, int32_t* event_start, int32_t* frame_event,
+                         float* frame_score,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 1b -- key event / key frame identification and adaptive pooling (Sec. 3.2.1 "Key
+ * Visual-Text Semantic Identification" and "Adaptive Pooling Strategy"; Algorithm 1 from the
+ * second comment on).
+ *
+ *   feats           device, [T, grid_h*grid_w, d] of `dtype`; tokens of a frame are row-major
+ *                   over the grid_h x grid_w patch grid.
+ *   text_emb        device, [d] of `dtype`; used only when frame_score_in is NULL.
+ *   frame_score_in  device, [T] float from metok_segment_events, or NULL to compute it here.
+ *   event_start     device, [k+1] int32 as written by metok_segment_events.
+ *   alpha, beta     key-event and key-frame ratios, 0 < ratio <= 1: ceil(alpha k) events with
+ *                   the best event score are key; in every event ceil(beta len) frames with the
+ *                   best frame score are key frames.
+ *   s1, s2          pooling strides (>= 1) of key / non-key frames in key events; non-key
+ *                   events use ceil(s1/alpha), ceil(s2/alpha).  Strides are clamped to
+ *                   max(grid_h, grid_w).
+ *   event_reduce    METOK_EVENT_MEAN (default of the paper's text) or METOK_EVENT_MAX.
+ *   pool_edge       METOK_POOL_FLOOR: output side max(1, floor(g/s)), trailing cells that do
+ *                   not fill a window are dropped; METOK_POOL_CEIL: side ceil(g/s), edge
+ *                   windows average their valid cells.  Pooling is a non-overlapping s x s mean.
+ *   out_tokens      device out, [out_capacity_rows, d] of `out_dtype`: pooled frames appended in
+ *                   temporal order; row count M = frame_offsets[T] (data dependent).  Means are
+ *                   accumulated in fp32 and rounded once (nearest even) to out_dtype.
+ *   out_capacity_rows  must be >= T * side(grid_h, min(s1,s2)) * side(grid_w, min(s1,s2)), the
+ *                   worst case, else METOK_ERR_CAPACITY.
+ *   frame_offsets   device out, [T+1] int32: pooled rows of frame i are [offsets[i], offsets[i+1]).
+ *   token_event     device out, [out_capacity_rows] int32: event id of every pooled row.
+ *   event_is_key    device out, [k] uint8.        frame_is_key  device out, [T] uint8.
+ *   frame_stride    device out, [T] int32.        event_score   device out, [k] float.
+ *   frame_score_out device out, [T] float or NULL (copy of the scores used).
+ * ------------------------------------------------------------------------------------------- */
+METOK_API size_t metok_compress_encoder_tokens_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype);
+
+METOK_API int metok_compress_encoder_tokens(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                                  const void* text_emb, const float* frame_score_in,
+                                  const int32_t* event_start, int k,
+                                  double alpha, double beta, int s1, int s2,
+                                  int event_reduce, int pool_edge,
+                                  void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                                  int32_t* frame_offsets, int32_t* token_event,
+                                  uint8_t* event_is_key, uint8_t* frame_is_key,
+                                  int32_t* frame_stride, float* event_score, float* frame_score_out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 2 -- one level of hierarchical token pruning (Sec. 3.2.2).
+ *
+ * Retention quotas of Eq. 6-7 (host arithmetic only): level 0 = before l_1, 1 = [l_1, l_2),
+ * 2 = [l_2, l_3), 3 = from l_3 on.  Key-event tokens keep 1, r, r^2, 0 of the n_key_orig tokens
+ * that entered the LLM, non-key tokens keep 1, alpha r, 0, 0 of n_non_orig.
+ * quota_out[0] = key quota, quota_out[1] = non-key quota.
+ * ------------------------------------------------------------------------------------------- */
+METOK_API int metok_retention_quotas(int level, double r, double alpha, int64_t n_key_orig, int64_t n_non_orig,
+                           int32_t quota_out[2]);
+
+/*
+ * The sequence is X = [prefix; X_vis; X_text] (Eq. 3): vis_start prefix rows, n_vis visual rows,
+ * then S - vis_start - n_vis text rows.
+ *
+ *   hidden       device, [S, D] of `dtype`.
+ *   q_text       device, [Hq, Tq, dh] of `dtype`: queries of the LAST Tq positions of the sequence
+ *                (Tq <= number of text rows), or NULL: then `scores` is an input and the
+ *                attention step is skipped.
+ *   k_all        device, [Hkv, S, dh] of `dtype`: keys of all S positions (ignored if q_text NULL).
+ *                Query head h reads kv head h / (Hq / Hkv).
+ *   token_seg    device, [n_vis] int32 in [0, n_seg): retention class of each visual token
+ *                (e.g. 0 = key event, 1 = non-key event; or the event id; or all 0).
+ *   token_event  device, [n_vis] int32 in [0, n_events): event of each visual token.
+ *   event_weight device, [n_events] float or NULL (= 1): importance multiplier w_e.
+ *   seg_quota    host, [n_seg] int32: tokens to keep per class, 0 <= quota <= class population.
+ *                (The populations live on the device and cannot be checked here: a quota above
+ *                its class population keeps the whole class and the tail of the outputs is
+ *                padded with index 0; nothing is read or written out of bounds.)
+ *   orig_idx_in  device, [n_vis] int32 or NULL (= 0..n_vis-1): index of each visual token in the
+ *                sequence that first entered the LLM (carried through the levels).
+ *   scores       device, [n_vis] float.  Out (in when q_text is NULL):
+ *                score_j = w_{e(j)} * mean over the Hq*Tq (head, query) pairs of the causal
+ *                softmax probability of visual key j, logits q.k / sqrt(dh), each query at
+ *                position p attending keys 0..p.
+ *   kept_idx     device out, [sum quota] int32: kept visual positions (0-based inside the visual
+ *                span), ascending.  Per class the quota highest scores are kept.
+ *   hidden_out   device out, [S - n_vis + sum quota, D]: prefix rows, kept visual rows in order,
+ *                text rows.  Must not overlap `hidden`.
+ *   token_seg_out, token_event_out, orig_idx_out  device out, [sum quota] int32 (each may be NULL).
+ *   Limits: dh in {32, 64, 128, 256} for bf16, {32, 64, 128} for f32; Hq a multiple of Hkv;
+ *   D * sizeof(dtype) a multiple of 16; n_seg <= METOK_MAX_SEGMENTS.
+ */
+METOK_API size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype);
+
+METOK_API int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
+                        const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                        int vis_start, int n_vis,
+                        const int32_t* token_seg, const int32_t* token_event,
+                        const float* event_weight, int n_events,
+                        int n_seg, const int32_t* seg_quota,
+                        const int32_t* orig_idx_in,
+                        float* scores, int32_t* kept_idx, void* hidden_out,
+                        int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 3 -- KV-cache compaction to the retained rows (Sec. 3.3), in place.
+ *
+ *   k_layers, v_layers  host arrays of L device pointers; layer l holds K (resp. V) as
+ *                [B, Hkv, S_cap, dh] of `dtype` (Eq. 3 per layer, head-major).
+ *   idx          host array of L device pointers; idx[l] is [B, n_keep[l]] int32, strictly
+ *                ascending positions 0 <= p < S_cap inside the current cache for each video b,
+ *                including the text rows that stay.  idx[l] == NULL: layer l is left untouched.
+ *                The paper's rule is "NULL below l_1, the text rows from l_1 on"; per-layer
+ *                retained sets of stage 2 are passed the same way.
+ *   n_keep       host, [L] int32 (ignored where idx[l] is NULL).
+ *   new_len      device out, [L] int32 or NULL: n_keep[l], or S_cap for untouched layers.
+ *   Effect: for every (l, b, head) and for K and V, row i <- row idx[l][b][i], i < n_keep[l].
+ *   Rows >= n_keep[l] are unspecified afterwards.  Positions that are not >= their rank or not
+ *   below S_cap are skipped (never dereferenced).  dh * sizeof(dtype) must be a multiple of 16.
+ *   No workspace is needed.
+ * ------------------------------------------------------------------------------------------- */
+METOK_API int metok_kv_compact(void* const* k_layers, void* const* v_layers, int L, int B, int Hkv,
+                     int64_t S_cap, int dh, int dtype,
+                     const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
+                     void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement helper (not part of the method): a plain device-to-device copy kernel with the
+ * same access width as the streaming kernels.  The bench uses it to calibrate the profiler's
+ * HBM byte counters against a transfer of known size.  bytes must be a multiple of 16.
+ * ------------------------------------------------------------------------------------------- */
+METOK_API int metok_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* METOK_H */

@@ -1,0 +1,294 @@
+"""Thin ctypes binding of libmetok.so: same names as the C calls, argument marshalling only.
+
+PyTorch is used for device memory and the current stream; every step of the method runs in
+the HIP kernels.  There is no CPU fallback: importing this module without the compiled library,
+or calling it without a GPU, raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch  # must be imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmetok.so")
+
+METOK_OK = 0
+F32, BF16 = 0, 1
+SIM_FLAT = 0
+EVENT_MEAN, EVENT_MAX = 0, 1
+POOL_FLOOR, POOL_CEIL = 0, 1
+
+EXPORTS = [
+    "metok_last_error", "metok_version",
+    "metok_segment_events_workspace_bytes", "metok_segment_events",
+    "metok_compress_encoder_tokens_workspace_bytes", "metok_compress_encoder_tokens",
+    "metok_retention_quotas",
+    "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
+    "metok_kv_compact", "metok_calib_copy",
+]
+
+
+class MetokError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"metok error {code}: {text}")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_02850_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, i64, sz, dbl = c.c_void_p, c.c_int, c.c_int64, c.c_size_t, c.c_double
+    lib.metok_last_error.restype = c.c_char_p
+    lib.metok_last_error.argtypes = []
+    lib.metok_version.restype = i32
+    lib.metok_segment_events_workspace_bytes.restype = sz
+    lib.metok_segment_events_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.metok_segment_events.restype = i32
+    lib.metok_segment_events.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.metok_compress_encoder_tokens_workspace_bytes.restype = sz
+    lib.metok_compress_encoder_tokens_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.metok_compress_encoder_tokens.restype = i32
+    lib.metok_compress_encoder_tokens.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, dbl, dbl, i32, i32,
+                                                  i32, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.metok_retention_quotas.restype = i32
+    lib.metok_retention_quotas.argtypes = [i32, dbl, dbl, i64, i64, c.POINTER(c.c_int32)]
+    lib.metok_prefill_prune_workspace_bytes.restype = sz
+    lib.metok_prefill_prune_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, i32]
+    lib.metok_prefill_prune.restype = i32
+    lib.metok_prefill_prune.argtypes = [vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
+                                        i32, c.POINTER(c.c_int32), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.metok_kv_compact.restype = i32
+    lib.metok_kv_compact.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, c.POINTER(vp),
+                                     c.POINTER(c.c_int32), vp, vp]
+    lib.metok_calib_copy.restype = i32
+    lib.metok_calib_copy.argtypes = [vp, vp, sz, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != METOK_OK:
+        raise MetokError(rc, _lib.metok_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"metok supports float32 and bfloat16 tensors, got {t.dtype}")
+
+
+def _torch_dtype(code: int) -> torch.dtype:
+    return torch.bfloat16 if code == BF16 else torch.float32
+
+
+def _dev(t: Optional[torch.Tensor], name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (there is no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def metok_last_error() -> str:
+    return _lib.metok_last_error().decode()
+
+
+def metok_version() -> int:
+    return int(_lib.metok_version())
+
+
+# -------------------------------------------------------------------------------------------------
+def metok_segment_events(feats: torch.Tensor, k: int, text_emb: Optional[torch.Tensor] = None,
+                         sim_mode: int = SIM_FLAT, workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """feats [T, N, d] -> sim [T-1], event_start [k+1], frame_event [T] (+ frame_score [T] if text_emb)."""
+    T, N, d = feats.shape
+    dt = _dtype_code(feats)
+    dev = feats.device
+    need = _lib.metok_segment_events_workspace_bytes(T, N, d, dt)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    sim = torch.empty(max(T - 1, 0), dtype=torch.float32, device=dev)
+    event_start = torch.empty(k + 1, dtype=torch.int32, device=dev)
+    frame_event = torch.empty(T, dtype=torch.int32, device=dev)
+    frame_score = torch.empty(T, dtype=torch.float32, device=dev) if text_emb is not None else None
+    _check(_lib.metok_segment_events(_dev(feats, "feats"), dt, T, N, d, _dev(text_emb, "text_emb"), k, sim_mode,
+                                     _dev(sim, "sim"), _dev(event_start, "event_start"), _dev(frame_event, "frame_event"),
+                                     _dev(frame_score, "frame_score"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    out = dict(sim=sim, event_start=event_start, frame_event=frame_event)
+    if frame_score is not None:
+        out["frame_score"] = frame_score
+    return out
+
+
+def pooled_capacity(T: int, grid_h: int, grid_w: int, s1: int, s2: int, pool_edge: int = POOL_FLOOR) -> int:
+    s = max(1, min(min(s1, s2), max(grid_h, grid_w)))
+    side = (lambda g: max(1, g // s)) if pool_edge == POOL_FLOOR else (lambda g: -(-g // s))
+    return T * side(grid_h) * side(grid_w)
+
+
+def metok_compress_encoder_tokens(feats: torch.Tensor, grid_h: int, grid_w: int, event_start: torch.Tensor,
+                                  alpha: float, beta: float, s1: int, s2: int,
+                                  text_emb: Optional[torch.Tensor] = None,
+                                  frame_score: Optional[torch.Tensor] = None,
+                                  event_reduce: int = EVENT_MEAN, pool_edge: int = POOL_FLOOR,
+                                  out_dtype: Optional[torch.dtype] = None,
+                                  out_tokens: Optional[torch.Tensor] = None,
+                                  workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """Key events / key frames and adaptive pooling.  Returns out_tokens (capacity rows; the first
+    frame_offsets[T] are valid) plus frame_offsets, token_event, event_is_key, frame_is_key, frame_stride,
+    event_score, frame_score -- all on the device; nothing is synchronised."""
+    T, N, d = feats.shape
+    if N != grid_h * grid_w:
+        raise ValueError("feats.shape[1] must equal grid_h * grid_w")
+    dt = _dtype_code(feats)
+    dev = feats.device
+    k = event_start.numel() - 1
+    odt = out_dtype if out_dtype is not None else feats.dtype
+    cap = pooled_capacity(T, grid_h, grid_w, s1, s2, pool_edge)
+    if out_tokens is None:
+        out_tokens = torch.empty((cap, d), dtype=odt, device=dev)
+    need = _lib.metok_compress_encoder_tokens_workspace_bytes(T, grid_h, grid_w, d, dt)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    frame_offsets = torch.empty(T + 1, dtype=torch.int32, device=dev)
+    token_event = torch.empty(out_tokens.shape[0], dtype=torch.int32, device=dev)
+    event_is_key = torch.empty(k, dtype=torch.uint8, device=dev)
+    frame_is_key = torch.empty(T, dtype=torch.uint8, device=dev)
+    frame_stride = torch.empty(T, dtype=torch.int32, device=dev)
+    event_score = torch.empty(k, dtype=torch.float32, device=dev)
+    frame_score_out = torch.empty(T, dtype=torch.float32, device=dev)
+    _check(_lib.metok_compress_encoder_tokens(
+        _dev(feats, "feats"), dt, T, grid_h, grid_w, d, _dev(text_emb, "text_emb"), _dev(frame_score, "frame_score"),
+        _dev(event_start, "event_start"), k, float(alpha), float(beta), int(s1), int(s2), event_reduce, pool_edge,
+        _dev(out_tokens, "out_tokens"), out_tokens.shape[0], _dtype_code(out_tokens),
+        _dev(frame_offsets, "frame_offsets"), _dev(token_event, "token_event"), _dev(event_is_key, "event_is_key"),
+        _dev(frame_is_key, "frame_is_key"), _dev(frame_stride, "frame_stride"), _dev(event_score, "event_score"),
+        _dev(frame_score_out, "frame_score_out"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    return dict(out_tokens=out_tokens, frame_offsets=frame_offsets, token_event=token_event,
+                event_is_key=event_is_key, frame_is_key=frame_is_key, frame_stride=frame_stride,
+                event_score=event_score, frame_score=frame_score_out)
+
+
+def metok_retention_quotas(level: int, r: float, alpha: float, n_key_orig: int, n_non_orig: int) -> List[int]:
+    out = (ctypes.c_int32 * 2)()
+    _check(_lib.metok_retention_quotas(level, float(r), float(alpha), int(n_key_orig), int(n_non_orig), out))
+    return [int(out[0]), int(out[1])]
+
+
+def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_seg: torch.Tensor,
+                        seg_quota: Sequence[int],
+                        q_text: Optional[torch.Tensor] = None, k_all: Optional[torch.Tensor] = None,
+                        token_event: Optional[torch.Tensor] = None, event_weight: Optional[torch.Tensor] = None,
+                        orig_idx: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                        hidden_out: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """One pruning level.  With q_text/k_all the attention scores are computed; otherwise `scores` is used as given."""
+    S, D = hidden.shape
+    dt = _dtype_code(hidden)
+    dev = hidden.device
+    n_seg = len(seg_quota)
+    total = int(sum(int(q) for q in seg_quota))
+    quota_arr = (ctypes.c_int32 * n_seg)(*[int(q) for q in seg_quota])
+    if q_text is not None:
+        if k_all is None:
+            raise ValueError("k_all is required with q_text")
+        Hq, Tq, dh = q_text.shape
+        Hkv = k_all.shape[0]
+        if k_all.shape[1] != S or k_all.shape[2] != dh or _dtype_code(q_text) != dt or _dtype_code(k_all) != dt:
+            raise ValueError("k_all must be [Hkv, S, dh] with the dtype of hidden and q_text")
+        scores = torch.empty(n_vis, dtype=torch.float32, device=dev)
+    else:
+        if scores is None:
+            raise ValueError("either q_text/k_all or scores must be given")
+        Hq = Hkv = dh = Tq = 0
+    need = _lib.metok_prefill_prune_workspace_bytes(S, Hq, Hkv, dh, Tq, n_vis, dt)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    kept_idx = torch.empty(total, dtype=torch.int32, device=dev)
+    out_rows = S - n_vis + total
+    if hidden_out is None:
+        hidden_out = torch.empty((out_rows, D), dtype=hidden.dtype, device=dev)
+    token_seg_out = torch.empty(total, dtype=torch.int32, device=dev)
+    token_event_out = torch.empty(total, dtype=torch.int32, device=dev) if token_event is not None else None
+    orig_idx_out = torch.empty(total, dtype=torch.int32, device=dev)
+    n_events = int(event_weight.numel()) if event_weight is not None else 0
+    _check(_lib.metok_prefill_prune(
+        _dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
+        int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
+        _dev(event_weight, "event_weight"), n_events, n_seg, quota_arr, _dev(orig_idx, "orig_idx"),
+        _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), _dev(hidden_out, "hidden_out"),
+        _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
+        _dev(orig_idx_out, "orig_idx_out"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    out = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
+               orig_idx_out=orig_idx_out)
+    if token_event_out is not None:
+        out["token_event_out"] = token_event_out
+    return out
+
+
+def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.Tensor],
+                     idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """In-place compaction of per-layer K/V caches [B, Hkv, S_cap, dh] to idx[l] [B, n_keep_l] (None = untouched)."""
+    L = len(k_layers)
+    if len(v_layers) != L or len(idx) != L:
+        raise ValueError("k_layers, v_layers and idx must have one entry per layer")
+    B, Hkv, S_cap, dh = k_layers[0].shape
+    dt = _dtype_code(k_layers[0])
+    dev = k_layers[0].device
+    vp = ctypes.c_void_p
+    karr, varr, iarr = (vp * L)(), (vp * L)(), (vp * L)()
+    nk = (ctypes.c_int32 * L)()
+    for l in range(L):
+        if tuple(k_layers[l].shape) != (B, Hkv, S_cap, dh) or tuple(v_layers[l].shape) != (B, Hkv, S_cap, dh):
+            raise ValueError("all layers must share one [B, Hkv, S_cap, dh] shape")
+        karr[l] = _dev(k_layers[l], "k_layers")
+        varr[l] = _dev(v_layers[l], "v_layers")
+        if idx[l] is None:
+            iarr[l] = None
+            nk[l] = 0
+        else:
+            if idx[l].dtype != torch.int32 or idx[l].dim() != 2 or idx[l].shape[0] != B:
+                raise ValueError("idx[l] must be int32 [B, n_keep]")
+            # an empty list (drop every row) still needs a non-NULL pointer: NULL means "leave the layer alone"
+            iarr[l] = _dev(idx[l], "idx") if idx[l].numel() else _dev(new_len_dummy(dev), "idx")
+            nk[l] = idx[l].shape[1]
+    if new_len is None:
+        new_len = torch.empty(L, dtype=torch.int32, device=dev)
+    _check(_lib.metok_kv_compact(karr, varr, L, B, Hkv, S_cap, dh, dt, iarr, nk, _dev(new_len, "new_len"), _stream()))
+    return new_len
+
+
+_DUMMY = {}
+
+
+def new_len_dummy(dev) -> torch.Tensor:
+    key = str(dev)
+    if key not in _DUMMY:
+        _DUMMY[key] = torch.zeros(4, dtype=torch.int32, device=dev)
+    return _DUMMY[key]
+
+
+def metok_calib_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(_lib.metok_calib_copy(_dev(dst, "dst"), _dev(src, "src"), nbytes, _stream()))

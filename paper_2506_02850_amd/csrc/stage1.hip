@@ -1,0 +1,564 @@
+// Stage 1 (Sec. 3.2.1, Algorithm 1): event segmentation, key event / key frame identification
+// and adaptive pooling of the frame features V [T, N, d].
+//
+// Kernels
+//   frame_stats_kernel   one streaming pass over V: per frame |v_i|^2 and <v_i, v_{i+1}> (Eq. 4) and
+//                        the mean per-token cosine with the text embedding (Eq. 5)
+//   segment_kernel       one workgroup: T-1 cosines, the k-1 lowest become boundaries
+//   plan_kernel          one workgroup: event scores, key events, key frames, strides, row offsets
+//   pool_kernel          second streaming pass: s x s mean pooling of every frame, packed output
+#include "common.h"
+
+namespace metok {
+
+constexpr int kStatsThreads = 256;
+constexpr int kStatsWaves = kStatsThreads / 64;
+constexpr float kZeroNorm = 1e-12f;
+
+// ---------------------------------------------------------------------------------------------
+// frame_stats_kernel
+//
+// A token row (d elements) is spread over G lanes in 16-byte chunks (lane j of the group takes
+// chunks j, j+G, ...; at most KL chunks per lane).  A wave therefore works on 64/G tokens at a
+// time and a workgroup on TOK = 4 * 64/G tokens.  blockIdx.x selects the token chunk, blockIdx.y
+// a run of consecutive frames; the workgroup walks its run keeping the current frame's rows in
+// registers, so that every frame is read once (plus one extra frame per run for the last pair).
+//
+// part[(t * C + c) * 3 + {0,1,2}] = over the tokens of chunk c of frame t:
+//     sum |v|^2,  sum <v_t, v_{t+1}>,  sum of cos(token, text)
+// ---------------------------------------------------------------------------------------------
+template <typename T, int G, int KL>
+__global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
+    const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int N, int d,
+    int frames_per_run, int do_pair, float* __restrict__ part, int C) {
+    using E = Elem<T>;
+    constexpr int TPW = 64 / G;                 // tokens per wave
+    constexpr int TOK = kStatsWaves * TPW;      // tokens per workgroup
+    __shared__ float red[2][TOK][3];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane % G, tw = lane / G;
+    const int slot = wave * TPW + tw;
+    const int n = blockIdx.x * TOK + slot;
+    const bool tok_ok = n < N;
+    const int nchunks = d / E::kVec;
+    const int t0 = blockIdx.y * frames_per_run;
+    const int t1 = min(T_frames, t0 + frames_per_run);
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const size_t row_chunks = static_cast<size_t>(nchunks);
+
+    // text embedding chunks and its norm
+    uint4 txt[KL];
+    float tn2 = 0.f;
+    const bool do_text = text != nullptr;
+#pragma unroll
+    for (int k = 0; k < KL; ++k) {
+        const int c = sub + k * G;
+        txt[k] = (do_text && c < nchunks) ? reinterpret_cast<const uint4*>(text)[c] : zero;
+        tn2 = E::dot(txt[k], txt[k], tn2);
+    }
+    const float tnorm = sqrtf(group_sum<G>(tn2));
+
+    auto load_row = [&](int t, uint4 (&dst)[KL]) {
+        const uint4* row = reinterpret_cast<const uint4*>(feats) + (static_cast<size_t>(t) * N + (tok_ok ? n : 0)) * row_chunks;
+#pragma unroll
+        for (int k = 0; k < KL; ++k) {
+            const int c = sub + k * G;
+            dst[k] = (tok_ok && c < nchunks) ? row[c] : zero;
+        }
+    };
+
+    uint4 cur[KL], nxt[KL];
+    load_row(t0, cur);
+    for (int t = t0; t < t1; ++t) {
+        const bool has_next = do_pair && (t + 1 < T_frames);
+        if (has_next) load_row(t + 1, nxt);
+        float p = 0.f, q = 0.f, cd = 0.f;
+#pragma unroll
+        for (int k = 0; k < KL; ++k) {
+            p = E::dot(cur[k], cur[k], p);
+            q = E::dot(cur[k], txt[k], q);
+        }
+        if (has_next) {
+#pragma unroll
+            for (int k = 0; k < KL; ++k) cd = E::dot(cur[k], nxt[k], cd);
+        }
+        p = group_sum<G>(p);
+        q = group_sum<G>(q);
+        cd = group_sum<G>(cd);
+        const float den = sqrtf(p) * tnorm;
+        const float cosv = (do_text && tok_ok && !(den < kZeroNorm)) ? q / den : 0.f;
+        const int buf = (t - t0) & 1;
+        if (sub == 0) {
+            red[buf][slot][0] = p;
+            red[buf][slot][1] = cd;
+            red[buf][slot][2] = cosv;
+        }
+        __syncthreads();
+        if (threadIdx.x < 3) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < TOK; ++i) s += red[buf][i][threadIdx.x];
+            part[(static_cast<size_t>(t) * C + blockIdx.x) * 3 + threadIdx.x] = s;
+        }
+        if (has_next) {
+#pragma unroll
+            for (int k = 0; k < KL; ++k) cur[k] = nxt[k];
+        } else if (t + 1 < t1) {
+            load_row(t + 1, cur);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// segment_kernel: one workgroup of 1024 threads.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSegThreads = 1024;
+
+__global__ __launch_bounds__(kSegThreads) void segment_kernel(
+    const float* __restrict__ part, int C, int T, int N, int k, int have_text,
+    float* __restrict__ sim, int32_t* __restrict__ event_start, int32_t* __restrict__ frame_event,
+    float* __restrict__ frame_score, float* __restrict__ frame_norm2) {
+    __shared__ uint32_t key[METOK_MAX_FRAMES];      // ordered keys of S_i, later boundary flags
+    __shared__ int scan_scratch[17];
+    const int tid = threadIdx.x;
+
+    // per-frame totals, chunk partials summed in index order
+    for (int t = tid; t < T; t += kSegThreads) {
+        float n2 = 0.f, fs = 0.f;
+        for (int c = 0; c < C; ++c) {
+            n2 += part[(static_cast<size_t>(t) * C + c) * 3 + 0];
+            fs += part[(static_cast<size_t>(t) * C + c) * 3 + 2];
+        }
+        frame_norm2[t] = n2;
+        if (have_text && frame_score) frame_score[t] = fs / static_cast<float>(N);
+    }
+    __syncthreads();
+    // Eq. 4
+    for (int t = tid; t < T - 1; t += kSegThreads) {
+        float dot = 0.f;
+        for (int c = 0; c < C; ++c) dot += part[(static_cast<size_t>(t) * C + c) * 3 + 1];
+        const float den = sqrtf(frame_norm2[t]) * sqrtf(frame_norm2[t + 1]);
+        const float s = (den < kZeroNorm) ? 0.f : dot / den;
+        sim[t] = s;
+        key[t] = ordered_key(s);
+    }
+    __syncthreads();
+    // rank of S_i among the T-1 similarities under the order (value, index); the k-1 lowest are boundaries
+    const int per = (T + kSegThreads - 1) / kSegThreads;      // frames per thread, consecutive
+    uint32_t my_flags = 0;                                    // bit j: frame tid*per + j opens an event (per <= 8)
+    for (int j = 0; j < per; ++j) {
+        const int f = tid * per + j;                          // frame f opens an event if pair f-1 is a boundary
+        if (f >= 1 && f < T) {
+            const int i = f - 1;
+            const uint32_t ki = key[i];
+            int rank = 0;
+            for (int m = 0; m < T - 1; ++m) {
+                const uint32_t km = key[m];
+                rank += (km < ki || (km == ki && m < i)) ? 1 : 0;
+            }
+            if (rank < k - 1) my_flags |= 1u << j;
+        }
+    }
+    int total = 0;
+    int prefix = block_exclusive_scan(__popc(my_flags), scan_scratch, &total);
+    // frame_event[f] = number of event openings at or before f
+    int ev = prefix;
+    for (int j = 0; j < per; ++j) {
+        const int f = tid * per + j;
+        if (f < T) {
+            if (my_flags & (1u << j)) {
+                ++ev;
+                if (ev <= k - 1) event_start[ev] = f;         // total == k-1 by construction; the guard is for NaN input
+            }
+            frame_event[f] = ev < k ? ev : k - 1;
+        }
+    }
+    if (tid == 0) {
+        event_start[0] = 0;
+        event_start[k] = T;
+    }
+}
+
+// Eq. 5 on its own: frame_score[t] = (sum of the chunk partials of the token cosines) / N.
+__global__ __launch_bounds__(kSegThreads) void frame_score_kernel(const float* __restrict__ part, int C, int T, int N,
+                                                                  float* __restrict__ frame_score) {
+    for (int t = threadIdx.x; t < T; t += kSegThreads) {
+        float fs = 0.f;
+        for (int c = 0; c < C; ++c) fs += part[(static_cast<size_t>(t) * C + c) * 3 + 2];
+        frame_score[t] = fs / static_cast<float>(N);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// plan_kernel: one workgroup.  Event scores, key events, key frames, strides and output offsets.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int pooled_side(int g, int s, int edge) {
+    return edge == METOK_POOL_FLOOR ? max(1, g / s) : (g + s - 1) / s;
+}
+
+__global__ __launch_bounds__(kSegThreads) void plan_kernel(
+    const float* __restrict__ frame_score, const int32_t* __restrict__ event_start, int T, int k,
+    int n_key_events, double beta, int s_key_kf, int s_key_nf, int s_non_kf, int s_non_nf,
+    int grid_h, int grid_w, int event_reduce, int pool_edge,
+    float* __restrict__ event_score, uint8_t* __restrict__ event_is_key, uint8_t* __restrict__ frame_is_key,
+    int32_t* __restrict__ frame_stride, int32_t* __restrict__ frame_offsets, int32_t* __restrict__ frame_event_ws,
+    float* __restrict__ frame_score_out) {
+    __shared__ uint32_t ekey[METOK_MAX_FRAMES];    // ordered keys of the event scores (k <= T)
+    __shared__ uint8_t ev_key[METOK_MAX_FRAMES];
+    __shared__ int scan_scratch[17];
+    const int tid = threadIdx.x;
+
+    // event score: mean (Sec. 3.2.1) or max (Algorithm 1) of the frame scores, frames in index order
+    for (int e = tid; e < k; e += kSegThreads) {
+        int a = event_start[e], b = event_start[e + 1];
+        a = max(0, min(a, T)); b = max(a, min(b, T));
+        float acc = (event_reduce == METOK_EVENT_MAX) ? -INFINITY : 0.f;
+        for (int f = a; f < b; ++f) acc = (event_reduce == METOK_EVENT_MAX) ? fmaxf(acc, frame_score[f]) : acc + frame_score[f];
+        if (event_reduce != METOK_EVENT_MAX) acc = (b > a) ? acc / static_cast<float>(b - a) : 0.f;
+        event_score[e] = acc;
+        ekey[e] = ordered_key(acc);
+    }
+    __syncthreads();
+    // key events: rank under (score descending, index ascending)
+    for (int e = tid; e < k; e += kSegThreads) {
+        const uint32_t ke = ekey[e];
+        int rank = 0;
+        for (int m = 0; m < k; ++m) rank += (ekey[m] > ke || (ekey[m] == ke && m < e)) ? 1 : 0;
+        const uint8_t is_key = rank < n_key_events ? 1 : 0;
+        ev_key[e] = is_key;
+        event_is_key[e] = is_key;
+    }
+    __syncthreads();
+    // per frame: event id (binary search), rank inside the event, stride, pooled row count
+    const int per = (T + kSegThreads - 1) / kSegThreads;
+    int counts[8];
+    int mine = 0;
+    for (int j = 0; j < per; ++j) {
+        const int f = tid * per + j;
+        counts[j] = 0;
+        if (f < T) {
+            int lo = 0, hi = k - 1;                       // last event whose start is <= f
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (event_start[mid] <= f) lo = mid; else hi = mid - 1;
+            }
+            const int e = lo;
+            int a = event_start[e], b = event_start[e + 1];
+            a = max(0, min(a, T)); b = max(a, min(b, T));
+            const uint32_t kf = ordered_key(frame_score[f]);
+            int rank = 0;
+            for (int m = a; m < b; ++m) {
+                const uint32_t km = ordered_key(frame_score[m]);
+                rank += (km > kf || (km == kf && m < f)) ? 1 : 0;
+            }
+            const int len = b - a;
+            int n_kf = static_cast<int>(ceil(beta * static_cast<double>(len) - 1e-9));
+            n_kf = min(len, n_kf);
+            const bool kf_flag = rank < n_kf;
+            const bool ek_flag = ev_key[e] != 0;
+            int s = ek_flag ? (kf_flag ? s_key_kf : s_key_nf) : (kf_flag ? s_non_kf : s_non_nf);
+            frame_is_key[f] = kf_flag ? 1 : 0;
+            frame_stride[f] = s;
+            frame_event_ws[f] = e;
+            if (frame_score_out) frame_score_out[f] = frame_score[f];
+            counts[j] = pooled_side(grid_h, s, pool_edge) * pooled_side(grid_w, s, pool_edge);
+            mine += counts[j];
+        }
+    }
+    int total = 0;
+    int run = block_exclusive_scan(mine, scan_scratch, &total);
+    for (int j = 0; j < per; ++j) {
+        const int f = tid * per + j;
+        if (f < T) {
+            frame_offsets[f] = run;
+            run += counts[j];
+        }
+    }
+    if (tid == 0) frame_offsets[T] = total;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pool_kernel: blockIdx.y = frame; the waves of the frame's workgroups share its work items.
+// A work item is (pooled row, column part of 64 chunks); a lane owns one 16-byte input chunk
+// of every cell of the window and writes the pooled chunk.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPoolThreads = 256;
+
+template <typename TO> struct Store;
+template <> struct Store<float> {
+    // 4 or 8 fp32 values -> 16 or 32 bytes
+    static __device__ __forceinline__ void put(float* row, int chunk, int vec, const float (&a)[8]) {
+        float4* dst = reinterpret_cast<float4*>(row + static_cast<size_t>(chunk) * vec);
+        dst[0] = make_float4(a[0], a[1], a[2], a[3]);
+        if (vec == 8) dst[1] = make_float4(a[4], a[5], a[6], a[7]);
+    }
+};
+template <> struct Store<bf16_t> {
+    static __device__ __forceinline__ void put(bf16_t* row, int chunk, int vec, const float (&a)[8]) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(row + static_cast<size_t>(chunk) * vec);
+        if (vec == 8) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]),
+                                                        pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+        } else {
+            *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+        }
+    }
+};
+
+template <typename TI, typename TO>
+__global__ __launch_bounds__(kPoolThreads) void pool_kernel(
+    const TI* __restrict__ feats, int grid_h, int grid_w, int d,
+    const int32_t* __restrict__ frame_stride, const int32_t* __restrict__ frame_offsets,
+    const int32_t* __restrict__ frame_event, int pool_edge, int64_t capacity_rows,
+    TO* __restrict__ out, int32_t* __restrict__ token_event) {
+    using E = Elem<TI>;
+    const int f = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int s = frame_stride[f];
+    const int oh = pooled_side(grid_h, s, pool_edge), ow = pooled_side(grid_w, s, pool_edge);
+    const int base = frame_offsets[f];
+    const int ev = frame_event[f];
+    const int nchunks = d / E::kVec;
+    const int colparts = (nchunks + 63) / 64;
+    const int items = oh * ow * colparts;
+    const uint4* frame = reinterpret_cast<const uint4*>(feats) + static_cast<size_t>(f) * grid_h * grid_w * nchunks;
+    const int stride_items = gridDim.x * (kPoolThreads / 64);
+
+    for (int item = blockIdx.x * (kPoolThreads / 64) + wave; item < items; item += stride_items) {
+        const int orow = item / colparts;
+        const int chunk = (item - orow * colparts) * 64 + lane;
+        const int oy = orow / ow, ox = orow - oy * ow;
+        const int y0 = oy * s, y1 = min(y0 + s, grid_h);
+        const int x0 = ox * s, x1 = min(x0 + s, grid_w);
+        const int64_t out_row = static_cast<int64_t>(base) + orow;
+        if (out_row >= capacity_rows) continue;              // cannot happen when the caller sized the buffer as required
+        if (chunk < nchunks) {
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int y = y0; y < y1; ++y) {
+                const uint4* cell = frame + (static_cast<size_t>(y) * grid_w + x0) * nchunks + chunk;
+                int x = x0;
+                for (; x + 4 <= x1; x += 4) {                 // four independent loads in flight
+                    const uint4 a = cell[0], b = cell[nchunks], c = cell[2 * static_cast<size_t>(nchunks)],
+                                e = cell[3 * static_cast<size_t>(nchunks)];
+                    E::accumulate(a, acc); E::accumulate(b, acc); E::accumulate(c, acc); E::accumulate(e, acc);
+                    cell += 4 * static_cast<size_t>(nchunks);
+                }
+                for (; x < x1; ++x) {
+                    E::accumulate(*cell, acc);
+                    cell += nchunks;
+                }
+            }
+            const float cnt = static_cast<float>((y1 - y0) * (x1 - x0));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = acc[i] / cnt;
+            Store<TO>::put(out + out_row * d, chunk, E::kVec, acc);
+        }
+        if (lane == 0 && item - orow * colparts == 0) token_event[out_row] = ev;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct StatsPlan {
+    int G, KL, tok_per_wg, C, frames_per_run, runs;
+};
+
+static bool plan_stats(int T, int N, int d, int dtype, StatsPlan* p) {
+    const int vec = dtype == METOK_BF16 ? 8 : 4;
+    if (d % vec) return false;
+    const int nchunks = d / vec;
+    int G = 16, KL = 0;
+    for (int g : {16, 64}) {
+        for (int kl : {1, 2, 4, 8, 16}) {
+            if (g == 16 && kl == 16) continue;
+            if (g * kl >= nchunks) { G = g; KL = kl; break; }
+        }
+        if (KL) break;
+    }
+    if (!KL) return false;
+    p->G = G; p->KL = KL;
+    p->tok_per_wg = kStatsWaves * (64 / G);
+    p->C = (N + p->tok_per_wg - 1) / p->tok_per_wg;
+    // enough workgroups to fill 256 CUs several times over, but runs of at least 4 frames so that the
+    // extra frame read per run stays a small fraction
+    int runs = (2048 + p->C * kStatsWaves - 1) / (p->C * kStatsWaves);
+    int fpr = (T + runs - 1) / runs;
+    if (fpr < 4) fpr = 4;
+    if (fpr > T) fpr = T;
+    p->frames_per_run = fpr;
+    p->runs = (T + fpr - 1) / fpr;
+    return true;
+}
+
+template <typename T, int G, int KL>
+static void launch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
+                         float* part, hipStream_t st) {
+    hipLaunchKernelGGL((frame_stats_kernel<T, G, KL>), dim3(p.C, p.runs), dim3(kStatsThreads), 0, st,
+                       static_cast<const T*>(feats), static_cast<const T*>(text), Tf, N, d, p.frames_per_run, do_pair,
+                       part, p.C);
+}
+
+template <typename T>
+static bool dispatch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
+                           float* part, hipStream_t st) {
+#define METOK_STATS_CASE(g, kl) \
+    if (p.G == g && p.KL == kl) { launch_stats<T, g, kl>(feats, text, Tf, N, d, p, do_pair, part, st); return true; }
+    METOK_STATS_CASE(16, 1) METOK_STATS_CASE(16, 2) METOK_STATS_CASE(16, 4) METOK_STATS_CASE(16, 8)
+    METOK_STATS_CASE(64, 1) METOK_STATS_CASE(64, 2) METOK_STATS_CASE(64, 4) METOK_STATS_CASE(64, 8) METOK_STATS_CASE(64, 16)
+#undef METOK_STATS_CASE
+    return false;
+}
+
+static size_t stats_part_bytes(int T, const StatsPlan& p) {
+    return round_up(static_cast<size_t>(T) * p.C * 3 * sizeof(float), 256);
+}
+
+static int check_feats(const void* feats, int dtype, int T, int N, int d, StatsPlan* p) {
+    if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    if (T < 1 || T > METOK_MAX_FRAMES) return fail(METOK_ERR_INVALID_ARG, "T must be in [1, %d], got %d", METOK_MAX_FRAMES, T);
+    if (N < 1 || d < 1) return fail(METOK_ERR_INVALID_ARG, "N and d must be positive");
+    if (static_cast<int64_t>(T) * N > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "T * N must fit int32");
+    if (!feats || !aligned16(feats)) return fail(METOK_ERR_INVALID_ARG, "feats is NULL or not 16-byte aligned");
+    if (!plan_stats(T, N, d, dtype, p))
+        return fail(METOK_ERR_UNSUPPORTED, "d = %d: need a multiple of %d and at most %d", d, dtype == METOK_BF16 ? 8 : 4,
+                    dtype == METOK_BF16 ? 8192 : 4096);
+    return METOK_OK;
+}
+
+}  // namespace metok
+
+using namespace metok;
+
+extern "C" size_t metok_segment_events_workspace_bytes(int T, int N, int d, int dtype) {
+    StatsPlan p;
+    if (T < 1 || N < 1 || d < 1 || !plan_stats(T, N, d, dtype, &p)) return 0;
+    return stats_part_bytes(T, p) + round_up(static_cast<size_t>(T) * sizeof(float), 256);
+}
+
+extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, int d,
+                                    const void* text_emb, int k, int sim_mode,
+                                    float* sim, int32_t* event_start, int32_t* frame_event,
+                                    float* frame_score,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    StatsPlan p;
+    int rc = check_feats(feats, dtype, T, N, d, &p);
+    if (rc) return rc;
+    if (sim_mode != METOK_SIM_FLAT) return fail(METOK_ERR_UNSUPPORTED, "sim_mode %d is not implemented", sim_mode);
+    if (k < 1 || k > T) return fail(METOK_ERR_INVALID_ARG, "k must be in [1, T] (k=%d, T=%d)", k, T);
+    if (!event_start || !frame_event || (T > 1 && !sim)) return fail(METOK_ERR_INVALID_ARG, "NULL output pointer");
+    if (frame_score && !text_emb) return fail(METOK_ERR_INVALID_ARG, "frame_score requested without text_emb");
+    if (text_emb && !aligned16(text_emb)) return fail(METOK_ERR_INVALID_ARG, "text_emb not 16-byte aligned");
+    const size_t need = metok_segment_events_workspace_bytes(T, N, d, dtype);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace))
+        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    float* part = static_cast<float*>(workspace);
+    float* norm2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats_part_bytes(T, p));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 1, part, st)
+                                        : dispatch_stats<float>(feats, text_emb, T, N, d, p, 1, part, st);
+    if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
+    if ((rc = check_launch("frame_stats"))) return rc;
+    hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, k, text_emb ? 1 : 0,
+                       sim, event_start, frame_event, frame_score, norm2);
+    return check_launch("segment");
+}
+
+extern "C" size_t metok_compress_encoder_tokens_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype) {
+    StatsPlan p;
+    if (T < 1 || grid_h < 1 || grid_w < 1 || d < 1 || !plan_stats(T, grid_h * grid_w, d, dtype, &p)) return 0;
+    // stats partials + frame norms + frame scores + frame -> event table
+    return stats_part_bytes(T, p) + 3 * round_up(static_cast<size_t>(T) * sizeof(float), 256);
+}
+
+extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                                             const void* text_emb, const float* frame_score_in,
+                                             const int32_t* event_start, int k,
+                                             double alpha, double beta, int s1, int s2,
+                                             int event_reduce, int pool_edge,
+                                             void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                                             int32_t* frame_offsets, int32_t* token_event,
+                                             uint8_t* event_is_key, uint8_t* frame_is_key,
+                                             int32_t* frame_stride, float* event_score, float* frame_score_out,
+                                             void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    if (grid_h < 1 || grid_w < 1 || static_cast<int64_t>(grid_h) * grid_w > (1 << 24))
+        return fail(METOK_ERR_INVALID_ARG, "bad patch grid %d x %d", grid_h, grid_w);
+    const int N = grid_h * grid_w;
+    StatsPlan p;
+    int rc = check_feats(feats, dtype, T, N, d, &p);
+    if (rc) return rc;
+    if (out_dtype != METOK_F32 && out_dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown out_dtype %d", out_dtype);
+    if (k < 1 || k > T) return fail(METOK_ERR_INVALID_ARG, "k must be in [1, T] (k=%d, T=%d)", k, T);
+    if (!(alpha > 0.0 && alpha <= 1.0) || !(beta > 0.0 && beta <= 1.0))
+        return fail(METOK_ERR_INVALID_ARG, "need 0 < alpha, beta <= 1 (alpha=%g beta=%g)", alpha, beta);
+    if (s1 < 1 || s2 < 1) return fail(METOK_ERR_INVALID_ARG, "strides must be >= 1 (s1=%d s2=%d)", s1, s2);
+    if (event_reduce != METOK_EVENT_MEAN && event_reduce != METOK_EVENT_MAX)
+        return fail(METOK_ERR_INVALID_ARG, "unknown event_reduce %d", event_reduce);
+    if (pool_edge != METOK_POOL_FLOOR && pool_edge != METOK_POOL_CEIL)
+        return fail(METOK_ERR_INVALID_ARG, "unknown pool_edge %d", pool_edge);
+    if (!frame_score_in && !text_emb) return fail(METOK_ERR_INVALID_ARG, "need text_emb or frame_score_in");
+    if (text_emb && !aligned16(text_emb)) return fail(METOK_ERR_INVALID_ARG, "text_emb not 16-byte aligned");
+    if (!event_start || !out_tokens || !frame_offsets || !token_event || !event_is_key || !frame_is_key ||
+        !frame_stride || !event_score)
+        return fail(METOK_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!aligned16(out_tokens)) return fail(METOK_ERR_INVALID_ARG, "out_tokens not 16-byte aligned");
+    if ((static_cast<size_t>(d) * dtype_size(out_dtype)) % 16)
+        return fail(METOK_ERR_INVALID_ARG, "d * sizeof(out_dtype) must be a multiple of 16");
+
+    const int gmax = grid_h > grid_w ? grid_h : grid_w;
+    auto clamp_stride = [&](double s) { int v = ceil_ratio(s); return v < 1 ? 1 : (v > gmax ? gmax : v); };
+    const int s_key_kf = clamp_stride(s1), s_key_nf = clamp_stride(s2);
+    const int s_non_kf = clamp_stride(s1 / alpha), s_non_nf = clamp_stride(s2 / alpha);
+    const int s_min = s_key_kf < s_key_nf ? s_key_kf : s_key_nf;      // s/alpha >= s
+    auto side = [&](int g) { return pool_edge == METOK_POOL_FLOOR ? (g / s_min > 1 ? g / s_min : 1) : (g + s_min - 1) / s_min; };
+    const int64_t worst = static_cast<int64_t>(T) * side(grid_h) * side(grid_w);
+    if (out_capacity_rows < worst)
+        return fail(METOK_ERR_CAPACITY, "out_capacity_rows = %lld, worst case needs %lld", (long long)out_capacity_rows, (long long)worst);
+    if (worst > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pooled row count must fit int32");
+
+    const size_t need = metok_compress_encoder_tokens_workspace_bytes(T, grid_h, grid_w, d, dtype);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace))
+        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    char* ws = static_cast<char*>(workspace);
+    float* part = reinterpret_cast<float*>(ws);
+    const size_t tslot = round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    float* norm2 = reinterpret_cast<float*>(ws + stats_part_bytes(T, p));
+    float* score_ws = reinterpret_cast<float*>(ws + stats_part_bytes(T, p) + tslot);
+    int32_t* frame_event_ws = reinterpret_cast<int32_t*>(ws + stats_part_bytes(T, p) + 2 * tslot);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const float* scores = frame_score_in;
+    if (!scores) {
+        // Eq. 5 pass on its own (no adjacent-frame products)
+        const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 0, part, st)
+                                            : dispatch_stats<float>(feats, text_emb, T, N, d, p, 0, part, st);
+        if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
+        if ((rc = check_launch("frame_stats"))) return rc;
+        hipLaunchKernelGGL(frame_score_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, score_ws);
+        if ((rc = check_launch("frame_score"))) return rc;
+        scores = score_ws;
+    }
+    (void)norm2;
+    const int n_key_events = ceil_ratio(alpha * k) > k ? k : ceil_ratio(alpha * k);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, scores, event_start, T, k, n_key_events, beta,
+                       s_key_kf, s_key_nf, s_non_kf, s_non_nf, grid_h, grid_w, event_reduce, pool_edge,
+                       event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
+                       frame_score_out);
+    if ((rc = check_launch("plan"))) return rc;
+
+    const int wg_per_frame = 18;
+    dim3 grid(wg_per_frame, T);
+#define METOK_POOL_CASE(TI, TO) \
+    hipLaunchKernelGGL((pool_kernel<TI, TO>), grid, dim3(kPoolThreads), 0, st, static_cast<const TI*>(feats), grid_h, grid_w, d, \
+                       frame_stride, frame_offsets, frame_event_ws, pool_edge, out_capacity_rows, static_cast<TO*>(out_tokens), token_event)
+    if (dtype == METOK_BF16 && out_dtype == METOK_BF16) METOK_POOL_CASE(bf16_t, bf16_t);
+    else if (dtype == METOK_BF16 && out_dtype == METOK_F32) METOK_POOL_CASE(bf16_t, float);
+    else if (dtype == METOK_F32 && out_dtype == METOK_BF16) METOK_POOL_CASE(float, bf16_t);
+    else METOK_POOL_CASE(float, float);
+#undef METOK_POOL_CASE
+    return check_launch("pool");
+}

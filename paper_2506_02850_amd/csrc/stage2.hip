@@ -1,0 +1,605 @@
+// Stage 2 (Sec. 3.2.2): one level of hierarchical pruning.
+//
+//   row_stats_kernel     MFMA pass 1 over all keys: per (head, text query) running max and sum of the
+//                        causal softmax, in the log2 domain, per workgroup
+//   merge_stats_kernel   merges the per-workgroup (max, sum) pairs into one normaliser per row
+//   col_sums_kernel      MFMA pass 2 over the visual keys: recomputes the logits and adds up the
+//                        probabilities of every visual key over the rows of a workgroup
+//   prepare_kernel       score_j = w_e(j) * mean probability, clears the keep flags
+//   select_kernel        one workgroup per retention class: radix select of the quota-th largest
+//                        score, lowest index first among equals -> keep flags
+//   scan_kernel          prefix sum of the flags -> ascending kept index list and carried metadata
+//   gather_rows_kernel   compaction of the hidden states
+//
+// Both MFMA passes hold the keys of a 32-key tile in registers (loaded straight from global memory in
+// fragment layout) and read the query fragments of the workgroup's rows from LDS.  The contraction
+// index may be permuted freely as long as both operands agree; here lane half h = lane/32 owns the
+// contiguous half h of the head dimension, so every lane loads contiguous 16-byte chunks.
+#include "common.h"
+
+namespace metok {
+
+constexpr int kScoreThreads = 256;
+constexpr int kScoreWaves = kScoreThreads / 64;
+constexpr int kTileKeys = kScoreWaves * 32;       // keys per workgroup tile
+constexpr int kMaxRowBlocks = 8;                  // 32-row blocks of queries per workgroup
+constexpr int kQFragBytes = 56 * 1024;            // LDS budget for the query fragments
+constexpr float kNegBig = -1.0e30f;
+constexpr float kPosBig = 1.0e30f;
+
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+    static constexpr int kChunkElems = 8;          // one 16-byte chunk feeds one 32x32x16 MFMA
+    static __device__ __forceinline__ f32x16_t mma(const uint4& a, const uint4& b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {
+    static constexpr int kChunkElems = 4;          // one chunk feeds four 32x32x2 MFMAs
+    static __device__ __forceinline__ f32x16_t mma(const uint4& a, const uint4& b, f32x16_t c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+        return c;
+    }
+};
+
+struct ScoreGeom {
+    int64_t S;
+    int Hq, Hkv, group, dh, Tq;
+    int R;              // rows per kv head = group * Tq
+    int rb_total;       // 32-row blocks per kv head
+    int rbw;            // row blocks per workgroup
+    int rs;             // row splits per kv head
+    int rpad;           // rb_total * 32
+    int vis_start, n_vis;
+    float scale_log2;   // log2(e) / sqrt(dh)
+};
+
+// Query fragments of row blocks [rb0, rb0 + nrb) of kv head g into LDS, fragment order:
+// qfrag[(rb * NCH + c) * 64 + lane] with lane = (row % 32) + 32 * half.
+template <typename T, int NCH>
+__device__ __forceinline__ void fill_qfrag(uint4* qfrag, const T* __restrict__ q_text, const ScoreGeom& g, int kvh, int rb0, int nrb) {
+    constexpr int CE = Mma<T>::kChunkElems;
+    const int total = nrb * NCH * 64;
+    for (int idx = threadIdx.x; idx < total; idx += kScoreThreads) {
+        const int l = idx & 63;
+        const int c = (idx >> 6) % NCH;
+        const int rb = idx / (NCH * 64);
+        const int r = (rb0 + rb) * 32 + (l & 31);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r < g.R) {
+            const int hq = kvh * g.group + r / g.Tq, i = r % g.Tq;
+            const T* src = q_text + (static_cast<size_t>(hq) * g.Tq + i) * g.dh + (l >> 5) * (g.dh / 2) + c * CE;
+            v = *reinterpret_cast<const uint4*>(src);
+        }
+        qfrag[idx] = v;
+    }
+}
+
+template <typename T, int NCH>
+__device__ __forceinline__ void load_kfrag(uint4 (&kf)[NCH], const T* __restrict__ k_all, const ScoreGeom& g, int kvh, int64_t j0, int lane) {
+    constexpr int CE = Mma<T>::kChunkElems;
+    int64_t j = j0 + (lane & 31);
+    j = j < g.S ? j : g.S - 1;                     // tiles may overhang the sequence; masked later
+    const T* src = k_all + (static_cast<size_t>(kvh) * g.S + j) * g.dh + (lane >> 5) * (g.dh / 2);
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) kf[c] = *reinterpret_cast<const uint4*>(src + c * CE);
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 1: blockIdx.x strides over the key tiles of the whole sequence, blockIdx.y = kvh * rs + split.
+// The product is taken as keys x queries, so a lane's 16 accumulators are 16 keys of ONE query row
+// (row = lane % 32) and the online softmax state is one (max, sum) pair per lane and row block.
+// pstat[((y * gridDim.x + x) * rbw * 32 + local_row) * 2 + {0, 1}]
+// ---------------------------------------------------------------------------------------------
+template <typename T, int NCH>
+__global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __restrict__ q_text, const T* __restrict__ k_all,
+                                                                  const ScoreGeom g, float* __restrict__ pstat) {
+    extern __shared__ uint4 lds[];
+    uint4* qfrag = lds;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kvh = blockIdx.y / g.rs, split = blockIdx.y % g.rs;
+    const int rb0 = split * g.rbw;
+    const int nrb = min(g.rbw, g.rb_total - rb0);
+    fill_qfrag<T, NCH>(qfrag, q_text, g, kvh, rb0, nrb);
+    __syncthreads();
+
+    float m[kMaxRowBlocks], l[kMaxRowBlocks];
+#pragma unroll
+    for (int rb = 0; rb < kMaxRowBlocks; ++rb) { m[rb] = kNegBig; l[rb] = 0.f; }
+
+    const int64_t text_start = g.S - g.Tq;
+    const int64_t n_tiles = (g.S + kTileKeys - 1) / kTileKeys;
+    const int h = lane >> 5;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t j0 = tile * kTileKeys + wave * 32;
+        if (j0 >= g.S) continue;
+        uint4 kf[NCH];
+        load_kfrag<T, NCH>(kf, k_all, g, kvh, j0, lane);
+        const bool full = j0 + 32 <= text_start;            // every key of the tile is visible to every query
+#pragma unroll
+        for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
+            if (rb < nrb) {
+                f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                const uint4* qf = qfrag + (rb * NCH) * 64 + lane;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(kf[c], qf[c * 64], acc);
+                // accumulator i <-> key j0 + 8 (i / 4) + 4 h + i % 4, query row = lane % 32
+                float s[16];
+                float m_new, sum = 0.f;
+                if (full) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s[i] = acc[i] * g.scale_log2;
+                    float tmax = s[0];
+#pragma unroll
+                    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
+                    m_new = fmaxf(m[rb], tmax);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sum += exp2f(s[i] - m_new);
+                } else {
+                    const int r = (rb0 + rb) * 32 + (lane & 31);
+                    const int64_t pos = text_start + (r % g.Tq);       // causal: keys 0..pos
+                    bool vis[16];
+                    float tmax = kNegBig;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int64_t j = j0 + 8 * (i >> 2) + 4 * h + (i & 3);
+                        vis[i] = j <= pos;
+                        s[i] = acc[i] * g.scale_log2;
+                        if (vis[i]) tmax = fmaxf(tmax, s[i]);
+                    }
+                    m_new = fmaxf(m[rb], tmax);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sum += vis[i] ? exp2f(s[i] - m_new) : 0.f;
+                }
+                l[rb] = l[rb] * exp2f(m[rb] - m_new) + sum;
+                m[rb] = m_new;
+            }
+        }
+    }
+    // merge the two lane halves (same row, different keys), then the four waves through LDS
+    __syncthreads();                                   // qfrag is dead from here on; reuse LDS
+    float* wstat = reinterpret_cast<float*>(lds);      // [wave][rbw * 32][2]
+#pragma unroll
+    for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
+        if (rb < nrb) {
+            const float m2 = __shfl_xor(m[rb], 32, 64), l2 = __shfl_xor(l[rb], 32, 64);
+            const float mm = fmaxf(m[rb], m2);
+            const float ll = l[rb] * exp2f(m[rb] - mm) + l2 * exp2f(m2 - mm);
+            if (h == 0) {
+                wstat[((wave * g.rbw + rb) * 32 + lane) * 2 + 0] = mm;
+                wstat[((wave * g.rbw + rb) * 32 + lane) * 2 + 1] = ll;
+            }
+        }
+    }
+    __syncthreads();
+    for (int lr = threadIdx.x; lr < nrb * 32; lr += kScoreThreads) {
+        float mm = kNegBig, ll = 0.f;
+        for (int w = 0; w < kScoreWaves; ++w) {
+            const float m2 = wstat[((w * g.rbw) * 32 + lr) * 2 + 0], l2 = wstat[((w * g.rbw) * 32 + lr) * 2 + 1];
+            const float mx = fmaxf(mm, m2);
+            ll = ll * exp2f(mm - mx) + l2 * exp2f(m2 - mx);
+            mm = mx;
+        }
+        float* dst = pstat + ((static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * (g.rbw * 32) + lr) * 2;
+        dst[0] = mm;
+        dst[1] = ll;
+    }
+}
+
+// norm[y * rbw * 32 + local_row] = log2-domain normaliser max + log2(sum) of the row (+big for padding rows)
+__global__ __launch_bounds__(256) void merge_stats_kernel(const float* __restrict__ pstat, const ScoreGeom g, int nx,
+                                                          float* __restrict__ norm) {
+    const int rows_per_y = g.rbw * 32;
+    const int total = g.Hkv * g.rs * rows_per_y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int y = i / rows_per_y, lr = i % rows_per_y;
+    const int r = (y % g.rs) * rows_per_y + lr;
+    float mm = kNegBig, ll = 0.f;
+    for (int x = 0; x < nx; ++x) {
+        const float* src = pstat + ((static_cast<size_t>(y) * nx + x) * rows_per_y + lr) * 2;
+        const float m2 = src[0], l2 = src[1];
+        const float mx = fmaxf(mm, m2);
+        ll = ll * exp2f(mm - mx) + l2 * exp2f(m2 - mx);
+        mm = mx;
+    }
+    norm[i] = (r < g.R && ll > 0.f) ? mm + log2f(ll) : kPosBig;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 2: queries x keys, a lane's 16 accumulators are 16 rows of ONE key (key = lane % 32).
+// colpart[y * n_vis + j] = sum over the rows of workgroup-row y of the probability of visual key j.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int NCH>
+__global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const T* __restrict__ q_text, const T* __restrict__ k_all,
+                                                                 const ScoreGeom g, const float* __restrict__ norm,
+                                                                 float* __restrict__ colpart) {
+    extern __shared__ uint4 lds[];
+    uint4* qfrag = lds;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int kvh = blockIdx.y / g.rs, split = blockIdx.y % g.rs;
+    const int rb0 = split * g.rbw;
+    const int nrb = min(g.rbw, g.rb_total - rb0);
+    float* cst = reinterpret_cast<float*>(qfrag + static_cast<size_t>(g.rbw) * NCH * 64);     // [rbw * 32] row normalisers
+    fill_qfrag<T, NCH>(qfrag, q_text, g, kvh, rb0, nrb);
+    for (int i = threadIdx.x; i < g.rbw * 32; i += kScoreThreads) cst[i] = norm[static_cast<size_t>(blockIdx.y) * g.rbw * 32 + i];
+    __syncthreads();
+
+    const int h = lane >> 5;
+    const int n_tiles = (g.n_vis + kTileKeys - 1) / kTileKeys;
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int jv = tile * kTileKeys + wave * 32;          // first visual key of this wave
+        if (jv >= g.n_vis) continue;
+        uint4 kf[NCH];
+        load_kfrag<T, NCH>(kf, k_all, g, kvh, static_cast<int64_t>(g.vis_start) + jv, lane);
+        float colsum = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
+            if (rb < nrb) {
+                f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                const uint4* qf = qfrag + (rb * NCH) * 64 + lane;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(qf[c * 64], kf[c], acc);
+                // accumulator i <-> query row rb * 32 + 8 (i / 4) + 4 h + i % 4, key = lane % 32
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float4 c4 = *reinterpret_cast<const float4*>(cst + rb * 32 + 8 * b + 4 * h);
+                    colsum += exp2f(acc[4 * b + 0] * g.scale_log2 - c4.x);
+                    colsum += exp2f(acc[4 * b + 1] * g.scale_log2 - c4.y);
+                    colsum += exp2f(acc[4 * b + 2] * g.scale_log2 - c4.z);
+                    colsum += exp2f(acc[4 * b + 3] * g.scale_log2 - c4.w);
+                }
+            }
+        }
+        colsum += __shfl_xor(colsum, 32, 64);
+        const int j = jv + (lane & 31);
+        if (h == 0 && j < g.n_vis) colpart[static_cast<size_t>(blockIdx.y) * g.n_vis + j] = colsum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// scores, selection, scan, gather
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prepare_kernel(const float* __restrict__ colpart, int n_parts, int n_vis, float rows_total,
+                                                      const int32_t* __restrict__ token_event, const float* __restrict__ event_weight,
+                                                      int n_events, float* __restrict__ scores, uint8_t* __restrict__ flags) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n_vis) return;
+    flags[j] = 0;
+    if (colpart) {
+        float a = 0.f;
+        for (int p = 0; p < n_parts; ++p) a += colpart[static_cast<size_t>(p) * n_vis + j];
+        a = a / rows_total;
+        if (event_weight) {
+            int e = token_event[j];
+            e = e < 0 ? 0 : (e >= n_events ? n_events - 1 : e);
+            a *= event_weight[e];
+        }
+        scores[j] = a;
+    }
+}
+
+struct Quotas { int32_t q[METOK_MAX_SEGMENTS]; };
+
+constexpr int kSelThreads = 1024;
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ token_seg,
+                                                             int n_vis, const Quotas quotas, uint8_t* __restrict__ flags) {
+    __shared__ int hist[256];
+    __shared__ int scan_scratch[17];
+    __shared__ int s_digit, s_remaining, s_count;
+    const int seg = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int quota = quotas.q[seg];
+    if (quota <= 0) return;                               // flags are already 0
+    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; }
+
+    // population of the class
+    int mine = 0;
+    for (int j = tid; j < n_vis; j += kSelThreads) mine += token_seg[j] == seg ? 1 : 0;
+    int pop = 0;
+    block_exclusive_scan(mine, scan_scratch, &pop);
+    if (quota >= pop) {
+        for (int j = tid; j < n_vis; j += kSelThreads)
+            if (token_seg[j] == seg) flags[j] = 1;
+        return;
+    }
+
+    // radix select, 8 bits per round from the top: after the last round `prefix` is the key of the
+    // quota-th largest score and `remaining` the number of tokens with exactly that key to keep
+    uint32_t prefix = 0;
+    int remaining = quota;
+    int count_equal = 0;
+    for (int round = 0; round < 4; ++round) {
+        const int shift = 24 - 8 * round;
+        const uint32_t hi_mask = round == 0 ? 0u : (0xffffffffu << (shift + 8));
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < n_vis; j += kSelThreads) {
+            if (token_seg[j] == seg) {
+                const uint32_t key = ordered_key(scores[j]);
+                if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+            }
+        }
+        __syncthreads();
+        // thread t < 256 looks at digit 255 - t; inclusive scan = keys with a digit at least that large
+        const int v = tid < 256 ? hist[255 - tid] : 0;
+        int total = 0;
+        const int excl = block_exclusive_scan(v, scan_scratch, &total);
+        if (tid < 256 && excl < remaining && excl + v >= remaining) {
+            s_digit = 255 - tid;
+            s_remaining = remaining - excl;
+            s_count = v;
+        }
+        __syncthreads();
+        prefix |= static_cast<uint32_t>(s_digit) << shift;
+        remaining = s_remaining;
+        count_equal = s_count;
+        __syncthreads();
+    }
+    const uint32_t tau = prefix;
+    if (remaining >= count_equal) {
+        // every token equal to the threshold is kept: no ordering among equals needed
+        for (int j = tid; j < n_vis; j += kSelThreads)
+            if (token_seg[j] == seg) flags[j] = ordered_key(scores[j]) >= tau ? 1 : 0;
+        return;
+    }
+    // equal scores at the threshold: the lowest indices win; walk the tokens in index order
+    int taken = 0;
+    for (int base = 0; base < n_vis; base += kSelThreads) {
+        const int j = base + tid;
+        uint32_t key = 0;
+        bool member = false;
+        if (j < n_vis && token_seg[j] == seg) { member = true; key = ordered_key(scores[j]); }
+        const int tie = (member && key == tau) ? 1 : 0;
+        int total = 0;
+        const int before = block_exclusive_scan(tie, scan_scratch, &total);
+        if (member) flags[j] = (key > tau || (tie && taken + before < remaining)) ? 1 : 0;
+        taken += total;
+    }
+}
+
+// One workgroup: prefix sum of the flags, kept index list and carried metadata in ascending order.
+__global__ __launch_bounds__(kSelThreads) void scan_kernel(const uint8_t* __restrict__ flags, int n_vis, int total_keep,
+                                                           const int32_t* __restrict__ token_seg, const int32_t* __restrict__ token_event,
+                                                           const int32_t* __restrict__ orig_idx_in,
+                                                           int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
+                                                           int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out) {
+    __shared__ int scan_scratch[17];
+    const int tid = threadIdx.x;
+    const int per = (n_vis + kSelThreads - 1) / kSelThreads;
+    const int a = min(n_vis, tid * per), b = min(n_vis, a + per);
+    int mine = 0;
+    for (int j = a; j < b; ++j) mine += flags[j];
+    int total = 0;
+    int pos = block_exclusive_scan(mine, scan_scratch, &total);
+    for (int j = a; j < b; ++j) {
+        if (flags[j]) {
+            if (pos < total_keep) {
+                kept_idx[pos] = j;
+                if (token_seg_out) token_seg_out[pos] = token_seg[j];
+                if (token_event_out) token_event_out[pos] = token_event[j];
+                if (orig_idx_out) orig_idx_out[pos] = orig_idx_in ? orig_idx_in[j] : j;
+            }
+            ++pos;
+        }
+    }
+    // fewer survivors than announced (a quota above its class population): pad so that the gather stays in bounds
+    for (int p = total + tid; p < total_keep; p += kSelThreads) {
+        kept_idx[p] = 0;
+        if (token_seg_out) token_seg_out[p] = 0;
+        if (token_event_out) token_event_out[p] = 0;
+        if (orig_idx_out) orig_idx_out[p] = 0;
+    }
+}
+
+constexpr int kGatherThreads = 256;
+constexpr int kGatherRows = 4;
+
+__global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                                     int64_t out_rows, int chunks_per_row, int vis_start,
+                                                                     int n_vis, int n_keep, const int32_t* __restrict__ kept_idx) {
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
+#pragma unroll
+    for (int rr = 0; rr < kGatherRows; ++rr) {
+        const int64_t r = r0 + rr;
+        if (r >= out_rows) break;
+        int64_t s;
+        if (r < vis_start) s = r;
+        else if (r < static_cast<int64_t>(vis_start) + n_keep) {
+            int kidx = kept_idx[r - vis_start];
+            kidx = kidx < 0 ? 0 : (kidx >= n_vis ? n_vis - 1 : kidx);
+            s = vis_start + kidx;
+        } else s = r - n_keep + n_vis;
+        const uint4* sp = src + s * chunks_per_row;
+        uint4* dp = dst + r * chunks_per_row;
+        for (int c = threadIdx.x; c < chunks_per_row; c += kGatherThreads) dp[c] = sp[c];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static int chunk_count(int dh, int dtype) { return dtype == METOK_BF16 ? dh / 16 : dh / 8; }     // 16-byte chunks per lane
+
+static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start, int n_vis, int dtype, ScoreGeom* g) {
+    g->S = S; g->Hq = Hq; g->Hkv = Hkv; g->group = Hq / Hkv; g->dh = dh; g->Tq = Tq;
+    g->R = g->group * Tq;
+    g->rb_total = (g->R + 31) / 32;
+    const int nch = chunk_count(dh, dtype);
+    int cap = kQFragBytes / (nch * 1024);
+    if (cap > kMaxRowBlocks) cap = kMaxRowBlocks;
+    if (cap < 1) return false;
+    g->rs = (g->rb_total + cap - 1) / cap;
+    g->rbw = (g->rb_total + g->rs - 1) / g->rs;
+    g->rpad = g->rs * g->rbw * 32;
+    g->vis_start = vis_start; g->n_vis = n_vis;
+    g->scale_log2 = static_cast<float>(1.4426950408889634 / sqrt(static_cast<double>(dh)));
+    return true;
+}
+
+struct ScorePlan {
+    int nx1, nx2;                   // workgroups along the key tiles in pass 1 / pass 2
+    size_t off_pstat, off_norm, off_colpart, off_flags, total;
+};
+
+static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
+    const int slots = 512;          // two workgroups per CU on 256 CUs
+    const int ny = g.Hkv * g.rs;
+    auto pick = [&](int64_t tiles) {
+        int nx = slots / ny;
+        if (nx < 1) nx = 1;
+        if (nx > tiles) nx = static_cast<int>(tiles);
+        if (nx < 1) nx = 1;
+        const int64_t per = (tiles + nx - 1) / nx;          // tiles per workgroup
+        nx = static_cast<int>((tiles + per - 1) / per);     // smallest grid with the same critical path
+        return nx < 1 ? 1 : nx;
+    };
+    p->nx1 = pick((g.S + kTileKeys - 1) / kTileKeys);
+    p->nx2 = pick((static_cast<int64_t>(n_vis) + kTileKeys - 1) / kTileKeys);
+    size_t off = 0;
+    p->off_pstat = off;   off += round_up(static_cast<size_t>(ny) * p->nx1 * g.rbw * 32 * 2 * sizeof(float), 256);
+    p->off_norm = off;    off += round_up(static_cast<size_t>(ny) * g.rbw * 32 * sizeof(float), 256);
+    p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
+    p->off_flags = off;   off += round_up(static_cast<size_t>(n_vis), 256);
+    p->total = off;
+}
+
+static bool dh_supported(int dh, int dtype) {
+    if (dtype == METOK_BF16) return dh == 32 || dh == 64 || dh == 128 || dh == 256;
+    return dh == 32 || dh == 64 || dh == 128;
+}
+
+template <typename T, int NCH>
+static void launch_scores(const void* q, const void* k, const ScoreGeom& g, const ScorePlan& p, char* ws, hipStream_t st) {
+    const size_t qbytes = static_cast<size_t>(g.rbw) * NCH * 1024;
+    const size_t lds1 = qbytes > static_cast<size_t>(kScoreWaves) * g.rbw * 32 * 2 * sizeof(float) ? qbytes
+                                                                                                    : static_cast<size_t>(kScoreWaves) * g.rbw * 32 * 2 * sizeof(float);
+    const size_t lds2 = qbytes + static_cast<size_t>(g.rbw) * 32 * sizeof(float);
+    const int ny = g.Hkv * g.rs;
+    float* pstat = reinterpret_cast<float*>(ws + p.off_pstat);
+    float* norm = reinterpret_cast<float*>(ws + p.off_norm);
+    float* colpart = reinterpret_cast<float*>(ws + p.off_colpart);
+    hipLaunchKernelGGL((row_stats_kernel<T, NCH>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
+                       static_cast<const T*>(q), static_cast<const T*>(k), g, pstat);
+    const int total_rows = ny * g.rbw * 32;
+    hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 255) / 256), dim3(256), 0, st, pstat, g, p.nx1, norm);
+    hipLaunchKernelGGL((col_sums_kernel<T, NCH>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
+                       static_cast<const T*>(q), static_cast<const T*>(k), g, norm, colpart);
+}
+
+}  // namespace metok
+
+using namespace metok;
+
+extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype) {
+    if (n_vis < 0 || S < 1) return 0;
+    ScoreGeom g;
+    ScorePlan p;
+    if (Hq >= 1 && Hkv >= 1 && Tq >= 1 && Hq % Hkv == 0 && dh_supported(dh, dtype) &&
+        make_geom(S, Hq, Hkv, dh, Tq, 0, n_vis, dtype, &g)) {
+        plan_score(g, n_vis, &p);
+        return p.total;
+    }
+    return round_up(static_cast<size_t>(n_vis), 256) + 256;      // flags only (scores supplied by the caller)
+}
+
+extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
+                                   const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                                   int vis_start, int n_vis,
+                                   const int32_t* token_seg, const int32_t* token_event,
+                                   const float* event_weight, int n_events,
+                                   int n_seg, const int32_t* seg_quota,
+                                   const int32_t* orig_idx_in,
+                                   float* scores, int32_t* kept_idx, void* hidden_out,
+                                   int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    if (S < 1 || S > INT32_MAX || D < 1) return fail(METOK_ERR_INVALID_ARG, "S must be in [1, 2^31) and D positive");
+    if (vis_start < 0 || n_vis < 1 || static_cast<int64_t>(vis_start) + n_vis > S)
+        return fail(METOK_ERR_INVALID_ARG, "visual span [%d, %d + %d) does not fit S = %lld", vis_start, vis_start, n_vis, (long long)S);
+    const size_t row_bytes = static_cast<size_t>(D) * dtype_size(dtype);
+    if (row_bytes % 16) return fail(METOK_ERR_INVALID_ARG, "D * sizeof(dtype) must be a multiple of 16");
+    if (!hidden || !hidden_out || !aligned16(hidden) || !aligned16(hidden_out))
+        return fail(METOK_ERR_INVALID_ARG, "hidden / hidden_out NULL or not 16-byte aligned");
+    if (!token_seg || !scores || !seg_quota) return fail(METOK_ERR_INVALID_ARG, "NULL pointer argument");
+    if (n_seg < 1 || n_seg > METOK_MAX_SEGMENTS) return fail(METOK_ERR_INVALID_ARG, "n_seg must be in [1, %d]", METOK_MAX_SEGMENTS);
+    if (!token_event && (event_weight || token_event_out)) return fail(METOK_ERR_INVALID_ARG, "token_event is NULL but needed");
+    if (event_weight && n_events < 1) return fail(METOK_ERR_INVALID_ARG, "event_weight given with n_events < 1");
+    Quotas quotas;
+    int64_t total_keep = 0;
+    for (int s = 0; s < METOK_MAX_SEGMENTS; ++s) quotas.q[s] = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        if (seg_quota[s] < 0 || seg_quota[s] > n_vis) return fail(METOK_ERR_INVALID_ARG, "seg_quota[%d] = %d outside [0, n_vis]", s, seg_quota[s]);
+        quotas.q[s] = seg_quota[s];
+        total_keep += seg_quota[s];
+    }
+    if (total_keep > n_vis) return fail(METOK_ERR_INVALID_ARG, "quotas add up to %lld > n_vis = %d", (long long)total_keep, n_vis);
+    if (total_keep > 0 && !kept_idx) return fail(METOK_ERR_INVALID_ARG, "kept_idx is NULL");
+    const int64_t out_rows = S - n_vis + total_keep;
+    {   // hidden_out must not overlap hidden (the gather is not an in-place algorithm)
+        const char* a0 = static_cast<const char*>(hidden); const char* a1 = a0 + static_cast<size_t>(S) * row_bytes;
+        const char* b0 = static_cast<const char*>(hidden_out); const char* b1 = b0 + static_cast<size_t>(out_rows) * row_bytes;
+        if (a0 < b1 && b0 < a1) return fail(METOK_ERR_INVALID_ARG, "hidden_out overlaps hidden");
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    int rc;
+    uint8_t* flags;
+    if (q_text) {
+        if (!k_all || !aligned16(q_text) || !aligned16(k_all)) return fail(METOK_ERR_INVALID_ARG, "q_text / k_all NULL or misaligned");
+        if (Hq < 1 || Hkv < 1 || Hq % Hkv) return fail(METOK_ERR_INVALID_ARG, "Hq = %d must be a positive multiple of Hkv = %d", Hq, Hkv);
+        if (!dh_supported(dh, dtype)) return fail(METOK_ERR_UNSUPPORTED, "head dimension %d is not supported for this dtype", dh);
+        if (Tq < 1 || static_cast<int64_t>(Tq) > S - vis_start - n_vis)
+            return fail(METOK_ERR_INVALID_ARG, "Tq = %d must be in [1, number of text rows = %lld]", Tq, (long long)(S - vis_start - n_vis));
+        ScoreGeom g;
+        if (!make_geom(S, Hq, Hkv, dh, Tq, vis_start, n_vis, dtype, &g)) return fail(METOK_ERR_UNSUPPORTED, "head dimension too large");
+        if (static_cast<int64_t>(g.Hkv) * g.rs > 65535) return fail(METOK_ERR_UNSUPPORTED, "too many query rows");
+        ScorePlan p;
+        plan_score(g, n_vis, &p);
+        if (!workspace || workspace_bytes < p.total || !aligned16(workspace))
+            return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", p.total, workspace_bytes);
+        const int nch = chunk_count(dh, dtype);
+        if (dtype == METOK_BF16) {
+            switch (nch) {
+                case 2: launch_scores<bf16_t, 2>(q_text, k_all, g, p, ws, st); break;
+                case 4: launch_scores<bf16_t, 4>(q_text, k_all, g, p, ws, st); break;
+                case 8: launch_scores<bf16_t, 8>(q_text, k_all, g, p, ws, st); break;
+                default: launch_scores<bf16_t, 16>(q_text, k_all, g, p, ws, st); break;
+            }
+        } else {
+            switch (nch) {
+                case 4: launch_scores<float, 4>(q_text, k_all, g, p, ws, st); break;
+                case 8: launch_scores<float, 8>(q_text, k_all, g, p, ws, st); break;
+                default: launch_scores<float, 16>(q_text, k_all, g, p, ws, st); break;
+            }
+        }
+        if ((rc = check_launch("attention scores"))) return rc;
+        flags = reinterpret_cast<uint8_t*>(ws + p.off_flags);
+        hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
+                           reinterpret_cast<const float*>(ws + p.off_colpart), g.Hkv * g.rs, n_vis,
+                           static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores, flags);
+    } else {
+        const size_t need = round_up(static_cast<size_t>(n_vis), 256);
+        if (!workspace || workspace_bytes < need) return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+        flags = reinterpret_cast<uint8_t*>(ws);
+        hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
+                           static_cast<const float*>(nullptr), 0, n_vis, 1.f, token_event, event_weight, n_events, scores, flags);
+    }
+    if ((rc = check_launch("prepare"))) return rc;
+    hipLaunchKernelGGL(select_kernel, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, quotas, flags);
+    if ((rc = check_launch("select"))) return rc;
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kSelThreads), 0, st, flags, n_vis, static_cast<int>(total_keep),
+                       token_seg, token_event, orig_idx_in, kept_idx, token_seg_out, token_event_out, orig_idx_out);
+    if ((rc = check_launch("scan"))) return rc;
+    const int chunks_per_row = static_cast<int>(row_bytes / 16);
+    const int64_t blocks = (out_rows + kGatherRows - 1) / kGatherRows;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGatherThreads), 0, st,
+                       static_cast<const uint4*>(hidden), static_cast<uint4*>(hidden_out), out_rows, chunks_per_row,
+                       vis_start, n_vis, static_cast<int>(total_keep), kept_idx);
+    return check_launch("gather");
+}

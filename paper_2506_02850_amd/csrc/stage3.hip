@@ -1,0 +1,181 @@
+// Stage 3 (Sec. 3.3): in-place compaction of the KV cache to the retained rows.
+//
+// A slab is one [S_cap, dh] matrix: K or V of one layer, one video, one kv head.  Inside a slab
+// row i must receive row idx[i] >= i.  One workgroup owns a slab (or a 16-byte-aligned column
+// slice of it) and walks it in ascending tiles: all loads of a tile complete, the workgroup meets
+// at a barrier, then the tile is stored.  Later tiles only read rows at or above their own first
+// row, which no earlier store has touched, so no row is overwritten before it is read.
+// Different slabs and different column slices never alias, so workgroups need no ordering.
+#include "common.h"
+
+namespace metok {
+
+constexpr int kMaxLayersPerLaunch = 40;
+constexpr int kCompactThreads = 256;
+constexpr int kCompactUnroll = 8;          // 16-byte loads in flight per thread and tile
+
+struct CompactLayer {
+    char* k;             // [B, Hkv, S_cap, row_bytes]
+    char* v;
+    const int32_t* idx;  // [B, n_keep]
+    int32_t n_keep;
+    int32_t pad;
+};
+
+struct CompactArgs {
+    CompactLayer layer[kMaxLayersPerLaunch];
+    int n_layers;
+    int B, Hkv;
+    int parts;            // column slices per row
+    int lanes_per_row;    // 16-byte chunks per column slice
+    int rows_per_pass;    // kCompactThreads / lanes_per_row
+    int64_t S_cap;
+    int64_t row_bytes;
+};
+
+__global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(const CompactArgs args) {
+    // block -> (layer slot, video, head, K|V, column slice); layer slots are sorted by work, largest first
+    const int units_per_layer = args.B * args.Hkv * 2 * args.parts;
+    const int slot = blockIdx.x / units_per_layer;
+    int rem = blockIdx.x - slot * units_per_layer;
+    const int part = rem % args.parts; rem /= args.parts;
+    const int which = rem & 1; rem >>= 1;
+    const int head = rem % args.Hkv;
+    const int b = rem / args.Hkv;
+
+    const CompactLayer& L = args.layer[slot];
+    const int rows = L.n_keep;
+    const int32_t* __restrict__ idx = L.idx + static_cast<int64_t>(b) * rows;
+    char* base = (which ? L.v : L.k) + (static_cast<int64_t>(b) * args.Hkv + head) * args.S_cap * args.row_bytes;
+
+    const int lpr = args.lanes_per_row;
+    const int r_in_pass = threadIdx.x / lpr;
+    const int col = (part * lpr + (threadIdx.x - r_in_pass * lpr)) * 16;
+    const bool active = r_in_pass < args.rows_per_pass;          // threads beyond the last whole row idle
+    const int rows_per_tile = args.rows_per_pass * kCompactUnroll;
+    const uint32_t s_cap = static_cast<uint32_t>(args.S_cap);
+
+    for (int tile = 0; tile < rows; tile += rows_per_tile) {
+        uint4 v[kCompactUnroll];
+        bool mv[kCompactUnroll];
+#pragma unroll
+        for (int u = 0; u < kCompactUnroll; ++u) {
+            const int i = tile + u * args.rows_per_pass + r_in_pass;
+            mv[u] = false;
+            if (active && i < rows) {
+                const uint32_t s = static_cast<uint32_t>(idx[i]);
+                // rows that stay where they are need no copy; positions outside [i, S_cap) are skipped
+                if (s > static_cast<uint32_t>(i) && s < s_cap) {
+                    mv[u] = true;
+                    v[u] = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(s) * args.row_bytes + col);
+                }
+            }
+        }
+        // every load of this tile has returned before any thread of the workgroup stores into it
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kCompactUnroll; ++u) {
+            const int i = tile + u * args.rows_per_pass + r_in_pass;
+            if (mv[u]) *reinterpret_cast<uint4*>(base + static_cast<int64_t>(i) * args.row_bytes + col) = v[u];
+        }
+    }
+}
+
+__global__ void write_lengths_kernel(int32_t* out, const CompactArgs args, int first_layer) {
+    // one thread per layer slot of this launch; slot order is arbitrary, the layer id is in `pad`
+    int i = threadIdx.x;
+    if (i < args.n_layers) out[args.layer[i].pad] = args.layer[i].n_keep;
+    (void)first_layer;
+}
+
+}  // namespace metok
+
+using namespace metok;
+
+extern "C" int metok_kv_compact(void* const* k_layers, void* const* v_layers, int L, int B, int Hkv,
+                                int64_t S_cap, int dh, int dtype,
+                                const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
+                                void* stream) {
+    clear_error();
+    if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    if (L < 1 || L > METOK_MAX_LAYERS) return fail(METOK_ERR_INVALID_ARG, "L must be in [1, %d], got %d", METOK_MAX_LAYERS, L);
+    if (B < 1 || Hkv < 1 || dh < 1 || S_cap < 1 || S_cap > INT32_MAX)
+        return fail(METOK_ERR_INVALID_ARG, "B, Hkv, dh, S_cap must be positive and S_cap < 2^31");
+    if (!k_layers || !v_layers || !idx || !n_keep) return fail(METOK_ERR_INVALID_ARG, "NULL layer table");
+    const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
+    if (row_bytes % 16 != 0) return fail(METOK_ERR_INVALID_ARG, "dh * sizeof(dtype) = %lld is not a multiple of 16", (long long)row_bytes);
+    const int chunks = static_cast<int>(row_bytes / 16);
+    if (chunks > kCompactThreads * 16) return fail(METOK_ERR_UNSUPPORTED, "rows longer than %d bytes", kCompactThreads * 256);
+    if (static_cast<int64_t>(B) * Hkv * 2 > (1 << 20)) return fail(METOK_ERR_INVALID_ARG, "B * Hkv too large");
+
+    // layers that move data, largest first so that the long slabs start early
+    int order[METOK_MAX_LAYERS];
+    int n_active = 0;
+    for (int l = 0; l < L; ++l) {
+        if (!idx[l]) continue;
+        if (n_keep[l] < 0 || n_keep[l] > S_cap)
+            return fail(METOK_ERR_INVALID_ARG, "n_keep[%d] = %d outside [0, S_cap]", l, n_keep[l]);
+        if (!k_layers[l] || !v_layers[l] || !aligned16(k_layers[l]) || !aligned16(v_layers[l]) ||
+            (reinterpret_cast<uintptr_t>(idx[l]) & 3u))
+            return fail(METOK_ERR_INVALID_ARG, "layer %d: NULL or misaligned pointer", l);
+        if (n_keep[l] == 0) continue;
+        order[n_active++] = l;
+    }
+    for (int i = 1; i < n_active; ++i) {          // insertion sort, stable, by n_keep descending
+        int l = order[i], j = i;
+        while (j > 0 && n_keep[order[j - 1]] < n_keep[l]) { order[j] = order[j - 1]; --j; }
+        order[j] = l;
+    }
+
+    // split a row into column slices only when it is too wide for one workgroup pass
+    int parts = 1;
+    while (chunks / parts > kCompactThreads || chunks % parts) ++parts;
+    const int lanes_per_row = chunks / parts;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (new_len) {
+        // lengths of untouched layers and of emptied layers are written by a tiny kernel below
+    }
+    int32_t host_len[METOK_MAX_LAYERS];
+    for (int l = 0; l < L; ++l) host_len[l] = idx[l] ? n_keep[l] : static_cast<int32_t>(S_cap);
+
+    for (int first = 0; first < n_active; first += kMaxLayersPerLaunch) {
+        CompactArgs args;
+        args.n_layers = (n_active - first < kMaxLayersPerLaunch) ? n_active - first : kMaxLayersPerLaunch;
+        for (int i = 0; i < args.n_layers; ++i) {
+            const int l = order[first + i];
+            args.layer[i].k = static_cast<char*>(k_layers[l]);
+            args.layer[i].v = static_cast<char*>(v_layers[l]);
+            args.layer[i].idx = idx[l];
+            args.layer[i].n_keep = n_keep[l];
+            args.layer[i].pad = l;
+        }
+        args.B = B; args.Hkv = Hkv; args.parts = parts; args.lanes_per_row = lanes_per_row;
+        args.rows_per_pass = kCompactThreads / lanes_per_row;
+        args.S_cap = S_cap; args.row_bytes = row_bytes;
+        const int64_t blocks = static_cast<int64_t>(args.n_layers) * B * Hkv * 2 * parts;
+        if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "too many slabs for one launch");
+        hipLaunchKernelGGL(kv_compact_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kCompactThreads), 0, st, args);
+        int rc = check_launch("kv_compact");
+        if (rc) return rc;
+    }
+    if (new_len) {
+        // all L lengths, in layer order, through the same kernel-argument path (no host buffer is read later)
+        for (int first = 0; first < L; first += kMaxLayersPerLaunch) {
+            CompactArgs args;
+            args.n_layers = (L - first < kMaxLayersPerLaunch) ? L - first : kMaxLayersPerLaunch;
+            for (int i = 0; i < args.n_layers; ++i) {
+                args.layer[i].k = nullptr; args.layer[i].v = nullptr; args.layer[i].idx = nullptr;
+                args.layer[i].n_keep = host_len[first + i];
+                args.layer[i].pad = first + i;
+            }
+            args.B = B; args.Hkv = Hkv; args.parts = 1; args.lanes_per_row = 1; args.rows_per_pass = 1;
+            args.S_cap = S_cap; args.row_bytes = row_bytes;
+            hipLaunchKernelGGL(write_lengths_kernel, dim3(1), dim3(64), 0, st, new_len, args, first);
+            int rc = check_launch("kv_compact lengths");
+            if (rc) return rc;
+        }
+    }
+    return METOK_OK;
+}

@@ -58,12 +58,14 @@ def to_torch(x: np.ndarray, dtype: str, device="cpu"):
 # event structure
 # --------------------------------------------------------------------------
 def event_lengths(rng: np.random.Generator, total: int, n_events: int, lo: int, hi: int) -> np.ndarray:
-    """Random lengths in [lo, hi] summing to ``total`` (rejection sampling)."""
+    """A uniformly random composition of ``total`` into ``n_events`` parts, redrawn until every part
+    lies in [lo, hi]."""
     if not (n_events * lo <= total <= n_events * hi):
         raise ValueError("no composition of total with these bounds")
     for _ in range(100000):
-        lens = rng.integers(lo, hi + 1, size=n_events)
-        if int(lens.sum()) == total:
+        cuts = np.sort(rng.choice(total - 1, size=n_events - 1, replace=False)) + 1 if n_events > 1 else np.zeros(0, dtype=np.int64)
+        lens = np.diff(np.concatenate([[0], cuts, [total]]))
+        if lens.min() >= lo and lens.max() <= hi:
             return lens.astype(np.int64)
     raise RuntimeError("rejection sampling of event lengths did not converge")
 

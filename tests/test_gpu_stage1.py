@@ -1,0 +1,182 @@
+"""GPU parity of stage 1 (metok_segment_events, metok_compress_encoder_tokens) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import metok_oracle as O
+from paper_2506_02850_amd import synth
+from tests.parity import RTOL, assert_rel, assert_rows_close, bf16_ulp
+
+pytestmark = pytest.mark.gpu
+
+
+def mk():
+    from paper_2506_02850_amd import binding
+    return binding
+
+
+def run_segment(v: synth.Video, k: int, with_text=True):
+    B = mk()
+    feats = synth.to_torch(v.feats, v.dtype, "cuda")
+    text = synth.to_torch(v.text_emb, v.dtype, "cuda") if with_text else None
+    out = B.metok_segment_events(feats, k, text)
+    torch.cuda.synchronize()
+    return feats, text, {n: t.cpu().numpy() for n, t in out.items()}
+
+
+def check_segment(v: synth.Video, k: int, got, with_text=True):
+    rtol = RTOL[v.dtype]
+    S = O.adjacent_frame_cosine(v.feats)
+    T = v.feats.shape[0]
+    if T > 1:
+        # cross-event similarities sit near 0: compare against the largest similarity
+        assert_rel(got["sim"], S, rtol, "sim", scale=np.abs(S).max())
+    es, fe = O.event_boundaries(S, k)
+    if k > 1 and T > 2:
+        # the boundary decision must not sit inside a near-tie band (the generators guarantee a wide gap)
+        srt = np.sort(S)
+        if k - 1 < len(srt):
+            assert srt[k - 1] - srt[k - 2] > 1e-3 * abs(srt[k - 2]), "generator produced a near-tie at the boundary threshold"
+    np.testing.assert_array_equal(got["event_start"], es)
+    np.testing.assert_array_equal(got["frame_event"], fe)
+    if with_text:
+        f = O.frame_text_score(v.feats, v.text_emb)
+        assert_rel(got["frame_score"], f, rtol, "frame_score")
+
+
+@pytest.mark.parametrize("shapes", [synth.TINY, synth.ENCODER], ids=["tiny", "encoder"])
+def test_segment_events_configs(shapes):
+    v = synth.video_for(shapes)
+    _, _, got = run_segment(v, shapes.n_events)
+    check_segment(v, shapes.n_events, got)
+    np.testing.assert_array_equal(got["event_start"], v.event_start)      # planted boundaries recovered
+
+
+@pytest.mark.parametrize("T,grid,d,dtype,k", [
+    (5, (3, 5), 40, "bf16", 3),        # ragged: N = 15 tokens, d = 5 chunks
+    (9, (7, 7), 1152, "bf16", 4),      # SigLIP width: 144 chunks -> whole-wave token groups
+    (6, (5, 5), 132, "f32", 2),        # 33 chunks
+    (1, (4, 4), 64, "f32", 1),         # single frame
+    (2, (2, 2), 8, "bf16", 2),         # smallest pair, every frame its own event
+    (40, (4, 6), 2048, "bf16", 7),     # several frame runs, 256 chunks
+    (12, (3, 3), 4096, "f32", 12),     # widest supported fp32 rows, k = T
+])
+def test_segment_events_shapes(T, grid, d, dtype, k):
+    n_events = min(k, T)
+    v = synth.planted_video(1234 + T + d, T, grid, d, n_events, 1, T, 0.15, dtype)
+    _, _, got = run_segment(v, k)
+    check_segment(v, k, got)
+
+
+def test_segment_without_text_and_equal_frames():
+    v = synth.planted_video(77, 10, (4, 4), 64, 1, 10, 10, 0.0, "f32")     # sigma 0: all frames identical
+    _, _, got = run_segment(v, 4, with_text=False)
+    np.testing.assert_allclose(got["sim"], np.ones(9), rtol=1e-6)
+    np.testing.assert_array_equal(got["event_start"], [0, 1, 2, 3, 10])    # ties -> lowest indices
+    assert "frame_score" not in got
+
+
+def test_segment_zero_frames_guard():
+    feats = np.zeros((4, 6, 16), dtype=np.float32)
+    feats[2] = 1.0
+    v = synth.Video(feats=feats, text_emb=np.ones(16, dtype=np.float32), dtype="f32", grid=(2, 3), n_events=1,
+                    event_start=np.array([0, 4]), centroids=np.zeros((1, 16)), text_weights=np.ones(1), sigma=0.0)
+    _, _, got = run_segment(v, 2)
+    np.testing.assert_array_equal(got["sim"], [0.0, 0.0, 0.0])
+    np.testing.assert_allclose(got["frame_score"], [0.0, 0.0, 1.0, 0.0], rtol=1e-6)
+    np.testing.assert_array_equal(got["event_start"], [0, 1, 4])
+
+
+def compress_case(v: synth.Video, grid, k, alpha, beta, s1, s2, event_reduce, edge, out_dtype, fused=True):
+    B = mk()
+    feats, text, seg = run_segment(v, k)
+    es_dev = torch.from_numpy(seg["event_start"]).cuda()
+    fs_dev = torch.from_numpy(seg["frame_score"]).cuda() if fused else None
+    out = B.metok_compress_encoder_tokens(feats, grid[0], grid[1], es_dev, alpha, beta, s1, s2,
+                                          text_emb=text, frame_score=fs_dev, event_reduce=event_reduce,
+                                          pool_edge=edge, out_dtype=torch.bfloat16 if out_dtype == "bf16" else torch.float32)
+    torch.cuda.synchronize()
+    got = {n: (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy() for n, t in out.items()}
+    rtol = RTOL[v.dtype]
+
+    # frame scores as the oracle computes them; the decisions are then re-derived by the oracle from
+    # the GPU's own float32 scores, so that an fp32-vs-fp64 rounding of a score cannot flip a ranking unnoticed
+    f_or = O.frame_text_score(v.feats, v.text_emb)
+    assert_rel(got["frame_score"], f_or, rtol, "frame_score")
+    ref = O.compress_encoder_tokens(v.feats, grid, v.text_emb, seg["event_start"], alpha, beta, s1, s2,
+                                    event_reduce, edge, frame_score=got["frame_score"].astype(np.float64))
+    ref_own = O.compress_encoder_tokens(v.feats, grid, v.text_emb, seg["event_start"], alpha, beta, s1, s2,
+                                        event_reduce, edge)
+    assert_rel(got["event_score"], ref_own["event_score"], rtol, "event_score")
+    np.testing.assert_array_equal(got["event_is_key"], ref["event_is_key"])
+    np.testing.assert_array_equal(got["frame_is_key"], ref["frame_is_key"])
+    np.testing.assert_array_equal(got["frame_stride"], ref["frame_stride"])
+    np.testing.assert_array_equal(got["frame_offsets"], ref["frame_offsets"])
+    M = int(ref["frame_offsets"][-1])
+    np.testing.assert_array_equal(got["token_event"][:M], ref["token_event"])
+    # the oracle's own decisions agree unless a ranking sits within rounding distance (never with these generators)
+    np.testing.assert_array_equal(ref["frame_stride"], ref_own["frame_stride"])
+    tokens = got["out_tokens"][:M]
+    if out_dtype == "f32":
+        assert_rows_close(tokens, ref["tokens"], rtol, "pooled tokens")
+    else:
+        # bf16 output: within one bf16 ulp of the exact mean; exact agreement with the rounded oracle mean
+        # except for rare double-rounding flips (fp32 mean -> bf16 vs fp64 mean -> bf16)
+        err = np.abs(tokens.astype(np.float64) - ref["tokens"])
+        assert (err <= bf16_ulp(ref["tokens"])).all(), "pooled bf16 token further than one ulp from the exact mean"
+        mismatch = float((tokens.astype(np.float64) != O.round_to_bf16(ref["tokens"])).mean())
+        assert mismatch < 1e-3, f"bf16 rounding mismatch fraction {mismatch}"
+    return got, ref
+
+
+def test_compress_tiny_both_settings():
+    v = synth.video_for(synth.TINY)
+    got, _ = compress_case(v, (4, 4), 4, 1.0, 1.0, 2, 2, O.EVENT_REDUCE_MEAN, O.POOL_FLOOR, "f32")
+    assert int(got["frame_offsets"][-1]) == 32 and set(got["frame_stride"].tolist()) == {2}
+    got, _ = compress_case(v, (4, 4), 4, 0.5, 0.5, 1, 2, O.EVENT_REDUCE_MEAN, O.POOL_FLOOR, "f32")
+    assert set(got["frame_stride"].tolist()) <= {1, 2, 4}
+
+
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_compress_encoder_config(out_dtype):
+    v = synth.video_for(synth.ENCODER)
+    # uniform stride 2: exactly 144 tokens per frame
+    got, _ = compress_case(v, (24, 24), 8, 1.0, 1.0, 2, 2, O.EVENT_REDUCE_MEAN, O.POOL_FLOOR, out_dtype)
+    assert int(got["frame_offsets"][-1]) == 32 * 144
+    # the paper's LongVA setting: (s1, s2) = (2, 3), alpha = 0.5, beta = 0.45
+    got, ref = compress_case(v, (24, 24), 8, 0.5, 0.45, 2, 3, O.EVENT_REDUCE_MEAN, O.POOL_FLOOR, out_dtype)
+    rows = np.diff(got["frame_offsets"])
+    assert set(rows.tolist()) <= {144, 64, 36, 16} and len(set(rows.tolist())) == 4
+
+
+@pytest.mark.parametrize("grid,d,dtype,s1,s2,alpha,edge,reduce_,fused", [
+    ((27, 27), 64, "bf16", 2, 3, 0.5, O.POOL_FLOOR, O.EVENT_REDUCE_MEAN, True),    # SigLIP grid, floor: 169/81/36/16
+    ((27, 27), 64, "bf16", 2, 3, 0.5, O.POOL_CEIL, O.EVENT_REDUCE_MAX, False),     # ceil: partial edge windows
+    ((5, 7), 24, "f32", 1, 2, 0.3, O.POOL_CEIL, O.EVENT_REDUCE_MEAN, False),       # non-square, s/alpha rounds up
+    ((6, 10), 1152, "bf16", 3, 4, 0.7, O.POOL_FLOOR, O.EVENT_REDUCE_MAX, True),    # wide rows, 144 chunks
+    ((4, 4), 16, "f32", 5, 9, 0.5, O.POOL_FLOOR, O.EVENT_REDUCE_MEAN, True),       # strides clamp to the grid
+])
+def test_compress_shapes(grid, d, dtype, s1, s2, alpha, edge, reduce_, fused):
+    T, k = 11, 4
+    v = synth.planted_video(99 + d, T, grid, d, k, 1, 6, 0.1, dtype)
+    for out_dtype in ("f32", "bf16"):
+        compress_case(v, grid, k, alpha, 0.4, s1, s2, reduce_, edge, out_dtype, fused=fused)
+
+
+def test_argument_errors_are_reported():
+    B = mk()
+    feats = torch.zeros((4, 4, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.MetokError) as e:
+        B.metok_segment_events(feats, 5)
+    assert e.value.code == -1 and "k must be" in str(e.value)
+    with pytest.raises(B.MetokError):
+        B.metok_segment_events(torch.zeros((4, 4, 6), dtype=torch.float32, device="cuda"), 2)      # d % 4
+    es = torch.tensor([0, 4], dtype=torch.int32, device="cuda")
+    with pytest.raises(B.MetokError) as e:
+        B.metok_compress_encoder_tokens(feats, 2, 2, es, 0.5, 0.5, 2, 2, text_emb=torch.zeros(64, device="cuda"),
+                                        out_tokens=torch.zeros((3, 64), device="cuda"))
+    assert e.value.code == -4
+    with pytest.raises(B.MetokError):
+        B.metok_compress_encoder_tokens(feats, 2, 2, es, 1.5, 0.5, 2, 2, text_emb=torch.zeros(64, device="cuda"))
+    with pytest.raises(ValueError):
+        B.metok_segment_events(feats.cpu(), 2)

@@ -1,0 +1,197 @@
+"""GPU parity of stage 2 (metok_prefill_prune, metok_retention_quotas) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import metok_oracle as O
+from paper_2506_02850_amd import synth
+from tests.parity import RTOL, assert_rel, near_tie_report
+
+pytestmark = pytest.mark.gpu
+
+
+def mk():
+    from paper_2506_02850_amd import binding
+    return binding
+
+
+def i32(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).cuda()
+
+
+def run_prune(layer: synth.PrefillLayer, token_seg, quotas, use_weight=True, orig_idx=None, Tq=None):
+    B = mk()
+    dt = layer.dtype
+    Tq = layer.n_text if Tq is None else Tq
+    q = layer.q_text[:, layer.n_text - Tq:, :]
+    out = B.metok_prefill_prune(
+        synth.to_torch(layer.hidden, dt, "cuda"), layer.vis_start, layer.n_vis, i32(token_seg), quotas,
+        q_text=synth.to_torch(q, dt, "cuda"), k_all=synth.to_torch(layer.k_all, dt, "cuda"),
+        token_event=i32(layer.token_event),
+        event_weight=torch.from_numpy(layer.event_weight).cuda() if use_weight else None,
+        orig_idx=None if orig_idx is None else i32(orig_idx))
+    torch.cuda.synchronize()
+    return {n: (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy() for n, t in out.items()}, q
+
+
+def check_prune(layer, token_seg, quotas, got, q, use_weight=True, orig_idx=None):
+    rtol = RTOL[layer.dtype]
+    w = layer.event_weight if use_weight else None
+    # (1) scores
+    a = O.text_to_visual_attention(q, layer.k_all, layer.vis_start, layer.n_vis)
+    s_or = O.event_weighted_scores(a, layer.token_event, w)
+    worst = assert_rel(got["scores"], s_or, rtol, "scores")
+    # (2) the selection is exactly the per-class top-quota of the GPU's own scores (bit-exact, ties by index) ...
+    kept_from_gpu_scores = O.segmented_topk(got["scores"], token_seg, quotas)
+    np.testing.assert_array_equal(got["kept_idx"], kept_from_gpu_scores)
+    # ... and agrees with the oracle's selection on the oracle's scores outside the near-tie band
+    kept_or = O.segmented_topk(s_or, token_seg, quotas)
+    report = near_tie_report(s_or, token_seg, quotas, got["kept_idx"], kept_or)
+    # (3) compaction: bit-exact against the oracle gather driven by the GPU's index list
+    ref = O.prefill_prune(layer.hidden, None, None, layer.vis_start, layer.n_vis, token_seg, layer.token_event,
+                          w, quotas, orig_idx=orig_idx, scores=got["scores"])
+    np.testing.assert_array_equal(got["hidden_out"], ref["hidden_out"].astype(np.float32))
+    np.testing.assert_array_equal(got["token_seg_out"], ref["token_seg_out"])
+    np.testing.assert_array_equal(got["token_event_out"], ref["token_event_out"])
+    np.testing.assert_array_equal(got["orig_idx_out"], ref["orig_idx_out"])
+    if report["disagreements_in_band"] == 0:
+        np.testing.assert_array_equal(got["kept_idx"], kept_or)
+    print(f"scores worst rel err {worst:.2e}; near-tie band population {report['band_population']}, "
+          f"disagreements in band {report['disagreements_in_band']}")
+    return report
+
+
+def make_layer(seed, n_frames, tpf, n_events, n_text, D, Hq, Hkv, dh, dtype, vis_start=0):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ev = synth.token_events_for_frames(rng, n_frames, tpf, n_events)
+    return synth.prefill_layer(seed + 1, ev, n_events, n_text, D, Hq, Hkv, dh, dtype, vis_start=vis_start)
+
+
+def test_tiny_config_single_segment():
+    # Tiny: 8 frames x 4 pooled tokens = 32 visual tokens, 16 text tokens, 2 heads x 32, fp32, keep 25 %
+    sh = synth.TINY
+    layer = make_layer(sh.seed, sh.T, sh.tokens_per_frame, sh.n_events, sh.n_text, sh.D, sh.Hq, sh.Hkv, sh.dh, "f32")
+    seg = np.zeros(layer.n_vis, dtype=np.int32)
+    quota = [O.ceil_ratio(0.25 * layer.n_vis)]
+    assert quota == [8]
+    got, q = run_prune(layer, seg, quota)
+    check_prune(layer, seg, quota, got, q)
+
+
+@pytest.mark.parametrize("dtype,dh,Hq,Hkv,n_text,vis_start", [
+    ("bf16", 128, 28, 4, 64, 0),       # LongVA head layout: 7 query heads per kv head, two row splits
+    ("bf16", 128, 8, 2, 19, 5),        # ragged rows (4 * 19 = 76), system prefix
+    ("bf16", 64, 6, 3, 33, 0),
+    ("bf16", 32, 4, 4, 7, 3),
+    ("bf16", 256, 4, 2, 16, 0),
+    ("f32", 32, 2, 2, 16, 0),
+    ("f32", 64, 4, 2, 21, 2),
+    ("f32", 128, 2, 1, 40, 0),
+])
+def test_prune_shapes_two_classes(dtype, dh, Hq, Hkv, n_text, vis_start):
+    # 37 frames x 24 tokens = 888 visual tokens: seven 128-key tiles with a ragged tail
+    layer = make_layer(500 + dh + Hq, 37, 24, 5, n_text, 48, Hq, Hkv, dh, dtype, vis_start=vis_start)
+    seg = (1 - layer.event_is_key[layer.token_event]).astype(np.int32)          # 0 = key event, 1 = non-key
+    n_key, n_non = int((seg == 0).sum()), int((seg == 1).sum())
+    B = mk()
+    quotas = B.metok_retention_quotas(1, 0.55, 0.5, n_key, n_non)
+    assert tuple(quotas) == O.retention_quotas(1, 0.55, 0.5, n_key, n_non)
+    got, q = run_prune(layer, seg, quotas)
+    check_prune(layer, seg, quotas, got, q)
+
+
+def test_hierarchy_is_nested_and_metadata_is_carried():
+    layer = make_layer(900, 30, 16, 6, 12, 32, 4, 2, 64, "bf16")
+    seg = (1 - layer.event_is_key[layer.token_event]).astype(np.int32)
+    n_key, n_non = int((seg == 0).sum()), int((seg == 1).sum())
+    B = mk()
+    q1 = B.metok_retention_quotas(1, 0.6, 0.5, n_key, n_non)
+    got1, q = run_prune(layer, seg, q1)
+    check_prune(layer, seg, q1, got1, q)
+    # level 2 works on the survivors with fresh activations of the shorter sequence
+    kept1 = got1["kept_idx"]
+    layer2 = synth.prefill_layer(901, layer.token_event[kept1], 6, 12, 32, 4, 2, 64, "bf16")
+    layer2.event_weight[:] = layer.event_weight
+    q2 = B.metok_retention_quotas(2, 0.6, 0.5, n_key, n_non)
+    assert q2[1] == 0
+    got2, qq = run_prune(layer2, got1["token_seg_out"], q2, orig_idx=got1["orig_idx_out"])
+    check_prune(layer2, got1["token_seg_out"], q2, got2, qq, orig_idx=got1["orig_idx_out"])
+    assert set(got2["orig_idx_out"].tolist()) <= set(kept1.tolist())
+    assert np.all(np.diff(got2["orig_idx_out"]) > 0) and np.all(got2["token_seg_out"] == 0)
+    # level 3 drops every visual token: only the text rows remain
+    q3 = B.metok_retention_quotas(3, 0.6, 0.5, n_key, n_non)
+    assert q3 == [0, 0]
+    layer3 = synth.prefill_layer(902, layer2.token_event[got2["kept_idx"]], 6, 12, 32, 4, 2, 64, "bf16")
+    got3, q3q = run_prune(layer3, got2["token_seg_out"], q3)
+    assert got3["kept_idx"].size == 0 and got3["hidden_out"].shape[0] == 12
+    np.testing.assert_array_equal(got3["hidden_out"], layer3.hidden[layer3.n_vis:])
+
+
+def test_last_token_only_query_and_per_event_segments():
+    layer = make_layer(950, 20, 12, 4, 9, 16, 4, 2, 64, "bf16")
+    seg = layer.token_event.astype(np.int32)                     # one class per event
+    quotas = [O.ceil_ratio(0.5 * int((seg == e).sum())) for e in range(4)]
+    got, q = run_prune(layer, seg, quotas, use_weight=False, Tq=1)
+    check_prune(layer, seg, quotas, got, q, use_weight=False)
+
+
+def select_only(scores, seg, quotas, D=8):
+    B = mk()
+    n = scores.shape[0]
+    hidden = np.arange((n + 2) * D, dtype=np.float32).reshape(n + 2, D)
+    out = B.metok_prefill_prune(torch.from_numpy(hidden).cuda(), 1, n, i32(seg), quotas,
+                                scores=torch.from_numpy(scores.astype(np.float32)).cuda())
+    torch.cuda.synchronize()
+    kept = out["kept_idx"].cpu().numpy()
+    np.testing.assert_array_equal(kept, O.segmented_topk(scores.astype(np.float32), seg, quotas))
+    np.testing.assert_array_equal(out["hidden_out"].cpu().numpy(), O.compact_hidden(hidden, 1, n, kept))
+    return kept
+
+
+def test_selection_with_supplied_scores_ties_and_edges():
+    rng = np.random.default_rng(3)
+    n = 5000
+    seg = rng.integers(0, 3, size=n).astype(np.int32)
+    pops = [int((seg == s).sum()) for s in range(3)]
+    # heavy exact ties, including at the threshold
+    scores = np.round(rng.standard_normal(n), 1).astype(np.float32)
+    select_only(scores, seg, [pops[0] // 2, 1, pops[2] - 1])
+    # all equal: the first `quota` indices of each class
+    kept = select_only(np.full(n, 0.25, dtype=np.float32), seg, [10, 0, pops[2]])
+    assert np.array_equal(kept[seg[kept] == 0], np.nonzero(seg == 0)[0][:10])
+    # negative, zero, signed-zero and denormal scores order like real numbers
+    special = np.array([-0.0, 0.0, -1e-40, 1e-40, -3.5, 2.0, -1e30, 1e30] * 8, dtype=np.float32)
+    select_only(special, np.zeros(64, dtype=np.int32), [11])
+    # keep everything / keep nothing / single token
+    select_only(scores, seg, pops)
+    select_only(scores, seg, [0, 0, 0])
+    select_only(np.array([0.5], dtype=np.float32), np.zeros(1, dtype=np.int32), [1])
+
+
+def test_repeat_calls_are_bit_identical():
+    layer = make_layer(970, 37, 24, 5, 16, 48, 28, 4, 128, "bf16")
+    seg = np.zeros(layer.n_vis, dtype=np.int32)
+    a, _ = run_prune(layer, seg, [300])
+    b, _ = run_prune(layer, seg, [300])
+    for key in a:
+        np.testing.assert_array_equal(a[key], b[key])
+
+
+def test_argument_errors_are_reported():
+    B = mk()
+    hidden = torch.zeros((20, 16), device="cuda")
+    seg = torch.zeros(10, dtype=torch.int32, device="cuda")
+    sc = torch.zeros(10, device="cuda")
+    with pytest.raises(B.MetokError):
+        B.metok_prefill_prune(hidden, 5, 16, seg, [3], scores=sc)                      # visual span beyond S
+    with pytest.raises(B.MetokError):
+        B.metok_prefill_prune(hidden, 0, 10, seg, [11], scores=sc)                     # quota > n_vis
+    with pytest.raises(B.MetokError):
+        B.metok_prefill_prune(hidden, 0, 10, seg, [3], scores=sc, hidden_out=hidden)   # aliasing
+    q = torch.zeros((3, 4, 48), device="cuda")
+    k = torch.zeros((1, 20, 48), device="cuda")
+    with pytest.raises(B.MetokError) as e:
+        B.metok_prefill_prune(hidden, 0, 10, seg, [3], q_text=q, k_all=k)              # head dim 48
+    assert e.value.code == -2
+    with pytest.raises(B.MetokError):
+        B.metok_retention_quotas(4, 0.5, 0.5, 10, 10)

@@ -1,0 +1,155 @@
+"""GPU parity of stage 3 (metok_kv_compact) against the CPU oracle: pure row copies, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import metok_oracle as O
+from paper_2506_02850_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def mk():
+    from paper_2506_02850_amd import binding
+    return binding
+
+
+def fill_cache(L, B, H, S, dh, dtype):
+    """Host copies of K and V per layer, filled with the per-row-unique integer pattern."""
+    ks, vs = [], []
+    rows = np.arange(S)
+    for l in range(L):
+        for which, dst in ((0, ks), (1, vs)):
+            t = np.empty((B, H, S, dh), dtype=np.int16)
+            for b in range(B):
+                for h in range(H):
+                    t[b, h] = synth.kv_pattern(l, which, b, h, rows, dh)
+            dst.append(t)
+    return ks, vs
+
+
+def as_device(arr, dtype):
+    t = torch.from_numpy(arr)
+    if dtype == "bf16":
+        return t.view(torch.bfloat16).cuda()
+    # fp32 cache: two int16 payload columns make one float column
+    return t.view(torch.float32).cuda()
+
+
+def as_host(t):
+    return t.cpu().view(torch.int16).numpy()
+
+
+def run_and_check(L, B, H, S, dh16, dtype, idx_lists):
+    """dh16 = row length in int16 units (the payload view); idx_lists[l] = None or [B, n] int32."""
+    Bm = mk()
+    ks, vs = fill_cache(L, B, H, S, dh16, dtype)
+    kd = [as_device(k, dtype) for k in ks]
+    vd = [as_device(v, dtype) for v in vs]
+    idx_dev = [None if ix is None else torch.from_numpy(np.ascontiguousarray(ix, dtype=np.int32)).cuda() for ix in idx_lists]
+    new_len = Bm.metok_kv_compact(kd, vd, idx_dev)
+    torch.cuda.synchronize()
+    want_len = [S if ix is None else ix.shape[1] for ix in idx_lists]
+    np.testing.assert_array_equal(new_len.cpu().numpy(), want_len)
+    for l in range(L):
+        for host, dev, name in ((ks[l], kd[l], "K"), (vs[l], vd[l], "V")):
+            out = as_host(dev).reshape(B, H, S, dh16)
+            for b in range(B):
+                for h in range(H):
+                    ix = None if idx_lists[l] is None else idx_lists[l][b]
+                    ref = O.kv_compact(host[b, h], ix)
+                    n = ref.shape[0]
+                    assert np.array_equal(out[b, h, :n], ref), f"layer {l} {name} video {b} head {h}"
+
+
+def test_tiny_two_layers():
+    # Tiny: layer 0 untouched, layer 1 keeps the stage-2 set (8 of 32 visual) plus the 16 text rows
+    keep = synth.nested_keep_sets(synth.TINY.seed, 32, [8])[0]
+    idx = synth.kv_layer_schedule(2, (1,), 32, 16, [keep])
+    run_and_check(2, 1, 2, 48, 32 * 2, "f32", [None if i is None else i[None, :] for i in idx])
+
+
+def adversarial_sets(S):
+    rng = np.random.default_rng(S)
+    return {
+        "identity": np.arange(S),
+        "all_tail": np.arange(S - S // 3, S),
+        "stride2": np.arange(0, S, 2),
+        "odd": np.arange(1, S, 2),
+        "single_last": np.array([S - 1]),
+        "single_first": np.array([0]),
+        "prefix_then_tail": np.concatenate([np.arange(S // 4), np.arange(S - S // 4, S)]),
+        "random_half": np.sort(rng.choice(S, S // 2, replace=False)),
+        "random_eighth": np.sort(rng.choice(S, S // 8, replace=False)),
+        "shift_by_one": np.arange(1, S),
+        "empty": np.zeros(0, dtype=np.int64),
+    }
+
+
+@pytest.mark.parametrize("S,dh,dtype", [(1000, 128, "bf16"), (517, 64, "bf16"), (300, 32, "f32"), (130, 192, "bf16")])
+def test_adversarial_index_sets(S, dh, dtype):
+    sets = adversarial_sets(S)
+    names = sorted(sets)
+    L = len(names)
+    dh16 = dh if dtype == "bf16" else dh * 2
+    idx_lists = []
+    for name in names:
+        base = sets[name].astype(np.int32)
+        idx_lists.append(np.stack([base, base]))          # B = 2 videos share the list here
+    run_and_check(L, 2, 3, S, dh16, dtype, idx_lists)
+
+
+def test_per_video_lists_and_untouched_layers():
+    S, n_vis, n_text = 2304 + 40, 2304, 40
+    per_video = []
+    for b in range(3):
+        sets = synth.nested_keep_sets(1000 + b, n_vis, [n_vis // 2, n_vis // 4, n_vis // 8])
+        per_video.append(synth.kv_layer_schedule(8, (2, 4, 6), n_vis, n_text, sets))
+    idx_lists = [None if per_video[0][l] is None else np.stack([per_video[b][l] for b in range(3)]) for l in range(8)]
+    run_and_check(8, 3, 4, S, 128, "bf16", idx_lists)
+
+
+def test_paper_rule_text_only_from_l1():
+    sched = O.kv_text_only_schedule(6, 2, 700, 33)
+    idx_lists = [None if s is None else np.stack([s, s]) for s in sched]
+    run_and_check(6, 2, 2, 733, 128, "bf16", idx_lists)
+
+
+def test_many_layers_use_several_launches():
+    S = 64
+    idx = np.arange(0, S, 2, dtype=np.int32)[None, :]
+    run_and_check(45, 1, 1, S, 16, "bf16", [idx] * 45)
+
+
+def test_repeated_runs_are_bit_identical_and_out_of_range_rows_are_skipped():
+    Bm = mk()
+    S, dh = 4096, 128
+    rng = np.random.default_rng(5)
+    idx = np.sort(rng.choice(S, S // 2, replace=False)).astype(np.int32)[None, :]
+    outs = []
+    for _ in range(3):
+        ks, vs = fill_cache(1, 1, 4, S, dh, "bf16")
+        kd, vd = [as_device(ks[0], "bf16")], [as_device(vs[0], "bf16")]
+        Bm.metok_kv_compact(kd, vd, [torch.from_numpy(idx).cuda()])
+        torch.cuda.synchronize()
+        outs.append(as_host(kd[0])[:, :, : S // 2].copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    # a position beyond the cache or below its rank is skipped, never dereferenced
+    bad = np.array([[3, 0, 9, 5000]], dtype=np.int32)
+    ks, vs = fill_cache(1, 1, 1, 16, 16, "bf16")
+    kd, vd = [as_device(ks[0], "bf16")], [as_device(vs[0], "bf16")]
+    Bm.metok_kv_compact(kd, vd, [torch.from_numpy(bad).cuda()])
+    torch.cuda.synchronize()
+    out = as_host(kd[0])[0, 0]
+    assert np.array_equal(out[0], ks[0][0, 0, 3]) and np.array_equal(out[2], ks[0][0, 0, 9])
+    assert np.array_equal(out[1], ks[0][0, 0, 1]) and np.array_equal(out[3], ks[0][0, 0, 3])
+
+
+def test_argument_errors_are_reported():
+    Bm = mk()
+    k = torch.zeros((1, 1, 8, 12), dtype=torch.bfloat16, device="cuda")       # 24-byte rows
+    with pytest.raises(Bm.MetokError):
+        Bm.metok_kv_compact([k], [k.clone()], [torch.zeros((1, 2), dtype=torch.int32, device="cuda")])
+    k = torch.zeros((1, 1, 8, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ValueError):
+        Bm.metok_kv_compact([k], [k.clone()], [torch.zeros((1, 2), dtype=torch.int64, device="cuda")])
