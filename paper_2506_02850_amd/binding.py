@@ -122,25 +122,38 @@ def metok_version() -> int:
 
 
 # -------------------------------------------------------------------------------------------------
+def _out(out: Optional[Dict[str, torch.Tensor]], name: str, shape, dtype, dev) -> torch.Tensor:
+    """A caller-provided output tensor (checked) or a fresh one."""
+    if out is not None and name in out and out[name] is not None:
+        t = out[name]
+        shape = tuple(shape) if isinstance(shape, (tuple, list)) else (shape,)
+        if t.dtype != dtype or tuple(t.shape) != shape:
+            raise ValueError(f"out[{name!r}] must be {dtype} of shape {shape}, got {t.dtype} {tuple(t.shape)}")
+        return t
+    return torch.empty(shape, dtype=dtype, device=dev)
+
+
 def metok_segment_events(feats: torch.Tensor, k: int, text_emb: Optional[torch.Tensor] = None,
-                         sim_mode: int = SIM_FLAT, workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
-    """feats [T, N, d] -> sim [T-1], event_start [k+1], frame_event [T] (+ frame_score [T] if text_emb)."""
+                         sim_mode: int = SIM_FLAT, workspace: Optional[torch.Tensor] = None,
+                         out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """feats [T, N, d] -> sim [T-1], event_start [k+1], frame_event [T] (+ frame_score [T] if text_emb).
+    `out` may carry preallocated tensors under the same names."""
     T, N, d = feats.shape
     dt = _dtype_code(feats)
     dev = feats.device
     need = _lib.metok_segment_events_workspace_bytes(T, N, d, dt)
     ws = workspace if workspace is not None else _workspace(need, dev)
-    sim = torch.empty(max(T - 1, 0), dtype=torch.float32, device=dev)
-    event_start = torch.empty(k + 1, dtype=torch.int32, device=dev)
-    frame_event = torch.empty(T, dtype=torch.int32, device=dev)
-    frame_score = torch.empty(T, dtype=torch.float32, device=dev) if text_emb is not None else None
+    sim = _out(out, "sim", max(T - 1, 0), torch.float32, dev)
+    event_start = _out(out, "event_start", k + 1, torch.int32, dev)
+    frame_event = _out(out, "frame_event", T, torch.int32, dev)
+    frame_score = _out(out, "frame_score", T, torch.float32, dev) if text_emb is not None else None
     _check(_lib.metok_segment_events(_dev(feats, "feats"), dt, T, N, d, _dev(text_emb, "text_emb"), k, sim_mode,
                                      _dev(sim, "sim"), _dev(event_start, "event_start"), _dev(frame_event, "frame_event"),
                                      _dev(frame_score, "frame_score"), _dev(ws, "workspace"), ws.numel(), _stream()))
-    out = dict(sim=sim, event_start=event_start, frame_event=frame_event)
+    res = dict(sim=sim, event_start=event_start, frame_event=frame_event)
     if frame_score is not None:
-        out["frame_score"] = frame_score
-    return out
+        res["frame_score"] = frame_score
+    return res
 
 
 def pooled_capacity(T: int, grid_h: int, grid_w: int, s1: int, s2: int, pool_edge: int = POOL_FLOOR) -> int:
@@ -156,7 +169,8 @@ def metok_compress_encoder_tokens(feats: torch.Tensor, grid_h: int, grid_w: int,
                                   event_reduce: int = EVENT_MEAN, pool_edge: int = POOL_FLOOR,
                                   out_dtype: Optional[torch.dtype] = None,
                                   out_tokens: Optional[torch.Tensor] = None,
-                                  workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+                                  workspace: Optional[torch.Tensor] = None,
+                                  out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
     """Key events / key frames and adaptive pooling.  Returns out_tokens (capacity rows; the first
     frame_offsets[T] are valid) plus frame_offsets, token_event, event_is_key, frame_is_key, frame_stride,
     event_score, frame_score -- all on the device; nothing is synchronised."""
@@ -168,17 +182,19 @@ def metok_compress_encoder_tokens(feats: torch.Tensor, grid_h: int, grid_w: int,
     k = event_start.numel() - 1
     odt = out_dtype if out_dtype is not None else feats.dtype
     cap = pooled_capacity(T, grid_h, grid_w, s1, s2, pool_edge)
+    if out_tokens is None and out is not None:
+        out_tokens = out.get("out_tokens")
     if out_tokens is None:
         out_tokens = torch.empty((cap, d), dtype=odt, device=dev)
     need = _lib.metok_compress_encoder_tokens_workspace_bytes(T, grid_h, grid_w, d, dt)
     ws = workspace if workspace is not None else _workspace(need, dev)
-    frame_offsets = torch.empty(T + 1, dtype=torch.int32, device=dev)
-    token_event = torch.empty(out_tokens.shape[0], dtype=torch.int32, device=dev)
-    event_is_key = torch.empty(k, dtype=torch.uint8, device=dev)
-    frame_is_key = torch.empty(T, dtype=torch.uint8, device=dev)
-    frame_stride = torch.empty(T, dtype=torch.int32, device=dev)
-    event_score = torch.empty(k, dtype=torch.float32, device=dev)
-    frame_score_out = torch.empty(T, dtype=torch.float32, device=dev)
+    frame_offsets = _out(out, "frame_offsets", T + 1, torch.int32, dev)
+    token_event = _out(out, "token_event", out_tokens.shape[0], torch.int32, dev)
+    event_is_key = _out(out, "event_is_key", k, torch.uint8, dev)
+    frame_is_key = _out(out, "frame_is_key", T, torch.uint8, dev)
+    frame_stride = _out(out, "frame_stride", T, torch.int32, dev)
+    event_score = _out(out, "event_score", k, torch.float32, dev)
+    frame_score_out = _out(out, "frame_score", T, torch.float32, dev)
     _check(_lib.metok_compress_encoder_tokens(
         _dev(feats, "feats"), dt, T, grid_h, grid_w, d, _dev(text_emb, "text_emb"), _dev(frame_score, "frame_score"),
         _dev(event_start, "event_start"), k, float(alpha), float(beta), int(s1), int(s2), event_reduce, pool_edge,
@@ -203,7 +219,8 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
                         token_event: Optional[torch.Tensor] = None, event_weight: Optional[torch.Tensor] = None,
                         orig_idx: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
                         hidden_out: Optional[torch.Tensor] = None,
-                        workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+                        workspace: Optional[torch.Tensor] = None,
+                        out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
     """One pruning level.  With q_text/k_all the attention scores are computed; otherwise `scores` is used as given."""
     S, D = hidden.shape
     dt = _dtype_code(hidden)
@@ -218,20 +235,24 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
         Hkv = k_all.shape[0]
         if k_all.shape[1] != S or k_all.shape[2] != dh or _dtype_code(q_text) != dt or _dtype_code(k_all) != dt:
             raise ValueError("k_all must be [Hkv, S, dh] with the dtype of hidden and q_text")
-        scores = torch.empty(n_vis, dtype=torch.float32, device=dev)
+        scores = _out(out, "scores", n_vis, torch.float32, dev)
     else:
         if scores is None:
             raise ValueError("either q_text/k_all or scores must be given")
         Hq = Hkv = dh = Tq = 0
     need = _lib.metok_prefill_prune_workspace_bytes(S, Hq, Hkv, dh, Tq, n_vis, dt)
     ws = workspace if workspace is not None else _workspace(need, dev)
-    kept_idx = torch.empty(total, dtype=torch.int32, device=dev)
+    kept_idx = _out(out, "kept_idx", total, torch.int32, dev)
     out_rows = S - n_vis + total
+    if hidden_out is None and out is not None:
+        hidden_out = out.get("hidden_out")
     if hidden_out is None:
         hidden_out = torch.empty((out_rows, D), dtype=hidden.dtype, device=dev)
-    token_seg_out = torch.empty(total, dtype=torch.int32, device=dev)
-    token_event_out = torch.empty(total, dtype=torch.int32, device=dev) if token_event is not None else None
-    orig_idx_out = torch.empty(total, dtype=torch.int32, device=dev)
+    elif tuple(hidden_out.shape) != (out_rows, D) or hidden_out.dtype != hidden.dtype:
+        raise ValueError(f"hidden_out must be {hidden.dtype} of shape {(out_rows, D)}")
+    token_seg_out = _out(out, "token_seg_out", total, torch.int32, dev)
+    token_event_out = _out(out, "token_event_out", total, torch.int32, dev) if token_event is not None else None
+    orig_idx_out = _out(out, "orig_idx_out", total, torch.int32, dev)
     n_events = int(event_weight.numel()) if event_weight is not None else 0
     _check(_lib.metok_prefill_prune(
         _dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
@@ -240,11 +261,11 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
         _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), _dev(hidden_out, "hidden_out"),
         _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
         _dev(orig_idx_out, "orig_idx_out"), _dev(ws, "workspace"), ws.numel(), _stream()))
-    out = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
+    res = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
                orig_idx_out=orig_idx_out)
     if token_event_out is not None:
-        out["token_event_out"] = token_event_out
-    return out
+        res["token_event_out"] = token_event_out
+    return res
 
 
 def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.Tensor],

