@@ -51,7 +51,7 @@ def level_counts():
 
 
 class Workload:
-    def __init__(self, batch: int, device: str, seed: int = 250602850 + 4):
+    def __init__(self, batch: int, device: str, n_streams: int = 4, seed: int = 250602850 + 4):
         import torch
         from paper_2506_02850_amd import binding, synth
 
@@ -107,11 +107,16 @@ class Workload:
         self.new_len = torch.empty(N_LAYERS, dtype=torch.int32, device=device)
         # ---- preallocated outputs and workspaces (nothing is allocated inside a step)
         lib = binding.lib()
-        self.ws1 = torch.empty(max(lib.metok_segment_events_workspace_bytes(FRAMES, GRID * GRID, D_VIS, binding.BF16),
-                                   lib.metok_compress_encoder_tokens_workspace_bytes(FRAMES, GRID, GRID, D_VIS, binding.BF16)),
-                               dtype=torch.uint8, device=device)
-        self.ws2 = torch.empty(lib.metok_prefill_prune_workspace_bytes(S0, HQ, HKV, DH, TQ, N_VIS, binding.BF16),
-                               dtype=torch.uint8, device=device)
+        # Videos are independent until stage 3, so their stage-1/2 calls are spread over a few streams: the
+        # one-workgroup planning and selection kernels of one video then overlap with the streaming kernels
+        # of another.  One workspace per stream (calls on a stream are ordered, so they can share it).
+        self.n_streams = max(1, min(n_streams, batch))
+        self.streams = [torch.cuda.Stream(device=device) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        self.ws1 = [torch.empty(max(lib.metok_segment_events_workspace_bytes(FRAMES, GRID * GRID, D_VIS, binding.BF16),
+                                    lib.metok_compress_encoder_tokens_workspace_bytes(FRAMES, GRID, GRID, D_VIS, binding.BF16)),
+                                dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
+        self.ws2 = [torch.empty(lib.metok_prefill_prune_workspace_bytes(S0, HQ, HKV, DH, TQ, N_VIS, binding.BF16),
+                                dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
         i32, f32, u8 = torch.int32, torch.float32, torch.uint8
         self.seg_out = [dict(sim=torch.empty(FRAMES - 1, dtype=f32, device=device),
                              event_start=torch.empty(N_EVENTS + 1, dtype=i32, device=device),
@@ -158,26 +163,40 @@ class Workload:
 
     def stage1(self, b):
         B = self.B
-        seg = B.metok_segment_events(self.feats[b], N_EVENTS, self.text[b], workspace=self.ws1, out=self.seg_out[b])
+        ws = self.ws1[b % self.n_streams]
+        seg = B.metok_segment_events(self.feats[b], N_EVENTS, self.text[b], workspace=ws, out=self.seg_out[b])
         return B.metok_compress_encoder_tokens(self.feats[b], GRID, GRID, seg["event_start"], 1.0, 1.0, 2, 2,
-                                               frame_score=seg["frame_score"], workspace=self.ws1, out=self.cmp_out[b])
+                                               frame_score=seg["frame_score"], workspace=ws, out=self.cmp_out[b])
 
     def stage2(self, b, token_event):
         B = self.B
+        ws2 = self.ws2[b % self.n_streams]
         h, tseg, tev, orig = self.hidden0[b], self.seg0, token_event, None
         for lv, (n, c) in enumerate(zip(self.n_in, self.counts)):
             r = B.metok_prefill_prune(h, 0, n, tseg, [c], q_text=self.Q[b][lv], k_all=self.K[b][lv], token_event=tev,
                                       event_weight=self.weight[b], orig_idx=orig, hidden_out=self.hidden_out[b][lv],
-                                      workspace=self.ws2, out=self.prune_out[b][lv])
+                                      workspace=ws2, out=self.prune_out[b][lv])
             h, tseg, tev, orig = r["hidden_out"], r["token_seg_out"], r["token_event_out"], r["orig_idx_out"]
 
     def stage3(self):
         self.B.metok_kv_compact(self.k_layers, self.v_layers, self.idx_layers, new_len=self.new_len)
 
     def step(self, kv_events=None):
-        for b in range(self.batch):
-            cmp = self.stage1(b)
-            self.stage2(b, cmp["token_event"])
+        torch = self.torch
+        if self.streams:
+            main = torch.cuda.current_stream()
+            for i, st in enumerate(self.streams):
+                st.wait_stream(main)                   # the previous step's KV compaction still reads the index lists
+                with torch.cuda.stream(st):
+                    for b in range(i, self.batch, self.n_streams):
+                        cmp = self.stage1(b)
+                        self.stage2(b, cmp["token_event"])
+            for st in self.streams:
+                main.wait_stream(st)
+        else:
+            for b in range(self.batch):
+                cmp = self.stage1(b)
+                self.stage2(b, cmp["token_event"])
         if kv_events is not None:
             kv_events[0].record()
         self.stage3()
@@ -267,6 +286,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=8)
+    ap.add_argument("--streams", type=int, default=4, help="streams that share the per-video stage-1/2 work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "kv", "copy"], default="all",
                     help="kv / copy: run only the KV compaction or the calibration copy (for profiler counter runs)")
@@ -293,7 +313,7 @@ def main():
         print(json.dumps({"calib_copy_bytes": n}))
         return
 
-    w = Workload(args.batch, dev)
+    w = Workload(args.batch, dev, args.streams)
     if args.only == "kv":
         for b in range(args.batch):                      # index lists as the full pipeline produces them
             w.stage2(b, w.stage1(b)["token_event"])
@@ -330,7 +350,7 @@ def main():
                                "chained behind stage 1 at 256 x 576 x 1024",
                    "batch_videos": args.batch, "frames": FRAMES, "tokens_per_frame_in": GRID * GRID,
                    "tokens_per_frame_pooled": TOK_PER_FRAME, "prune_levels": level_counts(), "text_tokens": N_TEXT,
-                   "text_queries": TQ, "kv_layers": N_LAYERS, "L_H": list(L_H)},
+                   "text_queries": TQ, "kv_layers": N_LAYERS, "L_H": list(L_H), "streams": w.n_streams},
         "roofline": {"kernel": "kv_compact_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(),
                      "algorithmic_bytes_per_launch": w.kv_bytes(), "ms_per_launch": kv_ms},

@@ -7,9 +7,9 @@
 //                        probabilities of every visual key over the rows of a workgroup
 //   prepare_kernel       score_j = w_e(j) * mean probability
 //   select_kernel        one workgroup per retention class: radix select of the quota-th largest
-//                        score, lowest index first among equals -> one threshold per class
-//   compact_index_kernel keep flags from the thresholds, prefix sum -> ascending kept index list and
-//                        carried metadata
+//                        score, lowest index first among equals -> keep flags and per-tile counts
+//   write_index_kernel   one workgroup per 1024-token tile: prefix sums -> ascending kept index list
+//                        and carried metadata
 //   gather_rows_kernel   compaction of the hidden states
 //
 // Both MFMA passes hold the keys of a 32-key tile in registers (loaded straight from global memory in
@@ -67,19 +67,29 @@ struct ScoreGeom {
 template <typename T, int NCH>
 __device__ __forceinline__ void fill_qfrag(uint4* qfrag, const T* __restrict__ q_text, const ScoreGeom& g, int kvh, int rb0, int nrb) {
     constexpr int CE = Mma<T>::kChunkElems;
+    constexpr int kBatch = 8;                      // independent loads in flight per thread
     const int total = nrb * NCH * 64;
-    for (int idx = threadIdx.x; idx < total; idx += kScoreThreads) {
-        const int l = idx & 63;
-        const int c = (idx >> 6) % NCH;
-        const int rb = idx / (NCH * 64);
-        const int r = (rb0 + rb) * 32 + (l & 31);
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (r < g.R) {
-            const int hq = kvh * g.group + r / g.Tq, i = r % g.Tq;
-            const T* src = q_text + (static_cast<size_t>(hq) * g.Tq + i) * g.dh + (l >> 5) * (g.dh / 2) + c * CE;
-            v = *reinterpret_cast<const uint4*>(src);
+    for (int idx0 = threadIdx.x; idx0 < total; idx0 += kBatch * kScoreThreads) {
+        uint4 v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int idx = idx0 + u * kScoreThreads;
+            const int l = idx & 63;
+            const int c = (idx >> 6) % NCH;
+            const int rb = idx / (NCH * 64);
+            const int r = (rb0 + rb) * 32 + (l & 31);
+            v[u] = make_uint4(0, 0, 0, 0);
+            if (idx < total && r < g.R) {
+                const int hq = kvh * g.group + r / g.Tq, i = r % g.Tq;
+                const T* src = q_text + (static_cast<size_t>(hq) * g.Tq + i) * g.dh + (l >> 5) * (g.dh / 2) + c * CE;
+                v[u] = *reinterpret_cast<const uint4*>(src);
+            }
         }
-        qfrag[idx] = v;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int idx = idx0 + u * kScoreThreads;
+            if (idx < total) qfrag[idx] = v[u];
+        }
     }
 }
 
@@ -305,213 +315,261 @@ __global__ __launch_bounds__(256) void prepare_kernel(const float* __restrict__ 
 
 struct Quotas { int32_t q[METOK_MAX_SEGMENTS]; };
 
-// A token of class s is kept iff  key > tau  or  (key == tau and index <= j_cut)  with key = ordered_key(score).
-struct SegThreshold { uint32_t tau; int32_t j_cut; };
-
-constexpr int kSelThreads = 1024;
+constexpr int kSelThreads = 1024;      // also the tile size of the selection: tile i = tokens [1024 i, 1024 i + 1024)
 constexpr int kSelCache = 40;          // keys per thread held in registers (n_vis <= 40960)
+constexpr int kSelCand = 4096;         // candidates kept in LDS once the top 16 key bits are fixed
 
-// One workgroup per retention class: radix select (8 bits per round from the top) of the quota-th
-// largest key of the class.  Thread t owns tokens t, t + 1024, ...; with CACHED their keys stay in
-// registers for all four rounds.  Histogram updates are run-length aggregated per thread, because
-// attention scores share their top bits and would otherwise serialise on one LDS counter.
+// One workgroup per retention class.  Radix select (8 bits per round from the top) of the quota-th
+// largest key of the class, then the keep flag of every token of the class and the number of kept
+// tokens per 1024-token tile.  Thread t owns tokens t, t + 1024, ... (token i of a thread lies in tile
+// i); with CACHED their keys stay in registers.  Attention scores share their top key bits, so the
+// first two rounds aggregate runs of equal digits per thread before touching the LDS histogram, and
+// once 16 bits are fixed the few remaining candidates move to an LDS list.
 template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ token_seg,
-                                                             int n_vis, const Quotas quotas, SegThreshold* __restrict__ thr) {
+                                                             int n_vis, int n_tiles, const Quotas quotas,
+                                                             uint8_t* __restrict__ flags, int32_t* __restrict__ tile_count) {
     __shared__ int hist[256];
     __shared__ int scan_scratch[17];
-    __shared__ int s_digit, s_remaining, s_count, s_cut;
+    __shared__ int s_digit, s_remaining, s_count, s_ncand;
+    __shared__ uint32_t cand[kSelCand];
+    __shared__ int cnt[64];
     const int seg = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int quota = quotas.q[seg];
-    if (quota <= 0) {
-        if (tid == 0) { thr[seg].tau = 0xffffffffu; thr[seg].j_cut = -1; }
-        return;
-    }
-    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; s_cut = 0x7fffffff; }
+    int32_t* my_count = tile_count + static_cast<size_t>(seg) * n_tiles;
 
-    const int per = (n_vis + kSelThreads - 1) / kSelThreads;
     uint32_t key[CACHED ? kSelCache : 1];
     uint64_t member = 0;
     int mine = 0;
     if (CACHED) {
+        // unconditional, clamped loads first so that all of them are in flight together
+        int sv[kSelCache];
 #pragma unroll
         for (int i = 0; i < kSelCache; ++i) {
-            const int j = tid + i * kSelThreads;
-            key[i] = 0;
-            if (j < n_vis && token_seg[j] == seg) { key[i] = ordered_key(scores[j]); member |= 1ull << i; }
+            const int j = min(tid + i * kSelThreads, n_vis - 1);
+            sv[i] = token_seg[j];
+            key[i] = __float_as_uint(scores[j]);
+        }
+#pragma unroll
+        for (int i = 0; i < kSelCache; ++i) {
+            key[i] = ordered_key(__uint_as_float(key[i]));
+            if (tid + i * kSelThreads < n_vis && sv[i] == seg) member |= 1ull << i;
         }
         mine = __popcll(member);
     } else {
-        for (int i = 0; i < per; ++i) {
+        for (int i = 0; i < n_tiles; ++i) {
             const int j = tid + i * kSelThreads;
             mine += (j < n_vis && token_seg[j] == seg) ? 1 : 0;
         }
     }
+    // f(key) for every token of the class owned by this thread
+    auto for_each_key = [&](auto&& f) {
+        if (CACHED) {
+#pragma unroll
+            for (int i = 0; i < kSelCache; ++i)
+                if (member & (1ull << i)) f(key[i]);
+        } else {
+            for (int i = 0; i < n_tiles; ++i) {
+                const int j = tid + i * kSelThreads;
+                if (j < n_vis && token_seg[j] == seg) f(ordered_key(scores[j]));
+            }
+        }
+    };
+    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; s_ncand = 0; }
     int pop = 0;
     block_exclusive_scan(mine, scan_scratch, &pop);
-    if (quota >= pop) {
-        if (tid == 0) { thr[seg].tau = 0u; thr[seg].j_cut = 0x7fffffff; }
-        return;
+
+    // keep rule: key > tau, or key == tau and fewer than `remaining` equal keys of the class precede the token
+    uint32_t tau = 0;
+    int remaining = 0x7fffffff;
+    bool ordered_ties = false;
+    if (quota <= 0) {
+        tau = 0xffffffffu; remaining = 0;                 // nothing is kept
+    } else if (quota < pop) {
+        uint32_t prefix = 0;
+        int count_equal = 0;
+        remaining = quota;
+        bool use_list = false;
+        for (int round = 0; round < 4; ++round) {
+            const int shift = 24 - 8 * round;
+            const uint32_t hi_mask = round == 0 ? 0u : (0xffffffffu << (shift + 8));
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            if (use_list) {
+                for (int c = tid; c < s_ncand; c += kSelThreads) {
+                    const uint32_t k = cand[c];
+                    if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+                }
+            } else {
+                int run_digit = -1, run_count = 0;
+                for_each_key([&](uint32_t k) {
+                    if ((k & hi_mask) == prefix) {
+                        const int d = static_cast<int>((k >> shift) & 255u);
+                        if (d == run_digit) ++run_count;
+                        else {
+                            if (run_count) atomicAdd(&hist[run_digit], run_count);
+                            run_digit = d; run_count = 1;
+                        }
+                    }
+                });
+                if (run_count) atomicAdd(&hist[run_digit], run_count);
+            }
+            __syncthreads();
+            // thread t < 256 looks at digit 255 - t; exclusive scan = keys with a larger digit
+            const int v = tid < 256 ? hist[255 - tid] : 0;
+            int total = 0;
+            const int excl = block_exclusive_scan(v, scan_scratch, &total);
+            if (tid < 256 && excl < remaining && excl + v >= remaining) {
+                s_digit = 255 - tid;
+                s_remaining = remaining - excl;
+                s_count = v;
+            }
+            __syncthreads();
+            prefix |= static_cast<uint32_t>(s_digit) << shift;
+            remaining = s_remaining;
+            count_equal = s_count;
+            if (round == 1 && count_equal <= kSelCand) {
+                // the keys that still match (top 16 bits fixed) move to the LDS list
+                for_each_key([&](uint32_t k) {
+                    if ((k & 0xffff0000u) == prefix) cand[atomicAdd(&s_ncand, 1)] = k;
+                });
+                use_list = true;
+            }
+            __syncthreads();
+        }
+        tau = prefix;
+        ordered_ties = remaining < count_equal;
+        if (!ordered_ties) remaining = 0x7fffffff;        // every token equal to the threshold is kept
     }
 
-    uint32_t prefix = 0;
-    int remaining = quota;
-    int count_equal = 0;
-    for (int round = 0; round < 4; ++round) {
-        const int shift = 24 - 8 * round;
-        const uint32_t hi_mask = round == 0 ? 0u : (0xffffffffu << (shift + 8));
-        if (tid < 256) hist[tid] = 0;
+    // flags and per-tile counts, tiles in groups of 64
+    int ties_before = 0;                                  // equal keys of the class in earlier tiles (ordered_ties only)
+    for (int g0 = 0; g0 < n_tiles; g0 += 64) {
+        if (tid < 64) cnt[tid] = 0;
         __syncthreads();
-        int run_digit = -1, run_count = 0;
-        auto visit = [&](uint32_t k) {
-            if ((k & hi_mask) == prefix) {
-                const int d = static_cast<int>((k >> shift) & 255u);
-                if (d == run_digit) ++run_count;
-                else {
-                    if (run_count) atomicAdd(&hist[run_digit], run_count);
-                    run_digit = d; run_count = 1;
-                }
+        const int g1 = min(n_tiles, g0 + 64);
+        auto tile_body = [&](int i, bool is_member, uint32_t k) {
+            bool keep = is_member && k > tau;
+            const bool tie = is_member && k == tau;
+            if (ordered_ties) {                            // uniform over the workgroup
+                int total = 0;
+                const int before = block_exclusive_scan(tie ? 1 : 0, scan_scratch, &total);
+                if (tie && ties_before + before < remaining) keep = true;
+                ties_before += total;
+            } else if (tie && remaining > 0) {
+                keep = true;
             }
+            if (is_member) flags[tid + i * kSelThreads] = keep ? 1 : 0;
+            const unsigned long long mask = __ballot(keep);
+            if (lane == 0 && mask) atomicAdd(&cnt[i - g0], __popcll(mask));
         };
         if (CACHED) {
 #pragma unroll
             for (int i = 0; i < kSelCache; ++i)
-                if (member & (1ull << i)) visit(key[i]);
+                if (i >= g0 && i < g1) tile_body(i, (member >> i) & 1ull, key[i]);
         } else {
-            for (int i = 0; i < per; ++i) {
+            for (int i = g0; i < g1; ++i) {
                 const int j = tid + i * kSelThreads;
-                if (j < n_vis && token_seg[j] == seg) visit(ordered_key(scores[j]));
+                const bool is_member = j < n_vis && token_seg[j] == seg;
+                tile_body(i, is_member, is_member ? ordered_key(scores[j]) : 0u);
             }
         }
-        if (run_count) atomicAdd(&hist[run_digit], run_count);
         __syncthreads();
-        // thread t < 256 looks at digit 255 - t; exclusive scan = keys with a larger digit
-        const int v = tid < 256 ? hist[255 - tid] : 0;
-        int total = 0;
-        const int excl = block_exclusive_scan(v, scan_scratch, &total);
-        if (tid < 256 && excl < remaining && excl + v >= remaining) {
-            s_digit = 255 - tid;
-            s_remaining = remaining - excl;
-            s_count = v;
-        }
-        __syncthreads();
-        prefix |= static_cast<uint32_t>(s_digit) << shift;
-        remaining = s_remaining;
-        count_equal = s_count;
+        if (tid < g1 - g0) my_count[g0 + tid] = cnt[tid];
         __syncthreads();
     }
-    const uint32_t tau = prefix;
-    if (remaining >= count_equal) {                       // every token equal to the threshold is kept
-        if (tid == 0) { thr[seg].tau = tau; thr[seg].j_cut = 0x7fffffff; }
-        return;
-    }
-    // equal scores at the threshold: the lowest indices win.  Walk the tokens in index order and find
-    // the index of the `remaining`-th one that equals the threshold.
-    int taken = 0;
-    for (int i = 0; i < per; ++i) {
-        const int j = tid + i * kSelThreads;
-        int tie = 0;
-        if (j < n_vis && token_seg[j] == seg) tie = ordered_key(scores[j]) == tau ? 1 : 0;
-        int total = 0;
-        const int before = block_exclusive_scan(tie, scan_scratch, &total);
-        if (tie && taken + before + 1 == remaining) s_cut = j;
-        taken += total;
-        if (taken >= remaining) break;                    // uniform: every thread sees the same totals
-    }
-    __syncthreads();
-    if (tid == 0) { thr[seg].tau = tau; thr[seg].j_cut = s_cut; }
 }
 
-// One workgroup: keep flags from the thresholds, prefix sum, kept index list and carried metadata in
-// ascending order.  A tile is 32768 tokens: flags are built with coalesced reads and wave ballots into
-// an LDS bitmap, then thread t owns the 32 consecutive tokens of bitmap word t.
-__global__ __launch_bounds__(kSelThreads) void compact_index_kernel(
-    const float* __restrict__ scores, const int32_t* __restrict__ token_seg, int n_vis, int n_seg,
-    const SegThreshold* __restrict__ thr, int total_keep, const int32_t* __restrict__ token_event,
+// One workgroup per 1024-token tile: position of the tile's first kept token from the per-class tile
+// counts, prefix sum inside the tile, kept index list and carried metadata in ascending order.
+constexpr int kIdxThreads = 256;
+
+__global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
+    const uint8_t* __restrict__ flags, const int32_t* __restrict__ tile_count, const int32_t* __restrict__ token_seg,
+    int n_vis, int n_seg, int n_tiles, int total_keep, const int32_t* __restrict__ token_event,
     const int32_t* __restrict__ orig_idx_in, int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
     int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out) {
-    __shared__ SegThreshold sthr[METOK_MAX_SEGMENTS];
-    __shared__ uint32_t bitmap[kSelThreads];
     __shared__ int scan_scratch[17];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int s = tid; s < n_seg; s += kSelThreads) sthr[s] = thr[s];
-    __syncthreads();
-    int running = 0;
-    for (int base = 0; base < n_vis; base += 32 * kSelThreads) {
-#pragma unroll 4
-        for (int i = 0; i < 32; ++i) {
-            const int j = base + i * kSelThreads + tid;
-            bool keep = false;
-            if (j < n_vis) {
-                const int s = token_seg[j];
-                if (s >= 0 && s < n_seg) {
-                    const uint32_t k = ordered_key(scores[j]);
-                    const SegThreshold t = sthr[s];
-                    keep = k > t.tau || (k == t.tau && j <= t.j_cut);
-                }
-            }
-            const unsigned long long mask = __ballot(keep);
-            if (lane == 0) {
-                bitmap[32 * i + 2 * wave] = static_cast<uint32_t>(mask);
-                bitmap[32 * i + 2 * wave + 1] = static_cast<uint32_t>(mask >> 32);
-            }
-        }
-        __syncthreads();
-        uint32_t word = bitmap[tid];
-        int total = 0;
-        int pos = running + block_exclusive_scan(__popc(word), scan_scratch, &total);
-        while (word) {
-            const int b = __ffs(word) - 1;
-            word &= word - 1;
-            const int j = base + 32 * tid + b;
+    const int tile = blockIdx.x, tid = threadIdx.x;
+    // kept tokens in earlier tiles, all classes
+    int before = 0;
+    for (int e = tid; e < n_seg * tile; e += kIdxThreads) before += tile_count[(e / tile) * n_tiles + (e % tile)];
+    int tile_off = 0;
+    block_exclusive_scan(before, scan_scratch, &tile_off);
+    // four consecutive tokens per thread
+    const int j0 = tile * kSelThreads + tid * 4;
+    bool keep[4];
+    int sv[4];
+    int mine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int j = min(j0 + u, n_vis - 1);
+        sv[u] = token_seg[j];
+        keep[u] = flags[j] != 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        keep[u] = keep[u] && (j0 + u < n_vis) && sv[u] >= 0 && sv[u] < n_seg;     // flags of other tokens were never written
+        mine += keep[u] ? 1 : 0;
+    }
+    int total = 0;
+    int pos = tile_off + block_exclusive_scan(mine, scan_scratch, &total);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (keep[u]) {
+            const int j = j0 + u;
             if (pos < total_keep) {
                 kept_idx[pos] = j;
-                if (token_seg_out) token_seg_out[pos] = token_seg[j];
+                if (token_seg_out) token_seg_out[pos] = sv[u];
                 if (token_event_out) token_event_out[pos] = token_event[j];
                 if (orig_idx_out) orig_idx_out[pos] = orig_idx_in ? orig_idx_in[j] : j;
             }
             ++pos;
         }
-        running += total;
-        __syncthreads();
     }
-    // fewer survivors than announced (a quota above its class population): pad so that the gather stays in bounds
-    for (int p = running + tid; p < total_keep; p += kSelThreads) {
-        kept_idx[p] = 0;
-        if (token_seg_out) token_seg_out[p] = 0;
-        if (token_event_out) token_event_out[p] = 0;
-        if (orig_idx_out) orig_idx_out[p] = 0;
+    // fewer survivors than announced (a quota above its class population): the last tile pads the tail so
+    // that the gather stays in bounds
+    if (tile == n_tiles - 1) {
+        for (int p = tile_off + total + tid; p < total_keep; p += kIdxThreads) {
+            kept_idx[p] = 0;
+            if (token_seg_out) token_seg_out[p] = 0;
+            if (token_event_out) token_event_out[p] = 0;
+            if (orig_idx_out) orig_idx_out[p] = 0;
+        }
     }
 }
 
 constexpr int kGatherThreads = 256;
-constexpr int kGatherRows = 4;
 
-__global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+// One 16-byte chunk per thread, non-temporal (the copy pattern that measured fastest on MI355X).
+__global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst,
                                                                      int64_t out_rows, int chunks_per_row, int vis_start,
                                                                      int n_vis, int n_keep, const int32_t* __restrict__ kept_idx) {
-    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
-#pragma unroll
-    for (int rr = 0; rr < kGatherRows; ++rr) {
-        const int64_t r = r0 + rr;
-        if (r >= out_rows) break;
-        int64_t s;
-        if (r < vis_start) s = r;
-        else if (r < static_cast<int64_t>(vis_start) + n_keep) {
-            int kidx = kept_idx[r - vis_start];
-            kidx = kidx < 0 ? 0 : (kidx >= n_vis ? n_vis - 1 : kidx);
-            s = vis_start + kidx;
-        } else s = r - n_keep + n_vis;
-        const uint4* sp = src + s * chunks_per_row;
-        uint4* dp = dst + r * chunks_per_row;
-        for (int c = threadIdx.x; c < chunks_per_row; c += kGatherThreads) dp[c] = sp[c];
-    }
+    const int64_t gidx = static_cast<int64_t>(blockIdx.x) * kGatherThreads + threadIdx.x;
+    const int64_t r = gidx / chunks_per_row;
+    if (r >= out_rows) return;
+    const int c = static_cast<int>(gidx - r * chunks_per_row);
+    int64_t s;
+    if (r < vis_start) s = r;
+    else if (r < static_cast<int64_t>(vis_start) + n_keep) {
+        int kidx = kept_idx[r - vis_start];
+        kidx = kidx < 0 ? 0 : (kidx >= n_vis ? n_vis - 1 : kidx);
+        s = vis_start + kidx;
+    } else s = r - n_keep + n_vis;
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + s * chunks_per_row + c), dst + r * chunks_per_row + c);
 }
 
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+// keep flags [n_vis] followed by the per-class tile counts [METOK_MAX_SEGMENTS][n_tiles]
+static int select_tiles(int n_vis) { return (n_vis + kSelThreads - 1) / kSelThreads; }
+static size_t select_flag_bytes(int n_vis) { return round_up(static_cast<size_t>(n_vis), 256); }
+static size_t select_bytes(int n_vis) {
+    return select_flag_bytes(n_vis) + round_up(static_cast<size_t>(METOK_MAX_SEGMENTS) * select_tiles(n_vis) * sizeof(int32_t), 256);
+}
+
 static int chunk_count(int dh, int dtype) { return dtype == METOK_BF16 ? dh / 16 : dh / 8; }     // 16-byte chunks per lane
 
 static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start, int n_vis, int dtype, ScoreGeom* g) {
@@ -532,7 +590,7 @@ static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start,
 
 struct ScorePlan {
     int nx1, nx2;                   // workgroups along the key tiles in pass 1 / pass 2
-    size_t off_pstat, off_norm, off_colpart, off_thr, total;
+    size_t off_pstat, off_norm, off_colpart, off_sel, total;
 };
 
 static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
@@ -553,7 +611,7 @@ static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
     p->off_pstat = off;   off += round_up(static_cast<size_t>(ny) * p->nx1 * g.rbw * 32 * 2 * sizeof(float), 256);
     p->off_norm = off;    off += round_up(static_cast<size_t>(ny) * g.rbw * 32 * sizeof(float), 256);
     p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
-    p->off_thr = off;     off += round_up(sizeof(SegThreshold) * METOK_MAX_SEGMENTS, 256);
+    p->off_sel = off;     off += select_bytes(n_vis);
     p->total = off;
 }
 
@@ -593,7 +651,7 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
         plan_score(g, n_vis, &p);
         return p.total;
     }
-    return round_up(sizeof(SegThreshold) * METOK_MAX_SEGMENTS, 256);      // thresholds only (scores supplied by the caller)
+    return select_bytes(n_vis);      // selection scratch only (scores supplied by the caller)
 }
 
 extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
@@ -638,7 +696,7 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     int rc;
-    SegThreshold* thr;
+    char* sel;
     if (q_text) {
         if (!k_all || !aligned16(q_text) || !aligned16(k_all)) return fail(METOK_ERR_INVALID_ARG, "q_text / k_all NULL or misaligned");
         if (Hq < 1 || Hkv < 1 || Hq % Hkv) return fail(METOK_ERR_INVALID_ARG, "Hq = %d must be a positive multiple of Hkv = %d", Hq, Hkv);
@@ -668,30 +726,36 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
             }
         }
         if ((rc = check_launch("attention scores"))) return rc;
-        thr = reinterpret_cast<SegThreshold*>(ws + p.off_thr);
+        sel = ws + p.off_sel;
         hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
                            reinterpret_cast<const float*>(ws + p.off_colpart), g.Hkv * g.rs, n_vis,
                            static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores);
         if ((rc = check_launch("prepare"))) return rc;
     } else {
-        const size_t need = round_up(sizeof(SegThreshold) * METOK_MAX_SEGMENTS, 256);
+        const size_t need = select_bytes(n_vis);
         if (!workspace || workspace_bytes < need || !aligned16(workspace))
             return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-        thr = reinterpret_cast<SegThreshold*>(ws);
+        sel = ws;
     }
+    uint8_t* flags = reinterpret_cast<uint8_t*>(sel);
+    int32_t* tile_count = reinterpret_cast<int32_t*>(sel + select_flag_bytes(n_vis));
+    const int n_tiles = select_tiles(n_vis);
     if (n_vis <= kSelCache * kSelThreads)
-        hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, quotas, thr);
+        hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
+                           flags, tile_count);
     else
-        hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, quotas, thr);
+        hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
+                           flags, tile_count);
     if ((rc = check_launch("select"))) return rc;
-    hipLaunchKernelGGL(compact_index_kernel, dim3(1), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_seg, thr,
-                       static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out, token_event_out,
-                       orig_idx_out);
-    if ((rc = check_launch("compact index"))) return rc;
+    hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, flags, tile_count, token_seg, n_vis, n_seg,
+                       n_tiles, static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out,
+                       token_event_out, orig_idx_out);
+    if ((rc = check_launch("write index"))) return rc;
     const int chunks_per_row = static_cast<int>(row_bytes / 16);
-    const int64_t blocks = (out_rows + kGatherRows - 1) / kGatherRows;
+    const int64_t blocks = (out_rows * chunks_per_row + kGatherThreads - 1) / kGatherThreads;
+    if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "hidden_out too large for one launch");
     hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGatherThreads), 0, st,
-                       static_cast<const uint4*>(hidden), static_cast<uint4*>(hidden_out), out_rows, chunks_per_row,
+                       static_cast<const u32x4_t*>(hidden), static_cast<u32x4_t*>(hidden_out), out_rows, chunks_per_row,
                        vis_start, n_vis, static_cast<int>(total_keep), kept_idx);
     return check_launch("gather");
 }
