@@ -1,0 +1,133 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header declares,
+its host-side arithmetic (Eq. 6-7 quotas, workspace sizes) is right, and argument errors are reported
+before anything reaches a GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch  # noqa: F401  (loaded first so that the library binds to the same HIP runtime)
+
+from oracle import metok_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "metok.h")
+LIB = os.path.join(ROOT, "paper_2506_02850_amd", "libmetok.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2506_02850_amd import build
+        build.build(verbose=False)
+    lib = ctypes.CDLL(LIB)
+    lib.metok_last_error.restype = ctypes.c_char_p
+    return lib
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return re.findall(r"METOK_API\s+[\w\s\*]+?\b(metok_\w+)\s*\(", text)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) == 11 and len(set(names)) == len(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
+    from paper_2506_02850_amd import binding
+    assert sorted(binding.EXPORTS) == sorted(names)
+
+
+def test_header_cites_the_paper_for_every_call():
+    text = open(HEADER).read()
+    for needle in ("Sec. 3.2.1", "Eq. 4", "Eq. 5", "Algorithm 1", "Sec. 3.2.2", "Eq. 6-7", "Sec. 3.3", "Eq. 3"):
+        assert needle in text
+
+
+def test_retention_quotas_match_eq_6_7(lib):
+    f = lib.metok_retention_quotas
+    f.argtypes = [ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int32)]
+    out = (ctypes.c_int32 * 2)()
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        level = int(rng.integers(0, 4))
+        r, alpha = float(rng.uniform(0.05, 1.0)), float(rng.uniform(0.05, 1.0))
+        nk, nn = int(rng.integers(0, 40000)), int(rng.integers(0, 40000))
+        assert f(level, r, alpha, nk, nn, out) == 0
+        assert (out[0], out[1]) == O.retention_quotas(level, r, alpha, nk, nn)
+    # the paper's LongVA setting (r = 0.55, alpha = 0.5) by hand
+    assert f(1, 0.55, 0.5, 10000, 8432, out) == 0 and (out[0], out[1]) == (5500, 2319)
+    assert f(2, 0.55, 0.5, 10000, 8432, out) == 0 and (out[0], out[1]) == (3025, 0)
+    assert f(3, 0.55, 0.5, 10000, 8432, out) == 0 and (out[0], out[1]) == (0, 0)
+    assert f(4, 0.55, 0.5, 1, 1, out) == -1 and b"level" in lib.metok_last_error()
+    assert f(1, 0.0, 0.5, 1, 1, out) == -1
+    assert f(1, 0.5, 1.5, 1, 1, out) == -1
+
+
+def test_workspace_queries(lib):
+    seg = lib.metok_segment_events_workspace_bytes
+    seg.restype = ctypes.c_size_t
+    seg.argtypes = [ctypes.c_int] * 4
+    # LongVA-shaped stage 1: 36 token chunks x 3 partials x 4 bytes per frame, plus two per-frame arrays
+    assert seg(256, 576, 1024, 1) == 256 * 36 * 3 * 4 + 2 * 1024
+    assert seg(256, 576, 1020, 1) == 0            # d not a multiple of 8
+    assert seg(8, 16, 64, 0) > 0
+    prune = lib.metok_prefill_prune_workspace_bytes
+    prune.restype = ctypes.c_size_t
+    prune.argtypes = [ctypes.c_int64] + [ctypes.c_int] * 6
+    full = prune(36992, 28, 4, 128, 64, 36864, 1)
+    no_attention = prune(36992, 0, 0, 0, 0, 36864, 1)
+    assert full > no_attention > 36864
+    assert full < 8 << 20                         # a few MB: partial column sums dominate
+
+
+def test_argument_errors_before_any_launch(lib):
+    vp, i32, i64, sz, dbl = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t, ctypes.c_double
+    seg = lib.metok_segment_events
+    seg.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    fake = 0x1000                                   # aligned, never dereferenced: validation fails first
+    assert seg(None, 1, 8, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 1 << 20, None) == -1
+    assert seg(fake, 1, 8, 16, 64, None, 9, 0, fake, fake, fake, None, fake, 1 << 20, None) == -1       # k > T
+    assert b"k must be" in lib.metok_last_error()
+    assert seg(fake, 1, 8, 16, 64, None, 2, 7, fake, fake, fake, None, fake, 1 << 20, None) == -2       # sim_mode
+    assert seg(fake, 1, 8, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 16, None) == -3            # workspace
+    assert seg(fake, 1, 8, 16, 64, None, 2, 0, fake, fake, fake, fake, fake, 1 << 20, None) == -1       # score without text
+    assert seg(fake, 3, 8, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 1 << 20, None) == -1       # dtype
+    assert seg(fake, 1, 9000, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 1 << 30, None) == -1    # T limit
+    kv = lib.metok_kv_compact
+    kv.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i64, i32, i32, ctypes.POINTER(vp),
+                   ctypes.POINTER(ctypes.c_int32), vp, vp]
+    k = (vp * 1)(fake); v = (vp * 1)(fake); idx = (vp * 1)(fake)
+    nk = (ctypes.c_int32 * 1)(4)
+    assert kv(k, v, 1, 1, 1, 16, 12, 1, idx, nk, None, None) == -1      # 24-byte rows
+    nk[0] = 17
+    assert kv(k, v, 1, 1, 1, 16, 16, 1, idx, nk, None, None) == -1      # n_keep > S_cap
+    assert kv(k, v, 0, 1, 1, 16, 16, 1, idx, nk, None, None) == -1      # L < 1
+    assert kv(k, v, 200, 1, 1, 16, 16, 1, idx, nk, None, None) == -1    # L > METOK_MAX_LAYERS
+    copy = lib.metok_calib_copy
+    copy.argtypes = [vp, vp, sz, vp]
+    assert copy(fake, fake, 24, None) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    from paper_2506_02850_amd import binding
+    with pytest.raises(ValueError):
+        binding.metok_segment_events(torch.zeros((4, 4, 64)), 2)
+    with pytest.raises(TypeError):
+        binding.metok_segment_events(torch.zeros((4, 4, 64), dtype=torch.float16), 2)
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may import it."""
+    pkg = os.path.join(ROOT, "paper_2506_02850_amd")
+    pat = re.compile(r"^\s*(from|import)\s+oracle\b|metok_oracle|oracle[/\\.]", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, name)).read()
+                assert not pat.search(text), f"{name} refers to the oracle"
+    # and the oracle does not import the package's binding or library
+    text = open(os.path.join(ROOT, "oracle", "metok_oracle.py")).read()
+    assert "binding" not in text and "libmetok" not in text and "ctypes" not in text
