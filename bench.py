@@ -288,8 +288,9 @@ def main():
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--streams", type=int, default=4, help="streams that share the per-video stage-1/2 work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["all", "kv", "copy"], default="all",
-                    help="kv / copy: run only the KV compaction or the calibration copy (for profiler counter runs)")
+    ap.add_argument("--only", choices=["all", "kv", "copy", "prune"], default="all",
+                    help="kv / copy / prune: run only the KV compaction, the calibration copy or the stage-2 calls "
+                         "(for profiler counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -321,6 +322,15 @@ def main():
             w.stage3()
         torch.cuda.synchronize()
         print(json.dumps({"kv_bytes_per_launch": w.kv_bytes()}))
+        return
+
+    if args.only == "prune":
+        toks = [w.stage1(b)["token_event"] for b in range(args.batch)]
+        for _ in range(args.warmup + args.steps):
+            for b in range(args.batch):
+                w.stage2(b, toks[b])
+        torch.cuda.synchronize()
+        print(json.dumps({"score_flops_per_step": w.score_flops()}))
         return
 
     for _ in range(args.warmup):

@@ -128,22 +128,34 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
     const int64_t text_start = g.S - g.Tq;
     const int64_t n_tiles = (g.S + kTileKeys - 1) / kTileKeys;
     const int h = lane >> 5;
+    // the key fragments of the next tile are requested before the current tile is processed
+    uint4 kf[NCH], kf_next[NCH];
+    if (static_cast<int64_t>(blockIdx.x) < n_tiles)
+        load_kfrag<T, NCH>(kf_next, k_all, g, kvh, static_cast<int64_t>(blockIdx.x) * kTileKeys + wave * 32, lane);
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t j0 = tile * kTileKeys + wave * 32;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) kf[c] = kf_next[c];
+        if (tile + gridDim.x < n_tiles)
+            load_kfrag<T, NCH>(kf_next, k_all, g, kvh, (tile + gridDim.x) * kTileKeys + wave * 32, lane);
         if (j0 >= g.S) continue;
-        uint4 kf[NCH];
-        load_kfrag<T, NCH>(kf, k_all, g, kvh, j0, lane);
         const bool full = j0 + 32 <= text_start;            // every key of the tile is visible to every query
+        // the query fragments of row block rb + 1 are read from LDS while block rb is multiplied and reduced
+        uint4 qf[2][NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) qf[0][c] = qfrag[c * 64 + lane];
 #pragma unroll
         for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
             if (rb < nrb) {
                 f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                const uint4* qp = qfrag + (rb * NCH) * 64 + lane;
-                uint4 qf[NCH];
+                if (rb + 1 < nrb) {
+                    const uint4* qp = qfrag + ((rb + 1) * NCH) * 64 + lane;
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) qf[c] = qp[c * 64];
+                    for (int c = 0; c < NCH; ++c) qf[(rb + 1) & 1][c] = qp[c * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(kf[c], qf[c], acc);
+                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(kf[c], qf[rb & 1][c], acc);
                 // accumulator i <-> key j0 + 8 (i / 4) + 4 h + i % 4, query row = lane % 32
                 float s[16];
                 float m_new, sum = 0.f;
@@ -261,22 +273,33 @@ __global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const T* __rest
 
     const int h = lane >> 5;
     const int n_tiles = (g.n_vis + kTileKeys - 1) / kTileKeys;
+    uint4 kf[NCH], kf_next[NCH];
+    if (static_cast<int>(blockIdx.x) < n_tiles)
+        load_kfrag<T, NCH>(kf_next, k_all, g, kvh, static_cast<int64_t>(g.vis_start) + blockIdx.x * kTileKeys + wave * 32, lane);
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int jv = tile * kTileKeys + wave * 32;          // first visual key of this wave
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) kf[c] = kf_next[c];
+        if (tile + static_cast<int>(gridDim.x) < n_tiles)
+            load_kfrag<T, NCH>(kf_next, k_all, g, kvh,
+                               static_cast<int64_t>(g.vis_start) + static_cast<int64_t>(tile + gridDim.x) * kTileKeys + wave * 32, lane);
         if (jv >= g.n_vis) continue;
-        uint4 kf[NCH];
-        load_kfrag<T, NCH>(kf, k_all, g, kvh, static_cast<int64_t>(g.vis_start) + jv, lane);
         float colsum = 0.f;
+        uint4 qf[2][NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) qf[0][c] = qfrag[c * 64 + lane];
 #pragma unroll
         for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
             if (rb < nrb) {
                 f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                const uint4* qp = qfrag + (rb * NCH) * 64 + lane;
-                uint4 qf[NCH];
+                if (rb + 1 < nrb) {
+                    const uint4* qp = qfrag + ((rb + 1) * NCH) * 64 + lane;
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) qf[c] = qp[c * 64];
+                    for (int c = 0; c < NCH; ++c) qf[(rb + 1) & 1][c] = qp[c * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(qf[c], kf[c], acc);
+                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(qf[rb & 1][c], kf[c], acc);
                 // accumulator i <-> query row rb * 32 + 8 (i / 4) + 4 h + i % 4, key = lane % 32
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
