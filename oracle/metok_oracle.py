@@ -32,6 +32,11 @@ CEIL_SLACK = 1e-9          # ceil(x - 1e-9): keeps 0.55 * 20 = 11.00000000000000
 
 EVENT_REDUCE_MEAN = 0      # Sec. 3.2.1 text: "average these scores per event"
 EVENT_REDUCE_MAX = 1       # Algorithm 1: r_j = max over the event's frames
+SIM_FLAT = 0               # Eq. 4 over all N*d entries of the two frames
+SIM_TOKEN_MEAN = 1         # mean over the N token positions of the cosine of matching tokens
+SIM_POOLED = 2             # cosine of the two frames' token-mean vectors
+SCORE_CAUSAL_ALL = 0       # softmax over every key a text query can see
+SCORE_VISUAL_ONLY = 1      # softmax over the visual keys only
 POOL_FLOOR = 0             # trailing cells that do not fill a window are dropped
 POOL_CEIL = 1              # partial edge windows are averaged over their valid cells
 
@@ -49,19 +54,34 @@ def _cos(num: float, den: float) -> float:
 # ---------------------------------------------------------------------------
 # Stage 1 (Sec. 3.2.1, Algorithm 1)
 # ---------------------------------------------------------------------------
-def adjacent_frame_cosine(V: np.ndarray) -> np.ndarray:
+def adjacent_frame_cosine(V: np.ndarray, mode: int = SIM_FLAT) -> np.ndarray:
     """Eq. 4: S_i = <v_i, v_{i+1}> / (||v_i|| ||v_{i+1}||) for the T-1 adjacent pairs.
 
-    v_i is the whole N x d frame, so the inner product and the norms run over
-    all N*d entries (Frobenius).  Index i = 0..T-2 pairs frame i with i+1.
+    v_i is the whole N x d frame.  SIM_FLAT (default reading): the inner product and the norms run
+    over all N*d entries (Frobenius).  The other two readings of "cosine of two N x d embeddings":
+    SIM_TOKEN_MEAN averages the cosines of the N matching token pairs, SIM_POOLED takes the cosine of
+    the frames' mean tokens.  Index i = 0..T-2 pairs frame i with i+1.
     """
     V = np.asarray(V, dtype=F64)
-    T = V.shape[0]
+    T, N, _ = V.shape
     S = np.zeros(max(T - 1, 0), dtype=F64)
     for i in range(T - 1):
-        a = V[i].reshape(-1)
-        b = V[i + 1].reshape(-1)
-        S[i] = _cos(float(np.dot(a, b)), math.sqrt(float(np.dot(a, a))) * math.sqrt(float(np.dot(b, b))))
+        if mode == SIM_FLAT:
+            a = V[i].reshape(-1)
+            b = V[i + 1].reshape(-1)
+            S[i] = _cos(float(np.dot(a, b)), math.sqrt(float(np.dot(a, a))) * math.sqrt(float(np.dot(b, b))))
+        elif mode == SIM_TOKEN_MEAN:
+            acc = 0.0
+            for n in range(N):
+                a, b = V[i, n], V[i + 1, n]
+                acc += _cos(float(np.dot(a, b)), math.sqrt(float(np.dot(a, a))) * math.sqrt(float(np.dot(b, b))))
+            S[i] = acc / N
+        elif mode == SIM_POOLED:
+            a = V[i].sum(axis=0) / N
+            b = V[i + 1].sum(axis=0) / N
+            S[i] = _cos(float(np.dot(a, b)), math.sqrt(float(np.dot(a, a))) * math.sqrt(float(np.dot(b, b))))
+        else:
+            raise ValueError("unknown similarity mode")
     return S
 
 
@@ -206,7 +226,8 @@ def compress_encoder_tokens(V: np.ndarray, grid: Tuple[int, int], t: np.ndarray,
 # ---------------------------------------------------------------------------
 # Stage 2 (Sec. 3.2.2, Eq. 6-7)
 # ---------------------------------------------------------------------------
-def text_to_visual_attention(q_text: np.ndarray, k_all: np.ndarray, vis_start: int, n_vis: int) -> np.ndarray:
+def text_to_visual_attention(q_text: np.ndarray, k_all: np.ndarray, vis_start: int, n_vis: int,
+                             mode: int = SCORE_CAUSAL_ALL) -> np.ndarray:
     """Sec. 3.2.2 "visual-text attention scores" (the paper gives no formula).
 
     Reading: q_text [Hq, Tq, dh] are the queries of the last Tq sequence
@@ -214,6 +235,8 @@ def text_to_visual_attention(q_text: np.ndarray, k_all: np.ndarray, vis_start: i
     query head h reads kv head h // (Hq / Hkv).  Each query at position p runs
     an ordinary causal softmax over keys 0..p of q.k / sqrt(dh); a_j is the
     probability that lands on visual key j, averaged over all heads and queries.
+    SCORE_VISUAL_ONLY normalises over the visual keys alone (prefix and text keys
+    take no probability mass).
     """
     q = np.asarray(q_text, dtype=F64)
     k = np.asarray(k_all, dtype=F64)
@@ -226,7 +249,10 @@ def text_to_visual_attention(q_text: np.ndarray, k_all: np.ndarray, vis_start: i
         logits = (q[h] @ k[h // group].T) / math.sqrt(dh)          # [Tq, S]
         for i in range(Tq):
             p_i = S - Tq + i
-            row = np.where(pos <= p_i, logits[i], -np.inf)
+            visible = pos <= p_i
+            if mode == SCORE_VISUAL_ONLY:
+                visible = visible & (pos >= vis_start) & (pos < vis_start + n_vis)
+            row = np.where(visible, logits[i], -np.inf)
             row = np.exp(row - row.max())
             row = row / row.sum()
             a += row[vis_start: vis_start + n_vis]

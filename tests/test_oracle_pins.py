@@ -90,6 +90,46 @@ def test_planted_events_recovered_and_closed_form(shapes):
         assert np.all(fe[es[e]:es[e + 1]] == e)
 
 
+def test_eq4_alternative_readings():
+    """Token-mean and pooled readings of Eq. 4: brute force, special cases, closed form of the generator."""
+    v = synth.video_for(synth.TINY)
+    V = v.feats.astype(np.float64)
+    T, N, d = V.shape
+    tm, pooled = [], []
+    for i in range(T - 1):
+        acc = 0.0
+        for n in range(N):
+            dot = sum(V[i, n, c] * V[i + 1, n, c] for c in range(d))
+            na = math.sqrt(sum(V[i, n, c] ** 2 for c in range(d)))
+            nb = math.sqrt(sum(V[i + 1, n, c] ** 2 for c in range(d)))
+            acc += dot / (na * nb)
+        tm.append(acc / N)
+        ma = [sum(V[i, n, c] for n in range(N)) / N for c in range(d)]
+        mb = [sum(V[i + 1, n, c] for n in range(N)) / N for c in range(d)]
+        pooled.append(sum(x * y for x, y in zip(ma, mb)) / math.sqrt(sum(x * x for x in ma) * sum(y * y for y in mb)))
+    np.testing.assert_allclose(O.adjacent_frame_cosine(v.feats, O.SIM_TOKEN_MEAN), tm, rtol=1e-12)
+    np.testing.assert_allclose(O.adjacent_frame_cosine(v.feats, O.SIM_POOLED), pooled, rtol=1e-12)
+    # one token per frame: all three readings coincide
+    one = v.feats[:, :1, :]
+    flat = O.adjacent_frame_cosine(one, O.SIM_FLAT)
+    np.testing.assert_allclose(O.adjacent_frame_cosine(one, O.SIM_TOKEN_MEAN), flat, rtol=1e-13)
+    np.testing.assert_allclose(O.adjacent_frame_cosine(one, O.SIM_POOLED), flat, rtol=1e-13)
+    # token-mean is invariant to a per-token rescaling, flat is not
+    W = v.feats.astype(np.float64).copy()
+    W[:, 3, :] *= 50.0
+    np.testing.assert_allclose(O.adjacent_frame_cosine(W, O.SIM_TOKEN_MEAN), tm, rtol=1e-12)
+    assert np.abs(O.adjacent_frame_cosine(W, O.SIM_FLAT) - O.adjacent_frame_cosine(v.feats, O.SIM_FLAT)).max() > 1e-3
+    # generator closed forms: token pairs behave like the flat case, the mean token averages the noise away
+    sh = synth.TINY
+    inside = [i for i in range(T - 1) if i + 1 not in set(v.event_start[1:-1].tolist())]
+    assert abs(np.mean([tm[i] for i in inside]) - 1.0 / (1.0 + sh.sigma ** 2 * sh.d)) < 0.06
+    assert abs(np.mean([pooled[i] for i in inside]) - 1.0 / (1.0 + sh.sigma ** 2 * sh.d / N)) < 0.03
+    # every reading recovers the planted events
+    for mode in (O.SIM_TOKEN_MEAN, O.SIM_POOLED):
+        es, _ = O.event_boundaries(O.adjacent_frame_cosine(v.feats, mode), sh.n_events)
+        np.testing.assert_array_equal(es, v.event_start)
+
+
 def test_boundary_rule_by_hand_and_ties():
     S = np.array([0.9, 0.1, 0.8, 0.1, 0.7, 0.1])
     es, fe = O.event_boundaries(S, 3)          # two lowest: ties at 0.1 -> indices 1 and 3
@@ -350,6 +390,24 @@ def test_attention_matches_library_sdpa():
                                                              attn_mask=mask)[0]
     want = probs.mean(dim=(0, 1))[5:5 + 30].numpy()
     np.testing.assert_allclose(O.text_to_visual_attention(q, k, 5, 30), want, rtol=1e-10)
+
+
+def test_attention_visual_only_normalisation():
+    rng = np.random.default_rng(12)
+    q = rng.standard_normal((4, 3, 8))
+    k = rng.standard_normal((2, 2 + 11 + 3, 8))
+    a_all = O.text_to_visual_attention(q, k, 2, 11)
+    a_vis = O.text_to_visual_attention(q, k, 2, 11, O.SCORE_VISUAL_ONLY)
+    assert abs(a_vis.sum() - 1.0) < 1e-12 and a_all.sum() < 1.0        # all mass on the visual keys
+    # equals the causal-all routine on a sequence from which prefix and text keys are cut out
+    k_cut = np.concatenate([k[:, 2:13], np.full((2, 3, 8), 0.0)], axis=1)
+    want = np.zeros(11)
+    for h in range(4):
+        logits = q[h] @ k[h // 2, 2:13].T / math.sqrt(8)
+        e = np.exp(logits - logits.max(axis=1, keepdims=True))
+        want += (e / e.sum(axis=1, keepdims=True)).sum(axis=0)
+    np.testing.assert_allclose(a_vis, want / 12, rtol=1e-12)
+    del k_cut
 
 
 def test_attention_gqa_head_mapping():
