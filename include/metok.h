@@ -51,7 +51,8 @@ enum {
 };
 
 enum { METOK_F32 = 0, METOK_BF16 = 1 };
-enum { METOK_SIM_FLAT = 0 };                       /* Eq. 4 over all N*d entries of a frame */
+enum { METOK_SIM_FLAT = 0, METOK_SIM_TOKEN_MEAN = 1, METOK_SIM_POOLED = 2 };  /* readings of Eq. 4, see below */
+enum { METOK_SCORE_CAUSAL_ALL = 0, METOK_SCORE_VISUAL_ONLY = 1 };             /* softmax support of the stage-2 score */
 enum { METOK_EVENT_MEAN = 0, METOK_EVENT_MAX = 1 };/* event score: Sec. 3.2.1 text / Algorithm 1 */
 enum { METOK_POOL_FLOOR = 0, METOK_POOL_CEIL = 1 };/* output side floor(g/s) or ceil(g/s) */
 
@@ -73,8 +74,12 @@ METOK_API int metok_version(void);
  *   feats        device, [T, N, d] of `dtype`: N patch tokens of width d for each of T frames.
  *   text_emb     device, [d] of `dtype`, or NULL.  When given, frame_score is produced.
  *   k            number of events, 1 <= k <= T.
- *   sim_mode     METOK_SIM_FLAT: S_i = <v_i, v_{i+1}> / (|v_i| |v_{i+1}|) with the inner product
+ *   sim_mode     METOK_SIM_FLAT (default): S_i = <v_i, v_{i+1}> / (|v_i| |v_{i+1}|) with the inner product
  *                and norms over all N*d entries (a denominator below 1e-12 gives S_i = 0).
+ *                METOK_SIM_TOKEN_MEAN: mean over the N token positions of the cosine of the two
+ *                frames' tokens at that position.  METOK_SIM_POOLED: cosine of the two frames'
+ *                mean tokens (one more pass over feats; d <= 4096).  Eq. 4 writes a cosine of two
+ *                N x d embeddings without saying which of these it means.
  *   sim          device out, [T-1] float: S_i for the pair (i, i+1), i = 0..T-2.
  *   event_start  device out, [k+1] int32: event e covers frames [event_start[e], event_start[e+1]);
  *                event_start[0] = 0, event_start[k] = T, strictly increasing.  The k-1 lowest
@@ -158,6 +163,10 @@ METOK_API int metok_retention_quotas(int level, double r, double alpha, int64_t 
  *                attention step is skipped.
  *   k_all        device, [Hkv, S, dh] of `dtype`: keys of all S positions (ignored if q_text NULL).
  *                Query head h reads kv head h / (Hq / Hkv).
+ *   score_mode   METOK_SCORE_CAUSAL_ALL: the softmax of a query at position p runs over keys 0..p
+ *                (prefix, visual and earlier text keys all take probability mass).
+ *                METOK_SCORE_VISUAL_ONLY: it runs over the n_vis visual keys alone.
+ *                Ignored if q_text is NULL.
  *   token_seg    device, [n_vis] int32 in [0, n_seg): retention class of each visual token
  *                (e.g. 0 = key event, 1 = non-key event; or the event id; or all 0).
  *   token_event  device, [n_vis] int32 in [0, n_events): event of each visual token.
@@ -184,7 +193,7 @@ METOK_API size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv,
 
 METOK_API int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
                         const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
-                        int vis_start, int n_vis,
+                        int score_mode, int vis_start, int n_vis,
                         const int32_t* token_seg, const int32_t* token_event,
                         const float* event_weight, int n_events,
                         int n_seg, const int32_t* seg_quota,

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libmetok.so")
 
 METOK_OK = 0
 F32, BF16 = 0, 1
-SIM_FLAT = 0
+SIM_FLAT, SIM_TOKEN_MEAN, SIM_POOLED = 0, 1, 2
+SCORE_CAUSAL_ALL, SCORE_VISUAL_ONLY = 0, 1
 EVENT_MEAN, EVENT_MAX = 0, 1
 POOL_FLOOR, POOL_CEIL = 0, 1
 
@@ -61,7 +62,7 @@ def _load() -> ctypes.CDLL:
     lib.metok_prefill_prune_workspace_bytes.restype = sz
     lib.metok_prefill_prune_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, i32]
     lib.metok_prefill_prune.restype = i32
-    lib.metok_prefill_prune.argtypes = [vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
+    lib.metok_prefill_prune.argtypes = [vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
                                         i32, c.POINTER(c.c_int32), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_kv_compact.restype = i32
     lib.metok_kv_compact.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, c.POINTER(vp),
@@ -220,7 +221,8 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
                         orig_idx: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
                         hidden_out: Optional[torch.Tensor] = None,
                         workspace: Optional[torch.Tensor] = None,
-                        out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+                        out: Optional[Dict[str, torch.Tensor]] = None,
+                        score_mode: int = 0) -> Dict[str, torch.Tensor]:
     """One pruning level.  With q_text/k_all the attention scores are computed; otherwise `scores` is used as given."""
     S, D = hidden.shape
     dt = _dtype_code(hidden)
@@ -256,7 +258,7 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
     n_events = int(event_weight.numel()) if event_weight is not None else 0
     _check(_lib.metok_prefill_prune(
         _dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
-        int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
+        int(score_mode), int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
         _dev(event_weight, "event_weight"), n_events, n_seg, quota_arr, _dev(orig_idx, "orig_idx"),
         _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), _dev(hidden_out, "hidden_out"),
         _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),

@@ -26,12 +26,12 @@ constexpr float kZeroNorm = 1e-12f;
 // the pair that straddles two runs).
 //
 // part[(t * C + c) * 3 + {0,1,2}] = over the tokens of chunk c of frame t:
-//     sum |v|^2,  sum <v_t, v_{t+1}>,  sum of cos(token, text)
+//     sum |v|^2,  sum <v_t, v_{t+1}> (token-mean mode: sum of cos(v_t[n], v_{t+1}[n])),  sum of cos(token, text)
 // ---------------------------------------------------------------------------------------------
 template <typename T, int G, int KL>
 __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
     const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int N, int d,
-    int frames_per_run, int do_pair, float* __restrict__ part, int C) {
+    int frames_per_run, int do_pair, int sim_mode, float* __restrict__ part, int C) {
     using E = Elem<T>;
     constexpr int TPW = 64 / G;                 // tokens per wave
     constexpr int TOK = kStatsWaves * TPW;      // tokens per workgroup
@@ -77,16 +77,16 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
 #pragma unroll
     for (int k = 0; k < KL; ++k) { prv[k] = zero; nxt[k] = zero; }
     const int t_last = (do_pair && t1 < T_frames) ? t1 : t1 - 1;      // last frame that is loaded
+    float p_prev = 0.f;
     for (int t = t0; t <= t_last; ++t) {
         if (t + 1 <= t_last) load_row(t + 1, nxt);
         float p = 0.f, q = 0.f, cd = 0.f;
         const bool own = t < t1;                                      // frame t belongs to this run
+#pragma unroll
+        for (int k = 0; k < KL; ++k) p = E::dot(cur[k], cur[k], p);
         if (own) {
 #pragma unroll
-            for (int k = 0; k < KL; ++k) {
-                p = E::dot(cur[k], cur[k], p);
-                q = E::dot(cur[k], txt[k], q);
-            }
+            for (int k = 0; k < KL; ++k) q = E::dot(cur[k], txt[k], q);
         }
         if (do_pair && t > t0) {
 #pragma unroll
@@ -95,8 +95,14 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
         p = group_sum<G>(p);
         q = group_sum<G>(q);
         cd = group_sum<G>(cd);
+        if (sim_mode == METOK_SIM_TOKEN_MEAN) {                       // cosine of the matching tokens of frames t-1 and t
+            const float dn = sqrtf(p_prev) * sqrtf(p);
+            cd = (tok_ok && !(dn < kZeroNorm)) ? cd / dn : 0.f;
+        }
+        p_prev = p;
         const float den = sqrtf(p) * tnorm;
         const float cosv = (own && do_text && tok_ok && !(den < kZeroNorm)) ? q / den : 0.f;
+        if (!own) p = 0.f;
         const int buf = (t - t0) & 1;
         if (sub == 0) {
             red[buf][slot][0] = p;
@@ -128,7 +134,7 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
 constexpr int kSegThreads = 1024;
 
 __global__ __launch_bounds__(kSegThreads) void segment_kernel(
-    const float* __restrict__ part, int C, int T, int N, int k, int have_text,
+    const float* __restrict__ part, int C, int T, int N, int k, int have_text, int sim_mode,
     float* __restrict__ sim, int32_t* __restrict__ event_start, int32_t* __restrict__ frame_event,
     float* __restrict__ frame_score, float* __restrict__ frame_norm2, float* __restrict__ pair_dot) {
     __shared__ uint32_t key[METOK_MAX_FRAMES];      // ordered keys of S_i, later boundary flags
@@ -157,7 +163,8 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     // Eq. 4
     for (int t = tid; t < T - 1; t += kSegThreads) {
         const float den = sqrtf(frame_norm2[t]) * sqrtf(frame_norm2[t + 1]);
-        const float s = (den < kZeroNorm) ? 0.f : pair_dot[t] / den;
+        const float s = sim_mode == METOK_SIM_TOKEN_MEAN ? pair_dot[t] / static_cast<float>(N)
+                                                         : ((den < kZeroNorm) ? 0.f : pair_dot[t] / den);
         sim[t] = s;
         key[t] = ordered_key(s);
     }
@@ -195,6 +202,36 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     if (tid == 0) {
         event_start[0] = 0;
         event_start[k] = T;
+    }
+}
+
+// Token-mean vector of every frame (pooled reading of Eq. 4): mean[t][:] = (1/N) sum_n v_t[n][:], fp32.
+// A workgroup takes one frame and 64 chunk columns; its four waves split the tokens and are added in order.
+template <typename T>
+__global__ __launch_bounds__(256) void frame_mean_kernel(const T* __restrict__ feats, int N, int d, float* __restrict__ mean) {
+    using E = Elem<T>;
+    __shared__ float red[4][64][8];
+    const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nchunks = d / E::kVec;
+    const int c = blockIdx.y * 64 + lane;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (c < nchunks) {
+        const uint4* base = reinterpret_cast<const uint4*>(feats) + static_cast<size_t>(t) * N * nchunks + c;
+        int n = wave;
+        for (; n + 12 < N; n += 16) {                  // four independent loads in flight
+            const uint4 a = load_stream(base + static_cast<size_t>(n) * nchunks), b = load_stream(base + static_cast<size_t>(n + 4) * nchunks),
+                        e = load_stream(base + static_cast<size_t>(n + 8) * nchunks), f = load_stream(base + static_cast<size_t>(n + 12) * nchunks);
+            E::accumulate(a, acc); E::accumulate(b, acc); E::accumulate(e, acc); E::accumulate(f, acc);
+        }
+        for (; n < N; n += 4) E::accumulate(load_stream(base + static_cast<size_t>(n) * nchunks), acc);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[wave][lane][i] = acc[i];
+    __syncthreads();
+    if (wave == 0 && c < nchunks) {
+        for (int i = 0; i < E::kVec; ++i)
+            mean[static_cast<size_t>(t) * d + static_cast<size_t>(c) * E::kVec + i] =
+                (((red[0][lane][i] + red[1][lane][i]) + red[2][lane][i]) + red[3][lane][i]) / static_cast<float>(N);
     }
 }
 
@@ -416,17 +453,17 @@ static bool plan_stats(int T, int N, int d, int dtype, StatsPlan* p) {
 
 template <typename T, int G, int KL>
 static void launch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
-                         float* part, hipStream_t st) {
+                         int sim_mode, float* part, hipStream_t st) {
     hipLaunchKernelGGL((frame_stats_kernel<T, G, KL>), dim3(p.C, p.runs), dim3(kStatsThreads), 0, st,
                        static_cast<const T*>(feats), static_cast<const T*>(text), Tf, N, d, p.frames_per_run, do_pair,
-                       part, p.C);
+                       sim_mode, part, p.C);
 }
 
 template <typename T>
 static bool dispatch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
-                           float* part, hipStream_t st) {
+                           int sim_mode, float* part, hipStream_t st) {
 #define METOK_STATS_CASE(g, kl) \
-    if (p.G == g && p.KL == kl) { launch_stats<T, g, kl>(feats, text, Tf, N, d, p, do_pair, part, st); return true; }
+    if (p.G == g && p.KL == kl) { launch_stats<T, g, kl>(feats, text, Tf, N, d, p, do_pair, sim_mode, part, st); return true; }
     METOK_STATS_CASE(16, 1) METOK_STATS_CASE(16, 2) METOK_STATS_CASE(16, 4) METOK_STATS_CASE(16, 8)
     METOK_STATS_CASE(64, 1) METOK_STATS_CASE(64, 2) METOK_STATS_CASE(64, 4) METOK_STATS_CASE(64, 8) METOK_STATS_CASE(64, 16)
 #undef METOK_STATS_CASE
@@ -453,10 +490,15 @@ static int check_feats(const void* feats, int dtype, int T, int N, int d, StatsP
 
 using namespace metok;
 
+// workspace: [chunk partials of V] [norm2 T] [pair T] [token-mean vectors T*d fp32] [chunk partials of the means]
+static size_t mean_bytes(int T, int d) { return round_up(static_cast<size_t>(T) * d * sizeof(float), 256); }
+
 extern "C" size_t metok_segment_events_workspace_bytes(int T, int N, int d, int dtype) {
-    StatsPlan p;
+    StatsPlan p, pm;
     if (T < 1 || N < 1 || d < 1 || !plan_stats(T, N, d, dtype, &p)) return 0;
-    return stats_part_bytes(T, p) + 2 * round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    size_t total = stats_part_bytes(T, p) + 2 * round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    if (plan_stats(T, 1, d, METOK_F32, &pm)) total += mean_bytes(T, d) + stats_part_bytes(T, pm);     // pooled mode
+    return total;
 }
 
 extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, int d,
@@ -468,25 +510,58 @@ extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, 
     StatsPlan p;
     int rc = check_feats(feats, dtype, T, N, d, &p);
     if (rc) return rc;
-    if (sim_mode != METOK_SIM_FLAT) return fail(METOK_ERR_UNSUPPORTED, "sim_mode %d is not implemented", sim_mode);
+    if (sim_mode != METOK_SIM_FLAT && sim_mode != METOK_SIM_TOKEN_MEAN && sim_mode != METOK_SIM_POOLED)
+        return fail(METOK_ERR_INVALID_ARG, "unknown sim_mode %d", sim_mode);
     if (k < 1 || k > T) return fail(METOK_ERR_INVALID_ARG, "k must be in [1, T] (k=%d, T=%d)", k, T);
     if (!event_start || !frame_event || (T > 1 && !sim)) return fail(METOK_ERR_INVALID_ARG, "NULL output pointer");
     if (frame_score && !text_emb) return fail(METOK_ERR_INVALID_ARG, "frame_score requested without text_emb");
     if (text_emb && !aligned16(text_emb)) return fail(METOK_ERR_INVALID_ARG, "text_emb not 16-byte aligned");
+    StatsPlan pm;
+    const bool can_pool = plan_stats(T, 1, d, METOK_F32, &pm);
+    if (sim_mode == METOK_SIM_POOLED && !can_pool)
+        return fail(METOK_ERR_UNSUPPORTED, "pooled similarity needs d <= 4096, got %d", d);
     const size_t need = metok_segment_events_workspace_bytes(T, N, d, dtype);
     if (!workspace || workspace_bytes < need || !aligned16(workspace))
         return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-    float* part = static_cast<float*>(workspace);
-    float* norm2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats_part_bytes(T, p));
-    float* pair_dot = norm2 + round_up(static_cast<size_t>(T) * sizeof(float), 256) / sizeof(float);
+    char* ws = static_cast<char*>(workspace);
+    const size_t tslot = round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    float* part = reinterpret_cast<float*>(ws);
+    float* norm2 = reinterpret_cast<float*>(ws + stats_part_bytes(T, p));
+    float* pair_dot = reinterpret_cast<float*>(ws + stats_part_bytes(T, p) + tslot);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 1, part, st)
-                                        : dispatch_stats<float>(feats, text_emb, T, N, d, p, 1, part, st);
-    if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
-    if ((rc = check_launch("frame_stats"))) return rc;
-    hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, k, text_emb ? 1 : 0,
-                       sim, event_start, frame_event, frame_score, norm2, pair_dot);
+    if (sim_mode != METOK_SIM_POOLED) {
+        const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 1, sim_mode, part, st)
+                                            : dispatch_stats<float>(feats, text_emb, T, N, d, p, 1, sim_mode, part, st);
+        if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
+        if ((rc = check_launch("frame_stats"))) return rc;
+        hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, k, text_emb ? 1 : 0, sim_mode,
+                           sim, event_start, frame_event, frame_score, norm2, pair_dot);
+        return check_launch("segment");
+    }
+    // pooled reading: Eq. 5 (if wanted) from the tokens, Eq. 4 from the frames' mean tokens (a [T, 1, d] fp32 "video")
+    if (text_emb && frame_score) {
+        const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 0, METOK_SIM_FLAT, part, st)
+                                            : dispatch_stats<float>(feats, text_emb, T, N, d, p, 0, METOK_SIM_FLAT, part, st);
+        if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
+        if ((rc = check_launch("frame_stats"))) return rc;
+        hipLaunchKernelGGL(frame_score_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, frame_score);
+        if ((rc = check_launch("frame_score"))) return rc;
+    }
+    float* mean = reinterpret_cast<float*>(ws + stats_part_bytes(T, p) + 2 * tslot);
+    float* part_m = reinterpret_cast<float*>(ws + stats_part_bytes(T, p) + 2 * tslot + mean_bytes(T, d));
+    const int vec = dtype == METOK_BF16 ? 8 : 4;
+    dim3 mgrid(T, (d / vec + 63) / 64);
+    if (dtype == METOK_BF16)
+        hipLaunchKernelGGL(frame_mean_kernel<bf16_t>, mgrid, dim3(256), 0, st, static_cast<const bf16_t*>(feats), N, d, mean);
+    else
+        hipLaunchKernelGGL(frame_mean_kernel<float>, mgrid, dim3(256), 0, st, static_cast<const float*>(feats), N, d, mean);
+    if ((rc = check_launch("frame_mean"))) return rc;
+    if (!dispatch_stats<float>(mean, nullptr, T, 1, d, pm, 1, METOK_SIM_FLAT, part_m, st))
+        return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
+    if ((rc = check_launch("frame_stats (means)"))) return rc;
+    hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part_m, pm.C, T, 1, k, 0, METOK_SIM_FLAT,
+                       sim, event_start, frame_event, static_cast<float*>(nullptr), norm2, pair_dot);
     return check_launch("segment");
 }
 
@@ -557,8 +632,8 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
     const float* scores = frame_score_in;
     if (!scores) {
         // Eq. 5 pass on its own (no adjacent-frame products)
-        const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 0, part, st)
-                                            : dispatch_stats<float>(feats, text_emb, T, N, d, p, 0, part, st);
+        const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 0, METOK_SIM_FLAT, part, st)
+                                            : dispatch_stats<float>(feats, text_emb, T, N, d, p, 0, METOK_SIM_FLAT, part, st);
         if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
         if ((rc = check_launch("frame_stats"))) return rc;
         hipLaunchKernelGGL(frame_score_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, score_ws);

@@ -59,6 +59,7 @@ struct ScoreGeom {
     int rs;             // row splits per kv head
     int rpad;           // rb_total * 32
     int vis_start, n_vis;
+    int64_t key_begin, key_end;   // keys the softmax of pass 1 normalises over (before the causal mask)
     float scale_log2;   // log2(e) / sqrt(dh)
 };
 
@@ -104,7 +105,7 @@ __device__ __forceinline__ void load_kfrag(uint4 (&kf)[NCH], const T* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-// pass 1: blockIdx.x strides over the key tiles of the whole sequence, blockIdx.y = kvh * rs + split.
+// pass 1: blockIdx.x strides over the tiles of keys [key_begin, key_end), blockIdx.y = kvh * rs + split.
 // The product is taken as keys x queries, so a lane's 16 accumulators are 16 keys of ONE query row
 // (row = lane % 32) and the online softmax state is one (max, sum) pair per lane and row block.
 // pstat[((y * gridDim.x + x) * rbw * 32 + local_row) * 2 + {0, 1}]
@@ -126,20 +127,21 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
     for (int rb = 0; rb < kMaxRowBlocks; ++rb) { m[rb] = kNegBig; l[rb] = 0.f; }
 
     const int64_t text_start = g.S - g.Tq;
-    const int64_t n_tiles = (g.S + kTileKeys - 1) / kTileKeys;
+    const int64_t full_end = text_start < g.key_end ? text_start : g.key_end;
+    const int64_t n_tiles = (g.key_end - g.key_begin + kTileKeys - 1) / kTileKeys;
     const int h = lane >> 5;
     // the key fragments of the next tile are requested before the current tile is processed
     uint4 kf[NCH], kf_next[NCH];
     if (static_cast<int64_t>(blockIdx.x) < n_tiles)
-        load_kfrag<T, NCH>(kf_next, k_all, g, kvh, static_cast<int64_t>(blockIdx.x) * kTileKeys + wave * 32, lane);
+        load_kfrag<T, NCH>(kf_next, k_all, g, kvh, g.key_begin + static_cast<int64_t>(blockIdx.x) * kTileKeys + wave * 32, lane);
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int64_t j0 = tile * kTileKeys + wave * 32;
+        const int64_t j0 = g.key_begin + tile * kTileKeys + wave * 32;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) kf[c] = kf_next[c];
         if (tile + gridDim.x < n_tiles)
-            load_kfrag<T, NCH>(kf_next, k_all, g, kvh, (tile + gridDim.x) * kTileKeys + wave * 32, lane);
-        if (j0 >= g.S) continue;
-        const bool full = j0 + 32 <= text_start;            // every key of the tile is visible to every query
+            load_kfrag<T, NCH>(kf_next, k_all, g, kvh, g.key_begin + (tile + gridDim.x) * kTileKeys + wave * 32, lane);
+        if (j0 >= g.key_end) continue;
+        const bool full = j0 + 32 <= full_end;              // every key of the tile is visible to every query
         // the query fragments of row block rb + 1 are read from LDS while block rb is multiplied and reduced
         uint4 qf[2][NCH];
 #pragma unroll
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __res
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int64_t j = j0 + 8 * (i >> 2) + 4 * h + (i & 3);
-                        vis[i] = j <= pos;
+                        vis[i] = j <= pos && j < g.key_end;
                         s[i] = acc[i] * g.scale_log2;
                         if (vis[i]) tmax = fmaxf(tmax, s[i]);
                     }
@@ -595,7 +597,8 @@ static size_t select_bytes(int n_vis) {
 
 static int chunk_count(int dh, int dtype) { return dtype == METOK_BF16 ? dh / 16 : dh / 8; }     // 16-byte chunks per lane
 
-static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start, int n_vis, int dtype, ScoreGeom* g) {
+static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start, int n_vis, int dtype, int score_mode,
+                      ScoreGeom* g) {
     g->S = S; g->Hq = Hq; g->Hkv = Hkv; g->group = Hq / Hkv; g->dh = dh; g->Tq = Tq;
     g->R = g->group * Tq;
     g->rb_total = (g->R + 31) / 32;
@@ -607,6 +610,8 @@ static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start,
     g->rbw = (g->rb_total + g->rs - 1) / g->rs;
     g->rpad = g->rs * g->rbw * 32;
     g->vis_start = vis_start; g->n_vis = n_vis;
+    g->key_begin = score_mode == METOK_SCORE_VISUAL_ONLY ? vis_start : 0;
+    g->key_end = score_mode == METOK_SCORE_VISUAL_ONLY ? static_cast<int64_t>(vis_start) + n_vis : S;
     g->scale_log2 = static_cast<float>(1.4426950408889634 / sqrt(static_cast<double>(dh)));
     return true;
 }
@@ -628,10 +633,15 @@ static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
         nx = static_cast<int>((tiles + per - 1) / per);     // smallest grid with the same critical path
         return nx < 1 ? 1 : nx;
     };
-    p->nx1 = pick((g.S + kTileKeys - 1) / kTileKeys);
+    p->nx1 = pick((g.key_end - g.key_begin + kTileKeys - 1) / kTileKeys);
     p->nx2 = pick((static_cast<int64_t>(n_vis) + kTileKeys - 1) / kTileKeys);
+    // the partial statistics are sized for the widest pass-1 grid of either score mode, so one
+    // workspace query serves both
+    int64_t nx1_cap = slots / ny < 1 ? 1 : slots / ny;
+    const int64_t tiles_all = (g.S + kTileKeys - 1) / kTileKeys;
+    if (nx1_cap > tiles_all) nx1_cap = tiles_all;
     size_t off = 0;
-    p->off_pstat = off;   off += round_up(static_cast<size_t>(ny) * p->nx1 * g.rbw * 32 * 2 * sizeof(float), 256);
+    p->off_pstat = off;   off += round_up(static_cast<size_t>(ny) * nx1_cap * g.rbw * 32 * 2 * sizeof(float), 256);
     p->off_norm = off;    off += round_up(static_cast<size_t>(ny) * g.rbw * 32 * sizeof(float), 256);
     p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
     p->off_sel = off;     off += select_bytes(n_vis);
@@ -670,7 +680,7 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
     ScoreGeom g;
     ScorePlan p;
     if (Hq >= 1 && Hkv >= 1 && Tq >= 1 && Hq % Hkv == 0 && dh_supported(dh, dtype) &&
-        make_geom(S, Hq, Hkv, dh, Tq, 0, n_vis, dtype, &g)) {
+        make_geom(S, Hq, Hkv, dh, Tq, 0, n_vis, dtype, METOK_SCORE_CAUSAL_ALL, &g)) {
         plan_score(g, n_vis, &p);
         return p.total;
     }
@@ -679,7 +689,7 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
 
 extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
                                    const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
-                                   int vis_start, int n_vis,
+                                   int score_mode, int vis_start, int n_vis,
                                    const int32_t* token_seg, const int32_t* token_event,
                                    const float* event_weight, int n_events,
                                    int n_seg, const int32_t* seg_quota,
@@ -726,8 +736,10 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
         if (!dh_supported(dh, dtype)) return fail(METOK_ERR_UNSUPPORTED, "head dimension %d is not supported for this dtype", dh);
         if (Tq < 1 || static_cast<int64_t>(Tq) > S - vis_start - n_vis)
             return fail(METOK_ERR_INVALID_ARG, "Tq = %d must be in [1, number of text rows = %lld]", Tq, (long long)(S - vis_start - n_vis));
+        if (score_mode != METOK_SCORE_CAUSAL_ALL && score_mode != METOK_SCORE_VISUAL_ONLY)
+            return fail(METOK_ERR_INVALID_ARG, "unknown score_mode %d", score_mode);
         ScoreGeom g;
-        if (!make_geom(S, Hq, Hkv, dh, Tq, vis_start, n_vis, dtype, &g)) return fail(METOK_ERR_UNSUPPORTED, "head dimension too large");
+        if (!make_geom(S, Hq, Hkv, dh, Tq, vis_start, n_vis, dtype, score_mode, &g)) return fail(METOK_ERR_UNSUPPORTED, "head dimension too large");
         if (static_cast<int64_t>(g.Hkv) * g.rs > 65535) return fail(METOK_ERR_UNSUPPORTED, "too many query rows");
         ScorePlan p;
         plan_score(g, n_vis, &p);

@@ -15,18 +15,18 @@ def mk():
     return binding
 
 
-def run_segment(v: synth.Video, k: int, with_text=True):
+def run_segment(v: synth.Video, k: int, with_text=True, sim_mode=0):
     B = mk()
     feats = synth.to_torch(v.feats, v.dtype, "cuda")
     text = synth.to_torch(v.text_emb, v.dtype, "cuda") if with_text else None
-    out = B.metok_segment_events(feats, k, text)
+    out = B.metok_segment_events(feats, k, text, sim_mode=sim_mode)
     torch.cuda.synchronize()
     return feats, text, {n: t.cpu().numpy() for n, t in out.items()}
 
 
-def check_segment(v: synth.Video, k: int, got, with_text=True):
+def check_segment(v: synth.Video, k: int, got, with_text=True, sim_mode=0):
     rtol = RTOL[v.dtype]
-    S = O.adjacent_frame_cosine(v.feats)
+    S = O.adjacent_frame_cosine(v.feats, sim_mode)
     T = v.feats.shape[0]
     if T > 1:
         # cross-event similarities sit near 0: compare against the largest similarity
@@ -66,6 +66,33 @@ def test_segment_events_shapes(T, grid, d, dtype, k):
     v = synth.planted_video(1234 + T + d, T, grid, d, n_events, 1, T, 0.15, dtype)
     _, _, got = run_segment(v, k)
     check_segment(v, k, got)
+
+
+@pytest.mark.parametrize("sim_mode", [O.SIM_TOKEN_MEAN, O.SIM_POOLED], ids=["token_mean", "pooled"])
+@pytest.mark.parametrize("T,grid,d,dtype,k,with_text", [
+    (8, (4, 4), 64, "f32", 3, True),           # the tiny configuration
+    (5, (3, 5), 40, "bf16", 3, True),          # ragged: 15 tokens, 5 chunks
+    (9, (7, 7), 1152, "bf16", 4, False),       # whole-wave token groups, no text pass
+    (64, (24, 24), 1024, "bf16", 8, True),     # the encoder configuration
+    (40, (4, 6), 2048, "bf16", 7, True),       # several frame runs per workgroup column
+    (1, (4, 4), 64, "f32", 1, True),           # single frame: no similarities
+    (12, (3, 3), 4096, "f32", 12, False),      # widest fp32 rows, k = T
+])
+def test_segment_events_alternative_similarity_readings(sim_mode, T, grid, d, dtype, k, with_text):
+    v = synth.planted_video(4321 + T + d, T, grid, d, min(k, T), 1, T, 0.15, dtype)
+    _, _, got = run_segment(v, k, with_text=with_text, sim_mode=sim_mode)
+    check_segment(v, k, got, with_text=with_text, sim_mode=sim_mode)
+    assert ("frame_score" in got) == with_text
+
+
+def test_segment_similarity_modes_differ_and_bad_mode_is_rejected():
+    B = mk()
+    v = synth.planted_video(99, 10, (4, 4), 64, 3, 1, 10, 0.4, "f32")
+    sims = [run_segment(v, 3, sim_mode=m)[2]["sim"] for m in (0, 1, 2)]
+    # with token noise of this size the three readings give visibly different numbers
+    assert np.abs(sims[0] - sims[1]).max() > 1e-4 and np.abs(sims[0] - sims[2]).max() > 1e-4
+    with pytest.raises(B.MetokError):
+        run_segment(v, 3, sim_mode=3)
 
 
 def test_segment_without_text_and_equal_frames():

@@ -19,7 +19,7 @@ def i32(x):
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).cuda()
 
 
-def run_prune(layer: synth.PrefillLayer, token_seg, quotas, use_weight=True, orig_idx=None, Tq=None):
+def run_prune(layer: synth.PrefillLayer, token_seg, quotas, use_weight=True, orig_idx=None, Tq=None, score_mode=0):
     B = mk()
     dt = layer.dtype
     Tq = layer.n_text if Tq is None else Tq
@@ -29,16 +29,16 @@ def run_prune(layer: synth.PrefillLayer, token_seg, quotas, use_weight=True, ori
         q_text=synth.to_torch(q, dt, "cuda"), k_all=synth.to_torch(layer.k_all, dt, "cuda"),
         token_event=i32(layer.token_event),
         event_weight=torch.from_numpy(layer.event_weight).cuda() if use_weight else None,
-        orig_idx=None if orig_idx is None else i32(orig_idx))
+        orig_idx=None if orig_idx is None else i32(orig_idx), score_mode=score_mode)
     torch.cuda.synchronize()
     return {n: (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy() for n, t in out.items()}, q
 
 
-def check_prune(layer, token_seg, quotas, got, q, use_weight=True, orig_idx=None):
+def check_prune(layer, token_seg, quotas, got, q, use_weight=True, orig_idx=None, score_mode=0):
     rtol = RTOL[layer.dtype]
     w = layer.event_weight if use_weight else None
     # (1) scores
-    a = O.text_to_visual_attention(q, layer.k_all, layer.vis_start, layer.n_vis)
+    a = O.text_to_visual_attention(q, layer.k_all, layer.vis_start, layer.n_vis, score_mode)
     s_or = O.event_weighted_scores(a, layer.token_event, w)
     worst = assert_rel(got["scores"], s_or, rtol, "scores")
     # (2) the selection is exactly the per-class top-quota of the GPU's own scores (bit-exact, ties by index) ...
@@ -98,6 +98,25 @@ def test_prune_shapes_two_classes(dtype, dh, Hq, Hkv, n_text, vis_start):
     assert tuple(quotas) == O.retention_quotas(1, 0.55, 0.5, n_key, n_non)
     got, q = run_prune(layer, seg, quotas)
     check_prune(layer, seg, quotas, got, q)
+
+
+@pytest.mark.parametrize("dtype,dh,Hq,Hkv,n_text,vis_start,n_frames", [
+    ("bf16", 128, 28, 4, 64, 0, 37),     # LongVA head layout
+    ("bf16", 128, 8, 2, 19, 5, 37),      # system prefix: the key range starts off a tile boundary
+    ("bf16", 64, 6, 3, 33, 131, 37),     # prefix longer than one key tile
+    ("f32", 64, 4, 2, 21, 2, 37),
+    ("f32", 32, 2, 2, 16, 0, 1),         # 24 visual keys: a single ragged tile
+])
+def test_visual_only_softmax_reading(dtype, dh, Hq, Hkv, n_text, vis_start, n_frames):
+    layer = make_layer(700 + dh + Hq, n_frames, 24, min(5, n_frames), n_text, 48, Hq, Hkv, dh, dtype, vis_start=vis_start)
+    seg = (1 - layer.event_is_key[layer.token_event]).astype(np.int32)
+    n_key, n_non = int((seg == 0).sum()), int((seg == 1).sum())
+    quotas = mk().metok_retention_quotas(1, 0.55, 0.5, n_key, n_non)
+    got, q = run_prune(layer, seg, quotas, score_mode=O.SCORE_VISUAL_ONLY)
+    check_prune(layer, seg, quotas, got, q, score_mode=O.SCORE_VISUAL_ONLY)
+    # every (head, query) row spends its whole probability mass on the visual keys
+    a = got["scores"] / layer.event_weight[layer.token_event]
+    np.testing.assert_allclose(a.sum(), 1.0, rtol=1e-4)
 
 
 def test_hierarchy_is_nested_and_metadata_is_carried():

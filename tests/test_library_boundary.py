@@ -70,8 +70,9 @@ def test_workspace_queries(lib):
     seg = lib.metok_segment_events_workspace_bytes
     seg.restype = ctypes.c_size_t
     seg.argtypes = [ctypes.c_int] * 4
-    # LongVA-shaped stage 1: 36 token chunks x 3 partials x 4 bytes per frame, plus two per-frame arrays
-    assert seg(256, 576, 1024, 1) == 256 * 36 * 3 * 4 + 2 * 1024
+    # LongVA-shaped stage 1: 36 token chunks x 3 partials x 4 bytes per frame, two per-frame arrays,
+    # and for the pooled reading of Eq. 4 the fp32 frame means with their own (one chunk) partials
+    assert seg(256, 576, 1024, 1) == 256 * 36 * 3 * 4 + 2 * 1024 + 256 * 1024 * 4 + 256 * 3 * 4
     assert seg(256, 576, 1020, 1) == 0            # d not a multiple of 8
     assert seg(8, 16, 64, 0) > 0
     prune = lib.metok_prefill_prune_workspace_bytes
@@ -91,7 +92,7 @@ def test_argument_errors_before_any_launch(lib):
     assert seg(None, 1, 8, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 1 << 20, None) == -1
     assert seg(fake, 1, 8, 16, 64, None, 9, 0, fake, fake, fake, None, fake, 1 << 20, None) == -1       # k > T
     assert b"k must be" in lib.metok_last_error()
-    assert seg(fake, 1, 8, 16, 64, None, 2, 7, fake, fake, fake, None, fake, 1 << 20, None) == -2       # sim_mode
+    assert seg(fake, 1, 8, 16, 64, None, 2, 7, fake, fake, fake, None, fake, 1 << 20, None) == -1       # sim_mode
     assert seg(fake, 1, 8, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 16, None) == -3            # workspace
     assert seg(fake, 1, 8, 16, 64, None, 2, 0, fake, fake, fake, fake, fake, 1 << 20, None) == -1       # score without text
     assert seg(fake, 3, 8, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 1 << 20, None) == -1       # dtype
