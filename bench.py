@@ -51,7 +51,7 @@ def level_counts():
 
 
 class Workload:
-    def __init__(self, batch: int, device: str, n_streams: int = 4, seed: int = 250602850 + 4):
+    def __init__(self, batch: int, device: str, n_streams: int = 8, seed: int = 250602850 + 4):
         import torch
         from paper_2506_02850_amd import binding, synth
 
@@ -286,7 +286,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=8)
-    ap.add_argument("--streams", type=int, default=4, help="streams that share the per-video stage-1/2 work")
+    ap.add_argument("--streams", type=int, default=8, help="streams that share the per-video stage-1/2 work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "kv", "copy", "prune"], default="all",
                     help="kv / copy / prune: run only the KV compaction, the calibration copy or the stage-2 calls "

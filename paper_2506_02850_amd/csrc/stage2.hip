@@ -1,5 +1,6 @@
 // Stage 2 (Sec. 3.2.2): one level of hierarchical pruning.
 //
+//   pack_q_kernel        text queries -> MFMA fragment order, once per call
 //   row_stats_kernel     MFMA pass 1 over all keys: per (head, text query) running max and sum of the
 //                        causal softmax, in the log2 domain, per workgroup
 //   merge_stats_kernel   merges the per-workgroup (max, sum) pairs into one normaliser per row
@@ -12,19 +13,16 @@
 //                        and carried metadata
 //   gather_rows_kernel   compaction of the hidden states
 //
-// Both MFMA passes hold the keys of a 32-key tile in registers (loaded straight from global memory in
-// fragment layout) and read the query fragments of the workgroup's rows from LDS.  The contraction
-// index may be permuted freely as long as both operands agree; here lane half h = lane/32 owns the
-// contiguous half h of the head dimension, so every lane loads contiguous 16-byte chunks.
+// Both MFMA passes are query-stationary: a wave keeps the fragments of its own 32-row blocks of queries in
+// registers and the workgroup streams its range of keys through LDS.  The contraction index may be
+// permuted freely as long as both operands agree; here lane half h = lane/32 owns the contiguous half h
+// of the head dimension, so every fragment is a contiguous 16-byte chunk of a row.
 #include "common.h"
 
 namespace metok {
 
-constexpr int kScoreThreads = 256;
+constexpr int kScoreThreads = 512;
 constexpr int kScoreWaves = kScoreThreads / 64;
-constexpr int kTileKeys = kScoreWaves * 32;       // keys per workgroup tile
-constexpr int kMaxRowBlocks = 8;                  // 32-row blocks of queries per workgroup
-constexpr int kQFragBytes = 56 * 1024;            // LDS budget for the query fragments
 constexpr float kNegBig = -1.0e30f;
 constexpr float kPosBig = 1.0e30f;
 
@@ -35,12 +33,14 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 template <typename T> struct Mma;
 template <> struct Mma<bf16_t> {
     static constexpr int kChunkElems = 8;          // one 16-byte chunk feeds one 32x32x16 MFMA
+    static constexpr int kMfmaPerChunk = 1;
     static __device__ __forceinline__ f32x16_t mma(const uint4& a, const uint4& b, f32x16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
 };
 template <> struct Mma<float> {
     static constexpr int kChunkElems = 4;          // one chunk feeds four 32x32x2 MFMAs
+    static constexpr int kMfmaPerChunk = 4;
     static __device__ __forceinline__ f32x16_t mma(const uint4& a, const uint4& b, f32x16_t c) {
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
@@ -55,169 +55,296 @@ struct ScoreGeom {
     int Hq, Hkv, group, dh, Tq;
     int R;              // rows per kv head = group * Tq
     int rb_total;       // 32-row blocks per kv head
-    int rbw;            // row blocks per workgroup
+    int rbw;            // row blocks per workgroup (<= kScoreWaves * RBW)
     int rs;             // row splits per kv head
-    int rpad;           // rb_total * 32
     int vis_start, n_vis;
     int64_t key_begin, key_end;   // keys the softmax of pass 1 normalises over (before the causal mask)
     float scale_log2;   // log2(e) / sqrt(dh)
 };
 
-// Query fragments of row blocks [rb0, rb0 + nrb) of kv head g into LDS, fragment order:
-// qfrag[(rb * NCH + c) * 64 + lane] with lane = (row % 32) + 32 * half.
+// ---------------------------------------------------------------------------------------------
+// Both MFMA passes are query-stationary: wave w of a workgroup keeps the fragments of its own row
+// blocks (local blocks w, w + 8, ...) in registers for the whole kernel, and the workgroup streams its
+// contiguous range of keys through LDS, one stage of SUBS 32-key subtiles at a time, double buffered,
+// one barrier per stage.  A stage is stored in fragment order,
+//     kbuf[(sub * NCH + c) * 64 + lane],   lane = key % 32 + 32 * half,
+// so a wave reads the NCH fragments of a subtile with conflict-free 16-byte LDS reads and uses them
+// against every row block it owns.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int NCH, int SUBS>
+struct KeyStage {
+    static constexpr int kKeys = SUBS * 32;
+    static constexpr int kSlots = SUBS * NCH * 64;                 // 16-byte pieces per stage
+    static constexpr int kPerThread = (kSlots + kScoreThreads - 1) / kScoreThreads;
+
+    // piece id -> (key in stage, half, chunk); the key runs fastest so that the LDS writes of a wave are contiguous
+    static __device__ __forceinline__ void load(u32x4_t (&v)[kPerThread], const T* __restrict__ k_head, int64_t j0, int64_t S, int dh) {
+        constexpr int CE = Mma<T>::kChunkElems;
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            int id = threadIdx.x + u * kScoreThreads;
+            id = id < kSlots ? id : 0;                              // surplus threads repeat piece 0 and do not store it
+            const int jl = id % kKeys, p = id / kKeys;
+            int64_t j = j0 + jl;
+            j = j < S ? j : S - 1;                                  // stages may overhang the sequence; masked later
+            v[u] = *reinterpret_cast<const u32x4_t*>(k_head + static_cast<size_t>(j) * dh + (p / NCH) * (dh / 2) + (p % NCH) * CE);
+        }
+    }
+    static __device__ __forceinline__ void store(const u32x4_t (&v)[kPerThread], uint4* __restrict__ kbuf) {
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int id = threadIdx.x + u * kScoreThreads;
+            const int jl = id % kKeys, p = id / kKeys;
+            if (id < kSlots) reinterpret_cast<u32x4_t*>(kbuf)[((jl >> 5) * NCH + (p % NCH)) * 64 + (jl & 31) + 32 * (p / NCH)] = v[u];
+        }
+    }
+};
+
+// Query fragments in MFMA operand order, written once per call and read by every workgroup of both passes:
+//     qfrag[((kvh * rb_total + rb) * NCH + c) * 64 + lane],  row = 32 rb + lane % 32, half = lane / 32,
+// 16 bytes each (elements half * dh/2 + c * CE ... of the row); rows past the last query are zero.
+// A wave then fetches a fragment with one fully coalesced 1 KB load instead of 64 strided 16-byte pieces.
 template <typename T, int NCH>
-__device__ __forceinline__ void fill_qfrag(uint4* qfrag, const T* __restrict__ q_text, const ScoreGeom& g, int kvh, int rb0, int nrb) {
+__global__ __launch_bounds__(256) void pack_q_kernel(const T* __restrict__ q_text, const ScoreGeom g, uint4* __restrict__ qfrag) {
     constexpr int CE = Mma<T>::kChunkElems;
-    constexpr int kBatch = 8;                      // independent loads in flight per thread
-    const int total = nrb * NCH * 64;
-    for (int idx0 = threadIdx.x; idx0 < total; idx0 += kBatch * kScoreThreads) {
-        uint4 v[kBatch];
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int total = g.Hkv * g.rb_total * NCH * 64;
+    if (idx >= total) return;
+    const int lane = idx & 63, c = (idx >> 6) % NCH, rbg = idx / (64 * NCH);
+    const int kvh = rbg / g.rb_total, rb = rbg % g.rb_total;
+    const int r = rb * 32 + (lane & 31);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < g.R) {
+        const int hq = kvh * g.group + r / g.Tq, qi = r % g.Tq;
+        v = *reinterpret_cast<const uint4*>(q_text + (static_cast<size_t>(hq) * g.Tq + qi) * g.dh + (lane >> 5) * (g.dh / 2) + c * CE);
+    }
+    qfrag[idx] = v;
+}
+
+// q[i][c] belongs to the wave's local row block wave + 8 i.
+template <int NCH, int RBW>
+__device__ __forceinline__ void load_qfrag(uint4 (&q)[RBW][NCH], const uint4* __restrict__ qfrag, const ScoreGeom& g, int kvh,
+                                           int rb0, int nrb, int wave, int lane) {
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int idx = idx0 + u * kScoreThreads;
-            const int l = idx & 63;
-            const int c = (idx >> 6) % NCH;
-            const int rb = idx / (NCH * 64);
-            const int r = (rb0 + rb) * 32 + (l & 31);
-            v[u] = make_uint4(0, 0, 0, 0);
-            if (idx < total && r < g.R) {
-                const int hq = kvh * g.group + r / g.Tq, i = r % g.Tq;
-                const T* src = q_text + (static_cast<size_t>(hq) * g.Tq + i) * g.dh + (l >> 5) * (g.dh / 2) + c * CE;
-                v[u] = *reinterpret_cast<const uint4*>(src);
-            }
-        }
+    for (int i = 0; i < RBW; ++i) {
+        const int rbl = wave + kScoreWaves * i;
+        const bool ok = rbl < nrb;
+        const uint4* src = qfrag + (static_cast<size_t>(kvh) * g.rb_total + rb0 + (ok ? rbl : 0)) * NCH * 64 + lane;
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int idx = idx0 + u * kScoreThreads;
-            if (idx < total) qfrag[idx] = v[u];
-        }
+        for (int c = 0; c < NCH; ++c) q[i][c] = ok ? src[c * 64] : make_uint4(0, 0, 0, 0);
     }
 }
 
 template <typename T, int NCH>
-__device__ __forceinline__ void load_kfrag(uint4 (&kf)[NCH], const T* __restrict__ k_all, const ScoreGeom& g, int kvh, int64_t j0, int lane) {
-    constexpr int CE = Mma<T>::kChunkElems;
-    int64_t j = j0 + (lane & 31);
-    j = j < g.S ? j : g.S - 1;                     // tiles may overhang the sequence; masked later
-    const T* src = k_all + (static_cast<size_t>(kvh) * g.S + j) * g.dh + (lane >> 5) * (g.dh / 2);
+__device__ __forceinline__ f32x16_t mma_chain(const uint4 (&a)[NCH], const uint4 (&b)[NCH]) {
+    f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) kf[c] = *reinterpret_cast<const uint4*>(src + c * CE);
+    for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(a[c], b[c], acc);
+    return acc;
 }
 
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// Online softmax step of one lane over its 16 accumulators when every key is visible (log2 domain).
+__device__ __forceinline__ void softmax_step_full(const f32x16_t& acc, float scale_log2, float& m, float& l) {
+    const float t0 = max3(acc[0], acc[1], acc[2]), t1 = max3(acc[3], acc[4], acc[5]), t2 = max3(acc[6], acc[7], acc[8]),
+                t3 = max3(acc[9], acc[10], acc[11]), t4 = max3(acc[12], acc[13], acc[14]);
+    const float tmax = max3(max3(t0, t1, t2), max3(t3, t4, acc[15]), acc[15]);
+    const float m_new = fmaxf(m, tmax * scale_log2);        // the scale is positive: max commutes with it
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += fast_exp2(fmaf(acc[e], scale_log2, -m_new));
+    l = l * fast_exp2(m - m_new) + sum;
+    m = m_new;
+}
+
+// Asks the scheduler to place `valu` vector instructions after each of the next `mfmas` MFMAs of the
+// region, so that the softmax arithmetic of one block runs while the matrix pipe works on the next block.
+template <int MFMAS, int VALU>
+__device__ __forceinline__ void interleave_mfma_valu() {
+#pragma unroll
+    for (int z = 0; z < MFMAS; ++z) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);
+    }
+}
+
+// Online softmax step of one lane over its 16 accumulators with the causal / range mask applied:
+// accumulator e is key j0 + 8 (e / 4) + 4 h + e % 4 and is visible iff that offset is <= lim.
+__device__ __forceinline__ void softmax_step_masked(const f32x16_t& acc, float scale_log2, int h, int lim, float& m, float& l) {
+    bool vis[16];
+    float tmax = kNegBig;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        vis[e] = 8 * (e >> 2) + 4 * h + (e & 3) <= lim;
+        if (vis[e]) tmax = fmaxf(tmax, acc[e] * scale_log2);
+    }
+    const float m_new = fmaxf(m, tmax);
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += vis[e] ? fast_exp2(fmaf(acc[e], scale_log2, -m_new)) : 0.f;
+    l = l * fast_exp2(m - m_new) + sum;
+    m = m_new;
+}
+
+constexpr int kStageBuffers = 3;       // LDS stages: one in use, one ready (its first fragments are read early), one being filled
+
 // ---------------------------------------------------------------------------------------------
-// pass 1: blockIdx.x strides over the tiles of keys [key_begin, key_end), blockIdx.y = kvh * rs + split.
-// The product is taken as keys x queries, so a lane's 16 accumulators are 16 keys of ONE query row
-// (row = lane % 32) and the online softmax state is one (max, sum) pair per lane and row block.
+// pass 1: blockIdx.x owns sub_per_wg consecutive 32-key subtiles of [key_begin, key_end),
+// blockIdx.y = kvh * rs + split.  The product is taken as keys x queries, so a lane's 16 accumulators
+// are 16 keys of ONE query row (row = lane % 32) and the online softmax state is one (max, sum) pair
+// per lane and row block, in the log2 domain.
 // pstat[((y * gridDim.x + x) * rbw * 32 + local_row) * 2 + {0, 1}]
+//
+// Key stages are fetched two ahead (global -> registers at the top of a stage, registers -> LDS at its
+// end, one barrier per stage).  A wave that owns two row blocks runs the stages in which every key is
+// visible to every query as one software pipeline over the blocks (subtile, row block): the MFMA chain
+// of block b + 1 is interleaved with the softmax arithmetic of block b, also across the barrier, and the
+// fragments of the next stage's first subtile are read from LDS as soon as their registers are free.
+// Stages that need the mask, and waves with a single row block, take the plain path.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int NCH>
-__global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const T* __restrict__ q_text, const T* __restrict__ k_all,
-                                                                  const ScoreGeom g, float* __restrict__ pstat) {
-    extern __shared__ uint4 lds[];
-    uint4* qfrag = lds;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+template <typename T, int NCH, int RBW, int SUBS>
+__global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* __restrict__ qfrag, const T* __restrict__ k_all,
+                                                                  const ScoreGeom g, int sub_per_wg, float* __restrict__ pstat) {
+    using Stage = KeyStage<T, NCH, SUBS>;
+    extern __shared__ uint4 lds[];                      // kStageBuffers stages
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5;
     const int kvh = blockIdx.y / g.rs, split = blockIdx.y % g.rs;
     const int rb0 = split * g.rbw;
     const int nrb = min(g.rbw, g.rb_total - rb0);
-    fill_qfrag<T, NCH>(qfrag, q_text, g, kvh, rb0, nrb);
+    const int nrb_w = nrb > wave ? (nrb - wave + kScoreWaves - 1) / kScoreWaves : 0;     // row blocks of this wave
+    const T* k_head = k_all + static_cast<size_t>(kvh) * g.S * g.dh;
+
+    const int64_t kb = g.key_begin + static_cast<int64_t>(blockIdx.x) * sub_per_wg * 32;
+    const int64_t ke = min(g.key_end, kb + static_cast<int64_t>(sub_per_wg) * 32);
+    const int n_stage = static_cast<int>((ke - kb + Stage::kKeys - 1) / Stage::kKeys);
+    const int64_t text_start = g.S - g.Tq;
+    const int64_t full_end = text_start < ke ? text_start : ke;
+
+    u32x4_t kv[Stage::kPerThread];
+    Stage::load(kv, k_head, kb, g.S, g.dh);
+    Stage::store(kv, lds);
+    if (n_stage > 1) {
+        Stage::load(kv, k_head, kb + Stage::kKeys, g.S, g.dh);
+        Stage::store(kv, lds + Stage::kSlots);
+    }
+    uint4 q[RBW][NCH];
+    load_qfrag<NCH, RBW>(q, qfrag, g, kvh, rb0, nrb, wave, lane);
+    float m[RBW], l[RBW];
+#pragma unroll
+    for (int i = 0; i < RBW; ++i) { m[i] = kNegBig; l[i] = 0.f; }
+    // Every load issued so far has to land before the loop: with query loads still pending at its head the
+    // first use of a fragment inside would wait for ALL outstanding loads, the prefetch of later stages included.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    float m[kMaxRowBlocks], l[kMaxRowBlocks];
-#pragma unroll
-    for (int rb = 0; rb < kMaxRowBlocks; ++rb) { m[rb] = kNegBig; l[rb] = 0.f; }
+    auto stage_buf = [&](int s) { return lds + (s % kStageBuffers) * Stage::kSlots; };
+    auto prefetch = [&](int s) {          // global -> registers for stage s + 2
+        if (s + 2 < n_stage) Stage::load(kv, k_head, kb + static_cast<int64_t>(s + 2) * Stage::kKeys, g.S, g.dh);
+    };
+    auto publish = [&](int s) {           // registers -> LDS; that buffer was last read before the previous barrier
+        if (s + 2 < n_stage) Stage::store(kv, stage_buf(s + 2));
+        __syncthreads();
+    };
 
-    const int64_t text_start = g.S - g.Tq;
-    const int64_t full_end = text_start < g.key_end ? text_start : g.key_end;
-    const int64_t n_tiles = (g.key_end - g.key_begin + kTileKeys - 1) / kTileKeys;
-    const int h = lane >> 5;
-    // the key fragments of the next tile are requested before the current tile is processed
-    uint4 kf[NCH], kf_next[NCH];
-    if (static_cast<int64_t>(blockIdx.x) < n_tiles)
-        load_kfrag<T, NCH>(kf_next, k_all, g, kvh, g.key_begin + static_cast<int64_t>(blockIdx.x) * kTileKeys + wave * 32, lane);
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int64_t j0 = g.key_begin + tile * kTileKeys + wave * 32;
+    int s = 0;
+    if constexpr (RBW == 2 && SUBS == 2) {
+        // leading stages whose 64 keys are all visible to every query
+        int n_fast = 0;
+        if (nrb_w == 2) {
+            const int64_t f = (full_end - kb) / Stage::kKeys;
+            n_fast = f < 0 ? 0 : (f > n_stage ? n_stage : static_cast<int>(f));
+        }
+        if (n_fast > 0) {
+            constexpr int kMfmas = NCH * Mma<T>::kMfmaPerChunk;
+            constexpr int kValu = (64 + kMfmas - 1) / kMfmas;
+            uint4 kf0[NCH], kf1[NCH];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) kf[c] = kf_next[c];
-        if (tile + gridDim.x < n_tiles)
-            load_kfrag<T, NCH>(kf_next, k_all, g, kvh, g.key_begin + (tile + gridDim.x) * kTileKeys + wave * 32, lane);
-        if (j0 >= g.key_end) continue;
-        const bool full = j0 + 32 <= full_end;              // every key of the tile is visible to every query
-        // the query fragments of row block rb + 1 are read from LDS while block rb is multiplied and reduced
-        uint4 qf[2][NCH];
+            for (int c = 0; c < NCH; ++c) kf0[c] = lds[c * 64 + lane];
+            f32x16_t A = mma_chain<T, NCH>(kf0, q[0]), B;
+            for (; s < n_fast; ++s) {
+                const uint4* kbuf = stage_buf(s);
+                prefetch(s);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) qf[0][c] = qfrag[c * 64 + lane];
+                for (int c = 0; c < NCH; ++c) kf1[c] = kbuf[(NCH + c) * 64 + lane];
+                __builtin_amdgcn_sched_barrier(0);
+                B = mma_chain<T, NCH>(kf0, q[1]);
+                softmax_step_full(A, g.scale_log2, m[0], l[0]);
+                interleave_mfma_valu<kMfmas, kValu>();
+                __builtin_amdgcn_sched_barrier(0);
+                if (s + 1 < n_fast) {       // subtile 0 of the next stage: published before the previous barrier
+                    const uint4* knext = stage_buf(s + 1);
 #pragma unroll
-        for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
-            if (rb < nrb) {
-                f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                if (rb + 1 < nrb) {
-                    const uint4* qp = qfrag + ((rb + 1) * NCH) * 64 + lane;
-#pragma unroll
-                    for (int c = 0; c < NCH; ++c) qf[(rb + 1) & 1][c] = qp[c * 64];
+                    for (int c = 0; c < NCH; ++c) kf0[c] = knext[c * 64 + lane];
                 }
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(kf[c], qf[rb & 1][c], acc);
-                // accumulator i <-> key j0 + 8 (i / 4) + 4 h + i % 4, query row = lane % 32
-                float s[16];
-                float m_new, sum = 0.f;
-                if (full) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) s[i] = acc[i] * g.scale_log2;
-                    float tmax = s[0];
-#pragma unroll
-                    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
-                    m_new = fmaxf(m[rb], tmax);
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += fast_exp2(s[i] - m_new);
+                A = mma_chain<T, NCH>(kf1, q[0]);
+                softmax_step_full(B, g.scale_log2, m[1], l[1]);
+                interleave_mfma_valu<kMfmas, kValu>();
+                __builtin_amdgcn_sched_barrier(0);
+                B = mma_chain<T, NCH>(kf1, q[1]);
+                softmax_step_full(A, g.scale_log2, m[0], l[0]);
+                interleave_mfma_valu<kMfmas, kValu>();
+                __builtin_amdgcn_sched_barrier(0);
+                publish(s);
+                if (s + 1 < n_fast) {
+                    A = mma_chain<T, NCH>(kf0, q[0]);
+                    softmax_step_full(B, g.scale_log2, m[1], l[1]);
+                    interleave_mfma_valu<kMfmas, kValu>();
+                    __builtin_amdgcn_sched_barrier(0);
                 } else {
-                    const int r = (rb0 + rb) * 32 + (lane & 31);
-                    const int64_t pos = text_start + (r % g.Tq);       // causal: keys 0..pos
-                    bool vis[16];
-                    float tmax = kNegBig;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int64_t j = j0 + 8 * (i >> 2) + 4 * h + (i & 3);
-                        vis[i] = j <= pos && j < g.key_end;
-                        s[i] = acc[i] * g.scale_log2;
-                        if (vis[i]) tmax = fmaxf(tmax, s[i]);
-                    }
-                    m_new = fmaxf(m[rb], tmax);
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += vis[i] ? fast_exp2(s[i] - m_new) : 0.f;
+                    softmax_step_full(B, g.scale_log2, m[1], l[1]);
                 }
-                l[rb] = l[rb] * fast_exp2(m[rb] - m_new) + sum;
-                m[rb] = m_new;
             }
         }
     }
-    // merge the two lane halves (same row, different keys), then the four waves through LDS
-    __syncthreads();                                   // qfrag is dead from here on; reuse LDS
-    float* wstat = reinterpret_cast<float*>(lds);      // [wave][rbw * 32][2]
+    for (; s < n_stage; ++s) {
+        const uint4* kbuf = stage_buf(s);
+        const int64_t js = kb + static_cast<int64_t>(s) * Stage::kKeys;
+        prefetch(s);
 #pragma unroll
-    for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
-        if (rb < nrb) {
-            const float m2 = __shfl_xor(m[rb], 32, 64), l2 = __shfl_xor(l[rb], 32, 64);
-            const float mm = fmaxf(m[rb], m2);
-            const float ll = l[rb] * fast_exp2(m[rb] - mm) + l2 * fast_exp2(m2 - mm);
-            if (h == 0) {
-                wstat[((wave * g.rbw + rb) * 32 + lane) * 2 + 0] = mm;
-                wstat[((wave * g.rbw + rb) * 32 + lane) * 2 + 1] = ll;
+        for (int sub = 0; sub < SUBS; ++sub) {
+            const int64_t j0 = js + sub * 32;
+            if (j0 < ke && nrb_w > 0) {
+                uint4 kf[NCH];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) kf[c] = kbuf[(sub * NCH + c) * 64 + lane];
+                const bool full = j0 + 32 <= full_end;      // every key of the subtile is visible to every query
+#pragma unroll
+                for (int i = 0; i < RBW; ++i) {
+                    if (i < nrb_w) {
+                        const f32x16_t acc = mma_chain<T, NCH>(kf, q[i]);
+                        if (full) {
+                            softmax_step_full(acc, g.scale_log2, m[i], l[i]);
+                        } else {
+                            const int r = (rb0 + wave + kScoreWaves * i) * 32 + (lane & 31);
+                            int64_t last = text_start + (r % g.Tq);            // causal: keys 0..last, and below ke
+                            last = last < ke - 1 ? last : ke - 1;
+                            const int64_t d = last - j0;
+                            const int lim = d < 0 ? -1 : (d > 31 ? 31 : static_cast<int>(d));
+                            softmax_step_masked(acc, g.scale_log2, h, lim, m[i], l[i]);
+                        }
+                    }
+                }
             }
         }
+        publish(s);
     }
-    __syncthreads();
-    for (int lr = threadIdx.x; lr < nrb * 32; lr += kScoreThreads) {
-        float mm = kNegBig, ll = 0.f;
-        for (int w = 0; w < kScoreWaves; ++w) {
-            const float m2 = wstat[((w * g.rbw) * 32 + lr) * 2 + 0], l2 = wstat[((w * g.rbw) * 32 + lr) * 2 + 1];
-            const float mx = fmaxf(mm, m2);
-            ll = ll * fast_exp2(mm - mx) + l2 * fast_exp2(m2 - mx);
-            mm = mx;
+    // the two lane halves hold different keys of the same row
+    const int rows_per_y = g.rbw * 32;
+#pragma unroll
+    for (int i = 0; i < RBW; ++i) {
+        const int rbl = wave + kScoreWaves * i;
+        if (rbl < g.rbw) {
+            const float m2 = __shfl_xor(m[i], 32, 64), l2 = __shfl_xor(l[i], 32, 64);
+            const float mm = fmaxf(m[i], m2);
+            const float ll = l[i] * fast_exp2(m[i] - mm) + l2 * fast_exp2(m2 - mm);
+            if (h == 0) {
+                float* dst = pstat + ((static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * rows_per_y + rbl * 32 + lane) * 2;
+                dst[0] = mm;
+                dst[1] = ll;
+            }
         }
-        float* dst = pstat + ((static_cast<size_t>(blockIdx.y) * gridDim.x + blockIdx.x) * (g.rbw * 32) + lr) * 2;
-        dst[0] = mm;
-        dst[1] = ll;
     }
 }
 
@@ -255,67 +382,85 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(const float* __restric
 }
 
 // ---------------------------------------------------------------------------------------------
-// pass 2: queries x keys, a lane's 16 accumulators are 16 rows of ONE key (key = lane % 32).
+// pass 2: queries x keys, a lane's 16 accumulators are 16 rows of ONE key (key = lane % 32), and the
+// normalisers of those rows stay in registers.  blockIdx.x owns sub_per_wg consecutive subtiles of the
+// visual keys.  The eight per-wave partial column sums of a stage are added in wave order through LDS.
 // colpart[y * n_vis + j] = sum over the rows of workgroup-row y of the probability of visual key j.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int NCH>
-__global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const T* __restrict__ q_text, const T* __restrict__ k_all,
-                                                                 const ScoreGeom g, const float* __restrict__ norm,
+template <typename T, int NCH, int RBW, int SUBS>
+__global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const uint4* __restrict__ qfrag, const T* __restrict__ k_all,
+                                                                 const ScoreGeom g, int sub_per_wg, const float* __restrict__ norm,
                                                                  float* __restrict__ colpart) {
-    extern __shared__ uint4 lds[];
-    uint4* qfrag = lds;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    using Stage = KeyStage<T, NCH, SUBS>;
+    extern __shared__ uint4 lds[];                      // two stages, then the column partials [2][waves][stage keys]
+    float* cs = reinterpret_cast<float*>(lds + 2 * Stage::kSlots);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5;
     const int kvh = blockIdx.y / g.rs, split = blockIdx.y % g.rs;
     const int rb0 = split * g.rbw;
     const int nrb = min(g.rbw, g.rb_total - rb0);
-    float* cst = reinterpret_cast<float*>(qfrag + static_cast<size_t>(g.rbw) * NCH * 64);     // [rbw * 32] row normalisers
-    fill_qfrag<T, NCH>(qfrag, q_text, g, kvh, rb0, nrb);
-    for (int i = threadIdx.x; i < g.rbw * 32; i += kScoreThreads) cst[i] = norm[static_cast<size_t>(blockIdx.y) * g.rbw * 32 + i];
-    __syncthreads();
+    const int nrb_w = nrb > wave ? (nrb - wave + kScoreWaves - 1) / kScoreWaves : 0;
+    const T* k_head = k_all + static_cast<size_t>(kvh) * g.S * g.dh;
 
-    const int h = lane >> 5;
-    const int n_tiles = (g.n_vis + kTileKeys - 1) / kTileKeys;
-    uint4 kf[NCH], kf_next[NCH];
-    if (static_cast<int>(blockIdx.x) < n_tiles)
-        load_kfrag<T, NCH>(kf_next, k_all, g, kvh, static_cast<int64_t>(g.vis_start) + blockIdx.x * kTileKeys + wave * 32, lane);
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int jv = tile * kTileKeys + wave * 32;          // first visual key of this wave
+    const int vb = blockIdx.x * sub_per_wg * 32;                       // visual keys [vb, ve) of this workgroup
+    const int ve = min(g.n_vis, vb + sub_per_wg * 32);
+    const int n_stage = (ve - vb + Stage::kKeys - 1) / Stage::kKeys;
+    u32x4_t kv[Stage::kPerThread];
+    Stage::load(kv, k_head, static_cast<int64_t>(g.vis_start) + vb, g.S, g.dh);
+
+    uint4 q[RBW][NCH];
+    load_qfrag<NCH, RBW>(q, qfrag, g, kvh, rb0, nrb, wave, lane);
+    // accumulator e <-> query row 32 rbl + 8 (e / 4) + 4 h + e % 4
+    float cr[RBW][16];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) kf[c] = kf_next[c];
-        if (tile + static_cast<int>(gridDim.x) < n_tiles)
-            load_kfrag<T, NCH>(kf_next, k_all, g, kvh,
-                               static_cast<int64_t>(g.vis_start) + static_cast<int64_t>(tile + gridDim.x) * kTileKeys + wave * 32, lane);
-        if (jv >= g.n_vis) continue;
-        float colsum = 0.f;
-        uint4 qf[2][NCH];
+    for (int i = 0; i < RBW; ++i) {
+        const int rbl = wave + kScoreWaves * i;
+        const float* src = norm + static_cast<size_t>(blockIdx.y) * g.rbw * 32 + (rbl < g.rbw ? rbl : 0) * 32 + 4 * h;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) qf[0][c] = qfrag[c * 64 + lane];
+        for (int b4 = 0; b4 < 4; ++b4) {
+            const float4 c4 = *reinterpret_cast<const float4*>(src + 8 * b4);
+            cr[i][4 * b4 + 0] = c4.x; cr[i][4 * b4 + 1] = c4.y; cr[i][4 * b4 + 2] = c4.z; cr[i][4 * b4 + 3] = c4.w;
+        }
+    }
+    Stage::store(kv, lds);
+    __builtin_amdgcn_s_waitcnt(0);      // queries and normalisers have landed: see row_stats_kernel
+    __syncthreads();
+    for (int s = 0; s < n_stage; ++s) {
+        const uint4* kbuf = lds + (s & 1) * Stage::kSlots;
+        float* csb = cs + (s & 1) * (kScoreWaves * Stage::kKeys);
+        const int vs = vb + s * Stage::kKeys;
+        if (s + 1 < n_stage) Stage::load(kv, k_head, static_cast<int64_t>(g.vis_start) + vs + Stage::kKeys, g.S, g.dh);
 #pragma unroll
-        for (int rb = 0; rb < kMaxRowBlocks; ++rb) {
-            if (rb < nrb) {
-                f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                if (rb + 1 < nrb) {
-                    const uint4* qp = qfrag + ((rb + 1) * NCH) * 64 + lane;
+        for (int sub = 0; sub < SUBS; ++sub) {
+            if (vs + sub * 32 < ve) {
+                float colsum = 0.f;
+                if (nrb_w > 0) {
+                    uint4 kf[NCH];
 #pragma unroll
-                    for (int c = 0; c < NCH; ++c) qf[(rb + 1) & 1][c] = qp[c * 64];
+                    for (int c = 0; c < NCH; ++c) kf[c] = kbuf[(sub * NCH + c) * 64 + lane];
+#pragma unroll
+                    for (int i = 0; i < RBW; ++i) {
+                        if (i < nrb_w) {
+                            const f32x16_t acc = mma_chain<T, NCH>(q[i], kf);
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) colsum += fast_exp2(fmaf(acc[e], g.scale_log2, -cr[i][e]));
+                        }
+                    }
+                    colsum += __shfl_xor(colsum, 32, 64);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) acc = Mma<T>::mma(qf[rb & 1][c], kf[c], acc);
-                // accumulator i <-> query row rb * 32 + 8 (i / 4) + 4 h + i % 4, key = lane % 32
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const float4 c4 = *reinterpret_cast<const float4*>(cst + rb * 32 + 8 * b + 4 * h);
-                    colsum += fast_exp2(acc[4 * b + 0] * g.scale_log2 - c4.x);
-                    colsum += fast_exp2(acc[4 * b + 1] * g.scale_log2 - c4.y);
-                    colsum += fast_exp2(acc[4 * b + 2] * g.scale_log2 - c4.z);
-                    colsum += fast_exp2(acc[4 * b + 3] * g.scale_log2 - c4.w);
-                }
+                if (h == 0) csb[wave * Stage::kKeys + sub * 32 + lane] = colsum;
             }
         }
-        colsum += __shfl_xor(colsum, 32, 64);
-        const int j = jv + (lane & 31);
-        if (h == 0 && j < g.n_vis) colpart[static_cast<size_t>(blockIdx.y) * g.n_vis + j] = colsum;
+        if (s + 1 < n_stage) Stage::store(kv, lds + ((s + 1) & 1) * Stage::kSlots);
+        __syncthreads();
+        if (threadIdx.x < Stage::kKeys) {
+            const int j = vs + threadIdx.x;
+            if (j < ve) {
+                float a = 0.f;
+#pragma unroll
+                for (int w = 0; w < kScoreWaves; ++w) a += csb[w * Stage::kKeys + threadIdx.x];
+                colpart[static_cast<size_t>(blockIdx.y) * g.n_vis + j] = a;
+            }
+        }
     }
 }
 
@@ -597,18 +742,19 @@ static size_t select_bytes(int n_vis) {
 
 static int chunk_count(int dh, int dtype) { return dtype == METOK_BF16 ? dh / 16 : dh / 8; }     // 16-byte chunks per lane
 
+// Row blocks a wave keeps in registers: two while the fragments of a block take at most 32 VGPRs, else one.
+static int row_blocks_per_wave(int nch) { return nch <= 8 ? 2 : 1; }
+
 static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start, int n_vis, int dtype, int score_mode,
                       ScoreGeom* g) {
     g->S = S; g->Hq = Hq; g->Hkv = Hkv; g->group = Hq / Hkv; g->dh = dh; g->Tq = Tq;
     g->R = g->group * Tq;
     g->rb_total = (g->R + 31) / 32;
     const int nch = chunk_count(dh, dtype);
-    int cap = kQFragBytes / (nch * 1024);
-    if (cap > kMaxRowBlocks) cap = kMaxRowBlocks;
-    if (cap < 1) return false;
+    if (nch > 16) return false;
+    const int cap = kScoreWaves * row_blocks_per_wave(nch);
     g->rs = (g->rb_total + cap - 1) / cap;
     g->rbw = (g->rb_total + g->rs - 1) / g->rs;
-    g->rpad = g->rs * g->rbw * 32;
     g->vis_start = vis_start; g->n_vis = n_vis;
     g->key_begin = score_mode == METOK_SCORE_VISUAL_ONLY ? vis_start : 0;
     g->key_end = score_mode == METOK_SCORE_VISUAL_ONLY ? static_cast<int64_t>(vis_start) + n_vis : S;
@@ -617,30 +763,33 @@ static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start,
 }
 
 struct ScorePlan {
-    int nx1, nx2;                   // workgroups along the key tiles in pass 1 / pass 2
-    size_t off_pstat, off_norm, off_colpart, off_sel, total;
+    int nx1, nx2;                   // workgroups along the keys in pass 1 / pass 2
+    int per1, per2;                 // 32-key subtiles per workgroup
+    size_t off_qfrag, off_pstat, off_norm, off_colpart, off_sel, total;
 };
 
-static void plan_score(const ScoreGeom& g, int n_vis, ScorePlan* p) {
-    const int slots = 512;          // two workgroups per CU on 256 CUs
+constexpr int kScoreSlots = 256;    // one 512-thread workgroup per CU
+
+static void plan_score(const ScoreGeom& g, int n_vis, int nch, ScorePlan* p) {
     const int ny = g.Hkv * g.rs;
-    auto pick = [&](int64_t tiles) {
-        int nx = slots / ny;
+    const int nx0 = kScoreSlots / ny < 1 ? 1 : kScoreSlots / ny;
+    auto pick = [&](int64_t subtiles, int* per) {
+        int64_t nx = nx0 < subtiles ? nx0 : subtiles;
         if (nx < 1) nx = 1;
-        if (nx > tiles) nx = static_cast<int>(tiles);
-        if (nx < 1) nx = 1;
-        const int64_t per = (tiles + nx - 1) / nx;          // tiles per workgroup
-        nx = static_cast<int>((tiles + per - 1) / per);     // smallest grid with the same critical path
-        return nx < 1 ? 1 : nx;
+        *per = static_cast<int>((subtiles + nx - 1) / nx);
+        if (*per < 1) *per = 1;
+        nx = (subtiles + *per - 1) / *per;                  // smallest grid with the same critical path
+        return static_cast<int>(nx < 1 ? 1 : nx);
     };
-    p->nx1 = pick((g.key_end - g.key_begin + kTileKeys - 1) / kTileKeys);
-    p->nx2 = pick((static_cast<int64_t>(n_vis) + kTileKeys - 1) / kTileKeys);
+    p->nx1 = pick((g.key_end - g.key_begin + 31) / 32, &p->per1);
+    p->nx2 = pick((static_cast<int64_t>(n_vis) + 31) / 32, &p->per2);
     // the partial statistics are sized for the widest pass-1 grid of either score mode, so one
     // workspace query serves both
-    int64_t nx1_cap = slots / ny < 1 ? 1 : slots / ny;
-    const int64_t tiles_all = (g.S + kTileKeys - 1) / kTileKeys;
-    if (nx1_cap > tiles_all) nx1_cap = tiles_all;
+    int64_t nx1_cap = nx0;
+    const int64_t sub_all = (g.S + 31) / 32;
+    if (nx1_cap > sub_all) nx1_cap = sub_all;
     size_t off = 0;
+    p->off_qfrag = off;   off += static_cast<size_t>(g.Hkv) * g.rb_total * nch * 1024;
     p->off_pstat = off;   off += round_up(static_cast<size_t>(ny) * nx1_cap * g.rbw * 32 * 2 * sizeof(float), 256);
     p->off_norm = off;    off += round_up(static_cast<size_t>(ny) * g.rbw * 32 * sizeof(float), 256);
     p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
@@ -655,20 +804,24 @@ static bool dh_supported(int dh, int dtype) {
 
 template <typename T, int NCH>
 static void launch_scores(const void* q, const void* k, const ScoreGeom& g, const ScorePlan& p, char* ws, hipStream_t st) {
-    const size_t qbytes = static_cast<size_t>(g.rbw) * NCH * 1024;
-    const size_t lds1 = qbytes > static_cast<size_t>(kScoreWaves) * g.rbw * 32 * 2 * sizeof(float) ? qbytes
-                                                                                                    : static_cast<size_t>(kScoreWaves) * g.rbw * 32 * 2 * sizeof(float);
-    const size_t lds2 = qbytes + static_cast<size_t>(g.rbw) * 32 * sizeof(float);
+    constexpr int RBW = NCH <= 8 ? 2 : 1;
+    constexpr int SUBS = NCH <= 8 ? 2 : 1;
+    using Stage = KeyStage<T, NCH, SUBS>;
+    const size_t lds1 = kStageBuffers * static_cast<size_t>(Stage::kSlots) * sizeof(uint4);
+    const size_t lds2 = 2 * static_cast<size_t>(Stage::kSlots) * sizeof(uint4) + 2 * static_cast<size_t>(kScoreWaves) * Stage::kKeys * sizeof(float);
     const int ny = g.Hkv * g.rs;
+    uint4* qfrag = reinterpret_cast<uint4*>(ws + p.off_qfrag);
     float* pstat = reinterpret_cast<float*>(ws + p.off_pstat);
     float* norm = reinterpret_cast<float*>(ws + p.off_norm);
     float* colpart = reinterpret_cast<float*>(ws + p.off_colpart);
-    hipLaunchKernelGGL((row_stats_kernel<T, NCH>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
-                       static_cast<const T*>(q), static_cast<const T*>(k), g, pstat);
+    const int qslots = g.Hkv * g.rb_total * NCH * 64;
+    hipLaunchKernelGGL((pack_q_kernel<T, NCH>), dim3((qslots + 255) / 256), dim3(256), 0, st, static_cast<const T*>(q), g, qfrag);
+    hipLaunchKernelGGL((row_stats_kernel<T, NCH, RBW, SUBS>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
+                       qfrag, static_cast<const T*>(k), g, p.per1, pstat);
     const int total_rows = ny * g.rbw * 32;
     hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 15) / 16), dim3(256), 0, st, pstat, g, p.nx1, norm);
-    hipLaunchKernelGGL((col_sums_kernel<T, NCH>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
-                       static_cast<const T*>(q), static_cast<const T*>(k), g, norm, colpart);
+    hipLaunchKernelGGL((col_sums_kernel<T, NCH, RBW, SUBS>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
+                       qfrag, static_cast<const T*>(k), g, p.per2, norm, colpart);
 }
 
 }  // namespace metok
@@ -681,7 +834,7 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
     ScorePlan p;
     if (Hq >= 1 && Hkv >= 1 && Tq >= 1 && Hq % Hkv == 0 && dh_supported(dh, dtype) &&
         make_geom(S, Hq, Hkv, dh, Tq, 0, n_vis, dtype, METOK_SCORE_CAUSAL_ALL, &g)) {
-        plan_score(g, n_vis, &p);
+        plan_score(g, n_vis, chunk_count(dh, dtype), &p);
         return p.total;
     }
     return select_bytes(n_vis);      // selection scratch only (scores supplied by the caller)
@@ -742,7 +895,7 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
         if (!make_geom(S, Hq, Hkv, dh, Tq, vis_start, n_vis, dtype, score_mode, &g)) return fail(METOK_ERR_UNSUPPORTED, "head dimension too large");
         if (static_cast<int64_t>(g.Hkv) * g.rs > 65535) return fail(METOK_ERR_UNSUPPORTED, "too many query rows");
         ScorePlan p;
-        plan_score(g, n_vis, &p);
+        plan_score(g, n_vis, chunk_count(dh, dtype), &p);
         if (!workspace || workspace_bytes < p.total || !aligned16(workspace))
             return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", p.total, workspace_bytes);
         const int nch = chunk_count(dh, dtype);
