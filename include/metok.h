@@ -154,6 +154,35 @@ METOK_API int metok_retention_quotas(int level, double r, double alpha, int64_t 
                            int32_t quota_out[2]);
 
 /*
+ * Closed-form bookkeeping of the three stages (host arithmetic only, no tensors): how many tokens
+ * each stage leaves and how many (token, layer) pairs the prefill computes and the cache holds.
+ *
+ *   event_len, event_is_key  host, [k]: frames per event and its key flag (Sec. 3.2.1).
+ *   grid_h, grid_w, alpha, beta, s1, s2, pool_edge  as in metok_compress_encoder_tokens: an event of
+ *                n frames has ceil(beta n) key frames; strides s1 / s2 (key / non-key frames), divided
+ *                by alpha and rounded up in non-key events; a frame pooled with stride s leaves
+ *                side(grid_h, s) * side(grid_w, s) tokens.
+ *   r, layers_h  Eq. 6-7: from layer layers_h[i-1] on (0-based, ascending) the level-i quotas of
+ *                metok_retention_quotas apply to the key / non-key counts that entered the LLM.
+ *   n_layers, n_text  LLM depth (<= METOK_MAX_LAYERS) and text rows.
+ * Multiply a (token, layer) count by 2 * Hkv * dh * sizeof(dtype) for cache bytes.
+ */
+typedef struct metok_account_t {
+    int64_t tokens_encoder;           /* frames * grid_h * grid_w */
+    int64_t tokens_llm;               /* visual tokens after stage 1 = tokens_key + tokens_non */
+    int64_t tokens_key, tokens_non;   /* of key / non-key events */
+    int64_t level_tokens[4];          /* visual tokens alive at pruning level 0..3 */
+    int64_t prefill_token_layers;     /* sum over layers of (visual tokens alive + n_text) */
+    int64_t kv_token_layers_full;     /* cache without stages 2 and 3 */
+    int64_t kv_token_layers_stage2;   /* every layer caches what it processed */
+    int64_t kv_token_layers_stage3;   /* Sec. 3.3: layers >= layers_h[0] keep the text rows only */
+} metok_account_t;
+
+METOK_API int metok_account(const int32_t* event_len, const uint8_t* event_is_key, int k, int grid_h, int grid_w,
+                  double alpha, double beta, int s1, int s2, int pool_edge, double r,
+                  const int32_t layers_h[3], int n_layers, int64_t n_text, metok_account_t* out);
+
+/*
  * The sequence is X = [prefix; X_vis; X_text] (Eq. 3): vis_start prefix rows, n_vis visual rows,
  * then S - vis_start - n_vis text rows.
  *

@@ -341,6 +341,43 @@ def kv_token_layers(n_layers: int, l1: int, n_vis: int, n_text: int) -> int:
     return l1 * (n_vis + n_text) + (n_layers - l1) * n_text
 
 
+def account(event_len: Sequence[int], event_is_key: Sequence[int], grid: Tuple[int, int], alpha: float, beta: float,
+            s1: int, s2: int, pool_edge: int, r: float, L_H: Sequence[int], n_layers: int, n_text: int) -> dict:
+    """Token and cache bookkeeping of the three stages in closed form (no tensors).
+
+    Stage 1 (Sec. 3.2.1): event j of length n has ceil(beta n) key frames; a frame pooled with stride s
+    leaves side(gh, s) * side(gw, s) tokens.  Stage 2 (Eq. 6-7): from layer l_i on, the key / non-key
+    populations shrink to the level-i quotas of the counts that entered the LLM.  Stage 3 (Sec. 3.3):
+    layers below l_1 cache everything they saw, the others the text rows only.
+    Counts are tokens or (token, layer) pairs; multiply the latter by the bytes of one token in one layer.
+    """
+    gh, gw = grid
+    g = max(grid)
+
+    def rows(s: float) -> int:
+        s = min(max(int(ceil_ratio(s)), 1), g)
+        return pooled_side(gh, s, pool_edge) * pooled_side(gw, s, pool_edge)
+
+    key = non = 0
+    for n, is_key in zip(event_len, event_is_key):
+        n = int(n)
+        n_kf = min(n, ceil_ratio(beta * n))
+        if is_key:
+            key += n_kf * rows(s1) + (n - n_kf) * rows(s2)
+        else:
+            non += n_kf * rows(s1 / alpha) + (n - n_kf) * rows(s2 / alpha)
+    level_tokens = [key + non] + [sum(retention_quotas(i, r, alpha, key, non)) for i in (1, 2, 3)]
+    prefill = 0
+    for l in range(n_layers):
+        level = sum(1 for b in L_H if l >= b)
+        prefill += level_tokens[level] + n_text
+    return dict(tokens_encoder=int(sum(int(n) for n in event_len)) * gh * gw, tokens_llm=key + non, tokens_key=key,
+                tokens_non=non, level_tokens=level_tokens, prefill_token_layers=prefill,
+                kv_token_layers_full=n_layers * (key + non + n_text),
+                kv_token_layers_stage2=prefill,
+                kv_token_layers_stage3=kv_token_layers(n_layers, min(int(L_H[0]), n_layers), key + non, n_text))
+
+
 # ---------------------------------------------------------------------------
 # output rounding used when a merged feature is stored in bf16
 # ---------------------------------------------------------------------------

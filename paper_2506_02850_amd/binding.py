@@ -26,10 +26,17 @@ EXPORTS = [
     "metok_last_error", "metok_version",
     "metok_segment_events_workspace_bytes", "metok_segment_events",
     "metok_compress_encoder_tokens_workspace_bytes", "metok_compress_encoder_tokens",
-    "metok_retention_quotas",
+    "metok_retention_quotas", "metok_account",
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
     "metok_kv_compact", "metok_calib_copy",
 ]
+
+
+class AccountStruct(ctypes.Structure):
+    _fields_ = [("tokens_encoder", ctypes.c_int64), ("tokens_llm", ctypes.c_int64), ("tokens_key", ctypes.c_int64),
+                ("tokens_non", ctypes.c_int64), ("level_tokens", ctypes.c_int64 * 4),
+                ("prefill_token_layers", ctypes.c_int64), ("kv_token_layers_full", ctypes.c_int64),
+                ("kv_token_layers_stage2", ctypes.c_int64), ("kv_token_layers_stage3", ctypes.c_int64)]
 
 
 class MetokError(RuntimeError):
@@ -59,6 +66,9 @@ def _load() -> ctypes.CDLL:
                                                   i32, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_retention_quotas.restype = i32
     lib.metok_retention_quotas.argtypes = [i32, dbl, dbl, i64, i64, c.POINTER(c.c_int32)]
+    lib.metok_account.restype = i32
+    lib.metok_account.argtypes = [c.POINTER(c.c_int32), c.POINTER(c.c_uint8), i32, i32, i32, dbl, dbl, i32, i32, i32, dbl,
+                                  c.POINTER(c.c_int32), i32, i64, c.POINTER(AccountStruct)]
     lib.metok_prefill_prune_workspace_bytes.restype = sz
     lib.metok_prefill_prune_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, i32]
     lib.metok_prefill_prune.restype = i32
@@ -212,6 +222,24 @@ def metok_retention_quotas(level: int, r: float, alpha: float, n_key_orig: int, 
     out = (ctypes.c_int32 * 2)()
     _check(_lib.metok_retention_quotas(level, float(r), float(alpha), int(n_key_orig), int(n_non_orig), out))
     return [int(out[0]), int(out[1])]
+
+
+def metok_account(event_len: Sequence[int], event_is_key: Sequence[int], grid_h: int, grid_w: int, alpha: float,
+                  beta: float, s1: int, s2: int, pool_edge: int, r: float, layers_h: Sequence[int], n_layers: int,
+                  n_text: int) -> Dict[str, object]:
+    """Host-only bookkeeping: token counts after each stage and (token, layer) counts of prefill and cache."""
+    k = len(event_len)
+    if len(event_is_key) != k or len(layers_h) != 3:
+        raise ValueError("event_is_key must match event_len and layers_h must have three entries")
+    lens = (ctypes.c_int32 * k)(*[int(x) for x in event_len])
+    keys = (ctypes.c_uint8 * k)(*[1 if x else 0 for x in event_is_key])
+    lh = (ctypes.c_int32 * 3)(*[int(x) for x in layers_h])
+    out = AccountStruct()
+    _check(_lib.metok_account(lens, keys, k, int(grid_h), int(grid_w), float(alpha), float(beta), int(s1), int(s2),
+                              int(pool_edge), float(r), lh, int(n_layers), int(n_text), ctypes.byref(out)))
+    res = {name: getattr(out, name) for name, _ in AccountStruct._fields_}
+    res["level_tokens"] = [int(x) for x in out.level_tokens]
+    return res
 
 
 def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_seg: torch.Tensor,

@@ -62,6 +62,61 @@ extern "C" int metok_retention_quotas(int level, double r, double alpha, int64_t
     return METOK_OK;
 }
 
+extern "C" int metok_account(const int32_t* event_len, const uint8_t* event_is_key, int k, int grid_h, int grid_w,
+                             double alpha, double beta, int s1, int s2, int pool_edge, double r,
+                             const int32_t layers_h[3], int n_layers, int64_t n_text, metok_account_t* out) {
+    clear_error();
+    if (!event_len || !event_is_key || !layers_h || !out) return fail(METOK_ERR_INVALID_ARG, "NULL pointer argument");
+    if (k < 1 || grid_h < 1 || grid_w < 1 || s1 < 1 || s2 < 1 || n_text < 0)
+        return fail(METOK_ERR_INVALID_ARG, "k, grid and strides must be positive, n_text non-negative");
+    if (!(alpha > 0.0 && alpha <= 1.0) || !(beta > 0.0 && beta <= 1.0) || !(r > 0.0 && r <= 1.0))
+        return fail(METOK_ERR_INVALID_ARG, "need 0 < alpha, beta, r <= 1");
+    if (pool_edge != METOK_POOL_FLOOR && pool_edge != METOK_POOL_CEIL) return fail(METOK_ERR_INVALID_ARG, "unknown pool_edge %d", pool_edge);
+    if (n_layers < 1 || n_layers > METOK_MAX_LAYERS) return fail(METOK_ERR_INVALID_ARG, "n_layers must be in [1, %d]", METOK_MAX_LAYERS);
+    if (!(0 <= layers_h[0] && layers_h[0] <= layers_h[1] && layers_h[1] <= layers_h[2]))
+        return fail(METOK_ERR_INVALID_ARG, "pruning layers must be non-negative and ascending");
+    const int gmax = grid_h > grid_w ? grid_h : grid_w;
+    auto rows = [&](double s) -> int64_t {
+        int v = ceil_ratio(s);
+        v = v < 1 ? 1 : (v > gmax ? gmax : v);
+        auto side = [&](int g) { return pool_edge == METOK_POOL_FLOOR ? (g / v > 1 ? g / v : 1) : (g + v - 1) / v; };
+        return static_cast<int64_t>(side(grid_h)) * side(grid_w);
+    };
+    const int64_t rows_kk = rows(s1), rows_kn = rows(s2), rows_nk = rows(s1 / alpha), rows_nn = rows(s2 / alpha);
+    int64_t key = 0, non = 0, frames = 0;
+    for (int j = 0; j < k; ++j) {
+        const int64_t n = event_len[j];
+        if (n < 1) return fail(METOK_ERR_INVALID_ARG, "event_len[%d] = %lld: every event has at least one frame", j, (long long)n);
+        int64_t n_kf = ceil_ratio(beta * static_cast<double>(n));       // key frames of the event (Sec. 3.2.1)
+        n_kf = n_kf > n ? n : n_kf;
+        if (event_is_key[j]) key += n_kf * rows_kk + (n - n_kf) * rows_kn;
+        else                 non += n_kf * rows_nk + (n - n_kf) * rows_nn;
+        frames += n;
+    }
+    if (key > INT32_MAX || non > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "token counts must fit int32");
+    out->tokens_encoder = frames * grid_h * grid_w;
+    out->tokens_llm = key + non;
+    out->tokens_key = key;
+    out->tokens_non = non;
+    const double key_ratio[4] = {1.0, r, r * r, 0.0}, non_ratio[4] = {1.0, alpha * r, 0.0, 0.0};      // Eq. 6-7
+    for (int level = 0; level < 4; ++level) {
+        int64_t qk = ceil_ratio(key_ratio[level] * static_cast<double>(key)), qn = ceil_ratio(non_ratio[level] * static_cast<double>(non));
+        out->level_tokens[level] = (qk > key ? key : qk) + (qn > non ? non : qn);
+    }
+    int64_t prefill = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int level = (l >= layers_h[0]) + (l >= layers_h[1]) + (l >= layers_h[2]);
+        prefill += out->level_tokens[level] + n_text;
+    }
+    out->prefill_token_layers = prefill;
+    out->kv_token_layers_full = static_cast<int64_t>(n_layers) * (key + non + n_text);
+    out->kv_token_layers_stage2 = prefill;
+    // Sec. 3.3: layers below l_1 keep every row, the others the text rows only
+    const int64_t l1 = layers_h[0] < n_layers ? layers_h[0] : n_layers;
+    out->kv_token_layers_stage3 = l1 * (key + non + n_text) + (n_layers - l1) * n_text;
+    return METOK_OK;
+}
+
 extern "C" int metok_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
     clear_error();
     if (!dst || !src || (bytes & 15u) || !aligned16(dst) || !aligned16(src))

@@ -33,7 +33,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert len(names) == 11 and len(set(names)) == len(names)
+    assert len(names) == 12 and len(set(names)) == len(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
     from paper_2506_02850_amd import binding
@@ -64,6 +64,30 @@ def test_retention_quotas_match_eq_6_7(lib):
     assert f(4, 0.55, 0.5, 1, 1, out) == -1 and b"level" in lib.metok_last_error()
     assert f(1, 0.0, 0.5, 1, 1, out) == -1
     assert f(1, 0.5, 1.5, 1, 1, out) == -1
+
+
+def test_account_matches_the_oracle_on_random_settings():
+    """metok_account is host arithmetic: it runs without a GPU and must agree with the oracle field by field."""
+    from paper_2506_02850_amd import binding as B
+    rng = np.random.Generator(np.random.PCG64(5))
+    for _ in range(200):
+        k = int(rng.integers(1, 14))
+        lens = [int(x) for x in rng.integers(1, 30, size=k)]
+        keys = [int(x) for x in rng.integers(0, 2, size=k)]
+        gh, gw = int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        alpha, beta, r = (float(rng.choice([0.25, 0.3, 0.5, 0.55, 0.76, 1.0])) for _ in range(3))
+        s1, s2 = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        edge = int(rng.integers(0, 2))
+        L = int(rng.integers(1, 41))
+        lh = sorted(int(x) for x in rng.integers(0, L + 3, size=3))
+        n_text = int(rng.integers(0, 200))
+        got = B.metok_account(lens, keys, gh, gw, alpha, beta, s1, s2, edge, r, lh, L, n_text)
+        want = O.account(lens, keys, (gh, gw), alpha, beta, s1, s2, edge, r, lh, L, n_text)
+        assert got == want, (lens, keys, gh, gw, alpha, beta, s1, s2, edge, r, lh, L, n_text)
+    with pytest.raises(B.MetokError):
+        B.metok_account([3, 0], [1, 0], 4, 4, 0.5, 0.5, 2, 3, 0, 0.5, [1, 2, 3], 4, 5)        # empty event
+    with pytest.raises(B.MetokError):
+        B.metok_account([3], [1], 4, 4, 0.5, 0.5, 2, 3, 0, 0.5, [3, 2, 1], 4, 5)              # layers not ascending
 
 
 def test_workspace_queries(lib):

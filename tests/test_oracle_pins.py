@@ -548,3 +548,86 @@ def test_headline_percentages_rederive():
     # LongVA's base cache is 128 frames x 144 tokens plus a prompt: 24 x 24 CLIP patches pooled with stride 2
     tokens = g["t2_longva_kv_base_mb"] * 2 ** 20 / (g["impl_layers_7b"] * 4 * 128 * 2 * 2)
     assert 20 < tokens - g["frames_longva"] * O.pool_frame(np.zeros((576, 1)), (24, 24), 2).shape[0] < 150
+
+
+# ---------------------------------------------------------------------------
+# closed-form accountant
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,grid,alpha,beta,s1,s2,edge", [
+    (1, (24, 24), 0.5, 0.45, 2, 3, O.POOL_FLOOR),        # LongVA settings (Appendix, implementation details)
+    (2, (27, 27), 0.5, 0.4, 2, 3, O.POOL_FLOOR),         # LLaVA-OneVision settings: non-divisible grid
+    (3, (27, 27), 0.5, 0.4, 2, 3, O.POOL_CEIL),
+    (4, (5, 7), 0.3, 1.0, 1, 2, O.POOL_CEIL),
+    (5, (4, 4), 1.0, 0.5, 2, 2, O.POOL_FLOOR),
+])
+def test_account_stage1_counts_equal_the_constructive_path(seed, grid, alpha, beta, s1, s2, edge):
+    """The closed-form token counts against counting the rows that the stage-1 steps actually produce."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    k = int(rng.integers(1, 9))
+    lens = rng.integers(1, 8, size=k)
+    event_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    f = rng.standard_normal(int(event_start[-1]))
+    _, ev_key, fr_key = O.key_events_and_frames(f, event_start, alpha, beta)
+    strides = O.pooling_strides(event_start, ev_key, fr_key, alpha, s1, s2, grid)
+    rows_key = rows_non = 0
+    for j in range(k):
+        for i in range(int(event_start[j]), int(event_start[j + 1])):
+            n = O.pool_frame(np.zeros((grid[0] * grid[1], 1)), grid, int(strides[i]), edge).shape[0]
+            if ev_key[j]:
+                rows_key += n
+            else:
+                rows_non += n
+    acc = O.account(lens, ev_key, grid, alpha, beta, s1, s2, edge, 0.6, [1, 2, 3], 4, 7)
+    assert (acc["tokens_key"], acc["tokens_non"], acc["tokens_llm"]) == (rows_key, rows_non, rows_key + rows_non)
+    assert acc["tokens_encoder"] == int(event_start[-1]) * grid[0] * grid[1]
+
+
+def test_account_layers_equal_a_simulated_prefill_and_cache():
+    """Token-layer counts against walking the layers with explicit token sets (nested top-k per class)."""
+    rng = np.random.Generator(np.random.PCG64(11))
+    lens, ev_key = [3, 2, 4, 1], [1, 0, 1, 0]
+    grid, alpha, beta, s1, s2, r = (6, 6), 0.5, 0.5, 1, 2, 0.55
+    L, L_H, n_text = 9, [2, 4, 7], 5
+    acc = O.account(lens, ev_key, grid, alpha, beta, s1, s2, O.POOL_FLOOR, r, L_H, L, n_text)
+    n_key, n_non = acc["tokens_key"], acc["tokens_non"]
+    seg = np.concatenate([np.zeros(n_key, dtype=np.int32), np.ones(n_non, dtype=np.int32)])
+    alive = np.arange(n_key + n_non)
+    processed = cached3 = 0
+    level = 0
+    for l in range(L):
+        while level < 3 and l >= L_H[level]:
+            level += 1
+            quota = O.retention_quotas(level, r, alpha, n_key, n_non)
+            kept = O.segmented_topk(rng.standard_normal(alive.size), seg[alive], quota)
+            alive = alive[kept]
+        assert alive.size == acc["level_tokens"][level]
+        processed += alive.size + n_text
+    sched = O.kv_text_only_schedule(L, L_H[0], n_key + n_non, n_text)
+    cached3 = sum(n_key + n_non + n_text if s is None else len(s) for s in sched)
+    assert acc["prefill_token_layers"] == acc["kv_token_layers_stage2"] == processed
+    assert acc["kv_token_layers_stage3"] == cached3
+    assert acc["kv_token_layers_full"] == L * (n_key + n_non + n_text)
+    assert acc["level_tokens"][3] == 0
+
+
+def test_account_against_the_papers_cache_sizes():
+    """Table 3 (LLaVA-OneVision-7B, 32 frames): uniform stride 2 on 27 x 27 gives the base cache; Table 2
+    (LongVA-7B, 128 frames): with the appendix settings and 13 equally long events the stage-3 cache lands
+    near the printed 65.0 MB (the paper does not print its event lengths, so this is a bracket, not an equality)."""
+    g = golden()
+    L, L_H = int(g["impl_layers_7b"]), [int(g["impl_l1"]), int(g["impl_l2"]), int(g["impl_l3"])]
+    mib = 4 * 128 * 2 * 2 / 2 ** 20                                 # MiB per (token, layer)
+    base = O.account([int(g["frames_ov"])], [1], (27, 27), 1.0, 1.0, 2, 2, O.POOL_FLOOR, g["impl_ov_r"], L_H, L, 63)
+    assert abs(base["kv_token_layers_full"] * mib - g["t3_kv_base_mb"]) < 0.1
+    k = int(g["impl_longva_k"])
+    frames = int(g["frames_longva"])
+    lens = [frames // k + (1 if j < frames % k else 0) for j in range(k)]
+    n_key_ev = O.ceil_ratio(g["impl_alpha"] * k)
+    brackets = []
+    for key_first in (True, False):                                   # key events the long or the short ones
+        flags = [1 if (j < n_key_ev) == key_first else 0 for j in range(k)]
+        a = O.account(lens, flags, (24, 24), g["impl_alpha"], g["impl_longva_beta"], int(g["impl_s1"]), int(g["impl_s2"]),
+                      O.POOL_FLOOR, g["impl_longva_r"], L_H, L, 78)
+        brackets.append(a["kv_token_layers_stage3"] * mib)
+        assert a["kv_token_layers_full"] * mib < g["t2_longva_kv_base_mb"]       # stage 1 alone already shrinks the cache
+    assert 0.7 * g["t2_longva_kv_metok_mb"] < min(brackets) <= max(brackets) < 1.3 * g["t2_longva_kv_metok_mb"]
