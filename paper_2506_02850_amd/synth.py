@@ -288,6 +288,16 @@ ENCODER_256 = Shapes("encoder_256", T=256, grid=(24, 24), d=1024, dtype="bf16", 
                      len_hi=40, sigma=0.2, tokens_per_frame=144, extra={"config": 6})
 
 
+# Second workload shapes (Appendix "Implementation Details"): SigLIP frames of 27 x 27 patches (stride-2
+# pooling does not divide the grid) in front of a 28-layer GQA decoder and of a 40-layer MHA decoder.
+OV_7B = Shapes("llava_onevision_7b", T=32, grid=(27, 27), d=1152, dtype="bf16", n_events=5, len_lo=3, len_hi=12,
+               sigma=0.2, n_text=64, D=3584, Hq=28, Hkv=4, dh=128, n_layers=28, L_H=(3, 10, 19),
+               extra={"config": 7, "alpha": 0.5, "beta": 0.4, "r": 0.76, "s1": 2, "s2": 3})
+VILA_13B = Shapes("vila_1_5_13b", T=64, grid=(27, 27), d=1152, dtype="bf16", n_events=3, len_lo=8, len_hi=40,
+                  sigma=0.2, n_text=64, D=5120, Hq=40, Hkv=40, dh=128, n_layers=40, L_H=(13, 24, 34),
+                  extra={"config": 8, "alpha": 0.5, "beta": 0.4, "r": 0.65, "s1": 2, "s2": 3})
+
+
 def video_for(shapes: Shapes, seed_offset: int = 0) -> Video:
     return planted_video(shapes.seed + 1000 * seed_offset, shapes.T, shapes.grid, shapes.d,
                          shapes.n_events, shapes.len_lo, shapes.len_hi, shapes.sigma, shapes.dtype)

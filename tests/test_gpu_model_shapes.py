@@ -1,0 +1,121 @@
+"""GPU parity of the whole path at the shapes and hyper-parameters of the paper's other two model families
+(Appendix "Implementation Details"): LLaVA-OneVision-7B (32 SigLIP frames of 27 x 27 patches, k = 5,
+beta = 0.4, r = 0.76, 28 layers, L_H = [3, 10, 19]) and VILA-1.5-13B (64 frames, k = 3, r = 0.65, 40 layers
+of 40 full attention heads, L_H = [13, 24, 34]).  The three stages are chained on the metadata they hand to
+each other, every stage is compared with the oracle, and the closed-form accountant must agree with what
+the kernels produced.  Inputs are synthetic stand-ins of these shapes, not the models' activations."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import metok_oracle as O
+from paper_2506_02850_amd import synth
+from tests.parity import RTOL, assert_rel, bf16_ulp
+from tests.test_gpu_full_size import i32, mk, prune_level
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("sh", [synth.OV_7B, synth.VILA_13B], ids=lambda s: s.name)
+def test_three_stages_at_model_shape(sh):
+    B = mk()
+    alpha, beta, r = sh.extra["alpha"], sh.extra["beta"], sh.extra["r"]
+    s1, s2 = int(sh.extra["s1"]), int(sh.extra["s2"])
+    gh, gw = sh.grid
+    k = sh.n_events
+
+    # ---- stage 1: segmentation, adaptive pooling on a grid the strides do not divide -------------------
+    v = synth.video_for(sh)
+    feats = synth.to_torch(v.feats, "bf16", "cuda")
+    text = synth.to_torch(v.text_emb, "bf16", "cuda")
+    seg = B.metok_segment_events(feats, k, text)
+    cmp = B.metok_compress_encoder_tokens(feats, gh, gw, seg["event_start"], alpha, beta, s1, s2,
+                                          frame_score=seg["frame_score"])
+    torch.cuda.synchronize()
+    S = O.adjacent_frame_cosine(v.feats)
+    assert_rel(seg["sim"].cpu().numpy(), S, RTOL["bf16"], "sim", scale=np.abs(S).max())
+    es, fe = O.event_boundaries(S, k)
+    np.testing.assert_array_equal(seg["event_start"].cpu().numpy(), es)
+    np.testing.assert_array_equal(es, v.event_start)
+    f_gpu = seg["frame_score"].cpu().numpy()
+    assert_rel(f_gpu, O.frame_text_score(v.feats, v.text_emb), RTOL["bf16"], "frame_score")
+    ref = O.compress_encoder_tokens(v.feats, sh.grid, None, es, alpha, beta, s1, s2, frame_score=f_gpu.astype(np.float64))
+    np.testing.assert_array_equal(cmp["event_is_key"].cpu().numpy(), ref["event_is_key"])
+    np.testing.assert_array_equal(cmp["frame_is_key"].cpu().numpy(), ref["frame_is_key"])
+    np.testing.assert_array_equal(cmp["frame_stride"].cpu().numpy(), ref["frame_stride"])
+    np.testing.assert_array_equal(cmp["frame_offsets"].cpu().numpy(), ref["frame_offsets"])
+    M = int(ref["frame_offsets"][-1])
+    assert set(np.unique(ref["frame_stride"]).tolist()) <= {2, 3, 4, 6}
+    np.testing.assert_array_equal(cmp["token_event"][:M].cpu().numpy(), ref["token_event"])
+    got = cmp["out_tokens"][:M].float().cpu().numpy().astype(np.float64)
+    want = ref["tokens"]
+    assert (np.abs(got - want) <= bf16_ulp(want)).all(), "pooled token further than one bf16 ulp from the oracle"
+    assert float((got != O.round_to_bf16(want)).mean()) < 1e-3
+
+    ev_key = ref["event_is_key"]
+    acc = B.metok_account(np.diff(es), ev_key, gh, gw, alpha, beta, s1, s2, B.POOL_FLOOR, r, sh.L_H, sh.n_layers, sh.n_text)
+    assert acc == O.account(np.diff(es), ev_key, sh.grid, alpha, beta, s1, s2, O.POOL_FLOOR, r, sh.L_H, sh.n_layers, sh.n_text)
+    assert acc["tokens_llm"] == M and acc["tokens_encoder"] == sh.T * gh * gw
+
+    # ---- stage 2: three pruning levels with the Eq. 6-7 quotas, fresh activations per level ------------
+    token_event = ref["token_event"].astype(np.int32)
+    token_seg = (1 - ev_key[token_event]).astype(np.int32)                  # class 0 = key events
+    n_key, n_non = int((token_seg == 0).sum()), int((token_seg == 1).sum())
+    assert (n_key, n_non) == (acc["tokens_key"], acc["tokens_non"])
+    orig = None
+    level_sets = []
+    weight = None
+    for level in (1, 2, 3):
+        layer = synth.prefill_layer(sh.seed + 10 + level, token_event, k, sh.n_text, sh.D, sh.Hq, sh.Hkv, sh.dh, "bf16")
+        weight = layer.event_weight.copy() if weight is None else weight
+        layer.event_weight[:] = weight
+        quotas = B.metok_retention_quotas(level, r, alpha, n_key, n_non)
+        assert tuple(quotas) == O.retention_quotas(level, r, alpha, n_key, n_non)
+        assert sum(quotas) == acc["level_tokens"][level]
+        if sum(quotas) == 0:
+            kept = np.zeros(0, dtype=np.int64)
+            out = B.metok_prefill_prune(synth.to_torch(layer.hidden, "bf16", "cuda"), 0, layer.n_vis, i32(token_seg), quotas,
+                                        q_text=synth.to_torch(layer.q_text, "bf16", "cuda"),
+                                        k_all=synth.to_torch(layer.k_all, "bf16", "cuda"), token_event=i32(token_event))
+            torch.cuda.synchronize()
+            assert out["kept_idx"].numel() == 0 and out["hidden_out"].shape[0] == sh.n_text
+            np.testing.assert_array_equal(out["hidden_out"].float().cpu().numpy(), layer.hidden[layer.n_vis:])
+        else:
+            kept = prune_level(B, layer, token_seg, quotas, True, orig, sh.n_text)
+        orig = (np.arange(M) if orig is None else orig)[kept]
+        token_event, token_seg = token_event[kept], token_seg[kept]
+        level_sets.append(orig.astype(np.int32))
+    assert level_sets[2].size == 0 and np.all(np.diff(level_sets[1]) > 0)
+    assert set(level_sets[1].tolist()) <= set(level_sets[0].tolist())
+
+    # ---- stage 3: every layer's cache compacted to what stage 2 kept at its level, then the Sec. 3.3 rule ----
+    n_text, Sc = sh.n_text, M + sh.n_text
+    rows = torch.arange(Sc, device="cuda")
+
+    def fresh_cache():
+        ks, vs = [], []
+        for l in range(sh.n_layers):
+            for which, dst in ((0, ks), (1, vs)):
+                t = torch.empty((1, sh.Hkv, Sc, sh.dh), dtype=torch.int16, device="cuda")
+                for h in range(sh.Hkv):
+                    t[0, h] = synth.kv_pattern(l, which, 0, h, rows, sh.dh, xp=torch)
+                dst.append(t.view(torch.bfloat16))
+        return ks, vs
+
+    rng = np.random.default_rng(3)
+    for name, sched in (("stage-2 sets", synth.kv_layer_schedule(sh.n_layers, sh.L_H, M, n_text, level_sets)),
+                        ("text only", O.kv_text_only_schedule(sh.n_layers, sh.L_H[0], M, n_text))):
+        k_layers, v_layers = fresh_cache()
+        idx_dev = [None if ix is None else i32(np.asarray(ix)[None, :]) for ix in sched]
+        new_len = B.metok_kv_compact(k_layers, v_layers, idx_dev)
+        torch.cuda.synchronize()
+        want_len = [Sc if ix is None else len(ix) for ix in sched]
+        np.testing.assert_array_equal(new_len.cpu().numpy(), want_len)
+        assert sum(want_len) == (acc["kv_token_layers_stage2"] if name == "stage-2 sets" else acc["kv_token_layers_stage3"])
+        for _ in range(12):
+            l = int(rng.integers(0, sh.n_layers)); which = int(rng.integers(0, 2)); h = int(rng.integers(0, sh.Hkv))
+            old = synth.kv_pattern(l, which, 0, h, np.arange(Sc), sh.dh)
+            want_slab = O.kv_compact(old, None if sched[l] is None else np.asarray(sched[l]))
+            got_slab = (v_layers if which else k_layers)[l][0, h, :want_slab.shape[0]].view(torch.int16).cpu().numpy()
+            assert np.array_equal(got_slab, want_slab), f"{name}: layer {l} which {which} head {h}"
+        del k_layers, v_layers
