@@ -3,8 +3,9 @@
 
 One step = one pass of stages 1-3 over a batch of synthetic, LongVA-7B-shaped 256-frame videos:
 
-  stage 1  per video: metok_segment_events + metok_compress_encoder_tokens on CLIP-ViT-L/336-shaped
-           features [256, 576, 1024] bf16 (16 planted events, uniform stride 2 -> 256 x 144 tokens);
+  stage 1  per video: metok_segment_compress (segmentation, scores, plan and pooling in one call) on
+           CLIP-ViT-L/336-shaped features [256, 576, 1024] bf16 (16 planted events, uniform stride 2 ->
+           256 x 144 tokens, so the pooled tokens come out of the statistics pass: one read of the features);
   stage 2  per video: three metok_prefill_prune levels (keep 0.5 / 0.5 / 0.5 of the current count) on
            hidden states [36864 + 128, 3584] bf16 with 28 query / 4 kv heads of 128 and the last 64 text
            positions as queries; event ids come from stage 1, retained indices are carried level to level;
@@ -131,6 +132,7 @@ class Workload:
                              frame_stride=torch.empty(FRAMES, dtype=i32, device=device),
                              event_score=torch.empty(N_EVENTS, dtype=f32, device=device),
                              frame_score=torch.empty(FRAMES, dtype=f32, device=device)) for _ in range(batch)]
+        self.s1_out = [{**self.seg_out[b], **self.cmp_out[b]} for b in range(batch)]
         self.prune_out = [[dict(scores=torch.empty(n, dtype=f32, device=device),
                                 kept_idx=torch.empty(c, dtype=i32, device=device),
                                 token_seg_out=torch.empty(c, dtype=i32, device=device),
@@ -141,8 +143,8 @@ class Workload:
 
     # algorithmic bytes (what the method itself must move)
     def stage1_bytes(self):
-        read = FRAMES * GRID * GRID * D_VIS * 2
-        return self.batch * (2 * read + N_VIS * D_VIS * 2)
+        read = FRAMES * GRID * GRID * D_VIS * 2          # uniform stride 2: statistics and pooling share one pass over V
+        return self.batch * (read + N_VIS * D_VIS * 2)
 
     def gather_bytes(self):
         return self.batch * sum(2 * (c + N_TEXT) * D_HID * 2 for c in self.counts)
@@ -163,11 +165,9 @@ class Workload:
         return self.batch * sum(2 * 2 * HQ * TQ * (n + N_TEXT) * DH for n in self.n_in)      # two passes
 
     def stage1(self, b):
-        B = self.B
         ws = self.ws1[b % self.n_streams]
-        seg = B.metok_segment_events(self.feats[b], N_EVENTS, self.text[b], workspace=ws, out=self.seg_out[b])
-        return B.metok_compress_encoder_tokens(self.feats[b], GRID, GRID, seg["event_start"], 1.0, 1.0, 2, 2,
-                                               frame_score=seg["frame_score"], workspace=ws, out=self.cmp_out[b])
+        return self.B.metok_segment_compress(self.feats[b], GRID, GRID, N_EVENTS, self.text[b], 1.0, 1.0, 2, 2,
+                                             workspace=ws, out=self.s1_out[b])
 
     def stage2(self, b, token_event):
         B = self.B

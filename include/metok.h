@@ -142,6 +142,29 @@ METOK_API int metok_compress_encoder_tokens(const void* feats, int dtype, int T,
                                   int32_t* frame_stride, float* event_score, float* frame_score_out,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Stage 1 in one call (Sec. 3.2.1, Algorithm 1: Eq. 4 segmentation, Eq. 5 scores, key events / key
+ * frames, adaptive pooling).  Arguments and outputs are those of metok_segment_events followed by
+ * metok_compress_encoder_tokens (N = grid_h * grid_w; text_emb and frame_score are required), and so are
+ * the results.  When every frame is pooled with stride 2 whatever the segmentation decides -- s1, s2,
+ * ceil(s1 / alpha), ceil(s2 / alpha) all equal 2 after clamping, e.g. the uniform setting s1 = s2 = 2,
+ * alpha = 1 -- and both grid sides are even, sim_mode is METOK_SIM_FLAT and d spans at most 256 16-byte
+ * chunks, the frame statistics and the pooled tokens are produced in ONE pass over the frame features;
+ * in every other case the two calls run back to back on the same stream (two passes).
+ * Workspace: metok_segment_compress_workspace_bytes.  Errors as for the two calls.
+ */
+METOK_API size_t metok_segment_compress_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype);
+
+METOK_API int metok_segment_compress(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                           const void* text_emb, int k, int sim_mode,
+                           double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
+                           float* sim, int32_t* event_start, int32_t* frame_event,
+                           void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                           int32_t* frame_offsets, int32_t* token_event,
+                           uint8_t* event_is_key, uint8_t* frame_is_key,
+                           int32_t* frame_stride, float* event_score, float* frame_score,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Stage 2 -- one level of hierarchical token pruning (Sec. 3.2.2).
  *

@@ -26,6 +26,7 @@ EXPORTS = [
     "metok_last_error", "metok_version",
     "metok_segment_events_workspace_bytes", "metok_segment_events",
     "metok_compress_encoder_tokens_workspace_bytes", "metok_compress_encoder_tokens",
+    "metok_segment_compress_workspace_bytes", "metok_segment_compress",
     "metok_retention_quotas", "metok_account",
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
     "metok_kv_compact", "metok_calib_copy",
@@ -64,6 +65,11 @@ def _load() -> ctypes.CDLL:
     lib.metok_compress_encoder_tokens.restype = i32
     lib.metok_compress_encoder_tokens.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i32, dbl, dbl, i32, i32,
                                                   i32, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.metok_segment_compress_workspace_bytes.restype = sz
+    lib.metok_segment_compress_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.metok_segment_compress.restype = i32
+    lib.metok_segment_compress.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, dbl, dbl, i32, i32, i32, i32,
+                                           vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_retention_quotas.restype = i32
     lib.metok_retention_quotas.argtypes = [i32, dbl, dbl, i64, i64, c.POINTER(c.c_int32)]
     lib.metok_account.restype = i32
@@ -216,6 +222,48 @@ def metok_compress_encoder_tokens(feats: torch.Tensor, grid_h: int, grid_w: int,
     return dict(out_tokens=out_tokens, frame_offsets=frame_offsets, token_event=token_event,
                 event_is_key=event_is_key, frame_is_key=frame_is_key, frame_stride=frame_stride,
                 event_score=event_score, frame_score=frame_score_out)
+
+
+def metok_segment_compress(feats: torch.Tensor, grid_h: int, grid_w: int, k: int, text_emb: torch.Tensor,
+                           alpha: float, beta: float, s1: int, s2: int,
+                           sim_mode: int = SIM_FLAT, event_reduce: int = EVENT_MEAN, pool_edge: int = POOL_FLOOR,
+                           out_dtype: Optional[torch.dtype] = None, workspace: Optional[torch.Tensor] = None,
+                           out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """Stage 1 in one call: the outputs of metok_segment_events and metok_compress_encoder_tokens together
+    (one pass over feats when all frames are pooled with stride 2 on an even grid, else two)."""
+    T, N, d = feats.shape
+    if N != grid_h * grid_w:
+        raise ValueError("feats.shape[1] must equal grid_h * grid_w")
+    dt = _dtype_code(feats)
+    dev = feats.device
+    odt = out_dtype if out_dtype is not None else feats.dtype
+    cap = pooled_capacity(T, grid_h, grid_w, s1, s2, pool_edge)
+    out_tokens = out.get("out_tokens") if out is not None else None
+    if out_tokens is None:
+        out_tokens = torch.empty((cap, d), dtype=odt, device=dev)
+    need = _lib.metok_segment_compress_workspace_bytes(T, grid_h, grid_w, d, dt)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    sim = _out(out, "sim", max(T - 1, 0), torch.float32, dev)
+    event_start = _out(out, "event_start", k + 1, torch.int32, dev)
+    frame_event = _out(out, "frame_event", T, torch.int32, dev)
+    frame_offsets = _out(out, "frame_offsets", T + 1, torch.int32, dev)
+    token_event = _out(out, "token_event", out_tokens.shape[0], torch.int32, dev)
+    event_is_key = _out(out, "event_is_key", k, torch.uint8, dev)
+    frame_is_key = _out(out, "frame_is_key", T, torch.uint8, dev)
+    frame_stride = _out(out, "frame_stride", T, torch.int32, dev)
+    event_score = _out(out, "event_score", k, torch.float32, dev)
+    frame_score = _out(out, "frame_score", T, torch.float32, dev)
+    _check(_lib.metok_segment_compress(
+        _dev(feats, "feats"), dt, T, grid_h, grid_w, d, _dev(text_emb, "text_emb"), int(k), int(sim_mode),
+        float(alpha), float(beta), int(s1), int(s2), event_reduce, pool_edge,
+        _dev(sim, "sim"), _dev(event_start, "event_start"), _dev(frame_event, "frame_event"),
+        _dev(out_tokens, "out_tokens"), out_tokens.shape[0], _dtype_code(out_tokens),
+        _dev(frame_offsets, "frame_offsets"), _dev(token_event, "token_event"), _dev(event_is_key, "event_is_key"),
+        _dev(frame_is_key, "frame_is_key"), _dev(frame_stride, "frame_stride"), _dev(event_score, "event_score"),
+        _dev(frame_score, "frame_score"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    return dict(sim=sim, event_start=event_start, frame_event=frame_event, out_tokens=out_tokens,
+                frame_offsets=frame_offsets, token_event=token_event, event_is_key=event_is_key,
+                frame_is_key=frame_is_key, frame_stride=frame_stride, event_score=event_score, frame_score=frame_score)
 
 
 def metok_retention_quotas(level: int, r: float, alpha: float, n_key_orig: int, n_non_orig: int) -> List[int]:

@@ -418,6 +418,139 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// frame_stats_pool2_kernel: the statistics of frame_stats_kernel (Eq. 4 over all entries, Eq. 5) and the
+// 2 x 2 mean pooling of every frame in ONE pass over V, for the case in which every frame is pooled with
+// stride 2 whatever the segmentation turns out to be (all four strides of the adaptive rule equal 2), on
+// a grid with even sides.  A wave owns one pooling window: lane j holds the 16-byte chunks j, j + 64, ...
+// (at most KL) of the window's four tokens, so the pooled chunk is a sum inside the lane (cells in the
+// order (y, x), (y, x+1), (y+1, x), (y+1, x+1), the order pool_kernel uses) and the per-token reductions
+// run over the whole wave.  Workgroup = 4 windows; blockIdx.y = run of frames, walked as in
+// frame_stats_kernel.  part[] has the same layout, with C = ceil(windows / 4) chunk partials per frame.
+// pooled[(t * windows + w) * d ...] receives window w of frame t.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int KL, typename TO>
+__global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
+    const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int grid_h, int grid_w, int d,
+    int frames_per_run, float* __restrict__ part, int C, TO* __restrict__ pooled) {
+    using E = Elem<T>;
+    __shared__ float red[2][kStatsWaves][3];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ow = grid_w / 2, n_win = (grid_h / 2) * ow, N = grid_h * grid_w;
+    const int w = blockIdx.x * kStatsWaves + wave;
+    const bool win_ok = w < n_win;
+    const int wy = win_ok ? w / ow : 0, wx = win_ok ? w % ow : 0;
+    const int nchunks = d / E::kVec;
+    const int t0 = blockIdx.y * frames_per_run;
+    const int t1 = min(T_frames, t0 + frames_per_run);
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    int tok[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) tok[c] = (2 * wy + (c >> 1)) * grid_w + 2 * wx + (c & 1);
+
+    uint4 txt[KL];
+    float tn2 = 0.f;
+    const bool do_text = text != nullptr;
+#pragma unroll
+    for (int k = 0; k < KL; ++k) {
+        const int ch = lane + 64 * k;
+        txt[k] = (do_text && ch < nchunks) ? reinterpret_cast<const uint4*>(text)[ch] : zero;
+        tn2 = E::dot(txt[k], txt[k], tn2);
+    }
+    const float tnorm = sqrtf(wave_sum(tn2));
+
+    auto load_rows = [&](int t, uint4 (&dst)[4][KL]) {
+        const uint4* frame = reinterpret_cast<const uint4*>(feats) + static_cast<size_t>(t) * N * nchunks;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint4* row = frame + static_cast<size_t>(tok[c]) * nchunks;
+#pragma unroll
+            for (int k = 0; k < KL; ++k) {
+                const int ch = lane + 64 * k;
+                dst[c][k] = (win_ok && ch < nchunks) ? load_stream(row + ch) : zero;
+            }
+        }
+    };
+
+    uint4 prv[4][KL], cur[4][KL], nxt[4][KL];
+    load_rows(t0, cur);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int k = 0; k < KL; ++k) { prv[c][k] = zero; nxt[c][k] = zero; }
+    const int t_last = t1 < T_frames ? t1 : t1 - 1;                   // last frame that is loaded (one past the run for the pair)
+    for (int t = t0; t <= t_last; ++t) {
+        if (t + 1 <= t_last) load_rows(t + 1, nxt);
+        const bool own = t < t1;
+        float p_sum = 0.f, cos_sum = 0.f, cd = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float p = 0.f, q = 0.f;
+#pragma unroll
+            for (int k = 0; k < KL; ++k) p = E::dot(cur[c][k], cur[c][k], p);
+            if (own && do_text) {
+#pragma unroll
+                for (int k = 0; k < KL; ++k) q = E::dot(cur[c][k], txt[k], q);
+            }
+            if (t > t0) {
+#pragma unroll
+                for (int k = 0; k < KL; ++k) cd = E::dot(prv[c][k], cur[c][k], cd);
+            }
+            p = wave_sum(p);
+            q = wave_sum(q);
+            const float den = sqrtf(p) * tnorm;
+            cos_sum += (own && do_text && win_ok && !(den < kZeroNorm)) ? q / den : 0.f;
+            p_sum += p;
+        }
+        cd = wave_sum(cd);
+        if (!own) p_sum = 0.f;
+        const int buf = (t - t0) & 1;
+        if (lane == 0) {
+            red[buf][wave][0] = p_sum;
+            red[buf][wave][1] = cd;
+            red[buf][wave][2] = cos_sum;
+        }
+        if (own && win_ok) {
+            TO* out_row = pooled + (static_cast<size_t>(t) * n_win + w) * d;
+#pragma unroll
+            for (int k = 0; k < KL; ++k) {
+                const int ch = lane + 64 * k;
+                if (ch < nchunks) {
+                    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) E::accumulate(cur[c][k], acc);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[i] = acc[i] / 4.f;
+                    Store<TO>::put(out_row, ch, E::kVec, acc);
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 3) {
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < kStatsWaves; ++i) sum += red[buf][i][threadIdx.x];
+            if (threadIdx.x == 1) {
+                if (t > t0) part[(static_cast<size_t>(t - 1) * C + blockIdx.x) * 3 + 1] = sum;
+            } else if (own) {
+                part[(static_cast<size_t>(t) * C + blockIdx.x) * 3 + threadIdx.x] = sum;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int k = 0; k < KL; ++k) { prv[c][k] = cur[c][k]; cur[c][k] = nxt[c][k]; }
+    }
+    if (threadIdx.x == 0 && t1 == T_frames) part[(static_cast<size_t>(T_frames - 1) * C + blockIdx.x) * 3 + 1] = 0.f;
+}
+
+// token_event of uniformly pooled frames: rows_per_frame consecutive rows carry their frame's event id.
+__global__ __launch_bounds__(256) void fill_token_event_kernel(const int32_t* __restrict__ frame_event, int T, int rows_per_frame,
+                                                               int32_t* __restrict__ token_event) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < T * rows_per_frame) token_event[i] = frame_event[i / rows_per_frame];
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 struct StatsPlan {
@@ -659,4 +792,126 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
     else METOK_POOL_CASE(float, float);
 #undef METOK_POOL_CASE
     return check_launch("pool");
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stage 1 in one call.  When every frame is pooled with stride 2 whatever the segmentation decides
+// (all four strides of the adaptive rule are 2, even grid), the statistics and the pooled tokens come
+// out of ONE pass over V; otherwise the two calls above run back to back (two passes over V).
+// ---------------------------------------------------------------------------------------------
+extern "C" size_t metok_segment_compress_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype) {
+    if (grid_h < 1 || grid_w < 1) return 0;
+    const size_t a = metok_segment_events_workspace_bytes(T, grid_h * grid_w, d, dtype);
+    const size_t b = metok_compress_encoder_tokens_workspace_bytes(T, grid_h, grid_w, d, dtype);
+    return a > b ? a : b;
+}
+
+template <typename T, typename TO>
+static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int grid_h, int grid_w, int d, int kl, int C, int fpr,
+                               int runs, float* part, void* pooled, hipStream_t st) {
+#define METOK_FUSED_CASE(KLV) \
+    if (kl == KLV) { \
+        hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs), dim3(kStatsThreads), 0, st, static_cast<const T*>(feats), \
+                           static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, C, static_cast<TO*>(pooled)); \
+        return true; \
+    }
+    METOK_FUSED_CASE(1) METOK_FUSED_CASE(2) METOK_FUSED_CASE(3) METOK_FUSED_CASE(4)
+#undef METOK_FUSED_CASE
+    return false;
+}
+
+extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                                      const void* text_emb, int k, int sim_mode,
+                                      double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
+                                      float* sim, int32_t* event_start, int32_t* frame_event,
+                                      void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                                      int32_t* frame_offsets, int32_t* token_event,
+                                      uint8_t* event_is_key, uint8_t* frame_is_key,
+                                      int32_t* frame_stride, float* event_score, float* frame_score,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    if (grid_h < 1 || grid_w < 1) return fail(METOK_ERR_INVALID_ARG, "grid sides must be positive");
+    if (!text_emb || !frame_score) return fail(METOK_ERR_INVALID_ARG, "text_emb and frame_score are required (Eq. 5 drives the pooling plan)");
+    const int N = grid_h * grid_w;
+    const size_t need = metok_segment_compress_workspace_bytes(T, grid_h, grid_w, d, dtype);
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace)))
+        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+
+    // can the pooled tokens be produced inside the statistics pass?
+    bool fused = sim_mode == METOK_SIM_FLAT && grid_h % 2 == 0 && grid_w % 2 == 0 && alpha > 0.0 && alpha <= 1.0 && s1 >= 1 && s2 >= 1 &&
+                 (dtype == METOK_F32 || dtype == METOK_BF16) && (out_dtype == METOK_F32 || out_dtype == METOK_BF16);
+    if (fused) {
+        const int gmax = grid_h > grid_w ? grid_h : grid_w;
+        auto clamp_stride = [&](double s) { int v = ceil_ratio(s); return v < 1 ? 1 : (v > gmax ? gmax : v); };
+        fused = clamp_stride(s1) == 2 && clamp_stride(s2) == 2 && clamp_stride(s1 / alpha) == 2 && clamp_stride(s2 / alpha) == 2;
+    }
+    const int vec = dtype == METOK_BF16 ? 8 : 4;
+    const int kl = (d > 0 && d % vec == 0) ? (d / vec + 63) / 64 : 0;
+    if (kl < 1 || kl > 4) fused = false;
+    if (!fused) {
+        int rc = metok_segment_events(feats, dtype, T, N, d, text_emb, k, sim_mode, sim, event_start, frame_event, frame_score,
+                                      workspace, workspace_bytes, stream);
+        if (rc) return rc;
+        return metok_compress_encoder_tokens(feats, dtype, T, grid_h, grid_w, d, nullptr, frame_score, event_start, k, alpha, beta, s1, s2,
+                                             event_reduce, pool_edge, out_tokens, out_capacity_rows, out_dtype, frame_offsets,
+                                             token_event, event_is_key, frame_is_key, frame_stride, event_score, nullptr,
+                                             workspace, workspace_bytes, stream);
+    }
+    // ---- one pass over V ------------------------------------------------------------------------
+    StatsPlan p;
+    int rc = check_feats(feats, dtype, T, N, d, &p);
+    if (rc) return rc;
+    if (k < 1 || k > T) return fail(METOK_ERR_INVALID_ARG, "k must be in [1, T] (k=%d, T=%d)", k, T);
+    if (!(beta > 0.0 && beta <= 1.0)) return fail(METOK_ERR_INVALID_ARG, "need 0 < beta <= 1 (beta=%g)", beta);
+    if (event_reduce != METOK_EVENT_MEAN && event_reduce != METOK_EVENT_MAX)
+        return fail(METOK_ERR_INVALID_ARG, "unknown event_reduce %d", event_reduce);
+    if (pool_edge != METOK_POOL_FLOOR && pool_edge != METOK_POOL_CEIL)
+        return fail(METOK_ERR_INVALID_ARG, "unknown pool_edge %d", pool_edge);
+    if (!event_start || !frame_event || (T > 1 && !sim) || !out_tokens || !frame_offsets || !token_event || !event_is_key ||
+        !frame_is_key || !frame_stride || !event_score)
+        return fail(METOK_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!aligned16(text_emb) || !aligned16(out_tokens)) return fail(METOK_ERR_INVALID_ARG, "text_emb / out_tokens not 16-byte aligned");
+    if ((static_cast<size_t>(d) * dtype_size(out_dtype)) % 16)
+        return fail(METOK_ERR_INVALID_ARG, "d * sizeof(out_dtype) must be a multiple of 16");
+    const int n_win = (grid_h / 2) * (grid_w / 2);
+    const int64_t rows = static_cast<int64_t>(T) * n_win;
+    if (out_capacity_rows < rows)
+        return fail(METOK_ERR_CAPACITY, "out_capacity_rows = %lld, worst case needs %lld", (long long)out_capacity_rows, (long long)rows);
+    if (rows > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pooled row count must fit int32");
+
+    const int C = (n_win + kStatsWaves - 1) / kStatsWaves;          // <= the chunk count of the two-pass plan: the partials fit
+    int runs = (2048 + C * kStatsWaves - 1) / (C * kStatsWaves);
+    int fpr = (T + runs - 1) / runs;
+    if (fpr < 4) fpr = 4;
+    if (fpr > T) fpr = T;
+    runs = (T + fpr - 1) / fpr;
+    char* ws = static_cast<char*>(workspace);
+    const size_t part_bytes = round_up(static_cast<size_t>(T) * C * 3 * sizeof(float), 256);
+    const size_t tslot = round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    float* part = reinterpret_cast<float*>(ws);
+    float* norm2 = reinterpret_cast<float*>(ws + part_bytes);
+    float* pair_dot = reinterpret_cast<float*>(ws + part_bytes + tslot);
+    int32_t* frame_event_ws = reinterpret_cast<int32_t*>(ws + part_bytes + 2 * tslot);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    bool ok;
+    if (dtype == METOK_BF16)
+        ok = out_dtype == METOK_BF16 ? launch_stats_pool2<bf16_t, bf16_t>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st)
+                                     : launch_stats_pool2<bf16_t, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st);
+    else
+        ok = out_dtype == METOK_BF16 ? launch_stats_pool2<float, bf16_t>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st)
+                                     : launch_stats_pool2<float, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st);
+    if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no fused kernel for d = %d", d);
+    if ((rc = check_launch("frame_stats_pool2"))) return rc;
+    hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, C, T, N, k, 1, METOK_SIM_FLAT,
+                       sim, event_start, frame_event, frame_score, norm2, pair_dot);
+    if ((rc = check_launch("segment"))) return rc;
+    const int n_key_events = ceil_ratio(alpha * k) > k ? k : ceil_ratio(alpha * k);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, frame_score, event_start, T, k, n_key_events, beta,
+                       2, 2, 2, 2, grid_h, grid_w, event_reduce, pool_edge,
+                       event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
+                       static_cast<float*>(nullptr));
+    if ((rc = check_launch("plan"))) return rc;
+    hipLaunchKernelGGL(fill_token_event_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, frame_event, T, n_win,
+                       token_event);
+    return check_launch("token events");
 }

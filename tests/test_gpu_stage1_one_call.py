@@ -1,0 +1,135 @@
+"""GPU parity of metok_segment_compress (stage 1 in one call) against the CPU oracle and against the two
+separate calls.  With every stride equal to 2 on an even grid the pooled tokens come out of the statistics
+pass (one read of the frame features); they must then be bit-identical to what the two-pass path writes,
+because both add the four cells of a window in the same order."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import metok_oracle as O
+from paper_2506_02850_amd import synth
+from tests.parity import RTOL, assert_rel, assert_rows_close, bf16_ulp
+
+pytestmark = pytest.mark.gpu
+
+
+def mk():
+    from paper_2506_02850_amd import binding
+    return binding
+
+
+def run_both(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce_=0):
+    B = mk()
+    feats = synth.to_torch(v.feats, v.dtype, "cuda")
+    text = synth.to_torch(v.text_emb, v.dtype, "cuda")
+    odt = torch.bfloat16 if out_dtype == "bf16" else torch.float32
+    one = B.metok_segment_compress(feats, grid[0], grid[1], k, text, alpha, beta, s1, s2, sim_mode=sim_mode,
+                                   event_reduce=reduce_, pool_edge=edge, out_dtype=odt)
+    seg = B.metok_segment_events(feats, k, text, sim_mode=sim_mode)
+    two = B.metok_compress_encoder_tokens(feats, grid[0], grid[1], seg["event_start"], alpha, beta, s1, s2,
+                                          frame_score=seg["frame_score"], event_reduce=reduce_, pool_edge=edge, out_dtype=odt)
+    torch.cuda.synchronize()
+    return one, seg, two
+
+
+def check(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce_=0, expect_strides=None):
+    one, seg, two = run_both(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode, edge, reduce_)
+    rtol = RTOL[v.dtype]
+    got = {n: (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy() for n, t in one.items()}
+    # segmentation and scores against the oracle
+    S = O.adjacent_frame_cosine(v.feats, sim_mode)
+    if v.feats.shape[0] > 1:
+        assert_rel(got["sim"], S, rtol, "sim", scale=np.abs(S).max())
+    es, fe = O.event_boundaries(S, k)
+    np.testing.assert_array_equal(got["event_start"], es)
+    np.testing.assert_array_equal(got["frame_event"], fe)
+    assert_rel(got["frame_score"], O.frame_text_score(v.feats, v.text_emb), rtol, "frame_score")
+    # plan re-derived by the oracle from the GPU's own frame scores, pooled tokens against the exact means
+    ref = O.compress_encoder_tokens(v.feats, grid, None, es, alpha, beta, s1, s2, reduce_, edge,
+                                    frame_score=got["frame_score"].astype(np.float64))
+    for name in ("event_is_key", "frame_is_key", "frame_stride", "frame_offsets"):
+        np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
+    assert_rel(got["event_score"], ref["event_score"], 1e-5, "event_score")
+    M = int(ref["frame_offsets"][-1])
+    np.testing.assert_array_equal(got["token_event"][:M], ref["token_event"])
+    tokens = got["out_tokens"][:M]
+    if out_dtype == "f32":
+        assert_rows_close(tokens, ref["tokens"], rtol, "pooled tokens")
+    else:
+        err = np.abs(tokens.astype(np.float64) - ref["tokens"])
+        assert (err <= bf16_ulp(ref["tokens"])).all(), "pooled bf16 token further than one ulp from the exact mean"
+        assert float((tokens.astype(np.float64) != O.round_to_bf16(ref["tokens"])).mean()) < 1e-3
+    if expect_strides is not None:
+        assert set(got["frame_stride"].tolist()) <= set(expect_strides)
+    # the two separate calls: same decisions, bit-identical tokens
+    for name in ("event_start", "frame_event"):
+        assert torch.equal(one[name], seg[name]), name
+    for name in ("event_is_key", "frame_is_key", "frame_stride", "frame_offsets"):
+        assert torch.equal(one[name], two[name]), name
+    assert torch.equal(one["token_event"][:M], two["token_event"][:M])
+    assert torch.equal(one["out_tokens"][:M], two["out_tokens"][:M]), "one-call and two-call pooled tokens differ"
+    return got
+
+
+@pytest.mark.parametrize("out_dtype", ["bf16", "f32"])
+def test_uniform_stride_two_encoder_config(out_dtype):
+    # 32 x 576 x 1024 bf16, 8 events: 144 tokens per frame out of the statistics pass
+    sh = synth.ENCODER
+    got = check(synth.video_for(sh), sh.grid, sh.n_events, 1.0, 1.0, 2, 2, out_dtype, expect_strides={2})
+    np.testing.assert_array_equal(got["frame_offsets"], 144 * np.arange(33))
+    np.testing.assert_array_equal(got["event_start"], synth.video_for(sh).event_start)
+
+
+@pytest.mark.parametrize("T,grid,d,dtype,k,alpha,beta,s1,s2", [
+    (9, (4, 4), 64, "f32", 4, 1.0, 0.5, 2, 2),          # tiny grid, fp32, 16 chunks: most lanes idle
+    (12, (6, 10), 512, "bf16", 3, 1.0, 1.0, 2, 2),      # 15 windows: the last workgroup is ragged
+    (7, (8, 6), 1152, "bf16", 3, 1.0, 0.4, 2, 2),       # 144 chunks: three chunks per lane
+    (10, (6, 6), 1024, "f32", 4, 1.0, 0.4, 2, 2),       # 256 chunks: four per lane
+    (1, (4, 6), 128, "bf16", 1, 1.0, 1.0, 2, 2),        # single frame
+    (2, (2, 2), 8, "bf16", 2, 1.0, 1.0, 2, 2),          # one window per frame
+    (40, (4, 6), 2048, "bf16", 7, 1.0, 0.5, 2, 2),      # 256 chunks of bf16, several frame runs
+    (6, (2, 2), 64, "f32", 2, 0.5, 0.5, 2, 3),          # 2, 3, 4, 6 all clamp to the 2 x 2 grid
+    (8, (6, 6), 64, "f32", 3, 0.5, 0.5, 1, 1),          # not uniform (1 and 2): two passes
+])
+def test_one_call_shapes(T, grid, d, dtype, k, alpha, beta, s1, s2):
+    v = synth.planted_video(777 + T + d, T, grid, d, min(k, T), 1, T, 0.15, dtype)
+    for out_dtype in ("f32", "bf16"):
+        check(v, grid, k, alpha, beta, s1, s2, out_dtype)
+
+
+@pytest.mark.parametrize("case", ["odd grid", "adaptive", "token mean", "ceil edge", "wide rows"])
+def test_one_call_falls_back_to_two_passes(case):
+    if case == "odd grid":            # SigLIP 27 x 27, uniform stride 2: the last row and column are dropped
+        v = synth.planted_video(31, 6, (27, 27), 64, 2, 2, 4, 0.15, "bf16")
+        got = check(v, (27, 27), 2, 1.0, 1.0, 2, 2, "bf16", expect_strides={2})
+        assert int(got["frame_offsets"][-1]) == 6 * 169
+    elif case == "adaptive":          # the paper's LongVA setting
+        v = synth.video_for(synth.ENCODER)
+        check(v, (24, 24), 8, 0.5, 0.45, 2, 3, "bf16", expect_strides={2, 3, 4, 6})
+    elif case == "token mean":
+        v = synth.planted_video(32, 8, (4, 4), 64, 3, 1, 8, 0.15, "f32")
+        check(v, (4, 4), 3, 1.0, 1.0, 2, 2, "f32", sim_mode=O.SIM_TOKEN_MEAN)
+    elif case == "ceil edge":
+        v = synth.planted_video(33, 5, (5, 7), 24, 2, 1, 5, 0.15, "f32")
+        check(v, (5, 7), 2, 1.0, 1.0, 2, 2, "f32", edge=O.POOL_CEIL)
+    else:                             # 4096 fp32 = 1024 chunks: too wide for the one-pass kernel
+        v = synth.planted_video(34, 5, (2, 2), 4096, 2, 1, 5, 0.15, "f32")
+        check(v, (2, 2), 2, 1.0, 1.0, 2, 2, "f32")
+
+
+def test_one_call_at_256_frames_and_errors():
+    B = mk()
+    sh = synth.ENCODER_256
+    v = synth.video_for(sh)
+    got = check(v, sh.grid, sh.n_events, 1.0, 1.0, 2, 2, "bf16", expect_strides={2})
+    assert int(got["frame_offsets"][-1]) == 256 * 144
+    feats = torch.zeros((4, 16, 64), dtype=torch.float32, device="cuda")
+    text = torch.ones(64, device="cuda")
+    with pytest.raises(B.MetokError) as e:
+        B.metok_segment_compress(feats, 4, 4, 9, text, 1.0, 1.0, 2, 2)
+    assert e.value.code == -1 and "k must be" in str(e.value)
+    with pytest.raises(B.MetokError) as e:
+        B.metok_segment_compress(feats, 4, 4, 2, text, 1.0, 1.0, 2, 2, out={"out_tokens": torch.zeros((3, 64), device="cuda")})
+    assert e.value.code == -4
+    with pytest.raises(B.MetokError):
+        B.metok_segment_compress(feats, 4, 4, 2, text, 1.0, 1.5, 2, 2)
