@@ -490,24 +490,28 @@ constexpr int kSelCache = 40;          // keys per thread held in registers (n_v
 constexpr int kSelCand = 4096;         // candidates kept in LDS once the top 16 key bits are fixed
 
 // One workgroup per retention class.  Radix select (8 bits per round from the top) of the quota-th
-// largest key of the class, then the keep flag of every token of the class and the number of kept
-// tokens per 1024-token tile.  Thread t owns tokens t, t + 1024, ... (token i of a thread lies in tile
+// largest key of the class: the threshold key tau and the number of tokens equal to tau that are still
+// kept (sel_info[2 seg], [2 seg + 1]; 0x7fffffff = every one), then per 1024-token tile the number of
+// class members above tau (gt_count) and equal to it (eq_count).  The keep rule itself -- above tau, or
+// equal and among the first `remaining` equal ones by index -- is applied by write_index_kernel.  Thread t owns tokens t, t + 1024, ... (token i of a thread lies in tile
 // i); with CACHED their keys stay in registers.  Attention scores share their top key bits, so the
 // first two rounds aggregate runs of equal digits per thread before touching the LDS histogram, and
 // once 16 bits are fixed the few remaining candidates move to an LDS list.
 template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ token_seg,
                                                              int n_vis, int n_tiles, const Quotas quotas,
-                                                             uint8_t* __restrict__ flags, int32_t* __restrict__ tile_count) {
+                                                             int32_t* __restrict__ gt_count, int32_t* __restrict__ eq_count,
+                                                             uint32_t* __restrict__ sel_info) {
     __shared__ int hist[256];
     __shared__ int scan_scratch[17];
     __shared__ int s_digit, s_remaining, s_count, s_ncand;
     __shared__ uint32_t cand[kSelCand];
-    __shared__ int cnt[64];
+    __shared__ int cnt[2][64];
     const int seg = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int quota = quotas.q[seg];
-    int32_t* my_count = tile_count + static_cast<size_t>(seg) * n_tiles;
+    int32_t* my_gt = gt_count + static_cast<size_t>(seg) * n_tiles;
+    int32_t* my_eq = eq_count + static_cast<size_t>(seg) * n_tiles;
 
     uint32_t key[CACHED ? kSelCache : 1];
     uint64_t member = 0;
@@ -553,7 +557,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     // keep rule: key > tau, or key == tau and fewer than `remaining` equal keys of the class precede the token
     uint32_t tau = 0;
     int remaining = 0x7fffffff;
-    bool ordered_ties = false;
     if (quota <= 0) {
         tau = 0xffffffffu; remaining = 0;                 // nothing is kept
     } else if (quota < pop) {
@@ -609,30 +612,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             __syncthreads();
         }
         tau = prefix;
-        ordered_ties = remaining < count_equal;
-        if (!ordered_ties) remaining = 0x7fffffff;        // every token equal to the threshold is kept
+        if (remaining >= count_equal) remaining = 0x7fffffff;      // every token equal to the threshold is kept
     }
 
-    // flags and per-tile counts, tiles in groups of 64
-    int ties_before = 0;                                  // equal keys of the class in earlier tiles (ordered_ties only)
+    if (tid == 0) {
+        sel_info[2 * seg] = tau;
+        sel_info[2 * seg + 1] = static_cast<uint32_t>(remaining);
+    }
+    // per-tile counts, tiles in groups of 64
     for (int g0 = 0; g0 < n_tiles; g0 += 64) {
-        if (tid < 64) cnt[tid] = 0;
+        if (tid < 128) cnt[tid >> 6][tid & 63] = 0;
         __syncthreads();
         const int g1 = min(n_tiles, g0 + 64);
         auto tile_body = [&](int i, bool is_member, uint32_t k) {
-            bool keep = is_member && k > tau;
-            const bool tie = is_member && k == tau;
-            if (ordered_ties) {                            // uniform over the workgroup
-                int total = 0;
-                const int before = block_exclusive_scan(tie ? 1 : 0, scan_scratch, &total);
-                if (tie && ties_before + before < remaining) keep = true;
-                ties_before += total;
-            } else if (tie && remaining > 0) {
-                keep = true;
+            const unsigned long long gt = __ballot(is_member && k > tau), eq = __ballot(is_member && k == tau);
+            if (lane == 0) {
+                if (gt) atomicAdd(&cnt[0][i - g0], __popcll(gt));
+                if (eq) atomicAdd(&cnt[1][i - g0], __popcll(eq));
             }
-            if (is_member) flags[tid + i * kSelThreads] = keep ? 1 : 0;
-            const unsigned long long mask = __ballot(keep);
-            if (lane == 0 && mask) atomicAdd(&cnt[i - g0], __popcll(mask));
         };
         if (CACHED) {
 #pragma unroll
@@ -646,43 +643,76 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             }
         }
         __syncthreads();
-        if (tid < g1 - g0) my_count[g0 + tid] = cnt[tid];
+        if (tid < g1 - g0) { my_gt[g0 + tid] = cnt[0][tid]; my_eq[g0 + tid] = cnt[1][tid]; }
         __syncthreads();
     }
 }
 
-// One workgroup per 1024-token tile: position of the tile's first kept token from the per-class tile
-// counts, prefix sum inside the tile, kept index list and carried metadata in ascending order.
+// One workgroup per 1024-token tile: applies the keep rule (key above the class threshold, or equal to it and
+// among the first `remaining` equal keys of the class by index), finds the position of the tile's first kept
+// token from the per-class tile counts, and writes the kept index list and carried metadata in ascending order.
 constexpr int kIdxThreads = 256;
 
 __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
-    const uint8_t* __restrict__ flags, const int32_t* __restrict__ tile_count, const int32_t* __restrict__ token_seg,
+    const float* __restrict__ scores, const uint32_t* __restrict__ sel_info, const int32_t* __restrict__ gt_count,
+    const int32_t* __restrict__ eq_count, const int32_t* __restrict__ token_seg,
     int n_vis, int n_seg, int n_tiles, int total_keep, const int32_t* __restrict__ token_event,
     const int32_t* __restrict__ orig_idx_in, int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
     int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out) {
     __shared__ int scan_scratch[17];
+    __shared__ uint32_t s_tau[METOK_MAX_SEGMENTS];
+    __shared__ int s_rem[METOK_MAX_SEGMENTS], s_eq_before[METOK_MAX_SEGMENTS];
+    __shared__ int tie_seg[kSelThreads];
     const int tile = blockIdx.x, tid = threadIdx.x;
-    // kept tokens in earlier tiles, all classes
+    // kept tokens in earlier tiles: thread s walks the tiles of class s
     int before = 0;
-    for (int e = tid; e < n_seg * tile; e += kIdxThreads) before += tile_count[(e / tile) * n_tiles + (e % tile)];
+    for (int sg = tid; sg < n_seg; sg += kIdxThreads) {
+        const uint32_t tau = sel_info[2 * sg];
+        const int rem = static_cast<int>(sel_info[2 * sg + 1]);
+        int eqcum = 0;
+        for (int t = 0; t < tile; ++t) {
+            const int eq = eq_count[static_cast<size_t>(sg) * n_tiles + t];
+            const int room = rem > eqcum ? rem - eqcum : 0;
+            before += gt_count[static_cast<size_t>(sg) * n_tiles + t] + (eq < room ? eq : room);
+            eqcum += eq;
+        }
+        s_tau[sg] = tau; s_rem[sg] = rem; s_eq_before[sg] = eqcum;
+    }
     int tile_off = 0;
-    block_exclusive_scan(before, scan_scratch, &tile_off);
+    block_exclusive_scan(before, scan_scratch, &tile_off);      // its barriers also publish the tables above
     // four consecutive tokens per thread
     const int j0 = tile * kSelThreads + tid * 4;
-    bool keep[4];
+    bool keep[4], tie[4];
     int sv[4];
-    int mine = 0;
+    bool any_tie = false;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int j = min(j0 + u, n_vis - 1);
         sv[u] = token_seg[j];
-        keep[u] = flags[j] != 0;
+        const uint32_t key = ordered_key(scores[j]);
+        const bool ok = (j0 + u < n_vis) && sv[u] >= 0 && sv[u] < n_seg;
+        const int sg = ok ? sv[u] : 0;
+        keep[u] = ok && key > s_tau[sg];
+        tie[u] = ok && key == s_tau[sg];
+        if (tie[u] && s_rem[sg] == 0x7fffffff) { keep[u] = true; tie[u] = false; }      // every equal key is kept
+        if (tie[u] && s_rem[sg] <= s_eq_before[sg]) tie[u] = false;                      // the equal keys kept lie in earlier tiles
+        any_tie = any_tie || tie[u];
+        tie_seg[tid * 4 + u] = tie[u] ? sg : -1;
     }
+    if (__syncthreads_or(any_tie ? 1 : 0)) {
+        // rank of an undecided equal key among the equal keys of its class (ties are rare; the walk is short)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        keep[u] = keep[u] && (j0 + u < n_vis) && sv[u] >= 0 && sv[u] < n_seg;     // flags of other tokens were never written
-        mine += keep[u] ? 1 : 0;
+        for (int u = 0; u < 4; ++u) {
+            if (tie[u]) {
+                int rank = s_eq_before[sv[u]];
+                for (int q = 0; q < tid * 4 + u; ++q) rank += tie_seg[q] == sv[u] ? 1 : 0;
+                keep[u] = rank < s_rem[sv[u]];
+            }
+        }
     }
+    int mine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) mine += keep[u] ? 1 : 0;
     int total = 0;
     int pos = tile_off + block_exclusive_scan(mine, scan_scratch, &total);
 #pragma unroll
@@ -733,12 +763,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const u32x4
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-// keep flags [n_vis] followed by the per-class tile counts [METOK_MAX_SEGMENTS][n_tiles]
+// selection scratch: per-class tile counts above / equal to the threshold [2][METOK_MAX_SEGMENTS][n_tiles], then
+// (threshold, equal keys kept) per class
 static int select_tiles(int n_vis) { return (n_vis + kSelThreads - 1) / kSelThreads; }
-static size_t select_flag_bytes(int n_vis) { return round_up(static_cast<size_t>(n_vis), 256); }
-static size_t select_bytes(int n_vis) {
-    return select_flag_bytes(n_vis) + round_up(static_cast<size_t>(METOK_MAX_SEGMENTS) * select_tiles(n_vis) * sizeof(int32_t), 256);
+static size_t select_count_bytes(int n_vis) {
+    return round_up(static_cast<size_t>(METOK_MAX_SEGMENTS) * select_tiles(n_vis) * sizeof(int32_t), 256);
 }
+static size_t select_bytes(int n_vis) { return 2 * select_count_bytes(n_vis) + METOK_MAX_SEGMENTS * 2 * sizeof(uint32_t); }
 
 static int chunk_count(int dh, int dtype) { return dtype == METOK_BF16 ? dh / 16 : dh / 8; }     // 16-byte chunks per lane
 
@@ -925,17 +956,18 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
             return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
         sel = ws;
     }
-    uint8_t* flags = reinterpret_cast<uint8_t*>(sel);
-    int32_t* tile_count = reinterpret_cast<int32_t*>(sel + select_flag_bytes(n_vis));
+    int32_t* gt_count = reinterpret_cast<int32_t*>(sel);
+    int32_t* eq_count = reinterpret_cast<int32_t*>(sel + select_count_bytes(n_vis));
+    uint32_t* sel_info = reinterpret_cast<uint32_t*>(sel + 2 * select_count_bytes(n_vis));
     const int n_tiles = select_tiles(n_vis);
     if (n_vis <= kSelCache * kSelThreads)
         hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                           flags, tile_count);
+                           gt_count, eq_count, sel_info);
     else
         hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                           flags, tile_count);
+                           gt_count, eq_count, sel_info);
     if ((rc = check_launch("select"))) return rc;
-    hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, flags, tile_count, token_seg, n_vis, n_seg,
+    hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
                        n_tiles, static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out,
                        token_event_out, orig_idx_out);
     if ((rc = check_launch("write index"))) return rc;
