@@ -8,9 +8,9 @@
 //                        probabilities of every visual key over the rows of a workgroup
 //   prepare_kernel       score_j = w_e(j) * mean probability
 //   select_kernel        one workgroup per retention class: radix select of the quota-th largest
-//                        score, lowest index first among equals -> keep flags and per-tile counts
-//   write_index_kernel   one workgroup per 1024-token tile: prefix sums -> ascending kept index list
-//                        and carried metadata
+//                        score -> class threshold, number of equal scores still kept, per-tile counts
+//   write_index_kernel   one workgroup per 1024-token tile: keep rule (lowest index first among equal
+//                        scores), prefix sums -> ascending kept index list and carried metadata
 //   gather_rows_kernel   compaction of the hidden states
 //
 // Both MFMA passes are query-stationary: a wave keeps the fragments of its own 32-row blocks of queries in
