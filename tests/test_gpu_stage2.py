@@ -187,6 +187,34 @@ def test_selection_with_supplied_scores_ties_and_edges():
     select_only(np.array([0.5], dtype=np.float32), np.zeros(1, dtype=np.int32), [1])
 
 
+def test_selection_ties_across_tiles_many_classes_and_long_sequences():
+    rng = np.random.default_rng(4)
+    # all scores equal: the equal keys that are kept end in the middle of a later 1024-token tile
+    n = 6000
+    seg = rng.integers(0, 2, size=n).astype(np.int32)
+    pops = [int((seg == s).sum()) for s in range(2)]
+    kept = select_only(np.full(n, -1.5, dtype=np.float32), seg, [pops[0] - 700, 1300])
+    assert np.array_equal(kept[seg[kept] == 1], np.nonzero(seg == 1)[0][:1300])
+    # two values only, threshold inside the lower one: every upper key plus the first few lower keys
+    scores = np.where(rng.random(n) < 0.3, 2.0, 1.0).astype(np.float32)
+    n_up = int(((scores == 2.0) & (seg == 0)).sum())
+    kept = select_only(scores, seg, [n_up + 333, 5])
+    lower0 = np.nonzero((scores == 1.0) & (seg == 0))[0][:333]
+    assert set(lower0.tolist()) <= set(kept.tolist())
+    # 256 classes (the most the call accepts), random quotas, some classes empty
+    seg = rng.integers(0, 256, size=n).astype(np.int32)
+    seg[seg == 17] = 18
+    pops = [int((seg == s).sum()) for s in range(256)]
+    quotas = [int(rng.integers(0, p + 1)) for p in pops]
+    select_only(np.round(rng.standard_normal(n), 2).astype(np.float32), seg, quotas)
+    # more than 40960 tokens: keys no longer fit the selection kernel's registers (the uncached path)
+    n = 45000
+    seg = rng.integers(0, 3, size=n).astype(np.int32)
+    pops = [int((seg == s).sum()) for s in range(3)]
+    select_only(np.round(rng.standard_normal(n), 3).astype(np.float32), seg, [pops[0] // 3, pops[1] - 1, 7], D=8)
+    select_only(np.full(n, 3.0, dtype=np.float32), seg, [pops[0] - 2000, pops[1], 7], D=8)
+
+
 def test_repeat_calls_are_bit_identical():
     layer = make_layer(970, 37, 24, 5, 16, 48, 28, 4, 128, "bf16")
     seg = np.zeros(layer.n_vis, dtype=np.int32)
