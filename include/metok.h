@@ -276,6 +276,26 @@ METOK_API int metok_kv_compact(void* const* k_layers, void* const* v_layers, int
                      const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
                      void* stream);
 
+/*
+ * The same compaction for a paged cache (Sec. 3.3).  Layer l holds K (resp. V) as a pool
+ * [n_pages_pool, Hkv, page_size, dh] of `dtype`; logical row p of video b is slot p % page_size of page
+ * page_table[b][p / page_size].
+ *   page_table   device, [B, pages_per_seq] int32, shared by all layers; the pages of the table must be
+ *                pairwise distinct (no page shared between or inside sequences), else rows alias and the
+ *                in-place move is not defined.  Entries outside [0, n_pages_pool) are never dereferenced
+ *                (rows that would touch them are skipped).
+ *   idx, n_keep, new_len  as in metok_kv_compact, positions being logical rows below
+ *                pages_per_seq * page_size.
+ * Afterwards the pages from ceil(n_keep[l] / page_size) on hold no live rows of layer l; the table itself is
+ * not modified (page ids are shared by the layers, whose lengths now differ: the caller keeps one length
+ * per layer, new_len, and may release a page once no layer needs it).
+ */
+METOK_API int metok_kv_compact_paged(void* const* k_pools, void* const* v_pools, int L, int B, int Hkv,
+                           int64_t n_pages_pool, int page_size, int dh, int dtype,
+                           const int32_t* page_table, int pages_per_seq,
+                           const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
+                           void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Measurement helper (not part of the method): a plain device-to-device copy kernel with the
  * same access width as the streaming kernels.  The bench uses it to calibrate the profiler's

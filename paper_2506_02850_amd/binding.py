@@ -29,7 +29,7 @@ EXPORTS = [
     "metok_segment_compress_workspace_bytes", "metok_segment_compress",
     "metok_retention_quotas", "metok_account",
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
-    "metok_kv_compact", "metok_calib_copy",
+    "metok_kv_compact", "metok_kv_compact_paged", "metok_calib_copy",
 ]
 
 
@@ -83,6 +83,9 @@ def _load() -> ctypes.CDLL:
     lib.metok_kv_compact.restype = i32
     lib.metok_kv_compact.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, c.POINTER(vp),
                                      c.POINTER(c.c_int32), vp, vp]
+    lib.metok_kv_compact_paged.restype = i32
+    lib.metok_kv_compact_paged.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, i32, vp, i32,
+                                           c.POINTER(vp), c.POINTER(c.c_int32), vp, vp]
     lib.metok_calib_copy.restype = i32
     lib.metok_calib_copy.argtypes = [vp, vp, sz, vp]
     return lib
@@ -375,6 +378,42 @@ def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.
     if new_len is None:
         new_len = torch.empty(L, dtype=torch.int32, device=dev)
     _check(_lib.metok_kv_compact(karr, varr, L, B, Hkv, S_cap, dh, dt, iarr, nk, _dev(new_len, "new_len"), _stream()))
+    return new_len
+
+
+def metok_kv_compact_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[torch.Tensor], page_table: torch.Tensor,
+                           idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """In-place compaction of paged per-layer K/V pools [n_pages, Hkv, page_size, dh] through page_table [B, pages_per_seq]
+    to the logical rows idx[l] [B, n_keep_l] (None = untouched)."""
+    L = len(k_pools)
+    if len(v_pools) != L or len(idx) != L:
+        raise ValueError("k_pools, v_pools and idx must have one entry per layer")
+    n_pages, Hkv, page_size, dh = k_pools[0].shape
+    if page_table.dtype != torch.int32 or page_table.dim() != 2:
+        raise ValueError("page_table must be int32 [B, pages_per_seq]")
+    B, pages_per_seq = page_table.shape
+    dt = _dtype_code(k_pools[0])
+    dev = k_pools[0].device
+    vp = ctypes.c_void_p
+    karr, varr, iarr = (vp * L)(), (vp * L)(), (vp * L)()
+    nk = (ctypes.c_int32 * L)()
+    for l in range(L):
+        if tuple(k_pools[l].shape) != (n_pages, Hkv, page_size, dh) or tuple(v_pools[l].shape) != (n_pages, Hkv, page_size, dh):
+            raise ValueError("all pools must share one [n_pages, Hkv, page_size, dh] shape")
+        karr[l] = _dev(k_pools[l], "k_pools")
+        varr[l] = _dev(v_pools[l], "v_pools")
+        if idx[l] is None:
+            iarr[l] = None
+            nk[l] = 0
+        else:
+            if idx[l].dtype != torch.int32 or idx[l].dim() != 2 or idx[l].shape[0] != B:
+                raise ValueError("idx[l] must be int32 [B, n_keep]")
+            iarr[l] = _dev(idx[l], "idx") if idx[l].numel() else _dev(new_len_dummy(dev), "idx")
+            nk[l] = idx[l].shape[1]
+    if new_len is None:
+        new_len = torch.empty(L, dtype=torch.int32, device=dev)
+    _check(_lib.metok_kv_compact_paged(karr, varr, L, B, Hkv, n_pages, page_size, dh, dt, _dev(page_table, "page_table"),
+                                       pages_per_seq, iarr, nk, _dev(new_len, "new_len"), _stream()))
     return new_len
 
 
