@@ -81,21 +81,29 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(const Compa
     for (int tile = 0; tile < rows; tile += args.rows_per_tile) {
         const int i = tile + r_in_tile;
         u32x4_t v;
-        char* dst = nullptr;
+        bool move = false;
+        char* dst = nullptr;                                      // paged only: looked up before the barrier
         if (active && i < rows) {
             const uint32_t s = static_cast<uint32_t>(idx[i]);
             // rows that stay where they are need no copy; positions outside [i, S_cap) are skipped
             if (s > static_cast<uint32_t>(i) && s < s_cap) {
                 const char* src = row_ptr(s);
-                dst = row_ptr(static_cast<uint32_t>(i));
-                if (!src) dst = nullptr;
-                if (dst) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + col));
+                if (PAGED) {
+                    dst = row_ptr(static_cast<uint32_t>(i));
+                    move = src != nullptr && dst != nullptr;
+                } else {
+                    move = true;
+                }
+                if (move) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + col));
             }
         }
         // every load of this tile has returned before any thread of the workgroup stores into it
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (dst) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(dst + col));
+        if (move) {
+            char* out = PAGED ? dst : base + static_cast<int64_t>(i) * args.row_bytes;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(out + col));
+        }
     }
 }
 
