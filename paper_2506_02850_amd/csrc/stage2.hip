@@ -221,18 +221,17 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
     const int64_t text_start = g.S - g.Tq;
     const int64_t full_end = text_start < ke ? text_start : ke;
 
-    u32x4_t kv[Stage::kPerThread];
+    // the first two key stages and the query fragments are requested together: one memory round trip
+    u32x4_t kv[Stage::kPerThread], kv1[Stage::kPerThread];
     Stage::load(kv, k_head, kb, g.S, g.dh);
-    Stage::store(kv, lds);
-    if (n_stage > 1) {
-        Stage::load(kv, k_head, kb + Stage::kKeys, g.S, g.dh);
-        Stage::store(kv, lds + Stage::kSlots);
-    }
+    Stage::load(kv1, k_head, kb + (n_stage > 1 ? Stage::kKeys : 0), g.S, g.dh);
     uint4 q[RBW][NCH];
     load_qfrag<NCH, RBW>(q, qfrag, g, kvh, rb0, nrb, wave, lane);
     float m[RBW], l[RBW];
 #pragma unroll
     for (int i = 0; i < RBW; ++i) { m[i] = kNegBig; l[i] = 0.f; }
+    Stage::store(kv, lds);
+    if (n_stage > 1) Stage::store(kv1, lds + Stage::kSlots);
     // Every load issued so far has to land before the loop: with query loads still pending at its head the
     // first use of a fragment inside would wait for ALL outstanding loads, the prefetch of later stages included.
     __builtin_amdgcn_s_waitcnt(0);
