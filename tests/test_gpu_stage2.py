@@ -87,6 +87,10 @@ def test_tiny_config_single_segment():
     ("f32", 32, 2, 2, 16, 0),
     ("f32", 64, 4, 2, 21, 2),
     ("f32", 128, 2, 1, 40, 0),
+    ("bf16", 128, 16, 1, 40, 0),       # 640 rows per kv head: 20 row blocks, two workgroup rows of 10
+    ("bf16", 256, 12, 1, 32, 4),       # one row block per wave at this width: 12 row blocks, two workgroup rows of 6
+    ("f32", 128, 10, 1, 32, 0),        # fp32, 16 chunks: 10 row blocks over two workgroup rows
+    ("bf16", 64, 40, 40, 64, 0),       # full multi-head attention: 40 kv heads, two row blocks each
 ])
 def test_prune_shapes_two_classes(dtype, dh, Hq, Hkv, n_text, vis_start):
     # 37 frames x 24 tokens = 888 visual tokens: seven 128-key tiles with a ragged tail
