@@ -349,23 +349,20 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
     return res
 
 
-def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.Tensor],
-                     idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """In-place compaction of per-layer K/V caches [B, Hkv, S_cap, dh] to idx[l] [B, n_keep_l] (None = untouched)."""
+def _layer_tables(k_layers, v_layers, idx, shape, B):
+    """ctypes pointer tables of the per-layer K / V buffers and index lists, plus the per-layer kept counts."""
     L = len(k_layers)
     if len(v_layers) != L or len(idx) != L:
-        raise ValueError("k_layers, v_layers and idx must have one entry per layer")
-    B, Hkv, S_cap, dh = k_layers[0].shape
-    dt = _dtype_code(k_layers[0])
+        raise ValueError("K buffers, V buffers and idx must have one entry per layer")
     dev = k_layers[0].device
     vp = ctypes.c_void_p
     karr, varr, iarr = (vp * L)(), (vp * L)(), (vp * L)()
     nk = (ctypes.c_int32 * L)()
     for l in range(L):
-        if tuple(k_layers[l].shape) != (B, Hkv, S_cap, dh) or tuple(v_layers[l].shape) != (B, Hkv, S_cap, dh):
-            raise ValueError("all layers must share one [B, Hkv, S_cap, dh] shape")
-        karr[l] = _dev(k_layers[l], "k_layers")
-        varr[l] = _dev(v_layers[l], "v_layers")
+        if tuple(k_layers[l].shape) != shape or tuple(v_layers[l].shape) != shape:
+            raise ValueError(f"every layer must have the shape {shape}")
+        karr[l] = _dev(k_layers[l], "K buffer")
+        varr[l] = _dev(v_layers[l], "V buffer")
         if idx[l] is None:
             iarr[l] = None
             nk[l] = 0
@@ -375,9 +372,19 @@ def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.
             # an empty list (drop every row) still needs a non-NULL pointer: NULL means "leave the layer alone"
             iarr[l] = _dev(idx[l], "idx") if idx[l].numel() else _dev(new_len_dummy(dev), "idx")
             nk[l] = idx[l].shape[1]
+    return L, karr, varr, iarr, nk
+
+
+def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.Tensor],
+                     idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """In-place compaction of per-layer K/V caches [B, Hkv, S_cap, dh] to idx[l] [B, n_keep_l] (None = untouched)."""
+    B, Hkv, S_cap, dh = k_layers[0].shape
+    L, karr, varr, iarr, nk = _layer_tables(k_layers, v_layers, idx, (B, Hkv, S_cap, dh), B)
+    dev = k_layers[0].device
     if new_len is None:
         new_len = torch.empty(L, dtype=torch.int32, device=dev)
-    _check(_lib.metok_kv_compact(karr, varr, L, B, Hkv, S_cap, dh, dt, iarr, nk, _dev(new_len, "new_len"), _stream()))
+    _check(_lib.metok_kv_compact(karr, varr, L, B, Hkv, S_cap, dh, _dtype_code(k_layers[0]), iarr, nk,
+                                 _dev(new_len, "new_len"), _stream()))
     return new_len
 
 
@@ -385,35 +392,17 @@ def metok_kv_compact_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[to
                            idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
     """In-place compaction of paged per-layer K/V pools [n_pages, Hkv, page_size, dh] through page_table [B, pages_per_seq]
     to the logical rows idx[l] [B, n_keep_l] (None = untouched)."""
-    L = len(k_pools)
-    if len(v_pools) != L or len(idx) != L:
-        raise ValueError("k_pools, v_pools and idx must have one entry per layer")
     n_pages, Hkv, page_size, dh = k_pools[0].shape
     if page_table.dtype != torch.int32 or page_table.dim() != 2:
         raise ValueError("page_table must be int32 [B, pages_per_seq]")
     B, pages_per_seq = page_table.shape
-    dt = _dtype_code(k_pools[0])
+    L, karr, varr, iarr, nk = _layer_tables(k_pools, v_pools, idx, (n_pages, Hkv, page_size, dh), B)
     dev = k_pools[0].device
-    vp = ctypes.c_void_p
-    karr, varr, iarr = (vp * L)(), (vp * L)(), (vp * L)()
-    nk = (ctypes.c_int32 * L)()
-    for l in range(L):
-        if tuple(k_pools[l].shape) != (n_pages, Hkv, page_size, dh) or tuple(v_pools[l].shape) != (n_pages, Hkv, page_size, dh):
-            raise ValueError("all pools must share one [n_pages, Hkv, page_size, dh] shape")
-        karr[l] = _dev(k_pools[l], "k_pools")
-        varr[l] = _dev(v_pools[l], "v_pools")
-        if idx[l] is None:
-            iarr[l] = None
-            nk[l] = 0
-        else:
-            if idx[l].dtype != torch.int32 or idx[l].dim() != 2 or idx[l].shape[0] != B:
-                raise ValueError("idx[l] must be int32 [B, n_keep]")
-            iarr[l] = _dev(idx[l], "idx") if idx[l].numel() else _dev(new_len_dummy(dev), "idx")
-            nk[l] = idx[l].shape[1]
     if new_len is None:
         new_len = torch.empty(L, dtype=torch.int32, device=dev)
-    _check(_lib.metok_kv_compact_paged(karr, varr, L, B, Hkv, n_pages, page_size, dh, dt, _dev(page_table, "page_table"),
-                                       pages_per_seq, iarr, nk, _dev(new_len, "new_len"), _stream()))
+    _check(_lib.metok_kv_compact_paged(karr, varr, L, B, Hkv, n_pages, page_size, dh, _dtype_code(k_pools[0]),
+                                       _dev(page_table, "page_table"), pages_per_seq, iarr, nk, _dev(new_len, "new_len"),
+                                       _stream()))
     return new_len
 
 
