@@ -68,7 +68,7 @@ METOK_API int metok_version(void);
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 1a -- temporal event segmentation (Sec. 3.2.1 "Temporal Event Segmentation", Eq. 4;
- * first two lines of Algorithm 1), optionally fused with the frame-text relevance of Eq. 5 so
+ * the segmentation step of Algorithm 1), optionally fused with the frame-text relevance of Eq. 5 so
  * that the frame features are streamed from HBM once.
  *
  *   feats        device, [T, N, d] of `dtype`: N patch tokens of width d for each of T frames.
@@ -100,8 +100,8 @@ METOK_API int metok_segment_events(const void* feats, int dtype, int T, int N, i
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 1b -- key event / key frame identification and adaptive pooling (Sec. 3.2.1 "Key
- * Visual-Text Semantic Identification" and "Adaptive Pooling Strategy"; Algorithm 1 from the
- * second comment on).
+ * Visual-Text Semantic Identification" and "Adaptive Pooling Strategy"; Algorithm 1 after its
+ * segmentation step).
  *
  *   feats           device, [T, grid_h*grid_w, d] of `dtype`; tokens of a frame are row-major
  *                   over the grid_h x grid_w patch grid.
