@@ -100,3 +100,50 @@ def test_kv_compaction_random_cases_dense_and_paged():
                         ref = O.kv_compact(dense[b, h], None if lists[l] is None else lists[l][b])
                         assert np.array_equal(got[b, h, :ref.shape[0]], ref), f"case {it} dense layer {l}"
                         assert np.array_equal(logical[h, :ref.shape[0]], ref), f"case {it} paged layer {l}"
+
+
+def test_stage1_random_cases_one_call_and_two_calls():
+    from paper_2506_02850_amd import synth
+    from tests.test_gpu_stage1_one_call import check
+
+    rng = np.random.default_rng(77)
+    for it in range(24):
+        T = int(rng.integers(2, 30))
+        grid = (int(rng.integers(1, 9)) * (2 if it % 2 == 0 else 1), int(rng.integers(1, 9)) * (2 if it % 2 == 0 else 1))
+        dtype = "bf16" if it % 3 else "f32"
+        d = 8 * int(rng.integers(1, 40))                          # bf16 output rows need a multiple of 8
+        k = int(rng.integers(1, min(T, 6) + 1))
+        if it % 2 == 0:
+            alpha, s1, s2 = 1.0, 2, 2                              # uniform stride 2 on an even grid: the one-pass kernel
+        else:
+            alpha, s1, s2 = float(rng.choice([0.3, 0.5, 1.0])), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        beta = float(rng.choice([0.4, 0.5, 1.0]))
+        edge = int(rng.integers(0, 2))
+        reduce_ = int(rng.integers(0, 2))
+        v = synth.planted_video(5000 + it, T, grid, d, k, 1, T, 0.12, dtype)
+        for out_dtype in ("f32", "bf16"):
+            check(v, grid, k, alpha, beta, s1, s2, out_dtype, edge=edge, reduce_=reduce_)
+
+
+def test_stage2_scores_random_cases():
+    from paper_2506_02850_amd import synth
+    from tests.test_gpu_stage2 import check_prune, run_prune
+
+    rng = np.random.default_rng(99)
+    for it in range(20):
+        dtype = "bf16" if it % 4 else "f32"
+        dh = int(rng.choice([32, 64, 128, 256] if dtype == "bf16" else [32, 64, 128]))
+        Hkv = int(rng.integers(1, 5))
+        Hq = Hkv * int(rng.integers(1, 8))
+        n_text = int(rng.integers(1, 70))
+        Tq = int(rng.integers(1, n_text + 1))
+        vis_start = int(rng.integers(0, 40))
+        n_events = int(rng.integers(1, 6))
+        n_vis = int(rng.integers(1, 1500))
+        token_event = np.sort(rng.integers(0, n_events, size=n_vis)).astype(np.int32)
+        layer = synth.prefill_layer(7000 + it, token_event, n_events, n_text, 16, Hq, Hkv, dh, dtype, vis_start=vis_start)
+        seg = rng.integers(0, 2, size=n_vis).astype(np.int32)
+        quotas = [int(rng.integers(0, int((seg == s).sum()) + 1)) for s in range(2)]
+        mode = int(rng.integers(0, 2))
+        got, q = run_prune(layer, seg, quotas, use_weight=bool(it % 2), Tq=Tq, score_mode=mode)
+        check_prune(layer, seg, quotas, got, q, use_weight=bool(it % 2), score_mode=mode)
