@@ -131,6 +131,30 @@ def test_argument_errors_before_any_launch(lib):
     assert kv(k, v, 1, 1, 1, 16, 16, 1, idx, nk, None, None) == -1      # n_keep > S_cap
     assert kv(k, v, 0, 1, 1, 16, 16, 1, idx, nk, None, None) == -1      # L < 1
     assert kv(k, v, 200, 1, 1, 16, 16, 1, idx, nk, None, None) == -1    # L > METOK_MAX_LAYERS
+    kvp = lib.metok_kv_compact_paged
+    kvp.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i64, i32, i32, i32, vp, i32, ctypes.POINTER(vp),
+                    ctypes.POINTER(ctypes.c_int32), vp, vp]
+    nk[0] = 4
+    assert kvp(k, v, 1, 1, 1, 8, 4, 16, 1, None, 4, idx, nk, None, None) == -1      # no page table
+    assert kvp(k, v, 1, 1, 1, 8, 0, 16, 1, fake, 4, idx, nk, None, None) == -1      # page_size < 1
+    nk[0] = 17
+    assert kvp(k, v, 1, 1, 1, 8, 4, 16, 1, fake, 4, idx, nk, None, None) == -1      # n_keep > pages_per_seq * page_size
+    one = lib.metok_segment_compress
+    one.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, dbl, dbl, i32, i32, i32, i32, vp, vp, vp, vp, i64, i32,
+                    vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    args = [fake, 1, 8, 4, 4, 64, fake, 2, 0, 1.0, 1.0, 2, 2, 0, 0, fake, fake, fake, fake, 8 * 4, 1] + [fake] * 7 + [fake, 1 << 22, None]
+    bad = list(args); bad[6] = None
+    assert one(*bad) == -1 and b"text_emb" in lib.metok_last_error()                 # Eq. 5 needs the text embedding
+    bad = list(args); bad[7] = 9
+    assert one(*bad) == -1 and b"k must be" in lib.metok_last_error()                # k > T on the one-pass path
+    bad = list(args); bad[19] = 31
+    assert one(*bad) == -4                                                           # out_tokens too small
+    bad = list(args); bad[10] = 1.5
+    assert one(*bad) == -1                                                           # beta > 1
+    bad = list(args); bad[11] = 3; bad[7] = 9
+    assert one(*bad) == -1 and b"k must be" in lib.metok_last_error()                # same check on the two-pass path
+    bad = list(args); bad[-2] = 16
+    assert one(*bad) == -3                                                           # workspace
     copy = lib.metok_calib_copy
     copy.argtypes = [vp, vp, sz, vp]
     assert copy(fake, fake, 24, None) == -1
