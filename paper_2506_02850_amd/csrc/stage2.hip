@@ -488,22 +488,24 @@ constexpr int kSelThreads = 1024;      // also the tile size of the selection: t
 constexpr int kSelCache = 40;          // keys per thread held in registers (n_vis <= 40960)
 constexpr int kSelCand = 4096;         // candidates kept in LDS once the top 16 key bits are fixed
 
-// One workgroup per retention class.  Radix select (8 bits per round from the top) of the quota-th
+// One workgroup per retention class.  Radix select (digits of up to 11 bits, starting at the highest bit in
+// which the keys of the class differ) of the quota-th
 // largest key of the class: the threshold key tau and the number of tokens equal to tau that are still
 // kept (sel_info[2 seg], [2 seg + 1]; 0x7fffffff = every one), then per 1024-token tile the number of
 // class members above tau (gt_count) and equal to it (eq_count).  The keep rule itself -- above tau, or
 // equal and among the first `remaining` equal ones by index -- is applied by write_index_kernel.  Thread t owns tokens t, t + 1024, ... (token i of a thread lies in tile
-// i); with CACHED their keys stay in registers.  Attention scores share their top key bits, so the
-// first two rounds aggregate runs of equal digits per thread before touching the LDS histogram, and
-// once 16 bits are fixed the few remaining candidates move to an LDS list.
+// i); with CACHED their keys stay in registers.  Attention scores share their top key bits, so a
+// thread aggregates runs of equal digits before touching the LDS histogram, and once the first digit is
+// fixed the remaining candidates (if at most 4096) move to an LDS list for the other two digits.
 template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ token_seg,
                                                              int n_vis, int n_tiles, const Quotas quotas,
                                                              int32_t* __restrict__ gt_count, int32_t* __restrict__ eq_count,
                                                              uint32_t* __restrict__ sel_info) {
-    __shared__ int hist[256];
+    __shared__ int hist[2 * kSelThreads];      // 2048 bins: one 11-bit digit
     __shared__ int scan_scratch[17];
     __shared__ int s_digit, s_remaining, s_count, s_ncand;
+    __shared__ uint32_t s_or, s_and;
     __shared__ uint32_t cand[kSelCand];
     __shared__ int cnt[2][64];
     const int seg = blockIdx.x;
@@ -549,9 +551,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             }
         }
     };
-    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; s_ncand = 0; }
+    if (tid == 0) { s_digit = 0; s_remaining = 0; s_count = 0; s_ncand = 0; s_or = 0u; s_and = 0xffffffffu; }
     int pop = 0;
     block_exclusive_scan(mine, scan_scratch, &pop);
+    // bits on which the keys of the class differ: the radix digits start at the highest of them, so that the
+    // first digit already separates scores that share sign, exponent and leading mantissa bits
+    {
+        uint32_t o = 0u, a = 0xffffffffu;
+        for_each_key([&](uint32_t k) { o |= k; a &= k; });
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) { o |= __shfl_xor(o, off, 64); a &= __shfl_xor(a, off, 64); }
+        if (lane == 0) { atomicOr(&s_or, o); atomicAnd(&s_and, a); }
+        __syncthreads();
+    }
 
     // keep rule: key > tau, or key == tau and fewer than `remaining` equal keys of the class precede the token
     uint32_t tau = 0;
@@ -559,25 +571,31 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     if (quota <= 0) {
         tau = 0xffffffffu; remaining = 0;                 // nothing is kept
     } else if (quota < pop) {
-        uint32_t prefix = 0;
-        int count_equal = 0;
+        const uint32_t differ = s_or ^ s_and;
+        const int width = differ ? 32 - __clz(differ) : 0;             // the low `width` bits vary, the rest is common
+        uint32_t prefix = width >= 32 ? 0u : (s_and & (0xffffffffu << width));
+        int count_equal = pop;                                          // width 0: all keys are equal
         remaining = quota;
         bool use_list = false;
-        for (int round = 0; round < 4; ++round) {
-            const int shift = 24 - 8 * round;
-            const uint32_t hi_mask = round == 0 ? 0u : (0xffffffffu << (shift + 8));
-            if (tid < 256) hist[tid] = 0;
+        // digits of up to 11 bits from the highest differing bit down (at most three rounds)
+        for (int top = width; top > 0; top -= 11) {
+            const int bits = top < 11 ? top : 11;
+            const int shift = top - bits;
+            const int bins = 1 << bits;
+            const uint32_t dmask = static_cast<uint32_t>(bins - 1);
+            const uint32_t hi_mask = top >= 32 ? 0u : (0xffffffffu << top);
+            hist[tid] = 0; hist[tid + kSelThreads] = 0;
             __syncthreads();
             if (use_list) {
                 for (int c = tid; c < s_ncand; c += kSelThreads) {
                     const uint32_t k = cand[c];
-                    if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+                    if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & dmask], 1);
                 }
             } else {
                 int run_digit = -1, run_count = 0;
                 for_each_key([&](uint32_t k) {
                     if ((k & hi_mask) == prefix) {
-                        const int d = static_cast<int>((k >> shift) & 255u);
+                        const int d = static_cast<int>((k >> shift) & dmask);
                         if (d == run_digit) ++run_count;
                         else {
                             if (run_count) atomicAdd(&hist[run_digit], run_count);
@@ -588,23 +606,25 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
                 if (run_count) atomicAdd(&hist[run_digit], run_count);
             }
             __syncthreads();
-            // thread t < 256 looks at digit 255 - t; exclusive scan = keys with a larger digit
-            const int v = tid < 256 ? hist[255 - tid] : 0;
+            // thread t looks at digits bins-1-2t and bins-2-2t; exclusive scan = keys with a larger digit
+            const int d0 = bins - 1 - 2 * tid, d1 = d0 - 1;
+            const int v0 = d0 >= 0 ? hist[d0] : 0, v1 = d1 >= 0 ? hist[d1] : 0;
             int total = 0;
-            const int excl = block_exclusive_scan(v, scan_scratch, &total);
-            if (tid < 256 && excl < remaining && excl + v >= remaining) {
-                s_digit = 255 - tid;
-                s_remaining = remaining - excl;
-                s_count = v;
+            const int excl = block_exclusive_scan(v0 + v1, scan_scratch, &total);
+            if (excl < remaining && excl + v0 >= remaining) {
+                s_digit = d0; s_remaining = remaining - excl; s_count = v0;
+            } else if (excl + v0 < remaining && excl + v0 + v1 >= remaining) {
+                s_digit = d1; s_remaining = remaining - excl - v0; s_count = v1;
             }
             __syncthreads();
             prefix |= static_cast<uint32_t>(s_digit) << shift;
             remaining = s_remaining;
             count_equal = s_count;
-            if (round == 1 && count_equal <= kSelCand) {
-                // the keys that still match (top 16 bits fixed) move to the LDS list
+            if (!use_list && shift > 0 && count_equal <= kSelCand) {
+                // the keys that still match move to the LDS list for the remaining digits
+                const uint32_t fixed = 0xffffffffu << shift;
                 for_each_key([&](uint32_t k) {
-                    if ((k & 0xffff0000u) == prefix) cand[atomicAdd(&s_ncand, 1)] = k;
+                    if ((k & fixed) == prefix) cand[atomicAdd(&s_ncand, 1)] = k;
                 });
                 use_list = true;
             }
@@ -618,17 +638,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         sel_info[2 * seg] = tau;
         sel_info[2 * seg + 1] = static_cast<uint32_t>(remaining);
     }
-    // per-tile counts, tiles in groups of 64
+    // per-tile counts, tiles in groups of 64: lane i of a wave keeps the wave's counts of tile g0 + i
     for (int g0 = 0; g0 < n_tiles; g0 += 64) {
         if (tid < 128) cnt[tid >> 6][tid & 63] = 0;
         __syncthreads();
         const int g1 = min(n_tiles, g0 + 64);
+        int my_gt_count = 0, my_eq_count = 0;
         auto tile_body = [&](int i, bool is_member, uint32_t k) {
             const unsigned long long gt = __ballot(is_member && k > tau), eq = __ballot(is_member && k == tau);
-            if (lane == 0) {
-                if (gt) atomicAdd(&cnt[0][i - g0], __popcll(gt));
-                if (eq) atomicAdd(&cnt[1][i - g0], __popcll(eq));
-            }
+            if (lane == i - g0) { my_gt_count = __popcll(gt); my_eq_count = __popcll(eq); }
         };
         if (CACHED) {
 #pragma unroll
@@ -641,6 +659,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
                 tile_body(i, is_member, is_member ? ordered_key(scores[j]) : 0u);
             }
         }
+        if (my_gt_count) atomicAdd(&cnt[0][lane], my_gt_count);
+        if (my_eq_count) atomicAdd(&cnt[1][lane], my_eq_count);
         __syncthreads();
         if (tid < g1 - g0) { my_gt[g0 + tid] = cnt[0][tid]; my_eq[g0 + tid] = cnt[1][tid]; }
         __syncthreads();
