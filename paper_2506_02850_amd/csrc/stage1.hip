@@ -142,20 +142,33 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     const int tid = threadIdx.x;
 
     // per-frame totals: one wave per frame, lane c takes chunk partials c, c + 64, ...; the lane sums are
-    // combined by a fixed butterfly, so the result does not depend on timing
+    // combined by a fixed butterfly, so the result does not depend on timing.  A wave takes four frames at a
+    // time so that their loads are in flight together.
     {
+        constexpr int kWaves = kSegThreads / 64, kBatch = 4;
         const int lane = tid & 63, wave = tid >> 6;
-        for (int t = wave; t < T; t += kSegThreads / 64) {
-            float n2 = 0.f, dot = 0.f, fs = 0.f;
-            for (int c = lane; c < C; c += 64) {
-                const float* src = part + (static_cast<size_t>(t) * C + c) * 3;
-                n2 += src[0]; dot += src[1]; fs += src[2];
+        for (int tb = wave; tb < T; tb += kWaves * kBatch) {
+            float n2[kBatch], dot[kBatch], fs[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int t = tb + u * kWaves;
+                n2[u] = 0.f; dot[u] = 0.f; fs[u] = 0.f;
+                if (t < T) {
+                    for (int c = lane; c < C; c += 64) {
+                        const float* src = part + (static_cast<size_t>(t) * C + c) * 3;
+                        n2[u] += src[0]; dot[u] += src[1]; fs[u] += src[2];
+                    }
+                }
             }
-            n2 = wave_sum(n2); dot = wave_sum(dot); fs = wave_sum(fs);
-            if (lane == 0) {
-                frame_norm2[t] = n2;
-                pair_dot[t] = dot;
-                if (have_text && frame_score) frame_score[t] = fs / static_cast<float>(N);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int t = tb + u * kWaves;
+                const float a = wave_sum(n2[u]), b = wave_sum(dot[u]), c3 = wave_sum(fs[u]);
+                if (lane == 0 && t < T) {
+                    frame_norm2[t] = a;
+                    pair_dot[t] = b;
+                    if (have_text && frame_score) frame_score[t] = c3 / static_cast<float>(N);
+                }
             }
         }
     }
