@@ -190,6 +190,25 @@ def test_compress_shapes(grid, d, dtype, s1, s2, alpha, edge, reduce_, fused):
         compress_case(v, grid, k, alpha, 0.4, s1, s2, reduce_, edge, out_dtype, fused=fused)
 
 
+def test_maximum_frame_count():
+    """T = METOK_MAX_FRAMES: the one-workgroup kernels rank 8191 similarities / 8192 frames, eight per thread."""
+    B = mk()
+    T, grid, d, k = 8192, (2, 2), 64, 61
+    v = synth.planted_video(8192, T, grid, d, k, 1, T, 0.15, "bf16")
+    _, _, got = run_segment(v, k)
+    check_segment(v, k, got)
+    np.testing.assert_array_equal(got["event_start"], v.event_start)
+    compress_case(v, grid, k, 0.5, 0.45, 1, 2, O.EVENT_REDUCE_MEAN, O.POOL_FLOOR, "f32")
+    # every frame its own event: k = T, all T - 1 similarities are boundaries
+    feats = synth.to_torch(v.feats, v.dtype, "cuda")
+    out = B.metok_segment_events(feats, T)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out["event_start"].cpu().numpy(), np.arange(T + 1))
+    np.testing.assert_array_equal(out["frame_event"].cpu().numpy(), np.arange(T))
+    with pytest.raises(B.MetokError):
+        B.metok_segment_events(torch.zeros((T + 1, 4, 8), dtype=torch.float32, device="cuda"), 2)
+
+
 def test_argument_errors_are_reported():
     B = mk()
     feats = torch.zeros((4, 4, 64), dtype=torch.float32, device="cuda")
