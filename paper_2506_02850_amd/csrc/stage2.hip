@@ -65,8 +65,8 @@ struct ScoreGeom {
 // ---------------------------------------------------------------------------------------------
 // Both MFMA passes are query-stationary: wave w of a workgroup keeps the fragments of its own row
 // blocks (local blocks w, w + 8, ...) in registers for the whole kernel, and the workgroup streams its
-// contiguous range of keys through LDS, one stage of SUBS 32-key subtiles at a time, double buffered,
-// one barrier per stage.  A stage is stored in fragment order,
+// contiguous range of keys through LDS, one stage of SUBS 32-key subtiles at a time (kStageBuffers
+// stages in LDS, one barrier per stage).  A stage is stored in fragment order,
 //     kbuf[(sub * NCH + c) * 64 + lane],   lane = key % 32 + 32 * half,
 // so a wave reads the NCH fragments of a subtile with conflict-free 16-byte LDS reads and uses them
 // against every row block it owns.
@@ -486,17 +486,18 @@ struct Quotas { int32_t q[METOK_MAX_SEGMENTS]; };
 
 constexpr int kSelThreads = 1024;      // also the tile size of the selection: tile i = tokens [1024 i, 1024 i + 1024)
 constexpr int kSelCache = 40;          // keys per thread held in registers (n_vis <= 40960)
-constexpr int kSelCand = 4096;         // candidates kept in LDS once the top 16 key bits are fixed
+constexpr int kSelCand = 4096;         // candidates kept in an LDS list once the first digit is fixed
 
-// One workgroup per retention class.  Radix select (digits of up to 11 bits, starting at the highest bit in
-// which the keys of the class differ) of the quota-th
-// largest key of the class: the threshold key tau and the number of tokens equal to tau that are still
-// kept (sel_info[2 seg], [2 seg + 1]; 0x7fffffff = every one), then per 1024-token tile the number of
-// class members above tau (gt_count) and equal to it (eq_count).  The keep rule itself -- above tau, or
-// equal and among the first `remaining` equal ones by index -- is applied by write_index_kernel.  Thread t owns tokens t, t + 1024, ... (token i of a thread lies in tile
-// i); with CACHED their keys stay in registers.  Attention scores share their top key bits, so a
-// thread aggregates runs of equal digits before touching the LDS histogram, and once the first digit is
-// fixed the remaining candidates (if at most 4096) move to an LDS list for the other two digits.
+// One workgroup per retention class.  Radix select of the quota-th largest key of the class: digits of up
+// to 11 bits, starting at the highest bit in which the keys of the class differ.  Outputs: the threshold
+// key tau and the number of tokens equal to tau that are still kept (sel_info[2 seg], [2 seg + 1];
+// 0x7fffffff = every one), and per 1024-token tile the number of class members above tau (gt_count) and
+// equal to it (eq_count).  The keep rule itself -- above tau, or equal and among the first `remaining`
+// equal ones by index -- is applied by write_index_kernel.
+// Thread t owns tokens t, t + 1024, ... (token i of a thread lies in tile i); with CACHED their keys stay
+// in registers.  Attention scores share their top key bits, so a thread aggregates runs of equal digits
+// before touching the LDS histogram, and once the first digit is fixed the remaining candidates (if at
+// most kSelCand) move to an LDS list for the other digits.
 template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, const int32_t* __restrict__ token_seg,
                                                              int n_vis, int n_tiles, const Quotas quotas,
