@@ -1,4 +1,5 @@
-"""GPU parity at the full sizes of the named configurations, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the named configurations, one call at a time (the replayed 8-stream launch
+configuration of bench.py is covered by test_gpu_bench_configuration.py).
 
 Where the oracle finishes in seconds the whole output is compared; for the 17 GB KV cache sampled rows
 are checked one by one against the oracle's row copy, plus whole slabs for a few (layer, video, head)."""
