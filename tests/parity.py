@@ -21,7 +21,7 @@ def assert_rel(got, want, rtol, what, scale=None):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
-    ref = np.abs(want) if scale is None else np.full(want.shape, float(scale))
+    ref = np.abs(want) if scale is None else np.broadcast_to(np.asarray(scale, dtype=np.float64), want.shape)
     err = np.abs(got - want)
     bad = err > rtol * ref
     if bad.any():
@@ -29,6 +29,17 @@ def assert_rel(got, want, rtol, what, scale=None):
         raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} beyond rtol {rtol}; worst at {i}: "
                              f"got {got.ravel()[i]!r} want {want.ravel()[i]!r}")
     return float((err / np.maximum(ref, 1e-300)).max()) if err.size else 0.0
+
+
+def frame_score_scale(V, t):
+    """Per frame, the mean over its tokens of |cos(token, t)|: the magnitude of the N signed terms that
+    Eq. 5 averages.  The rounding error of a frame score is relative to this magnitude, not to the score
+    itself, which can cancel to orders of magnitude less.  A tolerance scale only, never an expected value."""
+    V = np.asarray(V, dtype=np.float64)
+    t = np.asarray(t, dtype=np.float64).reshape(-1)
+    den = np.linalg.norm(V, axis=2) * np.linalg.norm(t)
+    cos = np.divide(V @ t, den, out=np.zeros_like(den), where=den >= 1e-12)
+    return np.abs(cos).mean(axis=1)
 
 
 def assert_rows_close(got, want, rtol, what):
@@ -50,6 +61,21 @@ def bf16_ulp(x: np.ndarray) -> np.ndarray:
     x = np.abs(np.asarray(x, dtype=np.float64))
     _, e = np.frexp(np.maximum(x, 2.0 ** -126))
     return np.ldexp(1.0, e - 8)
+
+
+def assert_pooled_bf16(got, exact_mean, vmax, cells, what):
+    """bf16 output of the pooled merge: fp32 accumulation of `cells` inputs, one division, one rounding to
+    bf16.  The result lies within one bf16 ulp of the exact mean plus the fp32 accumulation error, which is at
+    most cells * 2^-24 * max|input| for the mean of `cells` sequential additions; that term only shows where
+    the inputs of a window cancel and the mean is orders of magnitude below them.  Apart from rare double
+    rounding flips (fp32 mean -> bf16 against fp64 mean -> bf16) the result equals the rounded exact mean."""
+    got = np.asarray(got, dtype=np.float64)
+    exact_mean = np.asarray(exact_mean, dtype=np.float64)
+    assert got.shape == exact_mean.shape, f"{what}: shape {got.shape} vs {exact_mean.shape}"
+    tol = bf16_ulp(exact_mean) + cells * 2.0 ** -24 * float(vmax)
+    err = np.abs(got - exact_mean)
+    assert (err <= tol).all(), f"{what}: pooled bf16 token further than one ulp (+ fp32 accumulation) from the exact mean"
+    return err
 
 
 def near_tie_report(scores_oracle: np.ndarray, token_seg: np.ndarray, quotas: Sequence[int],
