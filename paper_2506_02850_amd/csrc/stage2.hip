@@ -90,12 +90,16 @@ struct KeyStage {
             v[u] = *reinterpret_cast<const u32x4_t*>(k_head + static_cast<size_t>(j) * dh + (p / NCH) * (dh / 2) + (p % NCH) * CE);
         }
     }
+    // UNCHECKED_ROUNDS: rounds in which every thread of the workgroup owns a piece skip the bounds check,
+    // which keeps a branch out of the caller's loop body.
+    template <bool UNCHECKED_ROUNDS = false>
     static __device__ __forceinline__ void store(const u32x4_t (&v)[kPerThread], uint4* __restrict__ kbuf) {
 #pragma unroll
         for (int u = 0; u < kPerThread; ++u) {
             const int id = threadIdx.x + u * kScoreThreads;
             const int jl = id % kKeys, p = id / kKeys;
-            if (id < kSlots) reinterpret_cast<u32x4_t*>(kbuf)[((jl >> 5) * NCH + (p % NCH)) * 64 + (jl & 31) + 32 * (p / NCH)] = v[u];
+            if ((UNCHECKED_ROUNDS && (u + 1) * kScoreThreads <= kSlots) || id < kSlots)
+                reinterpret_cast<u32x4_t*>(kbuf)[((jl >> 5) * NCH + (p % NCH)) * 64 + (jl & 31) + 32 * (p / NCH)] = v[u];
         }
     }
 };
@@ -261,9 +265,13 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
 #pragma unroll
             for (int c = 0; c < NCH; ++c) kf0[c] = lds[c * 64 + lane];
             f32x16_t A = mma_chain<T, NCH>(kf0, q[0]), B;
+            // The body is branch-free so that the whole stage is one scheduling region: loads and stores
+            // that a conditional would skip are done anyway on clamped addresses (a stage is fetched twice,
+            // a free buffer is overwritten, the chain started for a stage that is not fast is dropped).
             for (; s < n_fast; ++s) {
                 const uint4* kbuf = stage_buf(s);
-                prefetch(s);
+                const int s2 = s + 2 < n_stage ? s + 2 : n_stage - 1;
+                Stage::load(kv, k_head, kb + static_cast<int64_t>(s2) * Stage::kKeys, g.S, g.dh);
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) kf1[c] = kbuf[(NCH + c) * 64 + lane];
                 __builtin_amdgcn_sched_barrier(0);
@@ -271,7 +279,7 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
                 softmax_step_full(A, g.scale_log2, m[0], l[0]);
                 interleave_mfma_valu<kMfmas, kValu>();
                 __builtin_amdgcn_sched_barrier(0);
-                if (s + 1 < n_fast) {       // subtile 0 of the next stage: published before the previous barrier
+                {   // subtile 0 of the next stage: published before the previous barrier
                     const uint4* knext = stage_buf(s + 1);
 #pragma unroll
                     for (int c = 0; c < NCH; ++c) kf0[c] = knext[c * 64 + lane];
@@ -285,15 +293,12 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
                 softmax_step_full(A, g.scale_log2, m[0], l[0]);
                 interleave_mfma_valu<kMfmas, kValu>();
                 __builtin_amdgcn_sched_barrier(0);
-                publish(s);
-                if (s + 1 < n_fast) {
-                    A = mma_chain<T, NCH>(kf0, q[0]);
-                    softmax_step_full(B, g.scale_log2, m[1], l[1]);
-                    interleave_mfma_valu<kMfmas, kValu>();
-                    __builtin_amdgcn_sched_barrier(0);
-                } else {
-                    softmax_step_full(B, g.scale_log2, m[1], l[1]);
-                }
+                Stage::template store<true>(kv, stage_buf(s + 2));
+                __syncthreads();
+                A = mma_chain<T, NCH>(kf0, q[0]);
+                softmax_step_full(B, g.scale_log2, m[1], l[1]);
+                interleave_mfma_valu<kMfmas, kValu>();
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
