@@ -60,6 +60,35 @@ enum { METOK_POOL_FLOOR = 0, METOK_POOL_CEIL = 1 };/* output side floor(g/s) or 
 #define METOK_MAX_SEGMENTS 256    /* n_seg limit of metok_prefill_prune */
 #define METOK_MAX_LAYERS 128      /* L limit of metok_kv_compact */
 
+/*
+ * The method's hyperparameters for one base model (Appendix "Implementation Details"; frame counts from
+ * Sec. 4 "Implementation Details").  A plain record: the calls below take the individual values.
+ *   frames     frames sampled per video          n_layers   transformer layers of the LLM
+ *   k          events (Sec. 3.2.1)               layers_h   L_H = [l_1, l_2, l_3], 0-based (Sec. 3.2.2)
+ *   alpha      key-event ratio                   beta       key-frame ratio inside an event
+ *   s1, s2     pooling strides of key / non-key frames in key events
+ *   r          retention ratio of Eq. 6-7
+ */
+typedef struct metok_params {
+    int32_t frames;
+    int32_t n_layers;
+    int32_t k;
+    int32_t s1, s2;
+    int32_t layers_h[3];
+    double alpha, beta, r;
+} metok_params;
+
+/* Initialisers in field order: frames, n_layers, k, s1, s2, {l_1, l_2, l_3}, alpha, beta, r. */
+#define METOK_PRESET_LLAVA_OV_0_5B { 32, 24, 5, 2, 3, {3, 10, 19}, 0.5, 0.4, 0.76 }
+#define METOK_PRESET_LLAVA_OV_7B   { 32, 28, 5, 2, 3, {3, 10, 19}, 0.5, 0.4, 0.76 }
+#define METOK_PRESET_LONGVA_7B     { 128, 28, 13, 2, 3, {3, 10, 19}, 0.5, 0.45, 0.55 }
+#define METOK_PRESET_VILA_13B      { 16, 40, 3, 2, 3, {13, 24, 34}, 0.5, 0.4, 0.65 }
+
+enum { METOK_MODEL_LLAVA_OV_0_5B = 0, METOK_MODEL_LLAVA_OV_7B = 1, METOK_MODEL_LONGVA_7B = 2, METOK_MODEL_VILA_13B = 3 };
+
+/* Copies the preset of METOK_MODEL_* into *out (for callers that cannot use the initialiser macros). */
+METOK_API int metok_preset(int model, metok_params* out);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 METOK_API const char* metok_last_error(void);
 
@@ -130,6 +159,10 @@ METOK_API int metok_segment_events(const void* feats, int dtype, int T, int N, i
  *   frame_score_out device out, [T] float or NULL (copy of the scores used).
  * ------------------------------------------------------------------------------------------- */
 METOK_API size_t metok_compress_encoder_tokens_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype);
+
+/* Rows that out_tokens / token_event must hold for these settings (the worst case over all segmentations:
+ * every frame pooled with the smaller of s1, s2), or -1 for arguments the call would reject. */
+METOK_API int64_t metok_compress_encoder_tokens_capacity_rows(int T, int grid_h, int grid_w, int s1, int s2, int pool_edge);
 
 METOK_API int metok_compress_encoder_tokens(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
                                   const void* text_emb, const float* frame_score_in,

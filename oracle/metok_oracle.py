@@ -30,7 +30,7 @@ F64 = np.float64
 ZERO_NORM = 1e-12          # a cosine whose denominator is below this is defined as 0
 CEIL_SLACK = 1e-9          # ceil(x - 1e-9): keeps 0.55 * 20 = 11.000000000000002 at 11
 
-EVENT_REDUCE_MEAN = 0      # Sec. 3.2.1 text: "average these scores per event"
+EVENT_REDUCE_MEAN = 0      # Sec. 3.2.1: the event score is the mean of its frames' scores
 EVENT_REDUCE_MAX = 1       # Algorithm 1: r_j = max over the event's frames
 SIM_FLAT = 0               # Eq. 4 over all N*d entries of the two frames
 SIM_TOKEN_MEAN = 1         # mean over the N token positions of the cosine of matching tokens

@@ -30,6 +30,7 @@ EXPORTS = [
     "metok_retention_quotas", "metok_account",
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
     "metok_kv_compact", "metok_kv_compact_paged", "metok_calib_copy",
+    "metok_preset", "metok_compress_encoder_tokens_capacity_rows",
 ]
 
 
@@ -38,6 +39,15 @@ class AccountStruct(ctypes.Structure):
                 ("tokens_non", ctypes.c_int64), ("level_tokens", ctypes.c_int64 * 4),
                 ("prefill_token_layers", ctypes.c_int64), ("kv_token_layers_full", ctypes.c_int64),
                 ("kv_token_layers_stage2", ctypes.c_int64), ("kv_token_layers_stage3", ctypes.c_int64)]
+
+
+class ParamsStruct(ctypes.Structure):
+    _fields_ = [("frames", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("k", ctypes.c_int32), ("s1", ctypes.c_int32),
+                ("s2", ctypes.c_int32), ("layers_h", ctypes.c_int32 * 3), ("alpha", ctypes.c_double),
+                ("beta", ctypes.c_double), ("r", ctypes.c_double)]
+
+
+MODEL_LLAVA_OV_0_5B, MODEL_LLAVA_OV_7B, MODEL_LONGVA_7B, MODEL_VILA_13B = 0, 1, 2, 3
 
 
 class MetokError(RuntimeError):
@@ -88,6 +98,10 @@ def _load() -> ctypes.CDLL:
                                            c.POINTER(vp), c.POINTER(c.c_int32), vp, vp]
     lib.metok_calib_copy.restype = i32
     lib.metok_calib_copy.argtypes = [vp, vp, sz, vp]
+    lib.metok_preset.restype = i32
+    lib.metok_preset.argtypes = [i32, c.POINTER(ParamsStruct)]
+    lib.metok_compress_encoder_tokens_capacity_rows.restype = i64
+    lib.metok_compress_encoder_tokens_capacity_rows.argtypes = [i32, i32, i32, i32, i32, i32]
     return lib
 
 
@@ -176,10 +190,19 @@ def metok_segment_events(feats: torch.Tensor, k: int, text_emb: Optional[torch.T
     return res
 
 
-def pooled_capacity(T: int, grid_h: int, grid_w: int, s1: int, s2: int, pool_edge: int = POOL_FLOOR) -> int:
-    s = max(1, min(min(s1, s2), max(grid_h, grid_w)))
-    side = (lambda g: max(1, g // s)) if pool_edge == POOL_FLOOR else (lambda g: -(-g // s))
-    return T * side(grid_h) * side(grid_w)
+def metok_compress_encoder_tokens_capacity_rows(T: int, grid_h: int, grid_w: int, s1: int, s2: int,
+                                                pool_edge: int = POOL_FLOOR) -> int:
+    rows = int(_lib.metok_compress_encoder_tokens_capacity_rows(int(T), int(grid_h), int(grid_w), int(s1), int(s2), int(pool_edge)))
+    if rows < 0:
+        raise ValueError("metok_compress_encoder_tokens_capacity_rows: arguments out of range")
+    return rows
+
+
+def metok_preset(model: int) -> Dict[str, object]:
+    out = ParamsStruct()
+    _check(_lib.metok_preset(int(model), ctypes.byref(out)))
+    return dict(frames=out.frames, n_layers=out.n_layers, k=out.k, s1=out.s1, s2=out.s2,
+                layers_h=[int(x) for x in out.layers_h], alpha=out.alpha, beta=out.beta, r=out.r)
 
 
 def metok_compress_encoder_tokens(feats: torch.Tensor, grid_h: int, grid_w: int, event_start: torch.Tensor,
@@ -201,7 +224,7 @@ def metok_compress_encoder_tokens(feats: torch.Tensor, grid_h: int, grid_w: int,
     dev = feats.device
     k = event_start.numel() - 1
     odt = out_dtype if out_dtype is not None else feats.dtype
-    cap = pooled_capacity(T, grid_h, grid_w, s1, s2, pool_edge)
+    cap = metok_compress_encoder_tokens_capacity_rows(T, grid_h, grid_w, s1, s2, pool_edge)
     if out_tokens is None and out is not None:
         out_tokens = out.get("out_tokens")
     if out_tokens is None:
@@ -240,7 +263,7 @@ def metok_segment_compress(feats: torch.Tensor, grid_h: int, grid_w: int, k: int
     dt = _dtype_code(feats)
     dev = feats.device
     odt = out_dtype if out_dtype is not None else feats.dtype
-    cap = pooled_capacity(T, grid_h, grid_w, s1, s2, pool_edge)
+    cap = metok_compress_encoder_tokens_capacity_rows(T, grid_h, grid_w, s1, s2, pool_edge)
     out_tokens = out.get("out_tokens") if out is not None else None
     if out_tokens is None:
         out_tokens = torch.empty((cap, d), dtype=odt, device=dev)
@@ -335,13 +358,13 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
     token_event_out = _out(out, "token_event_out", total, torch.int32, dev) if token_event is not None else None
     orig_idx_out = _out(out, "orig_idx_out", total, torch.int32, dev)
     n_events = int(event_weight.numel()) if event_weight is not None else 0
-    _check(_lib.metok_prefill_prune(
-        _dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
-        int(score_mode), int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
-        _dev(event_weight, "event_weight"), n_events, n_seg, quota_arr, _dev(orig_idx, "orig_idx"),
-        _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), _dev(hidden_out, "hidden_out"),
-        _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
-        _dev(orig_idx_out, "orig_idx_out"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    args = [_dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
+            int(score_mode), int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
+            _dev(event_weight, "event_weight"), n_events, n_seg, quota_arr, _dev(orig_idx, "orig_idx"),
+            _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), _dev(hidden_out, "hidden_out"),
+            _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
+            _dev(orig_idx_out, "orig_idx_out")]
+    _check(_lib.metok_prefill_prune(*args, _dev(ws, "workspace"), ws.numel(), _stream()))
     res = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
                orig_idx_out=orig_idx_out)
     if token_event_out is not None:

@@ -44,6 +44,17 @@ extern "C" const char* metok_last_error(void) { return error_buffer(); }
 
 extern "C" int metok_version(void) { return 100; }
 
+extern "C" int metok_preset(int model, metok_params* out) {
+    clear_error();
+    // Appendix "Implementation Details": one setting per base model
+    static const metok_params presets[4] = {METOK_PRESET_LLAVA_OV_0_5B, METOK_PRESET_LLAVA_OV_7B, METOK_PRESET_LONGVA_7B,
+                                            METOK_PRESET_VILA_13B};
+    if (!out) return fail(METOK_ERR_INVALID_ARG, "out is NULL");
+    if (model < 0 || model > 3) return fail(METOK_ERR_INVALID_ARG, "unknown model %d", model);
+    *out = presets[model];
+    return METOK_OK;
+}
+
 extern "C" int metok_retention_quotas(int level, double r, double alpha, int64_t n_key_orig, int64_t n_non_orig,
                                       int32_t quota_out[2]) {
     clear_error();

@@ -711,6 +711,22 @@ extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, 
     return check_launch("segment");
 }
 
+// Pooled rows when every frame takes the smaller of the two strides (s / alpha >= s, so no frame yields more).
+static int64_t worst_case_rows(int T, int grid_h, int grid_w, int s1, int s2, int pool_edge) {
+    const int gmax = grid_h > grid_w ? grid_h : grid_w;
+    int s_min = s1 < s2 ? s1 : s2;
+    s_min = s_min < 1 ? 1 : (s_min > gmax ? gmax : s_min);
+    auto side = [&](int g) { return pool_edge == METOK_POOL_FLOOR ? (g / s_min > 1 ? g / s_min : 1) : (g + s_min - 1) / s_min; };
+    return static_cast<int64_t>(T) * side(grid_h) * side(grid_w);
+}
+
+extern "C" int64_t metok_compress_encoder_tokens_capacity_rows(int T, int grid_h, int grid_w, int s1, int s2, int pool_edge) {
+    if (T < 1 || T > METOK_MAX_FRAMES || grid_h < 1 || grid_w < 1 || static_cast<int64_t>(grid_h) * grid_w > (1 << 24) || s1 < 1 || s2 < 1 ||
+        (pool_edge != METOK_POOL_FLOOR && pool_edge != METOK_POOL_CEIL))
+        return -1;
+    return worst_case_rows(T, grid_h, grid_w, s1, s2, pool_edge);
+}
+
 extern "C" size_t metok_compress_encoder_tokens_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype) {
     StatsPlan p;
     if (T < 1 || grid_h < 1 || grid_w < 1 || d < 1 || !plan_stats(T, grid_h * grid_w, d, dtype, &p)) return 0;
@@ -757,9 +773,7 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
     auto clamp_stride = [&](double s) { int v = ceil_ratio(s); return v < 1 ? 1 : (v > gmax ? gmax : v); };
     const int s_key_kf = clamp_stride(s1), s_key_nf = clamp_stride(s2);
     const int s_non_kf = clamp_stride(s1 / alpha), s_non_nf = clamp_stride(s2 / alpha);
-    const int s_min = s_key_kf < s_key_nf ? s_key_kf : s_key_nf;      // s/alpha >= s
-    auto side = [&](int g) { return pool_edge == METOK_POOL_FLOOR ? (g / s_min > 1 ? g / s_min : 1) : (g + s_min - 1) / s_min; };
-    const int64_t worst = static_cast<int64_t>(T) * side(grid_h) * side(grid_w);
+    const int64_t worst = worst_case_rows(T, grid_h, grid_w, s1, s2, pool_edge);
     if (out_capacity_rows < worst)
         return fail(METOK_ERR_CAPACITY, "out_capacity_rows = %lld, worst case needs %lld", (long long)out_capacity_rows, (long long)worst);
     if (worst > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pooled row count must fit int32");

@@ -205,7 +205,7 @@ constexpr int kStageBuffers = 3;       // LDS stages: one in use, one ready (its
 // visible to every query as one software pipeline over the blocks (subtile, row block): the MFMA chain
 // of block b + 1 is interleaved with the softmax arithmetic of block b, also across the barrier, and the
 // fragments of the next stage's first subtile are read from LDS as soon as their registers are free.
-// Stages that need the mask, and waves with a single row block, take the plain path.
+// Stages that need the mask, and workgroups with fewer row blocks than waves, take the plain path.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int NCH, int RBW, int SUBS>
 __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* __restrict__ qfrag, const T* __restrict__ k_all,
@@ -253,8 +253,11 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
     int s = 0;
     if constexpr (RBW == 2 && SUBS == 2) {
         // leading stages whose 64 keys are all visible to every query
+        // The choice is the same for every wave of the workgroup (all waves must meet at the same barriers):
+        // with at least one row block per wave, waves that own a single block run the second chain on the
+        // zero fragments load_qfrag gave them; its statistics belong to a padding row and are ignored.
         int n_fast = 0;
-        if (nrb_w == 2) {
+        if (nrb >= kScoreWaves) {
             const int64_t f = (full_end - kb) / Stage::kKeys;
             n_fast = f < 0 ? 0 : (f > n_stage ? n_stage : static_cast<int>(f));
         }

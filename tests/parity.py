@@ -6,6 +6,11 @@ Tolerances (stated by the task definition, restated here so that the tests are s
   * boundaries, index sets and gathered tensors: bit-exact, where index sets are compared outside a
     band of relative width 1e-3 around the selection threshold; disagreements inside the band are
     reported, never silent.
+
+The named configurations and the bench configuration are held to exactly these bars (frame scores relative
+to the oracle's own value, bf16 merged features within one ulp).  Random sweeps draw inputs whose signed
+terms can cancel to a result orders of magnitude below the terms; only there the error is measured against
+the magnitude of the terms (frame_score_scale, assert_pooled_bf16).
 """
 from __future__ import annotations
 
@@ -75,6 +80,17 @@ def assert_pooled_bf16(got, exact_mean, vmax, cells, what):
     tol = bf16_ulp(exact_mean) + cells * 2.0 ** -24 * float(vmax)
     err = np.abs(got - exact_mean)
     assert (err <= tol).all(), f"{what}: pooled bf16 token further than one ulp (+ fp32 accumulation) from the exact mean"
+    return err
+
+
+def assert_pooled_bf16_strict(got, exact_mean, what):
+    """The plain bar for a bf16 merged feature: within one bf16 ulp of the exact mean.  Used on the named
+    configurations, whose windows do not cancel; the random sweeps use assert_pooled_bf16."""
+    got = np.asarray(got, dtype=np.float64)
+    exact_mean = np.asarray(exact_mean, dtype=np.float64)
+    assert got.shape == exact_mean.shape, f"{what}: shape {got.shape} vs {exact_mean.shape}"
+    err = np.abs(got - exact_mean)
+    assert (err <= bf16_ulp(exact_mean)).all(), f"{what}: pooled bf16 token further than one ulp from the exact mean"
     return err
 
 

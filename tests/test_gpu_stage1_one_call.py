@@ -8,7 +8,8 @@ import torch
 
 from oracle import metok_oracle as O
 from paper_2506_02850_amd import synth
-from tests.parity import RTOL, assert_pooled_bf16, assert_rel, assert_rows_close, frame_score_scale
+from tests.parity import (RTOL, assert_pooled_bf16, assert_pooled_bf16_strict, assert_rel, assert_rows_close,
+                          frame_score_scale)
 
 pytestmark = pytest.mark.gpu
 
@@ -32,7 +33,8 @@ def run_both(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, red
     return one, seg, two
 
 
-def check(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce_=0, expect_strides=None):
+def check(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce_=0, expect_strides=None, strict=False):
+    """strict: the named configurations, held to the plain bars (see tests/parity.py)."""
     one, seg, two = run_both(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode, edge, reduce_)
     rtol = RTOL[v.dtype]
     got = {n: (t.float() if t.dtype == torch.bfloat16 else t).cpu().numpy() for n, t in one.items()}
@@ -43,14 +45,15 @@ def check(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce
     es, fe = O.event_boundaries(S, k)
     np.testing.assert_array_equal(got["event_start"], es)
     np.testing.assert_array_equal(got["frame_event"], fe)
-    assert_rel(got["frame_score"], O.frame_text_score(v.feats, v.text_emb), rtol, "frame_score",
-               scale=frame_score_scale(v.feats, v.text_emb))
+    f_or = O.frame_text_score(v.feats, v.text_emb)
+    assert_rel(got["frame_score"], f_or, rtol, "frame_score", scale=None if strict else frame_score_scale(v.feats, v.text_emb))
     # plan re-derived by the oracle from the GPU's own frame scores, pooled tokens against the exact means
     ref = O.compress_encoder_tokens(v.feats, grid, None, es, alpha, beta, s1, s2, reduce_, edge,
                                     frame_score=got["frame_score"].astype(np.float64))
     for name in ("event_is_key", "frame_is_key", "frame_stride", "frame_offsets"):
         np.testing.assert_array_equal(got[name], ref[name], err_msg=name)
-    assert_rel(got["event_score"], ref["event_score"], 1e-5, "event_score", scale=np.abs(got["frame_score"]).max())
+    # ref's event scores are the oracle's reduction of the GPU's own frame scores: only the reduction differs
+    assert_rel(got["event_score"], ref["event_score"], 1e-5, "event_score", scale=np.abs(f_or).max())
     M = int(ref["frame_offsets"][-1])
     np.testing.assert_array_equal(got["token_event"][:M], ref["token_event"])
     tokens = got["out_tokens"][:M]
@@ -58,7 +61,10 @@ def check(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce
         assert_rows_close(tokens, ref["tokens"], rtol, "pooled tokens")
     else:
         cells = int(ref["frame_stride"].max()) ** 2
-        assert_pooled_bf16(tokens, ref["tokens"], np.abs(v.feats).max(), cells, "pooled tokens")
+        if strict:
+            assert_pooled_bf16_strict(tokens, ref["tokens"], "pooled tokens")
+        else:
+            assert_pooled_bf16(tokens, ref["tokens"], np.abs(v.feats).max(), cells, "pooled tokens")
         assert float((tokens.astype(np.float64) != O.round_to_bf16(ref["tokens"])).mean()) < 1e-3
     if expect_strides is not None:
         assert set(got["frame_stride"].tolist()) <= set(expect_strides)
@@ -76,7 +82,7 @@ def check(v, grid, k, alpha, beta, s1, s2, out_dtype, sim_mode=0, edge=0, reduce
 def test_uniform_stride_two_encoder_config(out_dtype):
     # 32 x 576 x 1024 bf16, 8 events: 144 tokens per frame out of the statistics pass
     sh = synth.ENCODER
-    got = check(synth.video_for(sh), sh.grid, sh.n_events, 1.0, 1.0, 2, 2, out_dtype, expect_strides={2})
+    got = check(synth.video_for(sh), sh.grid, sh.n_events, 1.0, 1.0, 2, 2, out_dtype, expect_strides={2}, strict=True)
     np.testing.assert_array_equal(got["frame_offsets"], 144 * np.arange(33))
     np.testing.assert_array_equal(got["event_start"], synth.video_for(sh).event_start)
 
@@ -106,7 +112,7 @@ def test_one_call_falls_back_to_two_passes(case):
         assert int(got["frame_offsets"][-1]) == 6 * 169
     elif case == "adaptive":          # the paper's LongVA setting
         v = synth.video_for(synth.ENCODER)
-        check(v, (24, 24), 8, 0.5, 0.45, 2, 3, "bf16", expect_strides={2, 3, 4, 6})
+        check(v, (24, 24), 8, 0.5, 0.45, 2, 3, "bf16", expect_strides={2, 3, 4, 6}, strict=True)
     elif case == "token mean":
         v = synth.planted_video(32, 8, (4, 4), 64, 3, 1, 8, 0.15, "f32")
         check(v, (4, 4), 3, 1.0, 1.0, 2, 2, "f32", sim_mode=O.SIM_TOKEN_MEAN)
@@ -122,7 +128,7 @@ def test_one_call_at_256_frames_and_errors():
     B = mk()
     sh = synth.ENCODER_256
     v = synth.video_for(sh)
-    got = check(v, sh.grid, sh.n_events, 1.0, 1.0, 2, 2, "bf16", expect_strides={2})
+    got = check(v, sh.grid, sh.n_events, 1.0, 1.0, 2, 2, "bf16", expect_strides={2}, strict=True)
     assert int(got["frame_offsets"][-1]) == 256 * 144
     feats = torch.zeros((4, 16, 64), dtype=torch.float32, device="cuda")
     text = torch.ones(64, device="cuda")

@@ -33,7 +33,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert len(names) == 15 and len(set(names)) == len(names)
+    assert len(names) == 17 and len(set(names)) == len(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
     from paper_2506_02850_amd import binding
@@ -158,6 +158,64 @@ def test_argument_errors_before_any_launch(lib):
     copy = lib.metok_calib_copy
     copy.argtypes = [vp, vp, sz, vp]
     assert copy(fake, fake, 24, None) == -1
+
+
+def test_presets_hold_the_appendix_settings(tmp_path):
+    """Appendix "Implementation Details": (s1, s2) = (2, 3) and alpha = 0.5 everywhere; L_H = [3, 10, 19] for the Qwen-based
+    models, [13, 24, 34] for VILA; k / beta / r = 5 / 0.4 / 0.76 (LLaVA-OneVision), 13 / 0.45 / 0.55 (LongVA),
+    3 / 0.4 / 0.65 (VILA); 24 / 28 / 28 / 40 layers; 32 / 32 / 128 / 16 frames."""
+    from paper_2506_02850_amd import binding as B
+    from paper_2506_02850_amd import synth
+    want = {
+        B.MODEL_LLAVA_OV_0_5B: dict(frames=32, n_layers=24, k=5, s1=2, s2=3, layers_h=[3, 10, 19], alpha=0.5, beta=0.4, r=0.76),
+        B.MODEL_LLAVA_OV_7B: dict(frames=32, n_layers=28, k=5, s1=2, s2=3, layers_h=[3, 10, 19], alpha=0.5, beta=0.4, r=0.76),
+        B.MODEL_LONGVA_7B: dict(frames=128, n_layers=28, k=13, s1=2, s2=3, layers_h=[3, 10, 19], alpha=0.5, beta=0.45, r=0.55),
+        B.MODEL_VILA_13B: dict(frames=16, n_layers=40, k=3, s1=2, s2=3, layers_h=[13, 24, 34], alpha=0.5, beta=0.4, r=0.65),
+    }
+    for model, params in want.items():
+        assert B.metok_preset(model) == params
+    with pytest.raises(B.MetokError):
+        B.metok_preset(4)
+    # the shapes the chained model tests run are these presets
+    ov, vila = B.metok_preset(B.MODEL_LLAVA_OV_7B), B.metok_preset(B.MODEL_VILA_13B)
+    for sh, pr in ((synth.OV_7B, ov), (synth.VILA_13B, vila)):
+        assert (sh.n_events, sh.n_layers, list(sh.L_H)) == (pr["k"], pr["n_layers"], pr["layers_h"])
+        assert (sh.extra["alpha"], sh.extra["beta"], sh.extra["r"], sh.extra["s1"], sh.extra["s2"]) == (
+            pr["alpha"], pr["beta"], pr["r"], pr["s1"], pr["s2"])
+    # the header is plain C and the initialiser macros agree with metok_preset(): compile and run a C program
+    src = tmp_path / "presets.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "metok.h"\n'
+        "int main(void) {\n"
+        "  const metok_params p[4] = {METOK_PRESET_LLAVA_OV_0_5B, METOK_PRESET_LLAVA_OV_7B, METOK_PRESET_LONGVA_7B, METOK_PRESET_VILA_13B};\n"
+        "  for (int i = 0; i < 4; ++i) printf(\"%d %d %d %d %d %d %d %d %.2f %.2f %.2f\\n\", p[i].frames, p[i].n_layers, p[i].k, p[i].s1,\n"
+        "    p[i].s2, p[i].layers_h[0], p[i].layers_h[1], p[i].layers_h[2], p[i].alpha, p[i].beta, p[i].r);\n"
+        "  return 0; }\n")
+    exe = tmp_path / "presets"
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    lines = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.strip().splitlines()
+    for model, line in enumerate(lines):
+        pr = want[model]
+        assert line == "%d %d %d %d %d %d %d %d %.2f %.2f %.2f" % (pr["frames"], pr["n_layers"], pr["k"], pr["s1"], pr["s2"],
+                                                                     *pr["layers_h"], pr["alpha"], pr["beta"], pr["r"])
+
+
+def test_capacity_rows_is_the_worst_case_of_the_pooling_plan():
+    from paper_2506_02850_amd import binding as B
+    cap = B.metok_compress_encoder_tokens_capacity_rows
+    assert cap(32, 24, 24, 2, 3) == 32 * 144                       # every frame a key frame of a key event
+    assert cap(32, 27, 27, 2, 3, B.POOL_FLOOR) == 32 * 169 and cap(32, 27, 27, 2, 3, B.POOL_CEIL) == 32 * 196
+    assert cap(8, 4, 4, 9, 7) == 8                                  # strides clamp to the grid: one token per frame
+    rng = np.random.Generator(np.random.PCG64(11))
+    for _ in range(100):
+        T, gh, gw = int(rng.integers(1, 50)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        s1, s2, edge = int(rng.integers(1, 7)), int(rng.integers(1, 7)), int(rng.integers(0, 2))
+        # the oracle's row count of a frame pooled with the smaller stride, for every frame
+        s = min(max(min(s1, s2), 1), max(gh, gw))
+        assert cap(T, gh, gw, s1, s2, edge) == T * O.pooled_side(gh, s, edge) * O.pooled_side(gw, s, edge)
+    with pytest.raises(ValueError):
+        cap(0, 4, 4, 2, 2)
 
 
 def test_binding_refuses_cpu_tensors():
