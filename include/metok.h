@@ -287,6 +287,33 @@ METOK_API int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtyp
                         int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * metok_prefill_prune without a workspace argument, for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the scratch
+ * memory is a fixed METOK_STATIC_SCRATCH_BYTES array inside the library's device image (every GPU the
+ * library runs on holds one copy until the process ends).  Arguments, results and errors are those of
+ * metok_prefill_prune; the call allocates nothing and launches the same kernels.
+ *   - Shapes whose metok_prefill_prune_workspace_bytes() exceeds METOK_STATIC_SCRATCH_BYTES are refused
+ *     with METOK_ERR_WORKSPACE before anything is enqueued.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *     streams or threads) race on it; serialise them or use metok_prefill_prune.  Nothing in the array
+ *     has to survive between calls and nothing has to be cleared: every kernel writes what it reads.
+ */
+#define METOK_STATIC_SCRATCH_BYTES (8u << 20)
+
+METOK_API size_t metok_static_scratch_bytes(void);
+
+METOK_API int metok_prefill_prune_static(const void* hidden, int64_t S, int D, int dtype,
+                               const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                               int score_mode, int vis_start, int n_vis,
+                               const int32_t* token_seg, const int32_t* token_event,
+                               const float* event_weight, int n_events,
+                               int n_seg, const int32_t* seg_quota,
+                               const int32_t* orig_idx_in,
+                               float* scores, int32_t* kept_idx, void* hidden_out,
+                               int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                               void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Stage 3 -- KV-cache compaction to the retained rows (Sec. 3.3), in place.
  *

@@ -31,6 +31,7 @@ EXPORTS = [
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
     "metok_kv_compact", "metok_kv_compact_paged", "metok_calib_copy",
     "metok_preset", "metok_compress_encoder_tokens_capacity_rows",
+    "metok_static_scratch_bytes", "metok_prefill_prune_static",
 ]
 
 
@@ -102,6 +103,10 @@ def _load() -> ctypes.CDLL:
     lib.metok_preset.argtypes = [i32, c.POINTER(ParamsStruct)]
     lib.metok_compress_encoder_tokens_capacity_rows.restype = i64
     lib.metok_compress_encoder_tokens_capacity_rows.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.metok_static_scratch_bytes.restype = sz
+    lib.metok_static_scratch_bytes.argtypes = []
+    lib.metok_prefill_prune_static.restype = i32
+    lib.metok_prefill_prune_static.argtypes = lib.metok_prefill_prune.argtypes[:-3] + [vp]
     return lib
 
 
@@ -324,8 +329,9 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
                         hidden_out: Optional[torch.Tensor] = None,
                         workspace: Optional[torch.Tensor] = None,
                         out: Optional[Dict[str, torch.Tensor]] = None,
-                        score_mode: int = 0) -> Dict[str, torch.Tensor]:
-    """One pruning level.  With q_text/k_all the attention scores are computed; otherwise `scores` is used as given."""
+                        score_mode: int = 0, static_scratch: bool = False) -> Dict[str, torch.Tensor]:
+    """One pruning level.  With q_text/k_all the attention scores are computed; otherwise `scores` is used as given.
+    static_scratch=True calls metok_prefill_prune_static (no workspace argument)."""
     S, D = hidden.shape
     dt = _dtype_code(hidden)
     dev = hidden.device
@@ -344,8 +350,11 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
         if scores is None:
             raise ValueError("either q_text/k_all or scores must be given")
         Hq = Hkv = dh = Tq = 0
-    need = _lib.metok_prefill_prune_workspace_bytes(S, Hq, Hkv, dh, Tq, n_vis, dt)
-    ws = workspace if workspace is not None else _workspace(need, dev)
+    if static_scratch:
+        ws = None
+    else:
+        need = _lib.metok_prefill_prune_workspace_bytes(S, Hq, Hkv, dh, Tq, n_vis, dt)
+        ws = workspace if workspace is not None else _workspace(need, dev)
     kept_idx = _out(out, "kept_idx", total, torch.int32, dev)
     out_rows = S - n_vis + total
     if hidden_out is None and out is not None:
@@ -364,7 +373,10 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
             _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), _dev(hidden_out, "hidden_out"),
             _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
             _dev(orig_idx_out, "orig_idx_out")]
-    _check(_lib.metok_prefill_prune(*args, _dev(ws, "workspace"), ws.numel(), _stream()))
+    if static_scratch:
+        _check(_lib.metok_prefill_prune_static(*args, _stream()))
+    else:
+        _check(_lib.metok_prefill_prune(*args, _dev(ws, "workspace"), ws.numel(), _stream()))
     res = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
                orig_idx_out=orig_idx_out)
     if token_event_out is not None:
@@ -437,6 +449,15 @@ def new_len_dummy(dev) -> torch.Tensor:
     if key not in _DUMMY:
         _DUMMY[key] = torch.zeros(4, dtype=torch.int32, device=dev)
     return _DUMMY[key]
+
+
+def metok_prefill_prune_static(*a, **kw) -> Dict[str, torch.Tensor]:
+    """metok_prefill_prune on the library's static scratch array (nothing is allocated for the workspace)."""
+    return metok_prefill_prune(*a, static_scratch=True, **kw)
+
+
+def metok_static_scratch_bytes() -> int:
+    return int(_lib.metok_static_scratch_bytes())
 
 
 def metok_calib_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

@@ -17,6 +17,8 @@
 // registers and the workgroup streams its range of keys through LDS.  The contraction index may be
 // permuted freely as long as both operands agree; here lane half h = lane/32 owns the contiguous half h
 // of the head dimension, so every fragment is a contiguous 16-byte chunk of a row.
+#include <mutex>
+
 #include "common.h"
 
 namespace metok {
@@ -899,17 +901,18 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
     return select_bytes(n_vis);      // selection scratch only (scores supplied by the caller)
 }
 
-extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
-                                   const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
-                                   int score_mode, int vis_start, int n_vis,
-                                   const int32_t* token_seg, const int32_t* token_event,
-                                   const float* event_weight, int n_events,
-                                   int n_seg, const int32_t* seg_quota,
-                                   const int32_t* orig_idx_in,
-                                   float* scores, int32_t* kept_idx, void* hidden_out,
-                                   int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
-    clear_error();
+// Shared body of metok_prefill_prune and metok_prefill_prune_static: `workspace` is the caller's buffer or
+// the library's static scratch array; nothing below allocates.
+static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
+                      const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                      int score_mode, int vis_start, int n_vis,
+                      const int32_t* token_seg, const int32_t* token_event,
+                      const float* event_weight, int n_events,
+                      int n_seg, const int32_t* seg_quota,
+                      const int32_t* orig_idx_in,
+                      float* scores, int32_t* kept_idx, void* hidden_out,
+                      int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
     if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
     if (S < 1 || S > INT32_MAX || D < 1) return fail(METOK_ERR_INVALID_ARG, "S must be in [1, 2^31) and D positive");
     if (vis_start < 0 || n_vis < 1 || static_cast<int64_t>(vis_start) + n_vis > S)
@@ -1006,4 +1009,78 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
                        static_cast<const u32x4_t*>(hidden), static_cast<u32x4_t*>(hidden_out), out_rows, chunks_per_row,
                        vis_start, n_vis, static_cast<int>(total_keep), kept_idx);
     return check_launch("gather");
+}
+
+extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtype,
+                                   const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                                   int score_mode, int vis_start, int n_vis,
+                                   const int32_t* token_seg, const int32_t* token_event,
+                                   const float* event_weight, int n_events,
+                                   int n_seg, const int32_t* seg_quota,
+                                   const int32_t* orig_idx_in,
+                                   float* scores, int32_t* kept_idx, void* hidden_out,
+                                   int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    return prune_impl(hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, hidden_out, token_seg_out,
+                      token_event_out, orig_idx_out, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// metok_prefill_prune_static: the same call for callers that cannot allocate a workspace.  The scratch
+// memory is a fixed array in the library's device image; every GPU holds its own copy at its own address,
+// looked up once per device.  In host code the array's name is only a handle for that lookup: kernels
+// and the shared body above always receive the looked-up device address.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[METOK_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+}  // namespace
+
+// Device address of this GPU's copy of `scratch` (cached after the first call on the device).
+static int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(METOK_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(METOK_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(METOK_ERR_DEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return METOK_OK;
+}
+
+extern "C" size_t metok_static_scratch_bytes(void) { return METOK_STATIC_SCRATCH_BYTES; }
+
+extern "C" int metok_prefill_prune_static(const void* hidden, int64_t S, int D, int dtype,
+                                          const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                                          int score_mode, int vis_start, int n_vis,
+                                          const int32_t* token_seg, const int32_t* token_event,
+                                          const float* event_weight, int n_events,
+                                          int n_seg, const int32_t* seg_quota,
+                                          const int32_t* orig_idx_in,
+                                          float* scores, int32_t* kept_idx, void* hidden_out,
+                                          int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                                          void* stream) {
+    clear_error();
+    // the size check comes first so that an oversized request is refused before anything touches the device
+    const size_t need = metok_prefill_prune_workspace_bytes(S, q_text ? Hq : 0, q_text ? Hkv : 0, q_text ? dh : 0, q_text ? Tq : 0,
+                                                            n_vis, dtype);
+    if (need > METOK_STATIC_SCRATCH_BYTES)
+        return fail(METOK_ERR_WORKSPACE, "this shape needs %zu bytes of scratch memory, the static array holds %zu: use metok_prefill_prune "
+                    "with a caller-provided workspace", need, static_cast<size_t>(METOK_STATIC_SCRATCH_BYTES));
+    void* ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+    return prune_impl(hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, hidden_out, token_seg_out,
+                      token_event_out, orig_idx_out, ws, METOK_STATIC_SCRATCH_BYTES, stream);
 }

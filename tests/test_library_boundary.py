@@ -33,7 +33,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert len(names) == 17 and len(set(names)) == len(names)
+    assert len(names) == 19 and len(set(names)) == len(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
     from paper_2506_02850_amd import binding
@@ -216,6 +216,20 @@ def test_capacity_rows_is_the_worst_case_of_the_pooling_plan():
         assert cap(T, gh, gw, s1, s2, edge) == T * O.pooled_side(gh, s, edge) * O.pooled_side(gw, s, edge)
     with pytest.raises(ValueError):
         cap(0, 4, 4, 2, 2)
+
+
+def test_static_scratch_call_refuses_shapes_beyond_its_array(lib):
+    """The entry point without a workspace argument checks the size before it touches the device."""
+    from paper_2506_02850_amd import binding as B
+    blib = B.lib()
+    # 40 kv heads x 200 000 visual keys need 32 MB of column partials alone
+    need = blib.metok_prefill_prune_workspace_bytes(200064, 40, 40, 128, 64, 200000, B.BF16)
+    assert need > B.metok_static_scratch_bytes() == 8 << 20
+    quota = (ctypes.c_int32 * 1)(10)
+    fake = 0x1000
+    rc = blib.metok_prefill_prune_static(fake, 200064, 8, B.BF16, fake, fake, 40, 40, 128, 64, 0, 0, 200000, fake, fake, None, 0,
+                                         1, quota, None, fake, fake, fake, None, None, None, None)
+    assert rc == -3 and "static array" in B.metok_last_error()
 
 
 def test_binding_refuses_cpu_tensors():
