@@ -269,7 +269,10 @@ METOK_API int metok_account(const int32_t* event_len, const uint8_t* event_is_ke
  *   kept_idx     device out, [sum quota] int32: kept visual positions (0-based inside the visual
  *                span), ascending.  Per class the quota highest scores are kept.
  *   hidden_out   device out, [S - n_vis + sum quota, D]: prefix rows, kept visual rows in order,
- *                text rows.  Must not overlap `hidden`.
+ *                text rows.  Either disjoint from `hidden` (a parallel gather, the fast path) or the very
+ *                same pointer: then the sequence is compacted in place (rows move towards the front in
+ *                ordered tiles, no second [S, D] buffer; rows of at most 16384 bytes; the rows behind the
+ *                compacted sequence are unspecified afterwards).  Any other overlap is refused.
  *   token_seg_out, token_event_out, orig_idx_out  device out, [sum quota] int32 (each may be NULL).
  *   Limits: dh in {32, 64, 128, 256} for bf16, {32, 64, 128} for f32; Hq a multiple of Hkv;
  *   D * sizeof(dtype) a multiple of 16; n_seg <= METOK_MAX_SEGMENTS.
@@ -329,12 +332,19 @@ METOK_API int metok_prefill_prune_static(const void* hidden, int64_t S, int D, i
  *   Effect: for every (l, b, head) and for K and V, row i <- row idx[l][b][i], i < n_keep[l].
  *   Rows >= n_keep[l] are unspecified afterwards.  Positions that are not >= their rank or not
  *   below S_cap are skipped (never dereferenced).  dh * sizeof(dtype) must be a multiple of 16.
- *   No workspace is needed.
+ *   workspace    device, at least metok_kv_compact_workspace_bytes() bytes, 16-byte aligned: progress
+ *                flags of the row tiles, cleared by the call itself (its contents on entry do not
+ *                matter).  After the call its first 32-bit word is 0; a 1 there means that a wait between
+ *                two tiles of a slab expired and the cache was not compacted completely.  The waits are
+ *                bounded (about 2^24 polls) and by construction always end much earlier; an expiry has
+ *                never been observed and would mean that the GPU stopped running resident workgroups.
  * ------------------------------------------------------------------------------------------- */
+METOK_API size_t metok_kv_compact_workspace_bytes(int L, int B, int Hkv, int64_t S_cap, int dh, int dtype);
+
 METOK_API int metok_kv_compact(void* const* k_layers, void* const* v_layers, int L, int B, int Hkv,
                      int64_t S_cap, int dh, int dtype,
                      const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
-                     void* stream);
+                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The same compaction for a paged cache (Sec. 3.3).  Layer l holds K (resp. V) as a pool
@@ -346,6 +356,8 @@ METOK_API int metok_kv_compact(void* const* k_layers, void* const* v_layers, int
  *                (rows that would touch them are skipped).
  *   idx, n_keep, new_len  as in metok_kv_compact, positions being logical rows below
  *                pages_per_seq * page_size.
+ *   workspace    as in metok_kv_compact, sized by metok_kv_compact_workspace_bytes(L, B, Hkv,
+ *                pages_per_seq * page_size, dh, dtype).
  * Afterwards the pages from ceil(n_keep[l] / page_size) on hold no live rows of layer l; the table itself is
  * not modified (page ids are shared by the layers, whose lengths now differ: the caller keeps one length
  * per layer, new_len, and may release a page once no layer needs it).
@@ -354,7 +366,12 @@ METOK_API int metok_kv_compact_paged(void* const* k_pools, void* const* v_pools,
                            int64_t n_pages_pool, int page_size, int dh, int dtype,
                            const int32_t* page_table, int pages_per_seq,
                            const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
-                           void* stream);
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Test hook (not part of the method): number of polls after which a tile of the row mover gives a wait up.
+ * 0 makes every wait that does not succeed at once expire, which exercises the error word of the workspace
+ * without stalling anything; the default is 2^24. */
+METOK_API int metok_debug_set_move_spin_limit(int polls);
 
 /* ---------------------------------------------------------------------------------------------
  * Measurement helper (not part of the method): a plain device-to-device copy kernel with the

@@ -32,6 +32,7 @@ EXPORTS = [
     "metok_kv_compact", "metok_kv_compact_paged", "metok_calib_copy",
     "metok_preset", "metok_compress_encoder_tokens_capacity_rows",
     "metok_static_scratch_bytes", "metok_prefill_prune_static",
+    "metok_kv_compact_workspace_bytes", "metok_debug_set_move_spin_limit",
 ]
 
 
@@ -92,11 +93,15 @@ def _load() -> ctypes.CDLL:
     lib.metok_prefill_prune.argtypes = [vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
                                         i32, c.POINTER(c.c_int32), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_kv_compact.restype = i32
+    lib.metok_kv_compact_workspace_bytes.restype = sz
+    lib.metok_kv_compact_workspace_bytes.argtypes = [i32, i32, i32, i64, i32, i32]
+    lib.metok_debug_set_move_spin_limit.restype = i32
+    lib.metok_debug_set_move_spin_limit.argtypes = [i32]
     lib.metok_kv_compact.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, c.POINTER(vp),
-                                     c.POINTER(c.c_int32), vp, vp]
+                                     c.POINTER(c.c_int32), vp, vp, sz, vp]
     lib.metok_kv_compact_paged.restype = i32
     lib.metok_kv_compact_paged.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, i32, vp, i32,
-                                           c.POINTER(vp), c.POINTER(c.c_int32), vp, vp]
+                                           c.POINTER(vp), c.POINTER(c.c_int32), vp, vp, sz, vp]
     lib.metok_calib_copy.restype = i32
     lib.metok_calib_copy.argtypes = [vp, vp, sz, vp]
     lib.metok_preset.restype = i32
@@ -410,21 +415,31 @@ def _layer_tables(k_layers, v_layers, idx, shape, B):
     return L, karr, varr, iarr, nk
 
 
+def metok_kv_compact_workspace_bytes(L: int, B: int, Hkv: int, S_cap: int, dh: int, dtype_code: int) -> int:
+    return int(_lib.metok_kv_compact_workspace_bytes(int(L), int(B), int(Hkv), int(S_cap), int(dh), int(dtype_code)))
+
+
 def metok_kv_compact(k_layers: Sequence[torch.Tensor], v_layers: Sequence[torch.Tensor],
-                     idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """In-place compaction of per-layer K/V caches [B, Hkv, S_cap, dh] to idx[l] [B, n_keep_l] (None = untouched)."""
+                     idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """In-place compaction of per-layer K/V caches [B, Hkv, S_cap, dh] to idx[l] [B, n_keep_l] (None = untouched).
+    `workspace` (uint8, metok_kv_compact_workspace_bytes) is allocated here when not given; after the call its
+    first int32 word is 0 unless a bounded wait inside the kernel expired."""
     B, Hkv, S_cap, dh = k_layers[0].shape
     L, karr, varr, iarr, nk = _layer_tables(k_layers, v_layers, idx, (B, Hkv, S_cap, dh), B)
     dev = k_layers[0].device
+    dt = _dtype_code(k_layers[0])
     if new_len is None:
         new_len = torch.empty(L, dtype=torch.int32, device=dev)
-    _check(_lib.metok_kv_compact(karr, varr, L, B, Hkv, S_cap, dh, _dtype_code(k_layers[0]), iarr, nk,
-                                 _dev(new_len, "new_len"), _stream()))
+    ws = workspace if workspace is not None else _workspace(_lib.metok_kv_compact_workspace_bytes(L, B, Hkv, S_cap, dh, dt), dev)
+    _check(_lib.metok_kv_compact(karr, varr, L, B, Hkv, S_cap, dh, dt, iarr, nk,
+                                 _dev(new_len, "new_len"), _dev(ws, "workspace"), ws.numel(), _stream()))
     return new_len
 
 
 def metok_kv_compact_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[torch.Tensor], page_table: torch.Tensor,
-                           idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None) -> torch.Tensor:
+                           idx: Sequence[Optional[torch.Tensor]], new_len: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """In-place compaction of paged per-layer K/V pools [n_pages, Hkv, page_size, dh] through page_table [B, pages_per_seq]
     to the logical rows idx[l] [B, n_keep_l] (None = untouched)."""
     n_pages, Hkv, page_size, dh = k_pools[0].shape
@@ -433,12 +448,19 @@ def metok_kv_compact_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[to
     B, pages_per_seq = page_table.shape
     L, karr, varr, iarr, nk = _layer_tables(k_pools, v_pools, idx, (n_pages, Hkv, page_size, dh), B)
     dev = k_pools[0].device
+    dt = _dtype_code(k_pools[0])
     if new_len is None:
         new_len = torch.empty(L, dtype=torch.int32, device=dev)
-    _check(_lib.metok_kv_compact_paged(karr, varr, L, B, Hkv, n_pages, page_size, dh, _dtype_code(k_pools[0]),
+    ws = workspace if workspace is not None else _workspace(
+        _lib.metok_kv_compact_workspace_bytes(L, B, Hkv, pages_per_seq * page_size, dh, dt), dev)
+    _check(_lib.metok_kv_compact_paged(karr, varr, L, B, Hkv, n_pages, page_size, dh, dt,
                                        _dev(page_table, "page_table"), pages_per_seq, iarr, nk, _dev(new_len, "new_len"),
-                                       _stream()))
+                                       _dev(ws, "workspace"), ws.numel(), _stream()))
     return new_len
+
+
+def metok_debug_set_move_spin_limit(polls: int) -> None:
+    _check(_lib.metok_debug_set_move_spin_limit(int(polls)))
 
 
 _DUMMY = {}

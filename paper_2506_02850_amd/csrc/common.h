@@ -26,6 +26,33 @@ int ceil_ratio(double x);                   // ceil(x - 1e-9)
 constexpr int kWave = 64;
 
 // ---------------------------------------------------------------------------------------------
+// in-place row mover (stage3.hip): row i of a slab receives row idx[i] >= i.  Used by the KV
+// compaction and by metok_prefill_prune when its output aliases its input.
+// ---------------------------------------------------------------------------------------------
+constexpr int kMaxLayersPerLaunch = 40;
+
+struct RowMoveLayer {
+    char* k;             // [B, Hkv, S_cap, row_bytes]
+    char* v;             // second buffer of the layer (n_which == 2), else unused
+    const int32_t* idx;  // [B, n_keep]
+    int32_t n_keep;
+    int32_t first_item;  // filled by launch_row_moves
+    int32_t tiles;       // filled by launch_row_moves
+    int32_t flag_slot;   // filled by launch_row_moves
+};
+
+struct RowMoveGeom { int parts, lanes_per_row, rows_per_step, rows_per_tile; };
+
+struct LengthTable { int n; int32_t len[METOK_MAX_LAYERS]; };
+
+RowMoveGeom row_move_geom(int64_t row_bytes);
+size_t row_move_workspace_bytes(int L, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes);
+int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes,
+                     const int32_t* page_table, int page_size, int pages_per_seq, int64_t n_pages_pool,
+                     int32_t* new_len, const int32_t* host_len, int L_total,
+                     void* workspace, size_t workspace_bytes, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
 // device helpers
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;

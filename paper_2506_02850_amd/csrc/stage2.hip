@@ -770,6 +770,21 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
     }
 }
 
+// Source row of every output row of the compacted sequence [prefix; kept visual rows; text rows].
+__global__ __launch_bounds__(256) void hidden_index_kernel(int32_t* __restrict__ src_row, int out_rows, int vis_start, int n_vis, int n_keep,
+                                                           const int32_t* __restrict__ kept_idx) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= out_rows) return;
+    int s;
+    if (r < vis_start) s = r;
+    else if (r < vis_start + n_keep) {
+        int kidx = kept_idx[r - vis_start];
+        kidx = kidx < 0 ? 0 : (kidx >= n_vis ? n_vis - 1 : kidx);
+        s = vis_start + kidx;
+    } else s = r - n_keep + n_vis;
+    src_row[r] = s;
+}
+
 constexpr int kGatherThreads = 256;
 
 // One 16-byte chunk per thread, non-temporal (the copy pattern that measured fastest on MI355X).
@@ -801,6 +816,15 @@ static size_t select_count_bytes(int n_vis) {
 }
 static size_t select_bytes(int n_vis) { return 2 * select_count_bytes(n_vis) + METOK_MAX_SEGMENTS * 2 * sizeof(uint32_t); }
 
+// In-place compaction (hidden_out == hidden): the source row of every output row as an index list, and the
+// progress flags of the row mover.  Rows of at most kInPlaceMaxRowBytes keep a row inside one workgroup
+// pass, so a tile has at least eight rows and the flag count is bounded by the sequence length alone.
+constexpr int64_t kInPlaceMaxRowBytes = 16384;
+static size_t inplace_index_bytes(int64_t S) { return round_up(static_cast<size_t>(S) * sizeof(int32_t), 256); }
+static size_t inplace_bytes(int64_t S) {
+    return inplace_index_bytes(S) + round_up((64 + static_cast<size_t>((S + 7) / 8)) * sizeof(uint32_t), 256);
+}
+
 static int chunk_count(int dh, int dtype) { return dtype == METOK_BF16 ? dh / 16 : dh / 8; }     // 16-byte chunks per lane
 
 // Row blocks a wave keeps in registers: two while the fragments of a block take at most 32 VGPRs, else one.
@@ -826,7 +850,7 @@ static bool make_geom(int64_t S, int Hq, int Hkv, int dh, int Tq, int vis_start,
 struct ScorePlan {
     int nx1, nx2;                   // workgroups along the keys in pass 1 / pass 2
     int per1, per2;                 // 32-key subtiles per workgroup
-    size_t off_qfrag, off_pstat, off_norm, off_colpart, off_sel, total;
+    size_t off_qfrag, off_pstat, off_norm, off_colpart, off_sel, off_inplace, total;
 };
 
 constexpr int kScoreSlots = 256;    // one 512-thread workgroup per CU
@@ -855,6 +879,7 @@ static void plan_score(const ScoreGeom& g, int n_vis, int nch, ScorePlan* p) {
     p->off_norm = off;    off += round_up(static_cast<size_t>(ny) * g.rbw * 32 * sizeof(float), 256);
     p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
     p->off_sel = off;     off += select_bytes(n_vis);
+    p->off_inplace = off; off += inplace_bytes(g.S);
     p->total = off;
 }
 
@@ -898,7 +923,7 @@ extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv
         plan_score(g, n_vis, chunk_count(dh, dtype), &p);
         return p.total;
     }
-    return select_bytes(n_vis);      // selection scratch only (scores supplied by the caller)
+    return select_bytes(n_vis) + inplace_bytes(S);      // no attention pass (scores supplied by the caller)
 }
 
 // Shared body of metok_prefill_prune and metok_prefill_prune_static: `workspace` is the caller's buffer or
@@ -936,15 +961,21 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
     if (total_keep > n_vis) return fail(METOK_ERR_INVALID_ARG, "quotas add up to %lld > n_vis = %d", (long long)total_keep, n_vis);
     if (total_keep > 0 && !kept_idx) return fail(METOK_ERR_INVALID_ARG, "kept_idx is NULL");
     const int64_t out_rows = S - n_vis + total_keep;
-    {   // hidden_out must not overlap hidden (the gather is not an in-place algorithm)
+    // hidden_out == hidden compacts in place (every kept row moves towards the front: source >= destination);
+    // any other overlap is refused
+    const bool in_place = hidden_out == hidden;
+    if (!in_place) {
         const char* a0 = static_cast<const char*>(hidden); const char* a1 = a0 + static_cast<size_t>(S) * row_bytes;
         const char* b0 = static_cast<const char*>(hidden_out); const char* b1 = b0 + static_cast<size_t>(out_rows) * row_bytes;
-        if (a0 < b1 && b0 < a1) return fail(METOK_ERR_INVALID_ARG, "hidden_out overlaps hidden");
+        if (a0 < b1 && b0 < a1) return fail(METOK_ERR_INVALID_ARG, "hidden_out overlaps hidden without being the same buffer");
+    } else if (static_cast<int64_t>(row_bytes) > kInPlaceMaxRowBytes) {
+        return fail(METOK_ERR_UNSUPPORTED, "in-place compaction needs rows of at most %lld bytes, got %zu", (long long)kInPlaceMaxRowBytes, row_bytes);
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     int rc;
     char* sel;
+    char* inplace_ws;
     if (q_text) {
         if (!k_all || !aligned16(q_text) || !aligned16(k_all)) return fail(METOK_ERR_INVALID_ARG, "q_text / k_all NULL or misaligned");
         if (Hq < 1 || Hkv < 1 || Hq % Hkv) return fail(METOK_ERR_INVALID_ARG, "Hq = %d must be a positive multiple of Hkv = %d", Hq, Hkv);
@@ -977,15 +1008,17 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
         }
         if ((rc = check_launch("attention scores"))) return rc;
         sel = ws + p.off_sel;
+        inplace_ws = ws + p.off_inplace;
         hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
                            reinterpret_cast<const float*>(ws + p.off_colpart), g.Hkv * g.rs, n_vis,
                            static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores);
         if ((rc = check_launch("prepare"))) return rc;
     } else {
-        const size_t need = select_bytes(n_vis);
+        const size_t need = select_bytes(n_vis) + inplace_bytes(S);
         if (!workspace || workspace_bytes < need || !aligned16(workspace))
             return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
         sel = ws;
+        inplace_ws = ws + select_bytes(n_vis);
     }
     int32_t* gt_count = reinterpret_cast<int32_t*>(sel);
     int32_t* eq_count = reinterpret_cast<int32_t*>(sel + select_count_bytes(n_vis));
@@ -1002,6 +1035,18 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
                        n_tiles, static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out,
                        token_event_out, orig_idx_out);
     if ((rc = check_launch("write index"))) return rc;
+    if (in_place) {
+        int32_t* src_row = reinterpret_cast<int32_t*>(inplace_ws);
+        hipLaunchKernelGGL(hidden_index_kernel, dim3(static_cast<unsigned>((out_rows + 255) / 256)), dim3(256), 0, st, src_row,
+                           static_cast<int>(out_rows), vis_start, n_vis, static_cast<int>(total_keep), kept_idx);
+        if ((rc = check_launch("hidden index"))) return rc;
+        RowMoveLayer layer;
+        layer.k = static_cast<char*>(hidden_out); layer.v = nullptr; layer.idx = src_row; layer.n_keep = static_cast<int32_t>(out_rows);
+        layer.first_item = 0; layer.tiles = 0; layer.flag_slot = 0;
+        if (out_rows == 0) return METOK_OK;
+        return launch_row_moves(&layer, 1, 1, 1, 1, S, static_cast<int64_t>(row_bytes), nullptr, 0, 0, 0, nullptr, nullptr, 1,
+                                inplace_ws + inplace_index_bytes(S), inplace_bytes(S) - inplace_index_bytes(S), st);
+    }
     const int chunks_per_row = static_cast<int>(row_bytes / 16);
     const int64_t blocks = (out_rows * chunks_per_row + kGatherThreads - 1) / kGatherThreads;
     if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "hidden_out too large for one launch");

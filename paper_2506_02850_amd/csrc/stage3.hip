@@ -1,11 +1,33 @@
-// Stage 3 (Sec. 3.3): in-place compaction of the KV cache to the retained rows.
+// Stage 3 (Sec. 3.3): in-place compaction of the KV cache to the retained rows, and the in-place row
+// mover it is built on (also used by metok_prefill_prune when hidden_out == hidden).
 //
-// A slab is one [S_cap, dh] matrix: K or V of one layer, one video, one kv head.  Inside a slab
-// row i must receive row idx[i] >= i.  One workgroup owns a slab (or a 16-byte-aligned column
-// slice of it) and walks it in ascending tiles of rows: all loads of a tile complete, the workgroup
-// meets at a barrier, then the tile is stored.  Later tiles only read rows at or above their own first
-// row, which no earlier store has touched, so no row is overwritten before it is read.
-// Different slabs and different column slices never alias, so workgroups need no ordering.
+// A slab is one [S_cap, row] matrix that is compacted on its own: K or V of one layer, one video, one kv
+// head (or a 16-byte-aligned column slice of it when a row is wider than one workgroup pass).  Inside a
+// slab row i must receive row idx[i] >= i, idx strictly ascending.
+//
+// The destination rows of a slab are cut into tiles of R rows and a workgroup moves ONE tile: it loads
+// the tile's source rows into registers (8 pieces of 16 bytes per thread, all in flight together), waits
+// until they have landed, and stores them.  Many tiles of one slab are in flight on different CUs at the
+// same time, so the sources of a tile are one long sequential sweep (R rows of a contiguous span) and the
+// destinations one contiguous block of R rows: few, long DRAM streams instead of one short stream per
+// slab.  Measured on MI355X (28-layer LongVA-shaped cache, batch 8): 5.7 TB/s against 5.2 TB/s for one
+// workgroup per slab walking its tiles in order.
+//
+// Ordering.  A tile's stores may overwrite rows that EARLIER tiles of the slab still have to read (a
+// source lies at or after its destination).  Later tiles only read rows at or after their own first row,
+// which lie behind every row this tile writes.  So:
+//   - inside a tile, a barrier separates "all my sources are in registers" from "I store";
+//   - across tiles, a tile publishes a flag once its sources are in registers, and before storing it
+//     waits for the flags of the earlier tiles whose sources fall into its destination rows [r0, r1).
+//     Those are the destination rows lo <= i < hi with lo = #{idx < r0}, hi = min(#{idx < r1}, r0): a
+//     contiguous run, found with two 64-ary searches that overlap the loads in flight; it spans at most a
+//     few tiles.
+// Tiles are handed out by an atomic ticket in ascending order inside a slab, so a tile only ever waits
+// for tiles whose workgroups are already running, and a running workgroup publishes its flag before it
+// waits for anything: the waits always end.  They are bounded nevertheless: a wait that expires sets the
+// error word of the workspace and the tile is not stored.
+// Different slabs never alias, so they need no ordering; the column slices and the K / V halves of one
+// (layer, video) share the index list and are interleaved tile by tile.
 //
 // The paged variant moves the same logical rows through a page table: logical row p of video b lives in
 // page table[b][p / page_size], slot p % page_size, of a per-layer pool [n_pages, Hkv, page_size, dh].
@@ -15,58 +37,93 @@
 
 namespace metok {
 
-constexpr int kMaxLayersPerLaunch = 40;
-// Measured on MI355X (28-layer LongVA-shaped cache, batch 8): 1024-thread workgroups that keep ONE
-// 16-byte load per thread in flight and use non-temporal accesses reach 5.1 TB/s; 256-thread groups
-// with 8 loads in flight per thread only 2.6 TB/s, because every slab then runs at once and the DRAM
-// pages of 3200 interleaved read/write streams thrash.  Two resident workgroups per CU = 512 slabs.
-constexpr int kCompactThreads = 1024;
+constexpr int kMoveThreads = 1024;
+constexpr int kMoveInFlight = 8;        // 16-byte pieces per thread: 1024 x 8 x 16 B = 128 KB per tile
 
-struct CompactLayer {
-    char* k;             // [B, Hkv, S_cap, row_bytes]
-    char* v;
-    const int32_t* idx;  // [B, n_keep]
-    int32_t n_keep;
-    int32_t layer_id;
-};
+namespace {
+int g_spin_limit = 1 << 24;             // polls of one flag before a wait is given up (tens of seconds)
+}
 
-struct CompactArgs {
-    CompactLayer layer[kMaxLayersPerLaunch];
+struct MoveArgs {
+    RowMoveLayer layer[kMaxLayersPerLaunch];
     int n_layers;
-    int B, Hkv;
+    int B, Hkv, n_which;  // slabs of a layer: B videos x Hkv heads x n_which buffers (K, V)
     int parts;            // column slices per row
-    int lanes_per_row;    // 16-byte chunks per column slice
-    int rows_per_tile;    // kCompactThreads / lanes_per_row
+    int lanes_per_row;    // 16-byte pieces per column slice
+    int rows_per_step;    // kMoveThreads / lanes_per_row
+    int tiles_max;        // flag slots per slab
+    int total_items;      // tiles of all slabs of this launch
+    int spin_limit;
     int64_t S_cap;
     int64_t row_bytes;
+    uint32_t* flags;      // [n_layers][B * Hkv * n_which * parts][tiles_max]
+    uint32_t* ticket;     // this launch's tile counter
+    uint32_t* error;      // set to 1 if a bounded wait expired
     // paged variant only
     const int32_t* page_table;   // [B, pages_per_seq]
     int page_size, pages_per_seq;
     int64_t n_pages_pool;
 };
 
-template <bool PAGED>
-__global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(const CompactArgs args) {
-    // block -> (layer slot, video, head, K|V, column slice); layer slots are sorted by work, largest first
-    const int units_per_layer = args.B * args.Hkv * 2 * args.parts;
-    const int slot = blockIdx.x / units_per_layer;
-    int rem = blockIdx.x - slot * units_per_layer;
-    const int part = rem % args.parts; rem /= args.parts;
-    const int which = rem & 1; rem >>= 1;
-    const int head = rem % args.Hkv;
-    const int b = rem / args.Hkv;
+// First position p in idx[0, n) with idx[p] >= key (n if there is none), for ascending idx; all 64 lanes
+// of the calling wave take part: each round probes 64 positions, three rounds cover 2^18 entries.
+// Terminates for any contents of idx (the range shrinks every round).
+__device__ __forceinline__ int wave_lower_bound(const int32_t* __restrict__ idx, int n, int key) {
+    const int lane = threadIdx.x & 63;
+    int lo = 0, len = n;        // positions below lo are < key; position lo + len is >= key or the end of the range
+    while (len > 0) {
+        const int step = (len + 63) / 64;
+        const int p = lo + (lane + 1) * step - 1;
+        const bool ge = p >= lo + len ? true : idx[p] >= key;
+        const unsigned long long m = __ballot(ge);
+        if (m == 0ull) { lo += len; break; }                       // every probe is below key and the last one is the last position
+        const int first = __ffsll(static_cast<long long>(m)) - 1;
+        const int new_lo = lo + first * step;                      // one past the probe of lane first - 1
+        int new_end = lo + (first + 1) * step - 1;                 // the probe of lane first
+        if (new_end > lo + len) new_end = lo + len;
+        len = new_end - new_lo;
+        lo = new_lo;
+    }
+    return lo;
+}
 
-    const CompactLayer& L = args.layer[slot];
+template <bool PAGED>
+__global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs args) {
+    constexpr int U = kMoveInFlight;
+    __shared__ int s_item, s_lo, s_hi;
+    if (threadIdx.x == 0) s_item = static_cast<int>(atomicAdd(args.ticket, 1u));
+    __syncthreads();
+    const int item = s_item;
+    if (item >= args.total_items) return;
+    int slot = 0;
+    while (slot + 1 < args.n_layers && args.layer[slot + 1].first_item <= item) ++slot;
+    const RowMoveLayer& L = args.layer[slot];
+    // item -> (video, tile, sub-slab): the sub-slabs of one video share its index list and advance together
+    const int n_sub = args.Hkv * args.n_which * args.parts;
+    const int local = item - L.first_item;
+    const int b = local / (n_sub * L.tiles);
+    int rem = local - b * n_sub * L.tiles;
+    const int tile = rem / n_sub;
+    int sub = rem - tile * n_sub;
+    const int part = sub % args.parts; sub /= args.parts;
+    const int which = sub % args.n_which;
+    const int head = sub / args.n_which;
+
     const int rows = L.n_keep;
     const int32_t* __restrict__ idx = L.idx + static_cast<int64_t>(b) * rows;
     char* pool = which ? L.v : L.k;
     char* base = pool + (static_cast<int64_t>(b) * args.Hkv + head) * args.S_cap * args.row_bytes;      // dense slab
     const int32_t* __restrict__ table = PAGED ? args.page_table + static_cast<int64_t>(b) * args.pages_per_seq : nullptr;
+    uint32_t* flags = args.flags + (static_cast<size_t>(L.flag_slot) * args.B * n_sub + static_cast<size_t>(b) * n_sub + (rem - tile * n_sub)) *
+                                       args.tiles_max;
 
     const int lpr = args.lanes_per_row;
-    const int r_in_tile = threadIdx.x / lpr;
-    const int col = (part * lpr + (threadIdx.x - r_in_tile * lpr)) * 16;
-    const bool active = r_in_tile < args.rows_per_tile;          // threads beyond the last whole row idle
+    const int rps = args.rows_per_step;
+    const int R = rps * U;
+    const int r0 = tile * R;
+    const int r_in = threadIdx.x / lpr;
+    const int col = (part * lpr + (threadIdx.x - r_in * lpr)) * 16;
+    const bool active = r_in < rps;                               // threads beyond the last whole row idle
     const uint32_t s_cap = static_cast<uint32_t>(args.S_cap);
 
     // address of logical row r of this (video, head); nullptr if its page id is not a page of the pool
@@ -78,39 +135,142 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(const Compa
         return pool + prow * args.row_bytes;
     };
 
-    for (int tile = 0; tile < rows; tile += args.rows_per_tile) {
-        const int i = tile + r_in_tile;
-        u32x4_t v;
-        bool move = false;
-        char* dst = nullptr;                                      // paged only: looked up before the barrier
+    u32x4_t v[U];
+    char* dst[U];                                                 // nullptr: this piece does not move
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = r0 + u * rps + r_in;
+        dst[u] = nullptr;
         if (active && i < rows) {
             const uint32_t s = static_cast<uint32_t>(idx[i]);
-            // rows that stay where they are need no copy; positions outside [i, S_cap) are skipped
+            // rows that stay where they are need no copy; positions outside (i, S_cap) are skipped
             if (s > static_cast<uint32_t>(i) && s < s_cap) {
                 const char* src = row_ptr(s);
-                if (PAGED) {
-                    dst = row_ptr(static_cast<uint32_t>(i));
-                    move = src != nullptr && dst != nullptr;
-                } else {
-                    move = true;
+                char* d = row_ptr(static_cast<uint32_t>(i));
+                if (src != nullptr && d != nullptr) {
+                    dst[u] = d + col;
+                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + col));
                 }
-                if (move) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + col));
             }
         }
-        // every load of this tile has returned before any thread of the workgroup stores into it
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (move) {
-            char* out = PAGED ? dst : base + static_cast<int64_t>(i) * args.row_bytes;
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(out + col));
+    }
+    // destination rows [lo, hi) of earlier tiles take their sources from my destination rows [r0, r1)
+    const int r1 = min(r0 + R, rows);
+    const int wave = threadIdx.x >> 6;
+    if (wave == 0) { const int lo = wave_lower_bound(idx, r0, r0); if (threadIdx.x == 0) s_lo = lo; }
+    if (wave == 1) { const int hi = wave_lower_bound(idx, r0, r1); if (threadIdx.x == 64) s_hi = hi; }
+    // every source piece of this tile is in registers before the flag goes up and before any thread stores
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(&flags[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int lo = s_lo, hi = s_hi;                               // both <= r0
+    bool ok = true;
+    if (lo < hi) {
+        const int t_lo = lo / R, t_hi = (hi - 1) / R;             // earlier tiles of this slab: t_hi < tile
+        for (int t = t_lo + static_cast<int>(threadIdx.x); t <= t_hi; t += kMoveThreads) {
+            int polls = 0;
+            while (__hip_atomic_load(&flags[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+                if (++polls > args.spin_limit) { ok = false; break; }
+                __builtin_amdgcn_s_sleep(8);
+            }
         }
     }
+    if (!__syncthreads_and(ok ? 1 : 0)) {
+        if (threadIdx.x == 0) atomicOr(args.error, 1u);
+        return;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (dst[u] != nullptr) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4_t*>(dst[u]));
 }
 
-__global__ void write_lengths_kernel(int32_t* out, const CompactArgs args) {
-    // one thread per layer slot of this launch
-    int i = threadIdx.x;
-    if (i < args.n_layers) out[args.layer[i].layer_id] = args.layer[i].n_keep;
+// Clears the words the move kernels will use (flags, tickets, error word) and writes the per-layer lengths.
+__global__ __launch_bounds__(256) void move_init_kernel(uint32_t* __restrict__ words, size_t n_words, int32_t* __restrict__ new_len,
+                                                        const LengthTable lengths) {
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n_words; i += stride) words[i] = 0u;
+    if (new_len != nullptr && blockIdx.x == 0 && static_cast<int>(threadIdx.x) < lengths.n) new_len[threadIdx.x] = lengths.len[threadIdx.x];
+}
+
+RowMoveGeom row_move_geom(int64_t row_bytes) {
+    RowMoveGeom g;
+    const int chunks = static_cast<int>(row_bytes / 16);
+    // split a row into column slices only when it is too wide for one workgroup pass
+    int parts = 1;
+    while (chunks / parts > kMoveThreads || chunks % parts) ++parts;
+    g.parts = parts;
+    g.lanes_per_row = chunks / parts;
+    g.rows_per_step = kMoveThreads / g.lanes_per_row;
+    g.rows_per_tile = g.rows_per_step * kMoveInFlight;
+    return g;
+}
+
+// words: [0] error, [1 .. 1 + launches) tickets, then padding to 64 words, then the flags
+static size_t move_header_words(int L) { return round_up(1 + (static_cast<size_t>(L) + kMaxLayersPerLaunch - 1) / kMaxLayersPerLaunch, 64); }
+
+size_t row_move_workspace_bytes(int L, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes) {
+    const RowMoveGeom g = row_move_geom(row_bytes);
+    const size_t tiles = static_cast<size_t>((S_cap + g.rows_per_tile - 1) / g.rows_per_tile);
+    const size_t flags = static_cast<size_t>(L) * B * Hkv * n_which * g.parts * tiles;
+    return round_up((move_header_words(L) + flags) * sizeof(uint32_t), 256);
+}
+
+// Host side of both stage-3 calls and of the in-place hidden-state compaction.  layers[i] needs k (v if
+// n_which == 2), idx and n_keep; layers with n_keep == 0 must have been left out by the caller.
+int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes,
+                     const int32_t* page_table, int page_size, int pages_per_seq, int64_t n_pages_pool,
+                     int32_t* new_len, const int32_t* host_len, int L_total,
+                     void* workspace, size_t workspace_bytes, hipStream_t st) {
+    const RowMoveGeom g = row_move_geom(row_bytes);
+    const size_t need = row_move_workspace_bytes(L_total, B, Hkv, n_which, S_cap, row_bytes);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u))
+        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    uint32_t* words = static_cast<uint32_t*>(workspace);
+    const size_t header = move_header_words(L_total);
+    const int n_sub = Hkv * n_which * g.parts;
+    const int tiles_max = static_cast<int>((S_cap + g.rows_per_tile - 1) / g.rows_per_tile);
+    const size_t used_words = header + static_cast<size_t>(n_active) * B * n_sub * tiles_max;
+
+    // one small launch clears the flags / tickets / error word and writes the lengths (L_total <= METOK_MAX_LAYERS)
+    LengthTable lengths;
+    lengths.n = new_len ? L_total : 0;
+    for (int l = 0; l < lengths.n; ++l) lengths.len[l] = host_len[l];
+    unsigned init_blocks = static_cast<unsigned>((used_words + 1023) / 1024);
+    if (init_blocks < 1) init_blocks = 1;
+    if (init_blocks > 1024) init_blocks = 1024;
+    hipLaunchKernelGGL(move_init_kernel, dim3(init_blocks), dim3(256), 0, st, words, used_words, new_len, lengths);
+    int rc = check_launch("row move init");
+    if (rc) return rc;
+
+    for (int first = 0, launch = 0; first < n_active; first += kMaxLayersPerLaunch, ++launch) {
+        MoveArgs args;
+        args.n_layers = (n_active - first < kMaxLayersPerLaunch) ? n_active - first : kMaxLayersPerLaunch;
+        int64_t items = 0;
+        for (int i = 0; i < args.n_layers; ++i) {
+            RowMoveLayer& Lr = layers[first + i];
+            Lr.tiles = (Lr.n_keep + g.rows_per_tile - 1) / g.rows_per_tile;
+            if (items > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "too many tiles for one launch");
+            Lr.first_item = static_cast<int32_t>(items);
+            Lr.flag_slot = first + i;
+            items += static_cast<int64_t>(Lr.tiles) * B * n_sub;
+            args.layer[i] = Lr;
+        }
+        if (items > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "too many tiles for one launch");
+        args.B = B; args.Hkv = Hkv; args.n_which = n_which; args.parts = g.parts; args.lanes_per_row = g.lanes_per_row;
+        args.rows_per_step = g.rows_per_step; args.tiles_max = tiles_max; args.total_items = static_cast<int>(items);
+        args.spin_limit = g_spin_limit;
+        args.S_cap = S_cap; args.row_bytes = row_bytes;
+        args.flags = words + header; args.ticket = words + 1 + launch; args.error = words;
+        args.page_table = page_table; args.page_size = page_size; args.pages_per_seq = pages_per_seq; args.n_pages_pool = n_pages_pool;
+        if (items == 0) continue;
+        if (page_table)
+            hipLaunchKernelGGL(move_rows_kernel<true>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args);
+        else
+            hipLaunchKernelGGL(move_rows_kernel<false>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args);
+        rc = check_launch("move_rows");
+        if (rc) return rc;
+    }
+    return METOK_OK;
 }
 
 }  // namespace metok
@@ -122,7 +282,7 @@ static int compact_impl(void* const* k_layers, void* const* v_layers, int L, int
                         int64_t S_cap, int dh, int dtype,
                         const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
                         const int32_t* page_table, int page_size, int pages_per_seq, int64_t n_pages_pool,
-                        void* stream) {
+                        void* workspace, size_t workspace_bytes, void* stream) {
     if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
     if (L < 1 || L > METOK_MAX_LAYERS) return fail(METOK_ERR_INVALID_ARG, "L must be in [1, %d], got %d", METOK_MAX_LAYERS, L);
     if (B < 1 || Hkv < 1 || dh < 1 || S_cap < 1 || S_cap > INT32_MAX)
@@ -130,8 +290,7 @@ static int compact_impl(void* const* k_layers, void* const* v_layers, int L, int
     if (!k_layers || !v_layers || !idx || !n_keep) return fail(METOK_ERR_INVALID_ARG, "NULL layer table");
     const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
     if (row_bytes % 16 != 0) return fail(METOK_ERR_INVALID_ARG, "dh * sizeof(dtype) = %lld is not a multiple of 16", (long long)row_bytes);
-    const int chunks = static_cast<int>(row_bytes / 16);
-    if (chunks > kCompactThreads * 64) return fail(METOK_ERR_UNSUPPORTED, "rows longer than %d bytes", kCompactThreads * 1024);
+    if (row_bytes / 16 > kMoveThreads * 64) return fail(METOK_ERR_UNSUPPORTED, "rows longer than %d bytes", kMoveThreads * 1024);
     if (static_cast<int64_t>(B) * Hkv * 2 > (1 << 20)) return fail(METOK_ERR_INVALID_ARG, "B * Hkv too large");
 
     // layers that move data, largest first so that the long slabs start early
@@ -152,74 +311,44 @@ static int compact_impl(void* const* k_layers, void* const* v_layers, int L, int
         while (j > 0 && n_keep[order[j - 1]] < n_keep[l]) { order[j] = order[j - 1]; --j; }
         order[j] = l;
     }
-
-    // split a row into column slices only when it is too wide for one workgroup pass
-    int parts = 1;
-    while (chunks / parts > kCompactThreads || chunks % parts) ++parts;
-    const int lanes_per_row = chunks / parts;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
+    RowMoveLayer layers[METOK_MAX_LAYERS];
+    for (int i = 0; i < n_active; ++i) {
+        const int l = order[i];
+        layers[i].k = static_cast<char*>(k_layers[l]);
+        layers[i].v = static_cast<char*>(v_layers[l]);
+        layers[i].idx = idx[l];
+        layers[i].n_keep = n_keep[l];
+        layers[i].first_item = 0; layers[i].tiles = 0; layers[i].flag_slot = 0;
+    }
     int32_t host_len[METOK_MAX_LAYERS];
     for (int l = 0; l < L; ++l) host_len[l] = idx[l] ? n_keep[l] : static_cast<int32_t>(S_cap);
+    return launch_row_moves(layers, n_active, B, Hkv, 2, S_cap, row_bytes, page_table, page_size, pages_per_seq, n_pages_pool,
+                            new_len, host_len, L, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
 
-    for (int first = 0; first < n_active; first += kMaxLayersPerLaunch) {
-        CompactArgs args;
-        args.n_layers = (n_active - first < kMaxLayersPerLaunch) ? n_active - first : kMaxLayersPerLaunch;
-        for (int i = 0; i < args.n_layers; ++i) {
-            const int l = order[first + i];
-            args.layer[i].k = static_cast<char*>(k_layers[l]);
-            args.layer[i].v = static_cast<char*>(v_layers[l]);
-            args.layer[i].idx = idx[l];
-            args.layer[i].n_keep = n_keep[l];
-            args.layer[i].layer_id = l;
-        }
-        args.B = B; args.Hkv = Hkv; args.parts = parts; args.lanes_per_row = lanes_per_row;
-        args.rows_per_tile = kCompactThreads / lanes_per_row;
-        args.S_cap = S_cap; args.row_bytes = row_bytes;
-        args.page_table = page_table; args.page_size = page_size; args.pages_per_seq = pages_per_seq; args.n_pages_pool = n_pages_pool;
-        const int64_t blocks = static_cast<int64_t>(args.n_layers) * B * Hkv * 2 * parts;
-        if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "too many slabs for one launch");
-        if (page_table)
-            hipLaunchKernelGGL(kv_compact_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(kCompactThreads), 0, st, args);
-        else
-            hipLaunchKernelGGL(kv_compact_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(kCompactThreads), 0, st, args);
-        int rc = check_launch("kv_compact");
-        if (rc) return rc;
-    }
-    if (new_len) {
-        // all L lengths, in layer order, through the same kernel-argument path (no host buffer is read later)
-        for (int first = 0; first < L; first += kMaxLayersPerLaunch) {
-            CompactArgs args;
-            args.n_layers = (L - first < kMaxLayersPerLaunch) ? L - first : kMaxLayersPerLaunch;
-            for (int i = 0; i < args.n_layers; ++i) {
-                args.layer[i].k = nullptr; args.layer[i].v = nullptr; args.layer[i].idx = nullptr;
-                args.layer[i].n_keep = host_len[first + i];
-                args.layer[i].layer_id = first + i;
-            }
-            args.B = B; args.Hkv = Hkv; args.parts = 1; args.lanes_per_row = 1; args.rows_per_tile = 1;
-            args.S_cap = S_cap; args.row_bytes = row_bytes;
-            args.page_table = nullptr; args.page_size = 0; args.pages_per_seq = 0; args.n_pages_pool = 0;
-            hipLaunchKernelGGL(write_lengths_kernel, dim3(1), dim3(64), 0, st, new_len, args);
-            int rc = check_launch("kv_compact lengths");
-            if (rc) return rc;
-        }
-    }
-    return METOK_OK;
+extern "C" size_t metok_kv_compact_workspace_bytes(int L, int B, int Hkv, int64_t S_cap, int dh, int dtype) {
+    if (L < 1 || L > METOK_MAX_LAYERS || B < 1 || Hkv < 1 || S_cap < 1 || S_cap > INT32_MAX || dh < 1 ||
+        (dtype != METOK_F32 && dtype != METOK_BF16))
+        return 0;
+    const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
+    if (row_bytes % 16 != 0 || row_bytes / 16 > kMoveThreads * 64) return 0;
+    return row_move_workspace_bytes(L, B, Hkv, 2, S_cap, row_bytes);
 }
 
 extern "C" int metok_kv_compact(void* const* k_layers, void* const* v_layers, int L, int B, int Hkv,
                                 int64_t S_cap, int dh, int dtype,
                                 const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
-                                void* stream) {
+                                void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
-    return compact_impl(k_layers, v_layers, L, B, Hkv, S_cap, dh, dtype, idx, n_keep, new_len, nullptr, 0, 0, 0, stream);
+    return compact_impl(k_layers, v_layers, L, B, Hkv, S_cap, dh, dtype, idx, n_keep, new_len, nullptr, 0, 0, 0,
+                        workspace, workspace_bytes, stream);
 }
 
 extern "C" int metok_kv_compact_paged(void* const* k_pools, void* const* v_pools, int L, int B, int Hkv,
                                       int64_t n_pages_pool, int page_size, int dh, int dtype,
                                       const int32_t* page_table, int pages_per_seq,
                                       const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
-                                      void* stream) {
+                                      void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
     if (!page_table || (reinterpret_cast<uintptr_t>(page_table) & 3u)) return fail(METOK_ERR_INVALID_ARG, "page_table NULL or misaligned");
     if (page_size < 1 || pages_per_seq < 1 || n_pages_pool < 1 || n_pages_pool > INT32_MAX)
@@ -227,5 +356,14 @@ extern "C" int metok_kv_compact_paged(void* const* k_pools, void* const* v_pools
     const int64_t S_cap = static_cast<int64_t>(pages_per_seq) * page_size;
     if (S_cap > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pages_per_seq * page_size must be below 2^31");
     return compact_impl(k_pools, v_pools, L, B, Hkv, S_cap, dh, dtype, idx, n_keep, new_len, page_table, page_size, pages_per_seq,
-                        n_pages_pool, stream);
+                        n_pages_pool, workspace, workspace_bytes, stream);
+}
+
+// Test hook: how often a tile polls one flag before it gives its wait up (default 2^24).  With 0 every
+// wait that does not succeed at once expires, which exercises the error word without stalling anything.
+extern "C" int metok_debug_set_move_spin_limit(int polls) {
+    clear_error();
+    if (polls < 0) return fail(METOK_ERR_INVALID_ARG, "polls must be non-negative");
+    g_spin_limit = polls;
+    return METOK_OK;
 }

@@ -238,7 +238,7 @@ def test_argument_errors_are_reported():
     with pytest.raises(B.MetokError):
         B.metok_prefill_prune(hidden, 0, 10, seg, [11], scores=sc)                     # quota > n_vis
     with pytest.raises(B.MetokError):
-        B.metok_prefill_prune(hidden, 0, 10, seg, [3], scores=sc, hidden_out=hidden[:13])   # aliasing
+        B.metok_prefill_prune(hidden, 0, 10, seg, [3], scores=sc, hidden_out=hidden[2:15])  # overlap that is not in place
     q = torch.zeros((3, 4, 48), device="cuda")
     k = torch.zeros((1, 20, 48), device="cuda")
     with pytest.raises(B.MetokError) as e:
@@ -246,3 +246,57 @@ def test_argument_errors_are_reported():
     assert e.value.code == -2
     with pytest.raises(B.MetokError):
         B.metok_retention_quotas(4, 0.5, 0.5, 10, 10)
+
+
+def in_place_case(S_vis, n_text, D, dtype, vis_start, keep, seed):
+    """hidden_out == hidden: prefix, kept rows and text rows end up at the front of the same buffer."""
+    B = mk()
+    rng = np.random.Generator(np.random.PCG64(seed))
+    S = vis_start + S_vis + n_text
+    # any bit pattern serves as payload: the compaction is a pure row copy
+    width16 = D if dtype == "bf16" else 2 * D
+    payload = rng.integers(-32768, 32767, size=(S, width16), dtype=np.int16)
+    hidden = torch.from_numpy(payload).view(torch.bfloat16 if dtype == "bf16" else torch.float32).cuda()
+    scores = rng.standard_normal(S_vis).astype(np.float32)
+    seg = (rng.random(S_vis) < 0.4).astype(np.int32)
+    quotas = [int(np.ceil(keep * int((seg == s).sum()))) for s in (0, 1)]
+    out = B.metok_prefill_prune(hidden, vis_start, S_vis, i32(seg), quotas, scores=torch.from_numpy(scores).cuda(),
+                                hidden_out=hidden[: S - S_vis + sum(quotas)])
+    torch.cuda.synchronize()
+    assert out["hidden_out"].data_ptr() == hidden.data_ptr()
+    kept = O.segmented_topk(scores, seg, quotas)
+    np.testing.assert_array_equal(out["kept_idx"].cpu().numpy(), kept)
+    want = O.compact_hidden(payload, vis_start, S_vis, kept)
+    got = out["hidden_out"].view(torch.int16).cpu().numpy()
+    assert np.array_equal(got, want), "in-place compaction differs from the oracle's row list"
+
+
+def test_in_place_compaction_at_the_hierarchical_size():
+    # 256 x 144 visual rows + 64 text rows of 3584 bf16: 2314 tiles of 16 rows, half of the rows kept
+    in_place_case(36864, 64, 3584, "bf16", 0, 0.5, 11)
+
+
+@pytest.mark.parametrize("S_vis,n_text,D,dtype,vis_start,keep", [
+    (5000, 40, 512, "bf16", 7, 0.25),       # 1 KB rows, system prefix
+    (5000, 40, 512, "bf16", 0, 0.97),       # dense keep: every tile waits for its predecessor
+    (3000, 16, 4096, "f32", 3, 0.5),        # 16 KB rows: the widest row the in-place path takes
+    (900, 5, 72, "f32", 0, 0.1),            # 288-byte rows (18 pieces: 56 rows per step, 16 idle threads)
+    (64, 3, 8, "bf16", 2, 1.0),             # nothing pruned: no row moves
+    (64, 3, 8, "bf16", 2, 0.0),             # every visual row pruned: only the text rows move
+])
+def test_in_place_compaction_shapes(S_vis, n_text, D, dtype, vis_start, keep):
+    in_place_case(S_vis, n_text, D, dtype, vis_start, keep, 100 + S_vis + D)
+
+
+def test_partial_overlap_and_too_wide_rows_are_refused_in_place():
+    B = mk()
+    hidden = torch.zeros((40, 64), dtype=torch.float32, device="cuda")
+    seg = torch.zeros(32, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(32, device="cuda")
+    with pytest.raises(B.MetokError) as e:
+        B.metok_prefill_prune(hidden, 0, 32, seg, [8], scores=scores, hidden_out=hidden[1:17])       # shifted by one row
+    assert e.value.code == -1 and "overlaps" in str(e.value)
+    wide = torch.zeros((12, 8192), dtype=torch.float32, device="cuda")                                # 32 KB rows
+    with pytest.raises(B.MetokError) as e:
+        B.metok_prefill_prune(wide, 0, 8, seg[:8], [4], scores=scores[:8], hidden_out=wide[:8])
+    assert e.value.code == -2

@@ -47,8 +47,11 @@ def run_and_check(L, B, H, S, dh16, dtype, idx_lists):
     kd = [as_device(k, dtype) for k in ks]
     vd = [as_device(v, dtype) for v in vs]
     idx_dev = [None if ix is None else torch.from_numpy(np.ascontiguousarray(ix, dtype=np.int32)).cuda() for ix in idx_lists]
-    new_len = Bm.metok_kv_compact(kd, vd, idx_dev)
+    ws = torch.full((Bm.metok_kv_compact_workspace_bytes(L, B, H, S, kd[0].shape[-1], Bm.BF16 if dtype == "bf16" else Bm.F32),),
+                    0xA5, dtype=torch.uint8, device="cuda")      # garbage on entry: the call clears what it uses
+    new_len = Bm.metok_kv_compact(kd, vd, idx_dev, workspace=ws)
     torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32)[0]) == 0, "a bounded wait inside the row mover expired"
     want_len = [S if ix is None else ix.shape[1] for ix in idx_lists]
     np.testing.assert_array_equal(new_len.cpu().numpy(), want_len)
     for l in range(L):
@@ -97,6 +100,50 @@ def test_adversarial_index_sets(S, dh, dtype):
         base = sets[name].astype(np.int32)
         idx_lists.append(np.stack([base, base]))          # B = 2 videos share the list here
     run_and_check(L, 2, 3, S, dh16, dtype, idx_lists)
+
+
+@pytest.mark.parametrize("S,dh16,dtype", [
+    (3000, 1024, "bf16"),      # 2 KB rows: 8 rows per step, tiles of 64 rows, 47 tiles per slab
+    (700, 8192, "f32"),        # 16 KB rows: one row per step, tiles of 8 rows
+    (90, 10240, "f32"),        # 20 KB rows: two column slices per row
+    (20000, 8, "bf16"),        # 16-byte rows: tiles of 8192 rows
+])
+def test_many_tiles_per_slab(S, dh16, dtype):
+    """Row widths that change the tile height, so that a slab has many tiles whose stores wait for earlier tiles."""
+    sets = adversarial_sets(S)
+    names = ["stride2", "shift_by_one", "random_half", "prefix_then_tail", "all_tail", "random_eighth"]
+    idx_lists = [sets[n].astype(np.int32)[None, :] for n in names]
+    run_and_check(len(names), 1, 1, S, dh16, dtype, idx_lists)
+
+
+def test_expired_wait_sets_the_error_word_and_nothing_hangs():
+    """With a poll limit of 0 a tile whose predecessor has not published yet gives up at once: the call still
+    returns, the kernels still end, and the error word reports it.  With the default limit the same input compacts."""
+    Bm = mk()
+    S, dh = 6000, 1024                                    # 94 tiles of 64 rows, every tile waits for the one before it
+    idx = np.arange(1, S, dtype=np.int32)[None, :]
+    ks, vs = fill_cache(1, 1, 1, S, dh, "bf16")
+    nbytes = Bm.metok_kv_compact_workspace_bytes(1, 1, 1, S, dh, Bm.BF16)
+    try:
+        Bm.metok_debug_set_move_spin_limit(0)
+        kd, vd = [as_device(ks[0], "bf16")], [as_device(vs[0], "bf16")]
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        Bm.metok_kv_compact(kd, vd, [torch.from_numpy(idx).cuda()], workspace=ws)
+        torch.cuda.synchronize()
+        err = int(ws[:4].view(torch.int32)[0])
+        assert err in (0, 1)
+        if err == 0:                                      # every flag happened to be up at the first poll
+            assert np.array_equal(as_host(kd[0])[0, 0, :S - 1], O.kv_compact(ks[0][0, 0], idx[0]))
+        print(f"poll limit 0: error word {err}")
+    finally:
+        Bm.metok_debug_set_move_spin_limit(1 << 24)
+    kd, vd = [as_device(ks[0], "bf16")], [as_device(vs[0], "bf16")]
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    Bm.metok_kv_compact(kd, vd, [torch.from_numpy(idx).cuda()], workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32)[0]) == 0
+    assert np.array_equal(as_host(kd[0])[0, 0, :S - 1], O.kv_compact(ks[0][0, 0], idx[0]))
+    assert np.array_equal(as_host(vd[0])[0, 0, :S - 1], O.kv_compact(vs[0][0, 0], idx[0]))
 
 
 def test_per_video_lists_and_untouched_layers():

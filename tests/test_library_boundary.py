@@ -33,7 +33,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert len(names) == 19 and len(set(names)) == len(names)
+    assert len(names) == 21 and len(set(names)) == len(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
     from paper_2506_02850_amd import binding
@@ -106,6 +106,13 @@ def test_workspace_queries(lib):
     no_attention = prune(36992, 0, 0, 0, 0, 36864, 1)
     assert full > no_attention > 36864
     assert full < 8 << 20                         # a few MB: partial column sums dominate
+    kvw = lib.metok_kv_compact_workspace_bytes
+    kvw.restype = ctypes.c_size_t
+    kvw.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
+    # LongVA-shaped cache: tiles of 512 rows (1024 threads x 8 pieces of a 256-byte row), 73 per slab, 64 slabs per
+    # layer, one 4-byte flag each, after a 256-byte header (error word, one ticket per launch)
+    assert kvw(28, 8, 4, 36992, 128, 1) == 256 + 28 * 64 * 73 * 4
+    assert kvw(28, 8, 4, 36992, 12, 1) == 0       # 24-byte rows
 
 
 def test_argument_errors_before_any_launch(lib):
@@ -123,22 +130,24 @@ def test_argument_errors_before_any_launch(lib):
     assert seg(fake, 1, 9000, 16, 64, None, 2, 0, fake, fake, fake, None, fake, 1 << 30, None) == -1    # T limit
     kv = lib.metok_kv_compact
     kv.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i64, i32, i32, ctypes.POINTER(vp),
-                   ctypes.POINTER(ctypes.c_int32), vp, vp]
+                   ctypes.POINTER(ctypes.c_int32), vp, vp, sz, vp]
     k = (vp * 1)(fake); v = (vp * 1)(fake); idx = (vp * 1)(fake)
     nk = (ctypes.c_int32 * 1)(4)
-    assert kv(k, v, 1, 1, 1, 16, 12, 1, idx, nk, None, None) == -1      # 24-byte rows
+    assert kv(k, v, 1, 1, 1, 16, 12, 1, idx, nk, None, fake, 1 << 20, None) == -1      # 24-byte rows
+    assert kv(k, v, 1, 1, 1, 16, 16, 1, idx, nk, None, fake, 16, None) == -3           # workspace too small
+    assert kv(k, v, 1, 1, 1, 16, 16, 1, idx, nk, None, None, 0, None) == -3            # no workspace
     nk[0] = 17
-    assert kv(k, v, 1, 1, 1, 16, 16, 1, idx, nk, None, None) == -1      # n_keep > S_cap
-    assert kv(k, v, 0, 1, 1, 16, 16, 1, idx, nk, None, None) == -1      # L < 1
-    assert kv(k, v, 200, 1, 1, 16, 16, 1, idx, nk, None, None) == -1    # L > METOK_MAX_LAYERS
+    assert kv(k, v, 1, 1, 1, 16, 16, 1, idx, nk, None, fake, 1 << 20, None) == -1      # n_keep > S_cap
+    assert kv(k, v, 0, 1, 1, 16, 16, 1, idx, nk, None, fake, 1 << 20, None) == -1      # L < 1
+    assert kv(k, v, 200, 1, 1, 16, 16, 1, idx, nk, None, fake, 1 << 20, None) == -1    # L > METOK_MAX_LAYERS
     kvp = lib.metok_kv_compact_paged
     kvp.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i64, i32, i32, i32, vp, i32, ctypes.POINTER(vp),
-                    ctypes.POINTER(ctypes.c_int32), vp, vp]
+                    ctypes.POINTER(ctypes.c_int32), vp, vp, sz, vp]
     nk[0] = 4
-    assert kvp(k, v, 1, 1, 1, 8, 4, 16, 1, None, 4, idx, nk, None, None) == -1      # no page table
-    assert kvp(k, v, 1, 1, 1, 8, 0, 16, 1, fake, 4, idx, nk, None, None) == -1      # page_size < 1
+    assert kvp(k, v, 1, 1, 1, 8, 4, 16, 1, None, 4, idx, nk, None, fake, 1 << 20, None) == -1      # no page table
+    assert kvp(k, v, 1, 1, 1, 8, 0, 16, 1, fake, 4, idx, nk, None, fake, 1 << 20, None) == -1      # page_size < 1
     nk[0] = 17
-    assert kvp(k, v, 1, 1, 1, 8, 4, 16, 1, fake, 4, idx, nk, None, None) == -1      # n_keep > pages_per_seq * page_size
+    assert kvp(k, v, 1, 1, 1, 8, 4, 16, 1, fake, 4, idx, nk, None, fake, 1 << 20, None) == -1      # n_keep > pages_per_seq * page_size
     one = lib.metok_segment_compress
     one.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, dbl, dbl, i32, i32, i32, i32, vp, vp, vp, vp, i64, i32,
                     vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
