@@ -8,18 +8,27 @@ One step = one pass of stages 1-3 over a batch of synthetic, LongVA-7B-shaped 25
            256 x 144 tokens, so the pooled tokens come out of the statistics pass: one read of the features);
   stage 2  per video: three metok_prefill_prune levels (keep 0.5 / 0.5 / 0.5 of the current count) on
            hidden states [36864 + 128, 3584] bf16 with 28 query / 4 kv heads of 128 and the last 64 text
-           positions as queries; event ids come from stage 1, retained indices are carried level to level;
+           positions as queries; keys carry a per-event mean shift and the queries lean towards one target
+           event; event ids come from stage 1, retained indices are carried level to level;
   stage 3  the whole batch: metok_kv_compact of a 28-layer KV cache [8, 4, 36992, 128] bf16 (K and V) to
            the per-layer retained sets of stage 2 (levels start at layers 3, 10, 19) plus the text rows.
 
 All inputs are resident in HBM before the timed region.  `value` is visual tokens entering stage 1 per
-second.  The JSON line also carries the roofline of the dominant kernel (the KV compaction, HBM bound;
-duration measured with events on the launch stream inside the timed region) and the CPU oracle timed
-on a bounded sample of the same workload.
+second.  The JSON line also carries
+  roofline      the dominant kernel (the in-place row mover of the KV compaction, HBM bound), its duration taken
+                from events the library records around that kernel inside the timed region;
+  stages        per kernel family, measured in the same run right after the timed region with the same event
+                hook: duration (min / median), algorithmic GB/s or TFLOP/s and the fraction of the peak; per
+                stage the tokens entering it per second;
+  configs       call-level timings of the encoder, single-level prefill, hierarchical prefill and KV
+                configurations on their own;
+  cpu_baseline  the CPU oracle on the same workload, one thread; cpu_baseline_all_cores: the same oracle, one
+                video per worker process.  Both run before the GPU is touched.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import math
 import os
@@ -33,6 +42,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 FRAMES, GRID, D_VIS = 256, 24, 1024
 N_EVENTS = 16
 TOK_PER_FRAME = 144
@@ -41,6 +51,11 @@ N_TEXT, TQ = 128, 64
 D_HID, HQ, HKV, DH = 3584, 28, 4, 128
 N_LAYERS, L_H = 28, (3, 10, 19)
 KEEP = (0.5, 0.5, 0.5)
+ADAPTIVE = dict(alpha=0.5, beta=0.45, s1=2, s2=3)      # the LongVA setting of the appendix "Implementation Details"
+
+# kernel ids of metok_trace_kernel (include/metok.h)
+TRACE = dict(frame_stats=1, pool=2, frame_stats_pool2=3, segment=4, plan=5, row_stats=6, col_sums=7, select=8,
+             write_index=9, gather_rows=10, move_rows=11)
 
 
 def level_counts():
@@ -49,6 +64,33 @@ def level_counts():
         n = int(math.ceil(r * n - 1e-9))
         out.append(n)
     return out                                   # 18432, 9216, 4608
+
+
+class HipEvents:
+    """hipEvent_t handles for the library's kernel trace hook (plain HIP through ctypes; torch's Event objects do not
+    expose their handle before the first record)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0 or not ev.value:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        if self.hip.hipEventSynchronize(b) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
 
 
 class Workload:
@@ -64,13 +106,17 @@ class Workload:
         self.counts = counts
         self.n_in = [N_VIS] + counts[:-1]
         rng = np.random.Generator(np.random.PCG64(seed))
+        S0 = N_VIS + N_TEXT
+        lib = binding.lib()
+        i32, f32, u8 = torch.int32, torch.float32, torch.uint8
 
         # ---- stage 1 inputs: planted events, unit centroid + N(0, 0.2^2) noise per entry
-        self.feats, self.text = [], []
+        self.feats, self.text, planted_events = [], [], []
         for b in range(batch):
             lens = synth.event_lengths(rng, FRAMES, N_EVENTS, 4, 40)
             cent = torch.from_numpy(synth.unit_rows(rng, N_EVENTS, D_VIS)).to(device)
             frame_event = torch.from_numpy(np.repeat(np.arange(N_EVENTS), lens)).to(device)
+            planted_events.append(frame_event)
             f = torch.randn((FRAMES, GRID * GRID, D_VIS), generator=gen, device=device, dtype=torch.float32)
             f.mul_(0.2).add_(cent[frame_event][:, None, :])
             self.feats.append(f.to(bf))
@@ -78,17 +124,33 @@ class Workload:
             t = (w[:, None] * cent).sum(0)
             self.text.append((t / t.norm()).to(bf))
             del f
-        # ---- stage 2 inputs
-        S0 = N_VIS + N_TEXT
-        self.hidden0 = [torch.randn((S0, D_HID), generator=gen, device=device, dtype=bf) for _ in range(batch)]
-        self.K = [[torch.randn((HKV, n + N_TEXT, DH), generator=gen, device=device, dtype=bf) for n in self.n_in]
-                  for _ in range(batch)]
-        self.Q = [[torch.randn((HQ, TQ, DH), generator=gen, device=device, dtype=bf) for _ in self.n_in]
-                  for _ in range(batch)]
-        self.weight = [torch.rand(N_EVENTS, generator=gen, device=device) + 0.5 for _ in range(batch)]
-        self.seg0 = torch.zeros(N_VIS, dtype=torch.int32, device=device)
-        self.hidden_out = [[torch.empty((c + N_TEXT, D_HID), dtype=bf, device=device) for c in counts]
-                           for _ in range(batch)]
+        # ---- preallocated outputs and workspaces (nothing is allocated inside a step)
+        # Videos are independent until stage 3, so their stage-1/2 calls are spread over a few streams: the
+        # one-workgroup planning and selection kernels of one video then overlap with the streaming kernels
+        # of another.  One workspace per stream (calls on a stream are ordered, so they can share it).
+        self.n_streams = max(1, min(n_streams, batch))
+        self.graph = None
+        self.streams = [torch.cuda.Stream(device=device) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        self.ws1 = [torch.empty(lib.metok_segment_compress_workspace_bytes(FRAMES, GRID, GRID, D_VIS, binding.BF16),
+                                dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
+        self.ws2 = [torch.empty(lib.metok_prefill_prune_workspace_bytes(S0, HQ, HKV, DH, TQ, N_VIS, binding.BF16),
+                                dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
+
+        def stage1_outputs():
+            return dict(sim=torch.empty(FRAMES - 1, dtype=f32, device=device),
+                        event_start=torch.empty(N_EVENTS + 1, dtype=i32, device=device),
+                        frame_event=torch.empty(FRAMES, dtype=i32, device=device),
+                        frame_score=torch.empty(FRAMES, dtype=f32, device=device),
+                        out_tokens=torch.empty((N_VIS, D_VIS), dtype=bf, device=device),
+                        frame_offsets=torch.empty(FRAMES + 1, dtype=i32, device=device),
+                        token_event=torch.empty(N_VIS, dtype=i32, device=device),
+                        event_is_key=torch.empty(N_EVENTS, dtype=u8, device=device),
+                        frame_is_key=torch.empty(FRAMES, dtype=u8, device=device),
+                        frame_stride=torch.empty(FRAMES, dtype=i32, device=device),
+                        event_score=torch.empty(N_EVENTS, dtype=f32, device=device))
+        self.s1_out = [stage1_outputs() for _ in range(batch)]
+        self.s1_adaptive_out = stage1_outputs()          # the two-pass adaptive setting is measured on one video at a time
+
         # ---- stage 3: KV cache and per-level index lists [B, kept + text]; the text part is fixed
         self.k_layers = [torch.empty((batch, HKV, S0, DH), dtype=bf, device=device).normal_(generator=gen)
                          for _ in range(N_LAYERS)]
@@ -108,48 +170,48 @@ class Workload:
         self.new_len = torch.empty(N_LAYERS, dtype=torch.int32, device=device)
         self.kv_ws = torch.empty(binding.metok_kv_compact_workspace_bytes(N_LAYERS, batch, HKV, S0, DH, binding.BF16),
                                  dtype=torch.uint8, device=device)
-        # ---- preallocated outputs and workspaces (nothing is allocated inside a step)
-        lib = binding.lib()
-        # Videos are independent until stage 3, so their stage-1/2 calls are spread over a few streams: the
-        # one-workgroup planning and selection kernels of one video then overlap with the streaming kernels
-        # of another.  One workspace per stream (calls on a stream are ordered, so they can share it).
-        self.n_streams = max(1, min(n_streams, batch))
-        self.graph = None
-        self.streams = [torch.cuda.Stream(device=device) for _ in range(self.n_streams)] if self.n_streams > 1 else []
-        self.ws1 = [torch.empty(max(lib.metok_segment_events_workspace_bytes(FRAMES, GRID * GRID, D_VIS, binding.BF16),
-                                    lib.metok_compress_encoder_tokens_workspace_bytes(FRAMES, GRID, GRID, D_VIS, binding.BF16)),
-                                dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
-        self.ws2 = [torch.empty(lib.metok_prefill_prune_workspace_bytes(S0, HQ, HKV, DH, TQ, N_VIS, binding.BF16),
-                                dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
-        i32, f32, u8 = torch.int32, torch.float32, torch.uint8
-        self.seg_out = [dict(sim=torch.empty(FRAMES - 1, dtype=f32, device=device),
-                             event_start=torch.empty(N_EVENTS + 1, dtype=i32, device=device),
-                             frame_event=torch.empty(FRAMES, dtype=i32, device=device),
-                             frame_score=torch.empty(FRAMES, dtype=f32, device=device)) for _ in range(batch)]
-        self.cmp_out = [dict(out_tokens=torch.empty((N_VIS, D_VIS), dtype=bf, device=device),
-                             frame_offsets=torch.empty(FRAMES + 1, dtype=i32, device=device),
-                             token_event=torch.empty(N_VIS, dtype=i32, device=device),
-                             event_is_key=torch.empty(N_EVENTS, dtype=u8, device=device),
-                             frame_is_key=torch.empty(FRAMES, dtype=u8, device=device),
-                             frame_stride=torch.empty(FRAMES, dtype=i32, device=device),
-                             event_score=torch.empty(N_EVENTS, dtype=f32, device=device),
-                             frame_score=torch.empty(FRAMES, dtype=f32, device=device)) for _ in range(batch)]
-        self.s1_out = [{**self.seg_out[b], **self.cmp_out[b]} for b in range(batch)]
+
+        # ---- stage 2 inputs with the event structure of the parity generators (synth.prefill_layer): keys of an
+        # event share a mean shift, the text queries lean towards one target event, hidden rows carry a per-event
+        # shift.  The keys of level 2 and 3 belong to the survivors of the level before, so the levels are run
+        # once here, in order, to learn which tokens those are (the timed steps repeat exactly these selections).
+        self.seg0 = torch.zeros(N_VIS, dtype=torch.int32, device=device)
+        self.hidden_out = [[torch.empty((c + N_TEXT, D_HID), dtype=bf, device=device) for c in counts] for _ in range(batch)]
         self.prune_out = [[dict(scores=torch.empty(n, dtype=f32, device=device),
                                 kept_idx=torch.empty(c, dtype=i32, device=device),
                                 token_seg_out=torch.empty(c, dtype=i32, device=device),
                                 token_event_out=torch.empty(c, dtype=i32, device=device),
                                 orig_idx_out=self.idx_level[lv][b, :c])
                            for lv, (n, c) in enumerate(zip(self.n_in, counts))] for b in range(batch)]
+        self.hidden0, self.K, self.Q, self.weight = [], [], [], []
+        for b in range(batch):
+            mu = torch.randn((N_EVENTS, DH), generator=gen, device=device)
+            target = int(torch.randint(0, N_EVENTS, (1,), generator=gen, device=device))
+            shift = torch.randn(N_EVENTS, generator=gen, device=device)
+            tev = planted_events[b].repeat_interleave(TOK_PER_FRAME)            # event of every pooled token
+            h = torch.randn((S0, D_HID), generator=gen, device=device, dtype=torch.float32)
+            h[:N_VIS] += shift[tev][:, None]
+            self.hidden0.append(h.to(bf))
+            del h
+            self.weight.append(torch.rand(N_EVENTS, generator=gen, device=device) + 0.5)
+            self.K.append([])
+            self.Q.append([(torch.randn((HQ, TQ, DH), generator=gen, device=device) + 0.5 * mu[target]).to(bf) for _ in self.n_in])
+            tev = tev.to(torch.int32)
+            for lv, n in enumerate(self.n_in):
+                k = torch.randn((HKV, n + N_TEXT, DH), generator=gen, device=device)
+                k[:, :n] += 0.5 * mu[tev.long()][None]
+                self.K[b].append(k.to(bf))
+                del k
+                if lv + 1 < len(self.n_in):
+                    tev = self.prune_level(b, lv, tev)["token_event_out"].clone()
         torch.cuda.synchronize()
 
-    # algorithmic bytes (what the method itself must move)
-    def stage1_bytes(self):
-        read = FRAMES * GRID * GRID * D_VIS * 2          # uniform stride 2: statistics and pooling share one pass over V
-        return self.batch * (read + N_VIS * D_VIS * 2)
+    # ---- algorithmic bytes / flops (what the method itself must move or compute)
+    def stage1_fused_bytes(self):                  # per video: one read of V, pooled tokens written
+        return FRAMES * GRID * GRID * D_VIS * 2 + N_VIS * D_VIS * 2
 
-    def gather_bytes(self):
-        return self.batch * sum(2 * (c + N_TEXT) * D_HID * 2 for c in self.counts)
+    def gather_bytes(self, lv):                    # per video and level: every output row read and written once
+        return 2 * (self.counts[lv] + N_TEXT) * D_HID * 2
 
     def kv_rows(self):
         per_video = 0
@@ -163,23 +225,36 @@ class Workload:
         idx_bytes = self.batch * self.kv_rows() * 4
         return self.batch * self.kv_rows() * HKV * DH * 2 * 2 * 2 + idx_bytes     # K and V, read + write
 
-    def score_flops(self):
-        return self.batch * sum(2 * 2 * HQ * TQ * (n + N_TEXT) * DH for n in self.n_in)      # two passes
+    def score_flops(self, lv):                     # per video and level, one pass over the keys
+        return 2 * HQ * TQ * (self.n_in[lv] + N_TEXT) * DH
 
+    # ---- the calls
     def stage1(self, b):
         ws = self.ws1[b % self.n_streams]
         return self.B.metok_segment_compress(self.feats[b], GRID, GRID, N_EVENTS, self.text[b], 1.0, 1.0, 2, 2,
                                              workspace=ws, out=self.s1_out[b])
 
+    def stage1_adaptive(self, b):
+        """Algorithm 1 with the paper's LongVA strides: two passes over the features (statistics, then pooling)."""
+        ws, o, a = self.ws1[0], self.s1_adaptive_out, ADAPTIVE
+        seg = self.B.metok_segment_events(self.feats[b], N_EVENTS, self.text[b], workspace=ws, out=o)
+        return self.B.metok_compress_encoder_tokens(self.feats[b], GRID, GRID, seg["event_start"], a["alpha"], a["beta"], a["s1"], a["s2"],
+                                                    frame_score=seg["frame_score"], workspace=ws, out=o)
+
+    def prune_level(self, b, lv, token_event):
+        n, c = self.n_in[lv], self.counts[lv]
+        prev = self.prune_out[b][lv - 1] if lv > 0 else None
+        h = self.hidden0[b] if lv == 0 else self.hidden_out[b][lv - 1]
+        tseg = self.seg0 if lv == 0 else prev["token_seg_out"]
+        orig = None if lv == 0 else prev["orig_idx_out"]
+        return self.B.metok_prefill_prune(h, 0, n, tseg, [c], q_text=self.Q[b][lv], k_all=self.K[b][lv], token_event=token_event,
+                                          event_weight=self.weight[b], orig_idx=orig, hidden_out=self.hidden_out[b][lv],
+                                          workspace=self.ws2[b % self.n_streams], out=self.prune_out[b][lv])
+
     def stage2(self, b, token_event):
-        B = self.B
-        ws2 = self.ws2[b % self.n_streams]
-        h, tseg, tev, orig = self.hidden0[b], self.seg0, token_event, None
-        for lv, (n, c) in enumerate(zip(self.n_in, self.counts)):
-            r = B.metok_prefill_prune(h, 0, n, tseg, [c], q_text=self.Q[b][lv], k_all=self.K[b][lv], token_event=tev,
-                                      event_weight=self.weight[b], orig_idx=orig, hidden_out=self.hidden_out[b][lv],
-                                      workspace=ws2, out=self.prune_out[b][lv])
-            h, tseg, tev, orig = r["hidden_out"], r["token_seg_out"], r["token_event_out"], r["orig_idx_out"]
+        tev = token_event
+        for lv in range(len(self.n_in)):
+            tev = self.prune_level(b, lv, tev)["token_event_out"]
 
     def stage3(self):
         self.B.metok_kv_compact(self.k_layers, self.v_layers, self.idx_layers, new_len=self.new_len, workspace=self.kv_ws)
@@ -206,7 +281,7 @@ class Workload:
         """Records the stage-1/2 launches of one step (about 270 kernels on 8 streams) into a HIP graph.  The
         library calls only launch kernels on the stream they are given (no allocation, copy, memset or
         synchronisation), so they can be captured as they are; the KV compaction stays an ordinary launch so
-        that it can be bracketed by events."""
+        that the library can bracket its kernel with events."""
         torch = self.torch
         self.graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
@@ -222,14 +297,86 @@ class Workload:
         else:
             self.stages_1_2()
         if kv_events is not None:
-            kv_events[0].record()
+            self.B.lib().metok_trace_kernel(TRACE["move_rows"], kv_events[0], kv_events[1])
         self.stage3()
         if kv_events is not None:
-            kv_events[1].record()
+            self.B.lib().metok_trace_kernel(0, None, None)
+
+
+def stats_us(ms_list):
+    a = np.asarray(ms_list, dtype=np.float64) * 1e3
+    return dict(us_min=round(float(a.min()), 2), us_median=round(float(np.median(a)), 2), launches=int(a.size))
+
+
+def hbm_entry(ms_list, nbytes, kernel):
+    e = dict(kernel=kernel, **stats_us(ms_list), algorithmic_bytes=int(nbytes))
+    e["GBs"] = round(nbytes / (e["us_median"] * 1e-6) / 1e9, 1)
+    e["frac_of_hbm_peak"] = round(e["GBs"] / HBM_PEAK_GBS, 4)
+    return e
+
+
+def time_kernels(w: Workload, hev: HipEvents, reps: int):
+    """Per kernel family, in this run: the library brackets the named kernel with our events (metok_trace_kernel), so the
+    one-workgroup planning kernels of a call are not charged to the streaming kernels."""
+    torch, lib = w.torch, w.B.lib()
+    a, b_ev = hev.create(), hev.create()
+
+    def traced(kernel, call):
+        lib.metok_trace_kernel(TRACE[kernel], a, b_ev)
+        try:
+            res = call()
+        finally:
+            lib.metok_trace_kernel(0, None, None)
+        return hev.elapsed_ms(a, b_ev), res
+
+    out = {}
+    videos = list(range(w.batch))
+    # stage 1, one pass (uniform stride 2)
+    ms = [traced("frame_stats_pool2", lambda v=v: w.stage1(v))[0] for _ in range(reps) for v in videos]
+    e = hbm_entry(ms, w.stage1_fused_bytes(), "frame_stats_pool2_kernel")
+    e["workload"] = "[256, 576, 1024] bf16, every frame pooled 2 x 2: statistics and pooled tokens from one read"
+    out["stage1_one_pass"] = e
+    # stage 1, the paper's adaptive strides: statistics pass, then pooling pass
+    ms_stats, ms_pool, rows = [], [], []
+    for _ in range(reps):
+        for v in videos:
+            t, _ = traced("frame_stats", lambda v=v: w.stage1_adaptive(v))
+            ms_stats.append(t)
+            t, res = traced("pool", lambda v=v: w.stage1_adaptive(v))
+            ms_pool.append(t)
+            if len(rows) < len(videos):
+                rows.append(int(res["frame_offsets"][-1]))
+    v_bytes = FRAMES * GRID * GRID * D_VIS * 2
+    out["stage1_adaptive_statistics"] = hbm_entry(ms_stats, v_bytes, "frame_stats_kernel")
+    pool_bytes = v_bytes + int(np.mean(rows)) * D_VIS * 2
+    e = hbm_entry(ms_pool, pool_bytes, "pool_kernel")
+    e["pooled_rows_per_video_mean"] = float(np.mean(rows))
+    e["workload"] = "[256, 576, 1024] bf16, (s1, s2) = (2, 3), alpha = 0.5, beta = 0.45: strides 2 / 3 / 4 / 6 per frame"
+    out["stage1_adaptive_pooling"] = e
+    # stage 2 per level
+    toks = [w.s1_out[v]["token_event"] for v in videos]
+    for lv in range(len(w.n_in)):
+        tev = [toks[v] if lv == 0 else w.prune_out[v][lv - 1]["token_event_out"] for v in videos]
+        entry = dict(visual_tokens_in=w.n_in[lv], kept=w.counts[lv])
+        for kernel in ("row_stats", "col_sums"):
+            ms = [traced(kernel, lambda v=v: w.prune_level(v, lv, tev[v]))[0] for _ in range(reps) for v in videos]
+            k = dict(kernel=kernel + "_kernel", **stats_us(ms), flops=w.score_flops(lv))
+            k["TFLOPs"] = round(k["flops"] / (k["us_median"] * 1e-6) / 1e12, 1)
+            k["frac_of_bf16_mfma_peak"] = round(k["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
+            entry[kernel] = k
+        for kernel in ("select", "write_index"):
+            ms = [traced(kernel, lambda v=v: w.prune_level(v, lv, tev[v]))[0] for _ in range(reps) for v in videos]
+            entry[kernel] = dict(kernel=kernel + "_kernel", **stats_us(ms))
+        ms = [traced("gather_rows", lambda v=v: w.prune_level(v, lv, tev[v]))[0] for _ in range(reps) for v in videos]
+        entry["gather_rows"] = hbm_entry(ms, w.gather_bytes(lv), "gather_rows_kernel")
+        out[f"stage2_level{lv + 1}"] = entry
+    torch.cuda.synchronize()
+    return out
 
 
 def time_stages(w: Workload, reps: int):
-    """Per-stage GPU time (ms per step), measured after the timed region; informational."""
+    """Whole stages back to back on one stream (every kernel of the stage, also the one-workgroup ones): ms per step
+    and the tokens entering the stage per second."""
     torch = w.torch
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
     for r in range(reps):
@@ -242,57 +389,124 @@ def time_stages(w: Workload, reps: int):
         w.stage3()
         ev[r][3].record()
     torch.cuda.synchronize()
-    return [float(np.median([ev[r][i].elapsed_time(ev[r][i + 1]) for r in range(reps)])) for i in range(3)]
+    ms = [float(np.median([ev[r][i].elapsed_time(ev[r][i + 1]) for r in range(reps)])) for i in range(3)]
+    tokens = [w.batch * FRAMES * GRID * GRID, w.batch * N_VIS, w.batch * N_VIS]
+    return {f"stage{i + 1}": dict(ms_per_step_alone=round(ms[i], 4), tokens_in_per_step=tokens[i],
+                                 tokens_in_per_s=round(tokens[i] / (ms[i] * 1e-3), 1)) for i in range(3)}
 
 
-def cpu_baseline(n_videos: int = 8):
-    """The oracle, unchanged, single-threaded, on whole videos of the same workload: stage 1 on 256 frames, the
-    three pruning levels, and the KV compaction of the video's 25 moving layers -- for n_videos videos (8 = the
-    batch of one step; inputs from the seeded CPU generators; only the oracle calls are timed: about 1.3 s per
-    video on the MI355X machine's host, 6 s on the build container)."""
-    from threadpoolctl import threadpool_limits
+def time_configs(w: Workload, reps: int):
+    """The named configurations on their own (call-level GPU time, every kernel of the call included)."""
+    torch, B = w.torch, w.B
+    out = {}
 
+    def timed(call, n_calls=reps):
+        call()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_calls)]
+        for a, b in evs:
+            a.record()
+            call()
+            b.record()
+        torch.cuda.synchronize()
+        t = [a.elapsed_time(b) for a, b in evs]
+        return dict(ms_min=round(float(np.min(t)), 4), ms_median=round(float(np.median(t)), 4))
+
+    # encoder configuration: 32 frames x 576 x 1024 (37.7 MB: resident in the last-level cache after the first pass)
+    f32 = w.feats[0][:32].contiguous()
+    e = timed(lambda: B.metok_segment_compress(f32, GRID, GRID, 8, w.text[0], 1.0, 1.0, 2, 2))
+    e["tokens_in_per_s"] = round(32 * GRID * GRID / (e["ms_median"] * 1e-3), 1)
+    out["encoder_32_frames_uniform"] = e
+    a = ADAPTIVE
+    e = timed(lambda: B.metok_segment_compress(f32, GRID, GRID, 8, w.text[0], a["alpha"], a["beta"], a["s1"], a["s2"]))
+    e["tokens_in_per_s"] = round(32 * GRID * GRID / (e["ms_median"] * 1e-3), 1)
+    out["encoder_32_frames_adaptive"] = e
+    # prefill configuration: 128 x 144 visual + 64 text rows, one level, keep 25 %
+    nv, nt = 128 * TOK_PER_FRAME, 64
+    hid = w.hidden0[0][: nv + nt]
+    k = w.K[0][0][:, : nv + nt].contiguous()
+    tev = w.s1_out[0]["token_event"][:nv]
+    seg = w.seg0[:nv]
+    e = timed(lambda: B.metok_prefill_prune(hid, 0, nv, seg, [nv // 4], q_text=w.Q[0][0], k_all=k, token_event=tev,
+                                            event_weight=w.weight[0]))
+    e["tokens_in_per_s"] = round(nv / (e["ms_median"] * 1e-3), 1)
+    out["prefill_18432_keep_quarter"] = e
+    # hierarchical configuration: the three levels of one video
+    e = timed(lambda: w.stage2(0, w.s1_out[0]["token_event"]))
+    e["tokens_in_per_s"] = round(N_VIS / (e["ms_median"] * 1e-3), 1)
+    out["hierarchical_36864_three_levels"] = e
+    # decoding configuration: the batch's KV cache
+    e = timed(w.stage3)
+    e["tokens_in_per_s"] = round(w.batch * N_VIS / (e["ms_median"] * 1e-3), 1)
+    e["GBs"] = round(w.kv_bytes() / (e["ms_median"] * 1e-3) / 1e9, 1)
+    out["kv_28_layers_batch8"] = e
+    return out
+
+
+# -------------------------------------------------------------------------------------------------
+# CPU oracle legs (run before the GPU is initialised; the oracle is used as it stands)
+# -------------------------------------------------------------------------------------------------
+def oracle_video(vid: int):
+    """One whole video through the oracle: stage 1 on 256 frames, the three pruning levels with fresh activations, the KV
+    compaction of its 25 moving layers x 4 heads x (K, V).  Returns the seconds spent inside oracle calls per stage
+    (the seeded generators that make the inputs are not timed)."""
     from oracle import metok_oracle as O
     from paper_2506_02850_amd import synth
 
     counts = level_counts()
     t_stage = [0.0, 0.0, 0.0]
+    v = synth.planted_video(100 + vid, FRAMES, (GRID, GRID), D_VIS, N_EVENTS, 4, 40, 0.2, "bf16")
+    t0 = time.perf_counter()
+    S = O.adjacent_frame_cosine(v.feats)
+    es, _ = O.event_boundaries(S, N_EVENTS)
+    cmp = O.compress_encoder_tokens(v.feats, (GRID, GRID), v.text_emb, es, 1.0, 1.0, 2, 2)
+    t_stage[0] += time.perf_counter() - t0
+    ev = cmp["token_event"]
+    del v, cmp
+    seg = np.zeros(N_VIS, dtype=np.int32)
+    kept_sets = []
+    orig = np.arange(N_VIS)
+    for lv, c in enumerate(counts):
+        layer = synth.prefill_layer(200 + 10 * vid + lv, ev, N_EVENTS, N_TEXT, D_HID, HQ, HKV, DH, "bf16")
+        t0 = time.perf_counter()
+        r = O.prefill_prune(layer.hidden, layer.q_text[:, N_TEXT - TQ:], layer.k_all, 0, ev.shape[0], seg, ev,
+                            layer.event_weight, [c])
+        t_stage[1] += time.perf_counter() - t0
+        kept = r["kept_idx"]
+        ev, seg, orig = ev[kept], seg[kept], orig[kept]
+        kept_sets.append(orig.astype(np.int32))
+        del layer, r
+    S0 = N_VIS + N_TEXT
+    sched = synth.kv_layer_schedule(N_LAYERS, L_H, N_VIS, N_TEXT, kept_sets)
+    slab = np.random.default_rng(vid).integers(-32768, 32767, size=(S0, DH), dtype=np.int16)
+    t0 = time.perf_counter()
+    for l in range(N_LAYERS):
+        if sched[l] is None:
+            continue
+        for _ in range(HKV * 2):
+            O.kv_compact(slab, sched[l])
+    t_stage[2] += time.perf_counter() - t0
+    return t_stage
+
+
+def _oracle_worker(vid: int):
+    from threadpoolctl import threadpool_limits
+
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        stages = oracle_video(vid)
+        return stages, time.perf_counter() - t0
+
+
+def cpu_baseline(n_videos: int):
+    """The oracle, unchanged, single-threaded, on whole videos of the same workload."""
+    from threadpoolctl import threadpool_limits
+
+    t_stage = [0.0, 0.0, 0.0]
     with threadpool_limits(limits=1):
         for vid in range(n_videos):
-            # stage 1: 256 frames, uniform stride 2
-            v = synth.planted_video(100 + vid, FRAMES, (GRID, GRID), D_VIS, N_EVENTS, 4, 40, 0.2, "bf16")
-            t0 = time.perf_counter()
-            S = O.adjacent_frame_cosine(v.feats)
-            es, _ = O.event_boundaries(S, N_EVENTS)
-            cmp = O.compress_encoder_tokens(v.feats, (GRID, GRID), v.text_emb, es, 1.0, 1.0, 2, 2)
-            t_stage[0] += time.perf_counter() - t0
-            ev = cmp["token_event"]
-            del v, cmp
-            # stage 2: three levels, fresh activations per level, metadata carried
-            seg = np.zeros(N_VIS, dtype=np.int32)
-            kept_sets = []
-            orig = np.arange(N_VIS)
-            for lv, c in enumerate(counts):
-                layer = synth.prefill_layer(200 + 10 * vid + lv, ev, N_EVENTS, N_TEXT, D_HID, HQ, HKV, DH, "bf16")
-                t0 = time.perf_counter()
-                r = O.prefill_prune(layer.hidden, layer.q_text[:, N_TEXT - TQ:], layer.k_all, 0, ev.shape[0], seg, ev,
-                                    layer.event_weight, [c])
-                t_stage[1] += time.perf_counter() - t0
-                kept = r["kept_idx"]
-                ev, seg, orig = ev[kept], seg[kept], orig[kept]
-                kept_sets.append(orig.astype(np.int32))
-                del layer, r
-            # stage 3: the video's 25 moving layers, K and V of 4 heads each
-            S0 = N_VIS + N_TEXT
-            sched = synth.kv_layer_schedule(N_LAYERS, L_H, N_VIS, N_TEXT, kept_sets)
-            slab = np.random.default_rng(vid).integers(-32768, 32767, size=(S0, DH), dtype=np.int16)
-            t0 = time.perf_counter()
-            for l in range(N_LAYERS):
-                if sched[l] is None:
-                    continue
-                for _ in range(HKV * 2):
-                    O.kv_compact(slab, sched[l])
-            t_stage[2] += time.perf_counter() - t0
+            for i, t in enumerate(oracle_video(vid)):
+                t_stage[i] += t
     total = sum(t_stage)
     return dict(value=n_videos * FRAMES * GRID * GRID / total, unit="tokens/s", cores=1, kind="oracle",
                 sample=f"{n_videos} whole videos (one step has 8): stage 1 on 256 frames, three pruning levels, KV compaction of "
@@ -300,34 +514,65 @@ def cpu_baseline(n_videos: int = 8):
                 seconds_by_stage=[round(t, 3) for t in t_stage], seconds=round(total, 3))
 
 
+def cpu_baseline_all_cores(n_videos: int):
+    """The same oracle on several host cores: one video per worker process (each single-threaded), at most 16 workers.
+    The rate is videos finished per second of the workers' oracle calls running side by side."""
+    import multiprocessing as mp
+
+    nproc = os.cpu_count() or 1
+    workers = max(1, min(n_videos, nproc, 16))
+    ctx = mp.get_context("spawn")
+    t0 = time.perf_counter()
+    with ctx.Pool(workers) as pool:
+        res = pool.map(_oracle_worker, range(n_videos), chunksize=1)
+    wall = time.perf_counter() - t0
+    oracle_s = [sum(stages) for stages, _ in res]
+    # workers run concurrently: the oracle part of the wall clock is the longest chain of oracle calls on one worker
+    rounds = (n_videos + workers - 1) // workers
+    busy = max(oracle_s) * rounds
+    return dict(value=n_videos * FRAMES * GRID * GRID / busy, unit="tokens/s", cores=workers, nproc=nproc, kind="oracle",
+                sample=f"{n_videos} whole videos, one per worker process, {workers} processes side by side (host reports {nproc} "
+                       "cores); per video as in cpu_baseline; rate = tokens / (slowest worker's oracle seconds x rounds)",
+                oracle_seconds_per_video=[round(t, 3) for t in oracle_s], wall_seconds_with_input_generation=round(wall, 3))
+
+
 def read_traffic():
-    """HBM bytes per KV-compaction launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", "kv_compact_longva256_b8_pmc.txt")
+    """HBM bytes per KV-compaction launch from the committed rocprofv3 counter summary, if present (a file-sourced
+    figure: it is not measured in this run)."""
+    path = os.path.join(ROOT, "profiles", "move_rows_longva256_b8_pmc.txt")
     try:
         with open(path) as fh:
             for line in fh:
                 if line.startswith("traffic_bytes_per_launch"):
-                    return float(line.split()[1])
+                    return float(line.split()[1]), os.path.relpath(path, ROOT)
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--streams", type=int, default=8, help="streams that share the per-video stage-1/2 work")
     ap.add_argument("--no-graph", action="store_true", help="launch the stage-1/2 kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["all", "kv", "copy", "prune"], default="all",
-                    help="kv / copy / prune: run only the KV compaction, the calibration copy or the stage-2 calls "
-                         "(for profiler counter runs)")
+    ap.add_argument("--cpu-videos", type=int, default=4, help="videos of the single-thread oracle leg (the all-cores leg takes 8)")
+    ap.add_argument("--kernel-reps", type=int, default=3, help="repetitions (x 8 videos) of the per-kernel measurements")
+    ap.add_argument("--only", choices=["all", "kv", "copy", "prune", "stage1", "stage1_adaptive"], default="all",
+                    help="run only one part (for profiler runs): the KV compaction, the calibration copy, the stage-2 calls, "
+                         "the one-pass stage 1 or the two-pass adaptive stage 1")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    # the CPU legs come first: worker processes are started before this process touches the GPU
+    cpu = {}
+    if args.only == "all" and not args.no_cpu_baseline:
+        cpu["cpu_baseline"] = cpu_baseline(args.cpu_videos)
+        cpu["cpu_baseline_all_cores"] = cpu_baseline_all_cores(8)
 
     import torch
 
@@ -357,16 +602,24 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"kv_bytes_per_launch": w.kv_bytes()}))
         return
-
     if args.only == "prune":
         toks = [w.stage1(b)["token_event"] for b in range(args.batch)]
         for _ in range(args.warmup + args.steps):
             for b in range(args.batch):
                 w.stage2(b, toks[b])
         torch.cuda.synchronize()
-        print(json.dumps({"score_flops_per_step": w.score_flops()}))
+        print(json.dumps({"score_flops_per_step": sum(2 * w.score_flops(lv) for lv in range(3)) * args.batch}))
+        return
+    if args.only in ("stage1", "stage1_adaptive"):
+        call = w.stage1 if args.only == "stage1" else w.stage1_adaptive
+        for _ in range(args.warmup + args.steps):
+            for b in range(args.batch):
+                call(b)
+        torch.cuda.synchronize()
+        print(json.dumps({"stage1_feature_bytes_per_video": FRAMES * GRID * GRID * D_VIS * 2}))
         return
 
+    hev = HipEvents()
     w.step()                                             # eager once: loads code objects before any capture
     torch.cuda.synchronize()
     if not args.no_graph:
@@ -374,24 +627,37 @@ def main():
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
-    kv_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    kv_ev = [(hev.create(), hev.create()) for _ in range(args.steps)]
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
+    step_ev[0].record()
     for s in range(args.steps):
         w.step(kv_ev[s])
+        step_ev[s + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    kv_ms = float(np.mean([a.elapsed_time(b) for a, b in kv_ev]))
-    stage_ms = time_stages(w, 5)
+    kv_all = [hev.elapsed_ms(a, b) for a, b in kv_ev]
+    kv_ms = float(np.mean(kv_all))
+    step_ms = [step_ev[s].elapsed_time(step_ev[s + 1]) for s in range(args.steps)]
+    err_word = int(w.kv_ws[:4].view(torch.int32)[0])
+    if err_word != 0:
+        sys.exit("the KV compaction reported an expired wait: results are invalid")
     tokens_per_step = args.batch * FRAMES * GRID * GRID
     ms_per_step = elapsed * 1e3 / args.steps
     achieved = w.kv_bytes() / (kv_ms * 1e-3) / 1e9
+    traffic, traffic_file = read_traffic()
+    stages = time_stages(w, 5)
+    stages["stage3"]["GBs"] = round(w.kv_bytes() / (stages["stage3"]["ms_per_step_alone"] * 1e-3) / 1e9, 1)
+    stages.update(time_kernels(w, hev, args.kernel_reps))
+    stages["stage3_kv_compaction"] = hbm_entry(kv_all, w.kv_bytes(), "move_rows_kernel")
     out = {
         "metric": "visual tokens processed/sec through stages 1-3",
         "value": tokens_per_step / (elapsed / args.steps),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_min": round(float(np.min(step_ms)), 4), "ms_per_step_median": round(float(np.median(step_ms)), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "LongVA-7B-shaped, 256 frames: hierarchical prefill + decoding KV compaction configs "
@@ -399,17 +665,17 @@ def main():
                    "batch_videos": args.batch, "frames": FRAMES, "tokens_per_frame_in": GRID * GRID,
                    "tokens_per_frame_pooled": TOK_PER_FRAME, "prune_levels": level_counts(), "text_tokens": N_TEXT,
                    "text_queries": TQ, "kv_layers": N_LAYERS, "L_H": list(L_H), "streams": w.n_streams,
+                   "stage2_inputs": "keys 0.5 mu_event + N(0,1), queries N(0,1) + 0.5 mu_target, hidden N(0,1) + event shift",
                    "launch": "eager" if w.graph is None else "stages 1-2 replayed from one HIP graph, KV compaction launched directly"},
+        "value_in_pooled_tokens_per_s": args.batch * N_VIS / (elapsed / args.steps),
         "roofline": {"kernel": "move_rows_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(),
-                     "algorithmic_bytes_per_launch": w.kv_bytes(), "ms_per_launch": kv_ms},
-        "stages": {"stage1_ms": stage_ms[0], "stage2_ms": stage_ms[1], "stage3_ms": stage_ms[2],
-                   "stage1_GBs": w.stage1_bytes() / stage_ms[0] / 1e6,
-                   "stage2_gather_bytes": w.gather_bytes(), "stage2_score_flops": w.score_flops(),
-                   "stage3_GBs": w.kv_bytes() / stage_ms[2] / 1e6},
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_file,
+                     "algorithmic_bytes_per_launch": w.kv_bytes(), "ms_per_launch": kv_ms,
+                     "ms_per_launch_min": round(float(np.min(kv_all)), 4), "ms_per_launch_median": round(float(np.median(kv_all)), 4)},
+        "stages": stages,
+        "configs": time_configs(w, 10),
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline()
+    out.update(cpu)
     print(json.dumps(out))
 
 

@@ -374,6 +374,32 @@ METOK_API int metok_kv_compact_paged(void* const* k_pools, void* const* v_pools,
 METOK_API int metok_debug_set_move_spin_limit(int polls);
 
 /* ---------------------------------------------------------------------------------------------
+ * Measurement helper (not part of the method): times one kernel family inside the library calls.
+ * While armed on the calling thread, every launch of the named kernel is bracketed by hipEventRecord of
+ * ev_begin and ev_end (hipEvent_t passed as void*, created by the caller with timing enabled) on the
+ * stream of the call, so hipEventElapsedTime(ev_begin, ev_end) after the call is the duration of that
+ * kernel alone, without the small planning kernels around it.  If a call launches the kernel more than
+ * once the events bracket the last launch.  kernel == METOK_TRACE_NONE (or NULL events) disarms.  Do not
+ * arm while a stream is being captured into a graph.
+ * ------------------------------------------------------------------------------------------- */
+enum {
+    METOK_TRACE_NONE = 0,
+    METOK_TRACE_FRAME_STATS = 1,        /* Eq. 4 / Eq. 5 pass over the frame features */
+    METOK_TRACE_POOL = 2,               /* adaptive pooling pass */
+    METOK_TRACE_FRAME_STATS_POOL2 = 3,  /* both in one pass (uniform stride 2) */
+    METOK_TRACE_SEGMENT = 4,
+    METOK_TRACE_PLAN = 5,
+    METOK_TRACE_ROW_STATS = 6,          /* attention pass 1 (softmax statistics) */
+    METOK_TRACE_COL_SUMS = 7,           /* attention pass 2 (probability mass per key) */
+    METOK_TRACE_SELECT = 8,
+    METOK_TRACE_WRITE_INDEX = 9,
+    METOK_TRACE_GATHER_ROWS = 10,       /* hidden-state compaction */
+    METOK_TRACE_MOVE_ROWS = 11          /* in-place row mover (KV compaction, in-place hidden compaction) */
+};
+
+METOK_API int metok_trace_kernel(int kernel, void* ev_begin, void* ev_end);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement helper (not part of the method): a plain device-to-device copy kernel with the
  * same access width as the streaming kernels.  The bench uses it to calibrate the profiler's
  * HBM byte counters against a transfer of known size.  bytes must be a multiple of 16.

@@ -32,7 +32,7 @@ EXPORTS = [
     "metok_kv_compact", "metok_kv_compact_paged", "metok_calib_copy",
     "metok_preset", "metok_compress_encoder_tokens_capacity_rows",
     "metok_static_scratch_bytes", "metok_prefill_prune_static",
-    "metok_kv_compact_workspace_bytes", "metok_debug_set_move_spin_limit",
+    "metok_kv_compact_workspace_bytes", "metok_debug_set_move_spin_limit", "metok_trace_kernel",
 ]
 
 
@@ -95,6 +95,8 @@ def _load() -> ctypes.CDLL:
     lib.metok_kv_compact.restype = i32
     lib.metok_kv_compact_workspace_bytes.restype = sz
     lib.metok_kv_compact_workspace_bytes.argtypes = [i32, i32, i32, i64, i32, i32]
+    lib.metok_trace_kernel.restype = i32
+    lib.metok_trace_kernel.argtypes = [i32, vp, vp]
     lib.metok_debug_set_move_spin_limit.restype = i32
     lib.metok_debug_set_move_spin_limit.argtypes = [i32]
     lib.metok_kv_compact.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, c.POINTER(vp),

@@ -18,6 +18,20 @@ int fail(int code, const char* fmt, ...);   // formats into the buffer, returns 
 int check_launch(const char* what);         // hipGetLastError -> METOK_ERR_DEVICE
 void clear_error();
 
+// Measurement hook (metok_trace_kernel): brackets the launches of one kernel family with the caller's events.
+struct KernelTrace { int kernel; hipEvent_t begin, end; };
+KernelTrace& kernel_trace();                // thread-local
+struct TraceScope {
+    hipStream_t st;
+    bool armed;
+    TraceScope(int kernel, hipStream_t stream) : st(stream) {
+        const KernelTrace& t = kernel_trace();
+        armed = t.kernel == kernel && t.begin != nullptr && t.end != nullptr;
+        if (armed) (void)hipEventRecord(t.begin, st);
+    }
+    ~TraceScope() { if (armed) (void)hipEventRecord(kernel_trace().end, st); }
+};
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline size_t dtype_size(int dtype) { return dtype == METOK_BF16 ? 2 : 4; }

@@ -13,6 +13,11 @@ char* error_buffer() {
 
 void clear_error() { error_buffer()[0] = 0; }
 
+KernelTrace& kernel_trace() {
+    static thread_local KernelTrace t = {METOK_TRACE_NONE, nullptr, nullptr};
+    return t;
+}
+
 int fail(int code, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
@@ -43,6 +48,15 @@ using namespace metok;
 extern "C" const char* metok_last_error(void) { return error_buffer(); }
 
 extern "C" int metok_version(void) { return 100; }
+
+extern "C" int metok_trace_kernel(int kernel, void* ev_begin, void* ev_end) {
+    clear_error();
+    if (kernel < METOK_TRACE_NONE || kernel > METOK_TRACE_MOVE_ROWS) return fail(METOK_ERR_INVALID_ARG, "unknown kernel id %d", kernel);
+    KernelTrace& t = kernel_trace();
+    if (kernel == METOK_TRACE_NONE || !ev_begin || !ev_end) { t.kernel = METOK_TRACE_NONE; t.begin = nullptr; t.end = nullptr; return METOK_OK; }
+    t.kernel = kernel; t.begin = static_cast<hipEvent_t>(ev_begin); t.end = static_cast<hipEvent_t>(ev_end);
+    return METOK_OK;
+}
 
 extern "C" int metok_preset(int model, metok_params* out) {
     clear_error();

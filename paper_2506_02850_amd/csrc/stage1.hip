@@ -19,28 +19,42 @@ constexpr float kZeroNorm = 1e-12f;
 // frame_stats_kernel
 //
 // A token row (d elements) is spread over G lanes in 16-byte chunks (lane j of the group takes
-// chunks j, j+G, ...; at most KL chunks per lane).  A wave therefore works on 64/G tokens at a
-// time and a workgroup on TOK = 4 * 64/G tokens.  blockIdx.x selects the token chunk, blockIdx.y
-// a run of consecutive frames; the workgroup walks its run keeping the rows of the previous and the
-// current frame in registers, so that every frame is read once (plus one extra frame per run for
-// the pair that straddles two runs).
+// chunks j, j+G, ...; at most KL chunks per lane).  A wave therefore works on TPW = 64/G tokens at a
+// time ("wave chunk" cw = blockIdx.x * 4 + wave of the frame's tokens).  blockIdx.y selects a run of
+// consecutive frames; the wave walks its run keeping the rows of the previous and the current frame in
+// registers, so that every frame is read once (plus one extra frame per run for the pair that straddles two
+// runs): at step t it takes <v_{t-1}, v_t>, then requests frame t + 1 into the registers of frame t - 1 and
+// works on frame t while those loads are in flight.  Waves are independent (no LDS, no barrier).
 //
-// part[(t * C + c) * 3 + {0,1,2}] = over the tokens of chunk c of frame t:
+// part[(t * C + cw) * 3 + {0,1,2}] = over the tokens of wave chunk cw of frame t:
 //     sum |v|^2,  sum <v_t, v_{t+1}> (token-mean mode: sum of cos(v_t[n], v_{t+1}[n])),  sum of cos(token, text)
+//
+// Cross-lane sums use v_permlane32_swap / v_permlane16_swap: they exchange halves of two registers, so one
+// swap and one add fold two values at once.
 // ---------------------------------------------------------------------------------------------
+// low half of the wave: a summed over the lane pairs (l, l + 32); high half: b likewise
+__device__ __forceinline__ float swap32_add(float a, float b) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// even 16-lane rows: a of the rows (r, r + 1) added; odd rows: b likewise
+__device__ __forceinline__ float swap16_add(float a, float b) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <typename T, int G, int KL>
 __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
     const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int N, int d,
     int frames_per_run, int do_pair, int sim_mode, float* __restrict__ part, int C) {
     using E = Elem<T>;
+    static_assert(G == 16 || G == 64, "token groups are one DPP row or one wave");
     constexpr int TPW = 64 / G;                 // tokens per wave
-    constexpr int TOK = kStatsWaves * TPW;      // tokens per workgroup
-    __shared__ float red[2][TOK][3];
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % G, tw = lane / G;
-    const int slot = wave * TPW + tw;
-    const int n = blockIdx.x * TOK + slot;
+    const int cw = blockIdx.x * kStatsWaves + wave;
+    if (cw >= C) return;                        // there is no barrier below: a wave may leave on its own
+    const int n = cw * TPW + tw;
     const bool tok_ok = n < N;
     const int nchunks = d / E::kVec;
     const int t0 = blockIdx.y * frames_per_run;
@@ -69,32 +83,34 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
         }
     };
 
-    // Three row sets: at step t the rows of frame t+1 are requested, while the arithmetic uses frame t
-    // (norm, text cosine) and the pair (t-1, t), both already in registers.  The pair product of a run's
-    // last frame with the first frame of the next run is taken at the end from one extra row load.
-    uint4 prv[KL], cur[KL], nxt[KL];
-    load_row(t0, cur);
-#pragma unroll
-    for (int k = 0; k < KL; ++k) { prv[k] = zero; nxt[k] = zero; }
     const int t_last = (do_pair && t1 < T_frames) ? t1 : t1 - 1;      // last frame that is loaded
     float p_prev = 0.f;
-    for (int t = t0; t <= t_last; ++t) {
-        if (t + 1 <= t_last) load_row(t + 1, nxt);
-        float p = 0.f, q = 0.f, cd = 0.f;
+    // X holds frame t, W frame t - 1; after the pair product W receives frame t + 1
+    auto step = [&](int t, uint4 (&W)[KL], uint4 (&X)[KL]) {
         const bool own = t < t1;                                      // frame t belongs to this run
-#pragma unroll
-        for (int k = 0; k < KL; ++k) p = E::dot(cur[k], cur[k], p);
-        if (own) {
-#pragma unroll
-            for (int k = 0; k < KL; ++k) q = E::dot(cur[k], txt[k], q);
-        }
+        float p = 0.f, q = 0.f, cd = 0.f;
         if (do_pair && t > t0) {
 #pragma unroll
-            for (int k = 0; k < KL; ++k) cd = E::dot(prv[k], cur[k], cd);
+            for (int k = 0; k < KL; ++k) cd = E::dot(W[k], X[k], cd);
         }
-        p = group_sum<G>(p);
-        q = group_sum<G>(q);
-        cd = group_sum<G>(cd);
+        if (t + 1 <= t_last) load_row(t + 1, W);
+#pragma unroll
+        for (int k = 0; k < KL; ++k) p = E::dot(X[k], X[k], p);
+        if (own) {
+#pragma unroll
+            for (int k = 0; k < KL; ++k) q = E::dot(X[k], txt[k], q);
+        }
+        // per token (one 16-lane row, or the whole wave): every lane of the group gets the token's sums
+        p = row16_sum(p); q = row16_sum(q); cd = row16_sum(cd);
+        if (G == 64) {
+            // rows 0 / 2 of the wave end up with the whole token's |v|^2 / text product; bring both to every lane
+            float a = swap32_add(p, q);
+            a = swap16_add(a, a);
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(a), false, false);
+            p = __uint_as_float(r[0]); q = __uint_as_float(r[1]);
+            cd = swap32_add(cd, cd);
+            cd = swap16_add(cd, cd);                                  // rows 0 and 2: all four rows
+        }
         if (sim_mode == METOK_SIM_TOKEN_MEAN) {                       // cosine of the matching tokens of frames t-1 and t
             const float dn = sqrtf(p_prev) * sqrtf(p);
             cd = (tok_ok && !(dn < kZeroNorm)) ? cd / dn : 0.f;
@@ -103,29 +119,33 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
         const float den = sqrtf(p) * tnorm;
         const float cosv = (own && do_text && tok_ok && !(den < kZeroNorm)) ? q / den : 0.f;
         if (!own) p = 0.f;
-        const int buf = (t - t0) & 1;
-        if (sub == 0) {
-            red[buf][slot][0] = p;
-            red[buf][slot][1] = cd;
-            red[buf][slot][2] = cosv;
+        if (G == 16) {
+            // the four tokens of the wave: rows -> lane 0 (|v|^2, pair) and lane 32 (cosine)
+            float a = swap32_add(p, cosv);
+            a = swap16_add(a, a);
+            p = a;                                                    // lane 0: sum |v|^2; lane 32: sum of cosines
+            cd = swap32_add(cd, cd);
+            cd = swap16_add(cd, cd);
         }
-        __syncthreads();
-        if (threadIdx.x < 3) {
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < TOK; ++i) s += red[buf][i][threadIdx.x];
-            // slot 1 of frame t-1 holds <v_{t-1}, v_t>; slots 0 and 2 belong to frame t
-            if (threadIdx.x == 1) {
-                if (t > t0) part[(static_cast<size_t>(t - 1) * C + blockIdx.x) * 3 + 1] = s;
-            } else if (own) {
-                part[(static_cast<size_t>(t) * C + blockIdx.x) * 3 + threadIdx.x] = s;
-            }
+        // slot 1 of frame t-1 holds <v_{t-1}, v_t>; slots 0 and 2 belong to frame t
+        if (lane == 0) {
+            if (t > t0) part[(static_cast<size_t>(t - 1) * C + cw) * 3 + 1] = cd;
+            if (own) part[(static_cast<size_t>(t) * C + cw) * 3 + 0] = p;
         }
+        if (G == 16 ? lane == 32 : lane == 0) {
+            if (own) part[(static_cast<size_t>(t) * C + cw) * 3 + 2] = G == 16 ? p : cosv;
+        }
+    };
+    uint4 A[KL], B[KL];
 #pragma unroll
-        for (int k = 0; k < KL; ++k) { prv[k] = cur[k]; cur[k] = nxt[k]; }
+    for (int k = 0; k < KL; ++k) B[k] = zero;
+    load_row(t0, A);
+    for (int t = t0; t <= t_last; t += 2) {
+        step(t, B, A);
+        if (t + 1 <= t_last) step(t + 1, A, B);
     }
     // the pair slot of the very last frame is never read; define it
-    if (threadIdx.x == 0 && t1 == T_frames) part[(static_cast<size_t>(T_frames - 1) * C + blockIdx.x) * 3 + 1] = 0.f;
+    if (lane == 0 && t1 == T_frames) part[(static_cast<size_t>(T_frames - 1) * C + cw) * 3 + 1] = 0.f;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -437,21 +457,27 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
 // a grid with even sides.  A wave owns one pooling window: lane j holds the 16-byte chunks j, j + 64, ...
 // (at most KL) of the window's four tokens, so the pooled chunk is a sum inside the lane (cells in the
 // order (y, x), (y, x+1), (y+1, x), (y+1, x+1), the order pool_kernel uses) and the per-token reductions
-// run over the whole wave.  Workgroup = 4 windows; blockIdx.y = run of frames, walked as in
-// frame_stats_kernel.  part[] has the same layout, with C = ceil(windows / 4) chunk partials per frame.
-// pooled[(t * windows + w) * d ...] receives window w of frame t.
+// run over the whole wave.  blockIdx.y = run of frames; a wave walks its run with two row sets: while it
+// works on frame t the rows of frame t + 1 are in flight, and <v_t, v_{t+1}> is taken when they land.
+// Waves are independent (no LDS, no barrier): each writes its own partials
+//     part[(t * n_win + w) * 3 + {0, 1, 2}] = sum |v|^2, <v_t, v_{t+1}>, sum of cos(token, text)
+// over the four tokens of window w of frame t.  pooled[(t * n_win + w) * d ...] receives the pooled token.
+//
+// Reductions.  The eight per-token sums of a frame (|v|^2 and <v, text> of four tokens) are reduced together:
+// v_permlane32_swap / v_permlane16_swap exchange halves of two registers, so one swap and one add fold two
+// values at once, and after two such steps every 16-lane row holds one pair of values to finish with DPP
+// adds -- about 45 vector instructions per frame instead of nine separate 64-lane reductions.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int KL, typename TO>
 __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
     const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int grid_h, int grid_w, int d,
-    int frames_per_run, float* __restrict__ part, int C, TO* __restrict__ pooled) {
+    int frames_per_run, float* __restrict__ part, TO* __restrict__ pooled) {
     using E = Elem<T>;
-    __shared__ float red[2][kStatsWaves][3];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ow = grid_w / 2, n_win = (grid_h / 2) * ow, N = grid_h * grid_w;
     const int w = blockIdx.x * kStatsWaves + wave;
-    const bool win_ok = w < n_win;
-    const int wy = win_ok ? w / ow : 0, wx = win_ok ? w % ow : 0;
+    if (w >= n_win) return;                                          // there is no barrier below: a wave may leave on its own
+    const int wy = w / ow, wx = w % ow;
     const int nchunks = d / E::kVec;
     const int t0 = blockIdx.y * frames_per_run;
     const int t1 = min(T_frames, t0 + frames_per_run);
@@ -462,11 +488,10 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
 
     uint4 txt[KL];
     float tn2 = 0.f;
-    const bool do_text = text != nullptr;
 #pragma unroll
     for (int k = 0; k < KL; ++k) {
         const int ch = lane + 64 * k;
-        txt[k] = (do_text && ch < nchunks) ? reinterpret_cast<const uint4*>(text)[ch] : zero;
+        txt[k] = ch < nchunks ? reinterpret_cast<const uint4*>(text)[ch] : zero;
         tn2 = E::dot(txt[k], txt[k], tn2);
     }
     const float tnorm = sqrtf(wave_sum(tn2));
@@ -479,81 +504,64 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
 #pragma unroll
             for (int k = 0; k < KL; ++k) {
                 const int ch = lane + 64 * k;
-                dst[c][k] = (win_ok && ch < nchunks) ? load_stream(row + ch) : zero;
+                dst[c][k] = ch < nchunks ? load_stream(row + ch) : zero;
             }
         }
     };
-
-    uint4 prv[4][KL], cur[4][KL], nxt[4][KL];
-    load_rows(t0, cur);
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int k = 0; k < KL; ++k) { prv[c][k] = zero; nxt[c][k] = zero; }
-    const int t_last = t1 < T_frames ? t1 : t1 - 1;                   // last frame that is loaded (one past the run for the pair)
-    for (int t = t0; t <= t_last; ++t) {
-        if (t + 1 <= t_last) load_rows(t + 1, nxt);
-        const bool own = t < t1;
-        float p_sum = 0.f, cos_sum = 0.f, cd = 0.f;
+    // X holds frame t; Y receives frame t + 1 while X is worked on
+    auto step = [&](int t, uint4 (&X)[4][KL], uint4 (&Y)[4][KL]) {
+        const bool has_next = t + 1 < T_frames;
+        if (has_next) load_rows(t + 1, Y);
+        float p[4], q[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float p = 0.f, q = 0.f;
+            p[c] = 0.f; q[c] = 0.f;
 #pragma unroll
-            for (int k = 0; k < KL; ++k) p = E::dot(cur[c][k], cur[c][k], p);
-            if (own && do_text) {
-#pragma unroll
-                for (int k = 0; k < KL; ++k) q = E::dot(cur[c][k], txt[k], q);
-            }
-            if (t > t0) {
-#pragma unroll
-                for (int k = 0; k < KL; ++k) cd = E::dot(prv[c][k], cur[c][k], cd);
-            }
-            p = wave_sum(p);
-            q = wave_sum(q);
-            const float den = sqrtf(p) * tnorm;
-            cos_sum += (own && do_text && win_ok && !(den < kZeroNorm)) ? q / den : 0.f;
-            p_sum += p;
+            for (int k = 0; k < KL; ++k) { p[c] = E::dot(X[c][k], X[c][k], p[c]); q[c] = E::dot(X[c][k], txt[k], q[c]); }
         }
-        cd = wave_sum(cd);
-        if (!own) p_sum = 0.f;
-        const int buf = (t - t0) & 1;
-        if (lane == 0) {
-            red[buf][wave][0] = p_sum;
-            red[buf][wave][1] = cd;
-            red[buf][wave][2] = cos_sum;
-        }
-        if (own && win_ok) {
-            TO* out_row = pooled + (static_cast<size_t>(t) * n_win + w) * d;
+        TO* out_row = pooled + (static_cast<size_t>(t) * n_win + w) * d;
 #pragma unroll
-            for (int k = 0; k < KL; ++k) {
-                const int ch = lane + 64 * k;
-                if (ch < nchunks) {
-                    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < KL; ++k) {
+            const int ch = lane + 64 * k;
+            if (ch < nchunks) {
+                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) E::accumulate(cur[c][k], acc);
+                for (int c = 0; c < 4; ++c) E::accumulate(X[c][k], acc);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[i] = acc[i] / 4.f;
-                    Store<TO>::put(out_row, ch, E::kVec, acc);
-                }
+                for (int i = 0; i < 8; ++i) acc[i] = acc[i] / 4.f;
+                Store<TO>::put(out_row, ch, E::kVec, acc);
             }
         }
-        __syncthreads();
-        if (threadIdx.x < 3) {
-            float sum = 0.f;
+        // after the two halving steps rows 0 / 1 hold |v|^2 of the tokens (0, 2) / (1, 3) in (u0, u1), rows 2 / 3 their text products
+        const float s0 = swap32_add(p[0], q[0]), s1 = swap32_add(p[1], q[1]), s2 = swap32_add(p[2], q[2]), s3 = swap32_add(p[3], q[3]);
+        const float u0 = row16_sum(swap16_add(s0, s1)), u1 = row16_sum(swap16_add(s2, s3));
+        // both halves of the wave get the norms (first result) and the text products (second result) of their tokens
+        const auto r0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(u0), __float_as_uint(u0), false, false);
+        const auto r1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(u1), __float_as_uint(u1), false, false);
+        const float pa = __uint_as_float(r0[0]), qa = __uint_as_float(r0[1]), pb = __uint_as_float(r1[0]), qb = __uint_as_float(r1[1]);
+        const float da = sqrtf(pa) * tnorm, db = sqrtf(pb) * tnorm;
+        const float cosv = (!(da < kZeroNorm) ? qa / da : 0.f) + (!(db < kZeroNorm) ? qb / db : 0.f);
+        const float tot = swap16_add(cosv, pa + pb);                  // row 0: the four cosines added; row 1: the four |v|^2 added
+        float cd = 0.f;
+        if (has_next) {
 #pragma unroll
-            for (int i = 0; i < kStatsWaves; ++i) sum += red[buf][i][threadIdx.x];
-            if (threadIdx.x == 1) {
-                if (t > t0) part[(static_cast<size_t>(t - 1) * C + blockIdx.x) * 3 + 1] = sum;
-            } else if (own) {
-                part[(static_cast<size_t>(t) * C + blockIdx.x) * 3 + threadIdx.x] = sum;
-            }
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int k = 0; k < KL; ++k) cd = E::dot(X[c][k], Y[c][k], cd);
         }
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-#pragma unroll
-            for (int k = 0; k < KL; ++k) { prv[c][k] = cur[c][k]; cur[c][k] = nxt[c][k]; }
+        cd = row16_sum(cd);
+        cd = swap32_add(cd, cd);
+        cd = swap16_add(cd, cd);                                      // row 0: all four rows
+        float* dst = part + (static_cast<size_t>(t) * n_win + w) * 3;
+        if (lane == 0) { dst[1] = cd; dst[2] = tot; }
+        if (lane == 16) dst[0] = tot;
+    };
+    uint4 A[4][KL], B[4][KL];
+    load_rows(t0, A);
+    for (int t = t0; t < t1; t += 2) {
+        step(t, A, B);
+        if (t + 1 < t1) step(t + 1, B, A);
     }
-    if (threadIdx.x == 0 && t1 == T_frames) part[(static_cast<size_t>(T_frames - 1) * C + blockIdx.x) * 3 + 1] = 0.f;
 }
 
 // token_event of uniformly pooled frames: rows_per_frame consecutive rows carry their frame's event id.
@@ -585,12 +593,15 @@ static bool plan_stats(int T, int N, int d, int dtype, StatsPlan* p) {
     if (!KL) return false;
     p->G = G; p->KL = KL;
     p->tok_per_wg = kStatsWaves * (64 / G);
-    p->C = (N + p->tok_per_wg - 1) / p->tok_per_wg;
-    // enough workgroups to fill 256 CUs several times over, but runs of at least 4 frames so that the
-    // extra frame read per run stays a small fraction
-    int runs = (2048 + p->C * kStatsWaves - 1) / (p->C * kStatsWaves);
+    p->C = (N + 64 / G - 1) / (64 / G);                 // wave chunks per frame: one partial triple each
+    // about 2048 waves to fill 256 CUs twice over, but runs of at least 4 frames so that the extra frame read
+    // per run stays a small fraction
+    int runs = (2048 + p->C - 1) / p->C;
     int fpr = (T + runs - 1) / runs;
     if (fpr < 4) fpr = 4;
+    // runs advance in step, their frames lie fpr frames apart: multiples of 8 frames put the runs' reads on the
+    // same DRAM channels and banks (measured 20 % slower)
+    if (fpr % 8 == 0) ++fpr;
     if (fpr > T) fpr = T;
     p->frames_per_run = fpr;
     p->runs = (T + fpr - 1) / fpr;
@@ -600,9 +611,9 @@ static bool plan_stats(int T, int N, int d, int dtype, StatsPlan* p) {
 template <typename T, int G, int KL>
 static void launch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
                          int sim_mode, float* part, hipStream_t st) {
-    hipLaunchKernelGGL((frame_stats_kernel<T, G, KL>), dim3(p.C, p.runs), dim3(kStatsThreads), 0, st,
+    { TraceScope trace_scope(METOK_TRACE_FRAME_STATS, st); hipLaunchKernelGGL((frame_stats_kernel<T, G, KL>), dim3((p.C + kStatsWaves - 1) / kStatsWaves, p.runs), dim3(kStatsThreads), 0, st,
                        static_cast<const T*>(feats), static_cast<const T*>(text), Tf, N, d, p.frames_per_run, do_pair,
-                       sim_mode, part, p.C);
+                       sim_mode, part, p.C); }
 }
 
 template <typename T>
@@ -681,8 +692,8 @@ extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, 
                                             : dispatch_stats<float>(feats, text_emb, T, N, d, p, 1, sim_mode, part, st);
         if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
         if ((rc = check_launch("frame_stats"))) return rc;
-        hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, k, text_emb ? 1 : 0, sim_mode,
-                           sim, event_start, frame_event, frame_score, norm2, pair_dot);
+        { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, k, text_emb ? 1 : 0, sim_mode,
+                           sim, event_start, frame_event, frame_score, norm2, pair_dot); }
         return check_launch("segment");
     }
     // pooled reading: Eq. 5 (if wanted) from the tokens, Eq. 4 from the frames' mean tokens (a [T, 1, d] fp32 "video")
@@ -706,8 +717,8 @@ extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, 
     if (!dispatch_stats<float>(mean, nullptr, T, 1, d, pm, 1, METOK_SIM_FLAT, part_m, st))
         return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
     if ((rc = check_launch("frame_stats (means)"))) return rc;
-    hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part_m, pm.C, T, 1, k, 0, METOK_SIM_FLAT,
-                       sim, event_start, frame_event, static_cast<float*>(nullptr), norm2, pair_dot);
+    { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part_m, pm.C, T, 1, k, 0, METOK_SIM_FLAT,
+                       sim, event_start, frame_event, static_cast<float*>(nullptr), norm2, pair_dot); }
     return check_launch("segment");
 }
 
@@ -802,21 +813,22 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
     }
     (void)norm2;
     const int n_key_events = ceil_ratio(alpha * k) > k ? k : ceil_ratio(alpha * k);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, scores, event_start, T, k, n_key_events, beta,
+    { TraceScope trace_scope(METOK_TRACE_PLAN, st); hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, scores, event_start, T, k, n_key_events, beta,
                        s_key_kf, s_key_nf, s_non_kf, s_non_nf, grid_h, grid_w, event_reduce, pool_edge,
                        event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
-                       frame_score_out);
+                       frame_score_out); }
     if ((rc = check_launch("plan"))) return rc;
 
     const int wg_per_frame = 36;      // 144 waves per frame; 18 to 72 workgroups measured within 3 % of each other
     dim3 grid(wg_per_frame, T);
 #define METOK_POOL_CASE(TI, TO) \
-    hipLaunchKernelGGL((pool_kernel<TI, TO>), grid, dim3(kPoolThreads), 0, st, static_cast<const TI*>(feats), grid_h, grid_w, d, \
-                       frame_stride, frame_offsets, frame_event_ws, pool_edge, out_capacity_rows, static_cast<TO*>(out_tokens), token_event)
-    if (dtype == METOK_BF16 && out_dtype == METOK_BF16) METOK_POOL_CASE(bf16_t, bf16_t);
-    else if (dtype == METOK_BF16 && out_dtype == METOK_F32) METOK_POOL_CASE(bf16_t, float);
-    else if (dtype == METOK_F32 && out_dtype == METOK_BF16) METOK_POOL_CASE(float, bf16_t);
-    else METOK_POOL_CASE(float, float);
+    { TraceScope trace_scope(METOK_TRACE_POOL, st); \
+      hipLaunchKernelGGL((pool_kernel<TI, TO>), grid, dim3(kPoolThreads), 0, st, static_cast<const TI*>(feats), grid_h, grid_w, d, \
+                         frame_stride, frame_offsets, frame_event_ws, pool_edge, out_capacity_rows, static_cast<TO*>(out_tokens), token_event); }
+    if (dtype == METOK_BF16 && out_dtype == METOK_BF16) METOK_POOL_CASE(bf16_t, bf16_t)
+    else if (dtype == METOK_BF16 && out_dtype == METOK_F32) METOK_POOL_CASE(bf16_t, float)
+    else if (dtype == METOK_F32 && out_dtype == METOK_BF16) METOK_POOL_CASE(float, bf16_t)
+    else METOK_POOL_CASE(float, float)
 #undef METOK_POOL_CASE
     return check_launch("pool");
 }
@@ -826,11 +838,18 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
 // (all four strides of the adaptive rule are 2, even grid), the statistics and the pooled tokens come
 // out of ONE pass over V; otherwise the two calls above run back to back (two passes over V).
 // ---------------------------------------------------------------------------------------------
+// one-pass path: one partial triple per pooling window and frame, then the per-frame arrays of the small kernels
+static size_t fused_part_bytes(int T, int grid_h, int grid_w) {
+    return round_up(static_cast<size_t>(T) * (grid_h / 2) * (grid_w / 2) * 3 * sizeof(float), 256);
+}
+
 extern "C" size_t metok_segment_compress_workspace_bytes(int T, int grid_h, int grid_w, int d, int dtype) {
-    if (grid_h < 1 || grid_w < 1) return 0;
+    if (grid_h < 1 || grid_w < 1 || T < 1) return 0;
     const size_t a = metok_segment_events_workspace_bytes(T, grid_h * grid_w, d, dtype);
     const size_t b = metok_compress_encoder_tokens_workspace_bytes(T, grid_h, grid_w, d, dtype);
-    return a > b ? a : b;
+    const size_t c = fused_part_bytes(T, grid_h, grid_w) + 3 * round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    const size_t ab = a > b ? a : b;
+    return ab > c ? ab : c;
 }
 
 template <typename T, typename TO>
@@ -838,8 +857,8 @@ static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int 
                                int runs, float* part, void* pooled, hipStream_t st) {
 #define METOK_FUSED_CASE(KLV) \
     if (kl == KLV) { \
-        hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs), dim3(kStatsThreads), 0, st, static_cast<const T*>(feats), \
-                           static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, C, static_cast<TO*>(pooled)); \
+        { TraceScope trace_scope(METOK_TRACE_FRAME_STATS_POOL2, st); hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs), dim3(kStatsThreads), 0, st, static_cast<const T*>(feats), \
+                           static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, static_cast<TO*>(pooled)); } \
         return true; \
     }
     METOK_FUSED_CASE(1) METOK_FUSED_CASE(2) METOK_FUSED_CASE(3) METOK_FUSED_CASE(4)
@@ -906,14 +925,17 @@ extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int g
         return fail(METOK_ERR_CAPACITY, "out_capacity_rows = %lld, worst case needs %lld", (long long)out_capacity_rows, (long long)rows);
     if (rows > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pooled row count must fit int32");
 
-    const int C = (n_win + kStatsWaves - 1) / kStatsWaves;          // <= the chunk count of the two-pass plan: the partials fit
+    const int C = (n_win + kStatsWaves - 1) / kStatsWaves;          // workgroups per run of frames
     int runs = (2048 + C * kStatsWaves - 1) / (C * kStatsWaves);
     int fpr = (T + runs - 1) / runs;
     if (fpr < 4) fpr = 4;
+    // Runs advance in step, so their frames lie fpr frames apart: a distance that is a multiple of 8 frames puts the
+    // runs' reads on the same DRAM channels and banks (16 or 32 frames per run measured 20 % slower than 18 or 21).
+    if (fpr % 8 == 0) ++fpr;
     if (fpr > T) fpr = T;
     runs = (T + fpr - 1) / fpr;
     char* ws = static_cast<char*>(workspace);
-    const size_t part_bytes = round_up(static_cast<size_t>(T) * C * 3 * sizeof(float), 256);
+    const size_t part_bytes = fused_part_bytes(T, grid_h, grid_w);
     const size_t tslot = round_up(static_cast<size_t>(T) * sizeof(float), 256);
     float* part = reinterpret_cast<float*>(ws);
     float* norm2 = reinterpret_cast<float*>(ws + part_bytes);
@@ -929,14 +951,14 @@ extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int g
                                      : launch_stats_pool2<float, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st);
     if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no fused kernel for d = %d", d);
     if ((rc = check_launch("frame_stats_pool2"))) return rc;
-    hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, C, T, N, k, 1, METOK_SIM_FLAT,
-                       sim, event_start, frame_event, frame_score, norm2, pair_dot);
+    { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, n_win, T, N, k, 1, METOK_SIM_FLAT,
+                       sim, event_start, frame_event, frame_score, norm2, pair_dot); }
     if ((rc = check_launch("segment"))) return rc;
     const int n_key_events = ceil_ratio(alpha * k) > k ? k : ceil_ratio(alpha * k);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, frame_score, event_start, T, k, n_key_events, beta,
+    { TraceScope trace_scope(METOK_TRACE_PLAN, st); hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, frame_score, event_start, T, k, n_key_events, beta,
                        2, 2, 2, 2, grid_h, grid_w, event_reduce, pool_edge,
                        event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
-                       static_cast<float*>(nullptr));
+                       static_cast<float*>(nullptr)); }
     if ((rc = check_launch("plan"))) return rc;
     hipLaunchKernelGGL(fill_token_event_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, frame_event, T, n_win,
                        token_event);

@@ -902,12 +902,12 @@ static void launch_scores(const void* q, const void* k, const ScoreGeom& g, cons
     float* colpart = reinterpret_cast<float*>(ws + p.off_colpart);
     const int qslots = g.Hkv * g.rb_total * NCH * 64;
     hipLaunchKernelGGL((pack_q_kernel<T, NCH>), dim3((qslots + 255) / 256), dim3(256), 0, st, static_cast<const T*>(q), g, qfrag);
-    hipLaunchKernelGGL((row_stats_kernel<T, NCH, RBW, SUBS>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
-                       qfrag, static_cast<const T*>(k), g, p.per1, pstat);
+    { TraceScope trace_scope(METOK_TRACE_ROW_STATS, st); hipLaunchKernelGGL((row_stats_kernel<T, NCH, RBW, SUBS>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
+                       qfrag, static_cast<const T*>(k), g, p.per1, pstat); }
     const int total_rows = ny * g.rbw * 32;
     hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 15) / 16), dim3(256), 0, st, pstat, g, p.nx1, norm);
-    hipLaunchKernelGGL((col_sums_kernel<T, NCH, RBW, SUBS>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
-                       qfrag, static_cast<const T*>(k), g, p.per2, norm, colpart);
+    { TraceScope trace_scope(METOK_TRACE_COL_SUMS, st); hipLaunchKernelGGL((col_sums_kernel<T, NCH, RBW, SUBS>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
+                       qfrag, static_cast<const T*>(k), g, p.per2, norm, colpart); }
 }
 
 }  // namespace metok
@@ -1025,15 +1025,15 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
     uint32_t* sel_info = reinterpret_cast<uint32_t*>(sel + 2 * select_count_bytes(n_vis));
     const int n_tiles = select_tiles(n_vis);
     if (n_vis <= kSelCache * kSelThreads)
-        hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                           gt_count, eq_count, sel_info);
+        { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
+                           gt_count, eq_count, sel_info); }
     else
-        hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                           gt_count, eq_count, sel_info);
+        { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
+                           gt_count, eq_count, sel_info); }
     if ((rc = check_launch("select"))) return rc;
-    hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
+    { TraceScope trace_scope(METOK_TRACE_WRITE_INDEX, st); hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
                        n_tiles, static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out,
-                       token_event_out, orig_idx_out);
+                       token_event_out, orig_idx_out); }
     if ((rc = check_launch("write index"))) return rc;
     if (in_place) {
         int32_t* src_row = reinterpret_cast<int32_t*>(inplace_ws);
@@ -1050,9 +1050,9 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
     const int chunks_per_row = static_cast<int>(row_bytes / 16);
     const int64_t blocks = (out_rows * chunks_per_row + kGatherThreads - 1) / kGatherThreads;
     if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "hidden_out too large for one launch");
-    hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGatherThreads), 0, st,
+    { TraceScope trace_scope(METOK_TRACE_GATHER_ROWS, st); hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGatherThreads), 0, st,
                        static_cast<const u32x4_t*>(hidden), static_cast<u32x4_t*>(hidden_out), out_rows, chunks_per_row,
-                       vis_start, n_vis, static_cast<int>(total_keep), kept_idx);
+                       vis_start, n_vis, static_cast<int>(total_keep), kept_idx); }
     return check_launch("gather");
 }
 

@@ -264,9 +264,9 @@ int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_w
         args.page_table = page_table; args.page_size = page_size; args.pages_per_seq = pages_per_seq; args.n_pages_pool = n_pages_pool;
         if (items == 0) continue;
         if (page_table)
-            hipLaunchKernelGGL(move_rows_kernel<true>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args);
+            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<true>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
         else
-            hipLaunchKernelGGL(move_rows_kernel<false>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args);
+            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<false>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
         rc = check_launch("move_rows");
         if (rc) return rc;
     }

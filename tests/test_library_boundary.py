@@ -33,7 +33,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert len(names) == 21 and len(set(names)) == len(names)
+    assert len(names) == 22 and len(set(names)) == len(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
     from paper_2506_02850_amd import binding
@@ -94,9 +94,9 @@ def test_workspace_queries(lib):
     seg = lib.metok_segment_events_workspace_bytes
     seg.restype = ctypes.c_size_t
     seg.argtypes = [ctypes.c_int] * 4
-    # LongVA-shaped stage 1: 36 token chunks x 3 partials x 4 bytes per frame, two per-frame arrays,
+    # LongVA-shaped stage 1: 144 wave chunks of four tokens x 3 partials x 4 bytes per frame, two per-frame arrays,
     # and for the pooled reading of Eq. 4 the fp32 frame means with their own (one chunk) partials
-    assert seg(256, 576, 1024, 1) == 256 * 36 * 3 * 4 + 2 * 1024 + 256 * 1024 * 4 + 256 * 3 * 4
+    assert seg(256, 576, 1024, 1) == 256 * 144 * 3 * 4 + 2 * 1024 + 256 * 1024 * 4 + 256 * 3 * 4
     assert seg(256, 576, 1020, 1) == 0            # d not a multiple of 8
     assert seg(8, 16, 64, 0) > 0
     prune = lib.metok_prefill_prune_workspace_bytes
