@@ -368,6 +368,47 @@ METOK_API int metok_kv_compact_paged(void* const* k_pools, void* const* v_pools,
                            const int32_t* const* idx, const int32_t* n_keep, int32_t* new_len,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Stage 3 on a paged cache by relinking pages (Sec. 3.3): the same compaction as metok_kv_compact_paged -- new
+ * logical row i of (layer l, video b) holds old logical row idx[l][b][i] -- but instead of moving every kept
+ * row, every layer gets a page table of its own:
+ *   - a new page whose rows are exactly one whole old page (in order, from that page's first slot) takes over
+ *     that page's physical page: nothing is copied;
+ *   - the other new pages are filled by row copies into physical pages the sequence already owns (the k-th
+ *     such new page takes the k-th old page, in table order, that no relinked page took over);
+ *   - the old pages that are left are released.
+ * With the paper's rule (from l_1 on only the text rows stay) and a visual span that ends on a page boundary
+ * every new page is relinked: no row moves at all and all visual pages are released.
+ *
+ *   page_table_in   device, int32: the tables the rows are read through, [B, pages_per_seq] shared by all layers
+ *                   (table_in_layer_stride = 0) or [L, B, pages_per_seq] (stride = B * pages_per_seq).  Pages of
+ *                   the tables must be pairwise distinct inside a layer; entries outside [0, n_pages_pool) are
+ *                   never dereferenced.
+ *   len_in          host, [L] int32 or NULL (= pages_per_seq * page_size): rows each layer holds now; the old
+ *                   pages of a layer are its first ceil(len_in[l] / page_size) table entries.
+ *   idx, n_keep     as in metok_kv_compact: idx[l] [B, n_keep[l]] strictly ascending logical rows below
+ *                   len_in[l]; idx[l] == NULL leaves the layer alone (its table is copied to the output).
+ *   page_table_out  device out, [L, B, pages_per_seq] int32: new table of every layer and video; entries from
+ *                   ceil(n_keep[l] / page_size) on are -1.  Must not overlap page_table_in.
+ *   free_pages      device out, [L, B, pages_per_seq] int32: physical pages layer l releases for video b, in the
+ *                   order of the old table, padded with -1;  n_free  device out, [L, B] int32: how many.
+ *   rows_copied     device out, [L, B] int32: rows whose physical place changed (per kv head and for K and V the
+ *                   same rows move).
+ *   new_len         device out, [L] int32 or NULL.
+ *   workspace       metok_kv_relink_paged_workspace_bytes(); its first word reports an expired wait as in
+ *                   metok_kv_compact.
+ */
+METOK_API size_t metok_kv_relink_paged_workspace_bytes(int L, int B, int Hkv, int page_size, int pages_per_seq, int dh, int dtype);
+
+METOK_API int metok_kv_relink_paged(void* const* k_pools, void* const* v_pools, int L, int B, int Hkv,
+                          int64_t n_pages_pool, int page_size, int dh, int dtype,
+                          const int32_t* page_table_in, int64_t table_in_layer_stride, int pages_per_seq,
+                          const int32_t* len_in,
+                          const int32_t* const* idx, const int32_t* n_keep,
+                          int32_t* page_table_out, int32_t* free_pages, int32_t* n_free, int32_t* rows_copied,
+                          int32_t* new_len,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* Test hook (not part of the method): number of polls after which a tile of the row mover gives a wait up.
  * 0 makes every wait that does not succeed at once expire, which exercises the error word of the workspace
  * without stalling anything; the default is 2^24. */

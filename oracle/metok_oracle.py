@@ -329,6 +329,45 @@ def kv_compact(slab: np.ndarray, idx: Optional[np.ndarray]) -> np.ndarray:
     return slab.copy() if idx is None else slab[np.asarray(idx, dtype=np.int64)]
 
 
+def kv_relink_pages(idx: np.ndarray, len_in: int, page_size: int, table_in: Sequence[int]) -> dict:
+    """Sec. 3.3 on a paged cache, as a pure index transformation (no rows are touched here).
+
+    The compacted sequence keeps the old logical rows idx[0] < idx[1] < ... as its rows 0, 1, ...; its
+    pages are described by a new page table over the physical pages the sequence already owns:
+      * a new page whose rows are exactly one whole old page (in order, from that page's first slot) is
+        "relinked": it takes over that old page's physical page and none of its rows is copied;
+      * the old pages not taken over in this way are free; the new pages that are not relinked take them
+        in ascending order (k-th such new page -> k-th free old page) and are filled by row copies;
+      * the free old pages that are left are released.
+    Returns table_out (physical page of every new page), free_pages (released physical pages, in
+    ascending old-page order), relinked (flag per new page), home (old logical page whose physical page
+    each new page occupies) and rows_copied (rows whose physical place changes).
+    """
+    idx = [int(x) for x in idx]
+    n = len(idx)
+    ps = int(page_size)
+    n_old = -(-int(len_in) // ps)
+    n_new = -(-n // ps)
+    relinked, home, taken = [], [], set()
+    for D in range(n_new):
+        rows = idx[D * ps: min((D + 1) * ps, n)]
+        whole = rows[0] % ps == 0 and rows == list(range(rows[0], rows[0] + len(rows))) and rows[0] + len(rows) <= len_in
+        relinked.append(bool(whole))
+        home.append(rows[0] // ps if whole else None)
+        if whole:
+            taken.add(rows[0] // ps)
+    free_old = [j for j in range(n_old) if j not in taken]
+    k = 0
+    for D in range(n_new):
+        if not relinked[D]:
+            home[D] = free_old[k]
+            k += 1
+    table_out = [int(table_in[h]) for h in home]
+    free_pages = [int(table_in[j]) for j in free_old[k:]]
+    rows_copied = sum(1 for d in range(n) if home[d // ps] * ps + d % ps != idx[d])
+    return dict(table_out=table_out, free_pages=free_pages, relinked=relinked, home=home, rows_copied=rows_copied)
+
+
 def kv_text_only_schedule(n_layers: int, l1: int, n_vis: int, n_text: int) -> List[Optional[np.ndarray]]:
     """Sec. 3.3: layers below l_1 cache visual and text tokens; from l_1 on every visual
     token leaves the cache.  Layers are numbered from 0."""

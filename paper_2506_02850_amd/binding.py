@@ -33,6 +33,7 @@ EXPORTS = [
     "metok_preset", "metok_compress_encoder_tokens_capacity_rows",
     "metok_static_scratch_bytes", "metok_prefill_prune_static",
     "metok_kv_compact_workspace_bytes", "metok_debug_set_move_spin_limit", "metok_trace_kernel",
+    "metok_kv_relink_paged_workspace_bytes", "metok_kv_relink_paged",
 ]
 
 
@@ -106,6 +107,11 @@ def _load() -> ctypes.CDLL:
                                            c.POINTER(vp), c.POINTER(c.c_int32), vp, vp, sz, vp]
     lib.metok_calib_copy.restype = i32
     lib.metok_calib_copy.argtypes = [vp, vp, sz, vp]
+    lib.metok_kv_relink_paged_workspace_bytes.restype = sz
+    lib.metok_kv_relink_paged_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
+    lib.metok_kv_relink_paged.restype = i32
+    lib.metok_kv_relink_paged.argtypes = [c.POINTER(vp), c.POINTER(vp), i32, i32, i32, i64, i32, i32, i32, vp, i64, i32,
+                                          c.POINTER(c.c_int32), c.POINTER(vp), c.POINTER(c.c_int32), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_preset.restype = i32
     lib.metok_preset.argtypes = [i32, c.POINTER(ParamsStruct)]
     lib.metok_compress_encoder_tokens_capacity_rows.restype = i64
@@ -459,6 +465,39 @@ def metok_kv_compact_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[to
                                        _dev(page_table, "page_table"), pages_per_seq, iarr, nk, _dev(new_len, "new_len"),
                                        _dev(ws, "workspace"), ws.numel(), _stream()))
     return new_len
+
+
+def metok_kv_relink_paged(k_pools: Sequence[torch.Tensor], v_pools: Sequence[torch.Tensor], page_table: torch.Tensor,
+                          idx: Sequence[Optional[torch.Tensor]], len_in: Optional[Sequence[int]] = None,
+                          workspace: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """Compaction of paged per-layer K/V pools [n_pages, Hkv, page_size, dh] by relinking whole pages and copying the rest.
+    page_table is [B, pages_per_seq] (shared by the layers) or [L, B, pages_per_seq]; returns page_table_out [L, B, pages],
+    free_pages [L, B, pages], n_free [L, B], rows_copied [L, B], new_len [L] and the workspace."""
+    n_pages, Hkv, page_size, dh = k_pools[0].shape
+    if page_table.dtype != torch.int32 or page_table.dim() not in (2, 3):
+        raise ValueError("page_table must be int32 [B, pages_per_seq] or [L, B, pages_per_seq]")
+    B, pages_per_seq = page_table.shape[-2:]
+    L, karr, varr, iarr, nk = _layer_tables(k_pools, v_pools, idx, (n_pages, Hkv, page_size, dh), B)
+    if page_table.dim() == 3 and page_table.shape[0] != L:
+        raise ValueError("a per-layer page_table needs one table per layer")
+    stride = 0 if page_table.dim() == 2 else B * pages_per_seq
+    dev = k_pools[0].device
+    dt = _dtype_code(k_pools[0])
+    i32 = torch.int32
+    out = dict(page_table_out=torch.empty((L, B, pages_per_seq), dtype=i32, device=dev),
+               free_pages=torch.empty((L, B, pages_per_seq), dtype=i32, device=dev),
+               n_free=torch.empty((L, B), dtype=i32, device=dev), rows_copied=torch.empty((L, B), dtype=i32, device=dev),
+               new_len=torch.empty(L, dtype=i32, device=dev))
+    ws = workspace if workspace is not None else _workspace(
+        _lib.metok_kv_relink_paged_workspace_bytes(L, B, Hkv, page_size, pages_per_seq, dh, dt), dev)
+    lens = None if len_in is None else (ctypes.c_int32 * L)(*[int(x) for x in len_in])
+    _check(_lib.metok_kv_relink_paged(karr, varr, L, B, Hkv, n_pages, page_size, dh, dt, _dev(page_table, "page_table"), stride,
+                                      pages_per_seq, lens, iarr, nk, _dev(out["page_table_out"], "page_table_out"),
+                                      _dev(out["free_pages"], "free_pages"), _dev(out["n_free"], "n_free"),
+                                      _dev(out["rows_copied"], "rows_copied"), _dev(out["new_len"], "new_len"),
+                                      _dev(ws, "workspace"), ws.numel(), _stream()))
+    out["workspace"] = ws
+    return out
 
 
 def metok_debug_set_move_spin_limit(polls: int) -> None:

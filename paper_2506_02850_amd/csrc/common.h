@@ -53,6 +53,13 @@ struct RowMoveLayer {
     int32_t first_item;  // filled by launch_row_moves
     int32_t tiles;       // filled by launch_row_moves
     int32_t flag_slot;   // filled by launch_row_moves
+    int32_t layer_id;    // index of the layer in per-layer tables (relink variant)
+};
+
+struct RelinkTables {
+    int64_t table_in_layer_stride;   // 0: one input table shared by the layers
+    const int32_t* table_out;        // [L, B, pages_per_seq]
+    const int32_t* home_page;        // [L, B, pages_per_seq]
 };
 
 struct RowMoveGeom { int parts, lanes_per_row, rows_per_step, rows_per_tile; };
@@ -64,7 +71,7 @@ size_t row_move_workspace_bytes(int L, int B, int Hkv, int n_which, int64_t S_ca
 int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes,
                      const int32_t* page_table, int page_size, int pages_per_seq, int64_t n_pages_pool,
                      int32_t* new_len, const int32_t* host_len, int L_total,
-                     void* workspace, size_t workspace_bytes, hipStream_t st);
+                     void* workspace, size_t workspace_bytes, hipStream_t st, const RelinkTables* relink);
 
 // ---------------------------------------------------------------------------------------------
 // device helpers

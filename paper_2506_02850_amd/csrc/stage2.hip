@@ -1042,10 +1042,10 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
         if ((rc = check_launch("hidden index"))) return rc;
         RowMoveLayer layer;
         layer.k = static_cast<char*>(hidden_out); layer.v = nullptr; layer.idx = src_row; layer.n_keep = static_cast<int32_t>(out_rows);
-        layer.first_item = 0; layer.tiles = 0; layer.flag_slot = 0;
+        layer.first_item = 0; layer.tiles = 0; layer.flag_slot = 0; layer.layer_id = 0;
         if (out_rows == 0) return METOK_OK;
         return launch_row_moves(&layer, 1, 1, 1, 1, S, static_cast<int64_t>(row_bytes), nullptr, 0, 0, 0, nullptr, nullptr, 1,
-                                inplace_ws + inplace_index_bytes(S), inplace_bytes(S) - inplace_index_bytes(S), st);
+                                inplace_ws + inplace_index_bytes(S), inplace_bytes(S) - inplace_index_bytes(S), st, nullptr);
     }
     const int chunks_per_row = static_cast<int>(row_bytes / 16);
     const int64_t blocks = (out_rows * chunks_per_row + kGatherThreads - 1) / kGatherThreads;

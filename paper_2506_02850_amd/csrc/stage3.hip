@@ -59,11 +59,18 @@ struct MoveArgs {
     uint32_t* flags;      // [n_layers][B * Hkv * n_which * parts][tiles_max]
     uint32_t* ticket;     // this launch's tile counter
     uint32_t* error;      // set to 1 if a bounded wait expired
-    // paged variant only
-    const int32_t* page_table;   // [B, pages_per_seq]
+    // paged variants only
+    const int32_t* page_table;   // [B, pages_per_seq] (relink: the tables the rows are read through, + layer_id * table_in_layer_stride)
     int page_size, pages_per_seq;
     int64_t n_pages_pool;
+    // relink variant only: rows are written through the new tables; home_page[D] is the OLD logical page whose
+    // physical page the new logical page D occupies
+    int64_t table_in_layer_stride;
+    const int32_t* table_out;    // [L, B, pages_per_seq]
+    const int32_t* home_page;    // [L, B, pages_per_seq]
 };
+
+enum { kMoveDense = 0, kMovePaged = 1, kMoveRelink = 2 };
 
 // First position p in idx[0, n) with idx[p] >= key (n if there is none), for ascending idx; all 64 lanes
 // of the calling wave take part: each round probes 64 positions, three rounds cover 2^18 entries.
@@ -87,8 +94,9 @@ __device__ __forceinline__ int wave_lower_bound(const int32_t* __restrict__ idx,
     return lo;
 }
 
-template <bool PAGED>
+template <int MODE>
 __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs args) {
+    constexpr bool PAGED = MODE != kMoveDense;
     constexpr int U = kMoveInFlight;
     __shared__ int s_item, s_lo, s_hi;
     if (threadIdx.x == 0) s_item = static_cast<int>(atomicAdd(args.ticket, 1u));
@@ -113,7 +121,10 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
     const int32_t* __restrict__ idx = L.idx + static_cast<int64_t>(b) * rows;
     char* pool = which ? L.v : L.k;
     char* base = pool + (static_cast<int64_t>(b) * args.Hkv + head) * args.S_cap * args.row_bytes;      // dense slab
-    const int32_t* __restrict__ table = PAGED ? args.page_table + static_cast<int64_t>(b) * args.pages_per_seq : nullptr;
+    const int32_t* __restrict__ table = PAGED ? args.page_table + (MODE == kMoveRelink ? L.layer_id * args.table_in_layer_stride : 0) +
+                                                    static_cast<int64_t>(b) * args.pages_per_seq : nullptr;
+    const int64_t lb = (static_cast<int64_t>(L.layer_id) * args.B + b) * args.pages_per_seq;
+    const int32_t* __restrict__ table_dst = MODE == kMoveRelink ? args.table_out + lb : table;
     uint32_t* flags = args.flags + (static_cast<size_t>(L.flag_slot) * args.B * n_sub + static_cast<size_t>(b) * n_sub + (rem - tile * n_sub)) *
                                        args.tiles_max;
 
@@ -126,10 +137,10 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
     const bool active = r_in < rps;                               // threads beyond the last whole row idle
     const uint32_t s_cap = static_cast<uint32_t>(args.S_cap);
 
-    // address of logical row r of this (video, head); nullptr if its page id is not a page of the pool
-    auto row_ptr = [&](uint32_t r) -> char* {
+    // address of logical row r of this (video, head) through a page table; nullptr if its page id is not a page of the pool
+    auto row_ptr = [&](const int32_t* __restrict__ tab, uint32_t r) -> char* {
         if (!PAGED) return base + static_cast<int64_t>(r) * args.row_bytes;
-        const int page = table[r / static_cast<uint32_t>(args.page_size)];
+        const int page = tab[r / static_cast<uint32_t>(args.page_size)];
         if (page < 0 || page >= args.n_pages_pool) return nullptr;
         const int64_t prow = (static_cast<int64_t>(page) * args.Hkv + head) * args.page_size + r % static_cast<uint32_t>(args.page_size);
         return pool + prow * args.row_bytes;
@@ -143,22 +154,44 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
         dst[u] = nullptr;
         if (active && i < rows) {
             const uint32_t s = static_cast<uint32_t>(idx[i]);
-            // rows that stay where they are need no copy; positions outside (i, S_cap) are skipped
-            if (s > static_cast<uint32_t>(i) && s < s_cap) {
-                const char* src = row_ptr(s);
-                char* d = row_ptr(static_cast<uint32_t>(i));
-                if (src != nullptr && d != nullptr) {
+            // rows that stay where they are need no copy; positions outside (i, S_cap) are skipped.  With relinked
+            // tables "where they are" is about the physical row: a row of a relinked page never moves, a row with
+            // s == i moves if its page changed.
+            if ((MODE == kMoveRelink ? s >= static_cast<uint32_t>(i) : s > static_cast<uint32_t>(i)) && s < s_cap) {
+                const char* src = row_ptr(table, s);
+                char* d = row_ptr(table_dst, static_cast<uint32_t>(i));
+                if (src != nullptr && d != nullptr && src != d) {
                     dst[u] = d + col;
                     v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + col));
                 }
             }
         }
     }
-    // destination rows [lo, hi) of earlier tiles take their sources from my destination rows [r0, r1)
+    // Destination rows [lo, hi) of earlier tiles take their sources from the rows this tile overwrites: its own
+    // destination rows [r0, r1), or with relinked tables the old logical rows of the pages its new pages occupy
+    // (home pages ascend with the new page and never lie after it, so those readers are earlier tiles too).
     const int r1 = min(r0 + R, rows);
     const int wave = threadIdx.x >> 6;
-    if (wave == 0) { const int lo = wave_lower_bound(idx, r0, r0); if (threadIdx.x == 0) s_lo = lo; }
-    if (wave == 1) { const int hi = wave_lower_bound(idx, r0, r1); if (threadIdx.x == 64) s_hi = hi; }
+    if (wave < 2) {
+        int key = wave == 0 ? r0 : r1;
+        if (MODE == kMoveRelink && r1 > r0) {
+            const int ps = args.page_size, d0 = r0 / ps, d1 = (r1 - 1) / ps;
+            int ext = wave == 0 ? 0x7fffffff : -1;                // wave 0: lowest home page of the tile, wave 1: highest
+            for (int D = d0 + (threadIdx.x & 63); D <= d1; D += 64) {
+                const int h = args.home_page[lb + D];
+                ext = wave == 0 ? min(ext, h) : max(ext, h);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const int o = __shfl_xor(ext, off, 64);
+                ext = wave == 0 ? min(ext, o) : max(ext, o);
+            }
+            const int64_t k64 = wave == 0 ? static_cast<int64_t>(ext) * ps : (static_cast<int64_t>(ext) + 1) * ps;
+            key = k64 > 0x7fffffff ? 0x7fffffff : static_cast<int>(k64);
+        }
+        const int pos = wave_lower_bound(idx, r0, key);
+        if ((threadIdx.x & 63) == 0) { if (wave == 0) s_lo = pos; else s_hi = pos; }
+    }
     // every source piece of this tile is in registers before the flag goes up and before any thread stores
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -220,7 +253,7 @@ size_t row_move_workspace_bytes(int L, int B, int Hkv, int n_which, int64_t S_ca
 int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes,
                      const int32_t* page_table, int page_size, int pages_per_seq, int64_t n_pages_pool,
                      int32_t* new_len, const int32_t* host_len, int L_total,
-                     void* workspace, size_t workspace_bytes, hipStream_t st) {
+                     void* workspace, size_t workspace_bytes, hipStream_t st, const RelinkTables* relink) {
     const RowMoveGeom g = row_move_geom(row_bytes);
     const size_t need = row_move_workspace_bytes(L_total, B, Hkv, n_which, S_cap, row_bytes);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u))
@@ -262,11 +295,16 @@ int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_w
         args.S_cap = S_cap; args.row_bytes = row_bytes;
         args.flags = words + header; args.ticket = words + 1 + launch; args.error = words;
         args.page_table = page_table; args.page_size = page_size; args.pages_per_seq = pages_per_seq; args.n_pages_pool = n_pages_pool;
+        args.table_in_layer_stride = relink ? relink->table_in_layer_stride : 0;
+        args.table_out = relink ? relink->table_out : nullptr;
+        args.home_page = relink ? relink->home_page : nullptr;
         if (items == 0) continue;
-        if (page_table)
-            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<true>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
+        if (relink)
+            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<kMoveRelink>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
+        else if (page_table)
+            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<kMovePaged>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
         else
-            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<false>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
+            { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<kMoveDense>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
         rc = check_launch("move_rows");
         if (rc) return rc;
     }
@@ -318,12 +356,12 @@ static int compact_impl(void* const* k_layers, void* const* v_layers, int L, int
         layers[i].v = static_cast<char*>(v_layers[l]);
         layers[i].idx = idx[l];
         layers[i].n_keep = n_keep[l];
-        layers[i].first_item = 0; layers[i].tiles = 0; layers[i].flag_slot = 0;
+        layers[i].first_item = 0; layers[i].tiles = 0; layers[i].flag_slot = 0; layers[i].layer_id = l;
     }
     int32_t host_len[METOK_MAX_LAYERS];
     for (int l = 0; l < L; ++l) host_len[l] = idx[l] ? n_keep[l] : static_cast<int32_t>(S_cap);
     return launch_row_moves(layers, n_active, B, Hkv, 2, S_cap, row_bytes, page_table, page_size, pages_per_seq, n_pages_pool,
-                            new_len, host_len, L, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+                            new_len, host_len, L, workspace, workspace_bytes, static_cast<hipStream_t>(stream), nullptr);
 }
 
 extern "C" size_t metok_kv_compact_workspace_bytes(int L, int B, int Hkv, int64_t S_cap, int dh, int dtype) {
@@ -366,4 +404,228 @@ extern "C" int metok_debug_set_move_spin_limit(int polls) {
     if (polls < 0) return fail(METOK_ERR_INVALID_ARG, "polls must be non-negative");
     g_spin_limit = polls;
     return METOK_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Page relinking (Sec. 3.3 on a paged cache): instead of moving every kept row, a new page table is
+// written per layer and video.  A new logical page whose rows are exactly one whole old page (all kept,
+// in order, aligned) simply takes over that page's physical page; the other new pages are filled by row
+// copies into physical pages the sequence already owns, and the pages left over are reported as free.
+//
+// Plan, one workgroup per (layer, video):
+//   1. new page D is "relinked" to old page P iff idx[D ps + t] = P ps + t for all its rows;
+//   2. the old pages that are not taken over this way are "free", in ascending order;
+//   3. the k-th new page that is not relinked takes the k-th free old page as its home.  Among the old pages
+//      0..D at most D - k are taken over by relinks, so that home is at most D: a copied page never lands
+//      behind its own logical position, and the rows it overwrites were read by new pages at or before it.
+//      This is what lets the row mover order its tiles exactly as in the plain compaction.
+//   4. table_out[D] = table_in[home[D]]; the free old pages beyond the ones used as homes are released.
+// ---------------------------------------------------------------------------------------------
+namespace metok {
+
+struct PlanLayer { const int32_t* idx; int32_t n_keep; int32_t len_in; };
+struct PlanArgs {
+    PlanLayer layer[METOK_MAX_LAYERS];
+    int B, page_size, pages_per_seq;
+    int64_t S_cap, table_in_layer_stride;
+    const int32_t* table_in;
+    int32_t* table_out;      // [L, B, pps]
+    int32_t* free_pages;     // [L, B, pps]
+    int32_t* n_free;         // [L, B]
+    int32_t* rows_copied;    // [L, B]
+    int32_t* home;           // [L, B, pps]  scratch kept for the row mover
+    int32_t* used;           // [L, B, pps]  scratch
+    int32_t* free_by_rank;   // [L, B, pps]  scratch
+    int32_t* relinked;       // [L, B, pps]  scratch
+};
+
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void relink_plan_kernel(const PlanArgs a) {
+    __shared__ int scan_scratch[17];
+    __shared__ int s_count;
+    const int l = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+    const int pps = a.pages_per_seq, ps = a.page_size;
+    const int64_t lb = (static_cast<int64_t>(l) * a.B + b) * pps;
+    const int32_t* __restrict__ tin = a.table_in + l * a.table_in_layer_stride + static_cast<int64_t>(b) * pps;
+    int32_t* tout = a.table_out + lb;
+    int32_t* freed = a.free_pages + lb;
+    int32_t* home = a.home + lb;
+    int32_t* used = a.used + lb;
+    int32_t* fbr = a.free_by_rank + lb;
+    int32_t* rel = a.relinked + lb;
+    const PlanLayer& L = a.layer[l];
+    if (L.idx == nullptr) {                      // untouched layer: the table is carried over
+        for (int D = tid; D < pps; D += kPlanThreads) { tout[D] = tin[D]; home[D] = D; freed[D] = -1; }
+        if (tid == 0) { a.n_free[static_cast<int64_t>(l) * a.B + b] = 0; a.rows_copied[static_cast<int64_t>(l) * a.B + b] = 0; }
+        return;
+    }
+    const int n = L.n_keep;
+    const int32_t* __restrict__ idx = L.idx + static_cast<int64_t>(b) * n;
+    const int np_old = (L.len_in + ps - 1) / ps, nd = (n + ps - 1) / ps;
+    for (int j = tid; j < pps; j += kPlanThreads) { used[j] = 0; freed[j] = -1; }
+    __syncthreads();
+    // 1. which new pages are whole old pages
+    for (int D = tid; D < nd; D += kPlanThreads) {
+        const int rows_d = min(ps, n - D * ps);
+        const int s0 = idx[D * ps];
+        bool ok = s0 >= 0 && s0 % ps == 0 && static_cast<int64_t>(s0) + rows_d <= L.len_in;
+        for (int t = 1; ok && t < rows_d; ++t) ok = idx[D * ps + t] == s0 + t;
+        rel[D] = ok ? 1 : 0;
+        home[D] = ok ? s0 / ps : -1;
+        if (ok) used[s0 / ps] = 1;
+    }
+    __syncthreads();
+    // 2. free old pages in ascending order
+    int carry = 0;
+    for (int base = 0; base < np_old; base += kPlanThreads) {
+        const int j = base + tid;
+        const int f = (j < np_old && used[j] == 0) ? 1 : 0;
+        int tot = 0;
+        const int ex = block_exclusive_scan(f, scan_scratch, &tot);
+        if (f) fbr[carry + ex] = j;
+        carry += tot;
+    }
+    const int total_free = carry;
+    __syncthreads();
+    // 3. homes of the new pages that are filled by copies
+    carry = 0;
+    for (int base = 0; base < nd; base += kPlanThreads) {
+        const int D = base + tid;
+        const int f = (D < nd && rel[D] == 0) ? 1 : 0;
+        int tot = 0;
+        const int ex = block_exclusive_scan(f, scan_scratch, &tot);
+        if (f) home[D] = carry + ex < total_free ? fbr[carry + ex] : D;      // the bound only fails for n_keep > len_in, refused by the host
+        carry += tot;
+    }
+    const int n_copied_pages = carry;
+    __syncthreads();
+    // 4. the new table and the released pages
+    for (int D = tid; D < pps; D += kPlanThreads) {
+        int page = -1;
+        if (D < nd) { const int h = home[D]; page = (h >= 0 && h < pps) ? tin[h] : -1; }
+        tout[D] = page;
+    }
+    for (int r = n_copied_pages + tid; r < total_free; r += kPlanThreads) freed[r - n_copied_pages] = tin[fbr[r]];
+    // rows that change their physical place
+    int mine = 0;
+    for (int d = tid; d < n; d += kPlanThreads) {
+        const int s = idx[d];
+        if (s >= d && s < a.S_cap && static_cast<int64_t>(home[d / ps]) * ps + d % ps != s) ++mine;
+    }
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    if (mine) atomicAdd(&s_count, mine);
+    __syncthreads();
+    if (tid == 0) {
+        a.n_free[static_cast<int64_t>(l) * a.B + b] = total_free > n_copied_pages ? total_free - n_copied_pages : 0;
+        a.rows_copied[static_cast<int64_t>(l) * a.B + b] = s_count;
+    }
+}
+
+static size_t relink_scratch_bytes(int L, int B, int pages_per_seq) {
+    return 4 * round_up(static_cast<size_t>(L) * B * pages_per_seq * sizeof(int32_t), 256);
+}
+
+}  // namespace metok
+
+extern "C" size_t metok_kv_relink_paged_workspace_bytes(int L, int B, int Hkv, int page_size, int pages_per_seq, int dh, int dtype) {
+    if (L < 1 || L > METOK_MAX_LAYERS || B < 1 || Hkv < 1 || page_size < 1 || pages_per_seq < 1 || dh < 1 ||
+        (dtype != METOK_F32 && dtype != METOK_BF16))
+        return 0;
+    const int64_t S_cap = static_cast<int64_t>(pages_per_seq) * page_size;
+    const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
+    if (S_cap > INT32_MAX || row_bytes % 16 != 0 || row_bytes / 16 > kMoveThreads * 64) return 0;
+    return row_move_workspace_bytes(L, B, Hkv, 2, S_cap, row_bytes) + relink_scratch_bytes(L, B, pages_per_seq);
+}
+
+extern "C" int metok_kv_relink_paged(void* const* k_pools, void* const* v_pools, int L, int B, int Hkv,
+                                     int64_t n_pages_pool, int page_size, int dh, int dtype,
+                                     const int32_t* page_table_in, int64_t table_in_layer_stride, int pages_per_seq,
+                                     const int32_t* len_in,
+                                     const int32_t* const* idx, const int32_t* n_keep,
+                                     int32_t* page_table_out, int32_t* free_pages, int32_t* n_free, int32_t* rows_copied,
+                                     int32_t* new_len,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+    if (L < 1 || L > METOK_MAX_LAYERS) return fail(METOK_ERR_INVALID_ARG, "L must be in [1, %d], got %d", METOK_MAX_LAYERS, L);
+    if (B < 1 || B > 65535 || Hkv < 1 || dh < 1) return fail(METOK_ERR_INVALID_ARG, "B (at most 65535), Hkv and dh must be positive");
+    if (page_size < 1 || pages_per_seq < 1 || n_pages_pool < 1 || n_pages_pool > INT32_MAX)
+        return fail(METOK_ERR_INVALID_ARG, "page_size, pages_per_seq and n_pages_pool must be positive");
+    const int64_t S_cap = static_cast<int64_t>(pages_per_seq) * page_size;
+    if (S_cap > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pages_per_seq * page_size must be below 2^31");
+    if (!k_pools || !v_pools || !idx || !n_keep) return fail(METOK_ERR_INVALID_ARG, "NULL layer table");
+    if (!page_table_in || !page_table_out || !free_pages || !n_free || !rows_copied ||
+        ((reinterpret_cast<uintptr_t>(page_table_in) | reinterpret_cast<uintptr_t>(page_table_out) | reinterpret_cast<uintptr_t>(free_pages) |
+          reinterpret_cast<uintptr_t>(n_free) | reinterpret_cast<uintptr_t>(rows_copied)) & 3u))
+        return fail(METOK_ERR_INVALID_ARG, "page tables and counters must be non-NULL and 4-byte aligned");
+    if (table_in_layer_stride != 0 && table_in_layer_stride != static_cast<int64_t>(B) * pages_per_seq)
+        return fail(METOK_ERR_INVALID_ARG, "table_in_layer_stride must be 0 (one table for all layers) or B * pages_per_seq");
+    {   // the new tables must not overwrite the tables the rows are read through
+        const char* a0 = reinterpret_cast<const char*>(page_table_in);
+        const char* a1 = a0 + (table_in_layer_stride ? static_cast<size_t>(L) : 1) * B * pages_per_seq * sizeof(int32_t);
+        const char* b0 = reinterpret_cast<const char*>(page_table_out);
+        const char* b1 = b0 + static_cast<size_t>(L) * B * pages_per_seq * sizeof(int32_t);
+        if (a0 < b1 && b0 < a1) return fail(METOK_ERR_INVALID_ARG, "page_table_out overlaps page_table_in");
+    }
+    const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
+    if (row_bytes % 16 != 0) return fail(METOK_ERR_INVALID_ARG, "dh * sizeof(dtype) = %lld is not a multiple of 16", (long long)row_bytes);
+    if (row_bytes / 16 > kMoveThreads * 64) return fail(METOK_ERR_UNSUPPORTED, "rows longer than %d bytes", kMoveThreads * 1024);
+    const size_t need = metok_kv_relink_paged_workspace_bytes(L, B, Hkv, page_size, pages_per_seq, dh, dtype);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u))
+        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+
+    PlanArgs plan;
+    int order[METOK_MAX_LAYERS];
+    int n_active = 0;
+    int32_t host_len[METOK_MAX_LAYERS];
+    for (int l = 0; l < L; ++l) {
+        const int32_t cur = len_in ? len_in[l] : static_cast<int32_t>(S_cap);
+        if (cur < 0 || cur > S_cap) return fail(METOK_ERR_INVALID_ARG, "len_in[%d] = %d outside [0, pages_per_seq * page_size]", l, cur);
+        plan.layer[l].idx = idx[l];
+        plan.layer[l].n_keep = idx[l] ? n_keep[l] : 0;
+        plan.layer[l].len_in = cur;
+        host_len[l] = idx[l] ? n_keep[l] : cur;
+        if (!idx[l]) continue;
+        if (n_keep[l] < 0 || n_keep[l] > cur) return fail(METOK_ERR_INVALID_ARG, "n_keep[%d] = %d outside [0, len_in]", l, n_keep[l]);
+        if (!k_pools[l] || !v_pools[l] || !aligned16(k_pools[l]) || !aligned16(v_pools[l]) || (reinterpret_cast<uintptr_t>(idx[l]) & 3u))
+            return fail(METOK_ERR_INVALID_ARG, "layer %d: NULL or misaligned pointer", l);
+        if (n_keep[l] == 0) continue;
+        order[n_active++] = l;
+    }
+    for (int l = L; l < METOK_MAX_LAYERS; ++l) { plan.layer[l].idx = nullptr; plan.layer[l].n_keep = 0; plan.layer[l].len_in = 0; }
+    for (int i = 1; i < n_active; ++i) {          // insertion sort, stable, by n_keep descending
+        int l = order[i], j = i;
+        while (j > 0 && n_keep[order[j - 1]] < n_keep[l]) { order[j] = order[j - 1]; --j; }
+        order[j] = l;
+    }
+    char* ws = static_cast<char*>(workspace);
+    const size_t move_bytes = row_move_workspace_bytes(L, B, Hkv, 2, S_cap, row_bytes);
+    const size_t slot = round_up(static_cast<size_t>(L) * B * pages_per_seq * sizeof(int32_t), 256);
+    plan.B = B; plan.page_size = page_size; plan.pages_per_seq = pages_per_seq; plan.S_cap = S_cap;
+    plan.table_in_layer_stride = table_in_layer_stride; plan.table_in = page_table_in;
+    plan.table_out = page_table_out; plan.free_pages = free_pages; plan.n_free = n_free; plan.rows_copied = rows_copied;
+    plan.home = reinterpret_cast<int32_t*>(ws + move_bytes);
+    plan.used = reinterpret_cast<int32_t*>(ws + move_bytes + slot);
+    plan.free_by_rank = reinterpret_cast<int32_t*>(ws + move_bytes + 2 * slot);
+    plan.relinked = reinterpret_cast<int32_t*>(ws + move_bytes + 3 * slot);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(relink_plan_kernel, dim3(B, L), dim3(kPlanThreads), 0, st, plan);
+    int rc = check_launch("relink plan");
+    if (rc) return rc;
+
+    RowMoveLayer layers[METOK_MAX_LAYERS];
+    for (int i = 0; i < n_active; ++i) {
+        const int l = order[i];
+        layers[i].k = static_cast<char*>(k_pools[l]);
+        layers[i].v = static_cast<char*>(v_pools[l]);
+        layers[i].idx = idx[l];
+        layers[i].n_keep = n_keep[l];
+        layers[i].first_item = 0; layers[i].tiles = 0; layers[i].flag_slot = 0; layers[i].layer_id = l;
+    }
+    RelinkTables tables;
+    tables.table_in_layer_stride = table_in_layer_stride; tables.table_out = page_table_out; tables.home_page = plan.home;
+    return launch_row_moves(layers, n_active, B, Hkv, 2, S_cap, row_bytes, page_table_in, page_size, pages_per_seq, n_pages_pool,
+                            new_len, host_len, L, workspace, move_bytes, st, &tables);
 }

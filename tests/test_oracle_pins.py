@@ -519,6 +519,82 @@ def test_kv_compact_is_a_pure_row_copy():
         50 if s is None else len(s) for s in sched)
 
 
+def _relink_brute_force(idx, len_in, ps, table_in):
+    """What a page-relinking plan has to satisfy, checked from the definitions alone on a simulated physical pool."""
+    r = O.kv_relink_pages(idx, len_in, ps, table_in)
+    idx = list(map(int, idx))
+    n, n_old, n_new = len(idx), -(-len_in // ps), -(-len(idx) // ps)
+    old_pages = [int(table_in[j]) for j in range(n_old)]
+    # physical pool: old logical row r lives at (table_in[r // ps], r % ps)
+    pool = {(int(table_in[r // ps]), r % ps): r for r in range(len_in)}
+    # (i) the new table uses distinct pages the sequence already owned; the rest is released, nothing is lost or invented
+    assert len(r["table_out"]) == n_new and len(set(r["table_out"])) == n_new
+    assert set(r["table_out"]).isdisjoint(r["free_pages"])
+    assert sorted(r["table_out"] + r["free_pages"]) == sorted(old_pages)
+    # (ii) a new page is relinked exactly when its rows are one whole old page from slot 0 on, and then it IS that page
+    for D in range(n_new):
+        rows = idx[D * ps: min((D + 1) * ps, n)]
+        whole = rows[0] % ps == 0 and all(b == a + 1 for a, b in zip(rows, rows[1:]))
+        assert r["relinked"][D] == whole
+        if whole:
+            assert r["table_out"][D] == int(table_in[rows[0] // ps])
+            assert all(pool[(r["table_out"][D], t)] == rows[t] for t in range(len(rows)))       # already in place
+    # (iii) rows_copied counts the rows whose physical place changes
+    moved = sum(1 for d in range(n) if (r["table_out"][d // ps], d % ps) != (int(table_in[idx[d] // ps]), idx[d] % ps))
+    assert r["rows_copied"] == moved
+    # (iv) a copied page never lands behind its own logical position (what makes the in-place move safe), and the
+    #      copied pages take the free old pages in ascending order
+    copied_homes = [r["home"][D] for D in range(n_new) if not r["relinked"][D]]
+    assert all(r["home"][D] <= D for D in range(n_new) if not r["relinked"][D])
+    assert copied_homes == sorted(copied_homes)
+    taken = {r["home"][D] for D in range(n_new) if r["relinked"][D]}
+    assert copied_homes == [j for j in range(n_old) if j not in taken][:len(copied_homes)]
+    return r
+
+
+def test_kv_relink_pages_hand_case_and_paper_rule():
+    # pages of 4 rows; keep old rows 4..7 (a whole page), then 9, 12, 13, 14 and 15
+    table = [40, 41, 42, 43]
+    r = _relink_brute_force([4, 5, 6, 7, 9, 12, 13, 14, 15], 16, 4, table)
+    assert r["relinked"] == [True, False, False]
+    assert r["home"] == [1, 0, 2] and r["table_out"] == [41, 40, 42] and r["free_pages"] == [43]
+    assert r["rows_copied"] == 5
+    # Sec. 3.3: from l_1 on only the text rows stay.  With a visual span that ends on a page boundary every new page
+    # is an old page: nothing moves and every visual page is released.
+    n_vis, n_text, ps = 48, 10, 8
+    table = list(range(100, 100 + 8))
+    text_rows = O.kv_text_only_schedule(3, 1, n_vis, n_text)[1]
+    r = _relink_brute_force(text_rows, n_vis + n_text, ps, table)
+    assert r["relinked"] == [True, True] and r["rows_copied"] == 0
+    assert r["table_out"] == [106, 107] and r["free_pages"] == [100, 101, 102, 103, 104, 105]
+    # a visual span that ends inside a page: every text row shifts inside its page, so every one is copied
+    r = _relink_brute_force(list(range(45, 58)), 58, ps, table)
+    assert r["relinked"] == [False, False] and r["rows_copied"] == 13 and r["table_out"] == [100, 101]
+    # identity keep: every page is itself
+    r = _relink_brute_force(list(range(20)), 20, 8, [7, 5, 3])
+    assert r["relinked"] == [True, True, True] and r["rows_copied"] == 0 and r["free_pages"] == []
+
+
+def test_kv_relink_pages_invariants_on_random_keeps():
+    rng = np.random.Generator(np.random.PCG64(17))
+    for _ in range(300):
+        ps = int(rng.choice([1, 2, 4, 7, 16]))
+        n_old = int(rng.integers(1, 20))
+        len_in = int(rng.integers((n_old - 1) * ps + 1, n_old * ps + 1))
+        table = rng.permutation(200)[:n_old + 2]
+        mode = int(rng.integers(0, 3))
+        if mode == 0:                                   # scattered rows
+            keep = np.nonzero(rng.random(len_in) < rng.random())[0]
+        elif mode == 1:                                 # whole pages kept or dropped, plus a few loose rows
+            pages = rng.random(n_old) < 0.5
+            keep = np.nonzero(np.repeat(pages, ps)[:len_in] | (rng.random(len_in) < 0.05))[0]
+        else:                                           # a tail block
+            keep = np.arange(int(rng.integers(0, len_in)), len_in)
+        if keep.size == 0:
+            continue
+        _relink_brute_force(keep, len_in, ps, table)
+
+
 def test_stage3_reading_reproduces_table3():
     """Table 3: with l_1 = 3 of 28 layers, 'layers below l_1 keep everything, the rest keep text only'
     must turn the stage-1 cache (171.8 MB) into the stage-3 cache (22.3 MB) for a plausible prompt length."""
