@@ -162,10 +162,10 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     const int tid = threadIdx.x;
 
     // per-frame totals: one wave per frame, lane c takes chunk partials c, c + 64, ...; the lane sums are
-    // combined by a fixed butterfly, so the result does not depend on timing.  A wave takes four frames at a
+    // combined by a fixed butterfly, so the result does not depend on timing.  A wave takes eight frames at a
     // time so that their loads are in flight together.
     {
-        constexpr int kWaves = kSegThreads / 64, kBatch = 4;
+        constexpr int kWaves = kSegThreads / 64, kBatch = 8;
         const int lane = tid & 63, wave = tid >> 6;
         for (int tb = wave; tb < T; tb += kWaves * kBatch) {
             float n2[kBatch], dot[kBatch], fs[kBatch];

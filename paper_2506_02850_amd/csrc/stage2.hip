@@ -110,10 +110,13 @@ struct KeyStage {
 //     qfrag[((kvh * rb_total + rb) * NCH + c) * 64 + lane],  row = 32 rb + lane % 32, half = lane / 32,
 // 16 bytes each (elements half * dh/2 + c * CE ... of the row); rows past the last query are zero.
 // A wave then fetches a fragment with one fully coalesced 1 KB load instead of 64 strided 16-byte pieces.
+// As the first kernel of a call it also clears the counters and histograms of the later kernels (`clear`, n_clear words).
 template <typename T, int NCH>
-__global__ __launch_bounds__(256) void pack_q_kernel(const T* __restrict__ q_text, const ScoreGeom g, uint4* __restrict__ qfrag) {
+__global__ __launch_bounds__(256) void pack_q_kernel(const T* __restrict__ q_text, const ScoreGeom g, uint4* __restrict__ qfrag,
+                                                     uint32_t* __restrict__ clear, int n_clear) {
     constexpr int CE = Mma<T>::kChunkElems;
     const int idx = blockIdx.x * 256 + threadIdx.x;
+    for (int i = idx; i < n_clear; i += gridDim.x * 256) clear[i] = 0u;
     const int total = g.Hkv * g.rb_total * NCH * 64;
     if (idx >= total) return;
     const int lane = idx & 63, c = (idx >> 6) % NCH, rbg = idx / (64 * NCH);
@@ -688,14 +691,22 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
     const int32_t* __restrict__ eq_count, const int32_t* __restrict__ token_seg,
     int n_vis, int n_seg, int n_tiles, int total_keep, const int32_t* __restrict__ token_event,
     const int32_t* __restrict__ orig_idx_in, int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
-    int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out) {
+    int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out,
+    const int32_t* __restrict__ given_tile_off, const int32_t* __restrict__ given_eq_before /*[class][kSelCache]*/) {
     __shared__ int scan_scratch[17];
     __shared__ uint32_t s_tau[METOK_MAX_SEGMENTS];
     __shared__ int s_rem[METOK_MAX_SEGMENTS], s_eq_before[METOK_MAX_SEGMENTS];
     __shared__ int tie_seg[kSelThreads];
     const int tile = blockIdx.x, tid = threadIdx.x;
-    // kept tokens in earlier tiles: thread s walks the tiles of class s
+    // kept tokens in earlier tiles: given by the fast path, else thread s walks the tiles of class s
     int before = 0;
+    if (given_tile_off != nullptr) {
+        for (int sg = tid; sg < n_seg; sg += kIdxThreads) {
+            s_tau[sg] = sel_info[2 * sg]; s_rem[sg] = static_cast<int>(sel_info[2 * sg + 1]);
+            s_eq_before[sg] = given_eq_before[sg * kSelCache + tile];
+        }
+        if (tid == 0) before = given_tile_off[tile];
+    } else
     for (int sg = tid; sg < n_seg; sg += kIdxThreads) {
         const uint32_t tau = sel_info[2 * sg];
         const int rem = static_cast<int>(sel_info[2 * sg + 1]);
@@ -770,6 +781,334 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fast selection path: at most kFastSeg retention classes and at most kFastTiles tiles of 1024 tokens.
+// The single-workgroup radix select above costs 20-25 us at 36864 tokens, most of it barriers of a 1024-thread
+// workgroup; here the token-parallel parts run on one workgroup per tile and only the short serial parts run
+// on the workgroup that arrives last at an atomic counter (it is the one that knows every other workgroup's
+// results are complete; nobody waits for anybody):
+//   score_hist_kernel   per tile: scores (the former prepare_kernel), histogram of the top 11 key bits per class
+//                       -> global histogram.  Last workgroup: per class the histogram bucket that holds the
+//                       quota-th largest key, how many keys of that bucket are still needed, or keep all / none.
+//   candidate_kernel    per tile: tokens above the bucket are kept for sure (counted per tile), tokens inside it are
+//                       appended to a candidate list.  Last workgroup: radix select of the remaining 21 bits on the
+//                       list -> class threshold and number of equal keys kept; per tile the candidates above / equal
+//                       to it; exclusive sums over the tiles -> output offset of every tile.
+//   write_index_kernel  per tile, as before, with the offsets given.
+// Results are the same integers as on the general path: the keep rule (key above the threshold, or equal and among
+// the first equal keys by index) does not depend on how the threshold was found.
+// ---------------------------------------------------------------------------------------------
+constexpr int kFastSeg = 4;
+constexpr int kFastTiles = kSelCache;
+constexpr uint32_t kKeepAll = 0x7fffffffu;
+
+struct FastSel {
+    // cleared before the first kernel that uses them
+    uint32_t arrive_a, arrive_b, cand_total, pad;
+    int32_t hist[kFastSeg][2048];
+    // written before they are read
+    int32_t state[kFastSeg][4];             // bucket digit, keys of the bucket still needed, bucket population, mode
+    int32_t tile_sure[kFastSeg][kFastTiles];
+    int32_t tile_off[kFastTiles];
+    int32_t eq_before[kFastSeg][kFastTiles];
+    uint32_t sel_info[kFastSeg][2];         // threshold key, equal keys kept (kKeepAll = every one)
+};
+constexpr int kFastClearWords = 4 + kFastSeg * 2048;
+static size_t fast_state_bytes() { return round_up(sizeof(FastSel), 256); }
+enum { kModeSearch = 0, kModeNone = 1, kModeAll = 2 };
+
+struct FastArgs {
+    FastSel* fs;
+    uint32_t* cand_key;                     // [n_vis]
+    uint32_t* cand_tok;                     // [n_vis]: class << 24 | token
+    const float* colpart;                   // NULL: scores are given
+    int n_parts;
+    float rows_total;
+    const int32_t* token_event;
+    const float* event_weight;
+    int n_events;
+    float* scores;
+    const int32_t* token_seg;
+    int n_vis, n_seg;
+    int32_t quota[kFastSeg];
+};
+
+// Values handed from one workgroup to another inside a kernel travel through device-scope accesses (they pass the
+// caches that are not coherent between the chip's dies), so that no whole-cache write-back or invalidate is needed:
+// the writers store, wait until their stores have completed, meet at a barrier and count their arrival; the workgroup
+// that arrives last loads.
+template <typename V> __device__ __forceinline__ void store_shared_between_workgroups(V* p, V v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename V> __device__ __forceinline__ V load_shared_between_workgroups(const V* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by every thread of the workgroup after its last store: true in the workgroup that arrives last of gridDim.x.
+__device__ __forceinline__ bool arrive_and_check_last(uint32_t* counter, int* s_flag) {
+    __builtin_amdgcn_s_waitcnt(0);          // this thread's stores and atomics have completed
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = ticket == gridDim.x - 1 ? 1 : 0;
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
+
+__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t* __restrict__ words, int n) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) words[i] = 0u;
+}
+
+// Orders the LDS traffic of one wave's lanes among themselves: LDS serves a wave's instructions in issue order, so
+// only the compiler has to be kept from moving accesses across this point.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// One wave walks a histogram in LDS from the largest digit down and returns the digit at which the running count
+// reaches `need`, how many keys of that digit are still needed and how many keys the digit holds.  bins is 1024 or 2048.
+__device__ __forceinline__ void wave_find_bucket(const int* hist, int bins, int need, int* digit, int* rem, int* cnt) {
+    const int lane = threadIdx.x & 63;
+    const int per = bins / 64;
+    const int hi = bins - 1 - lane * per;                          // the largest digit of this lane
+    int mine_sum = 0;
+    for (int u = 0; u < per; ++u) mine_sum += hist[hi - u];
+    int incl = mine_sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
+    }
+    const int excl = incl - mine_sum;
+    const bool mine = excl < need && incl >= need;
+    int d = 0, r = 0, c = 0;
+    if (mine) {
+        int run = excl;
+        for (int u = 0; u < per; ++u) {
+            const int v = hist[hi - u];
+            if (run + v >= need) { d = hi - u; r = need - run; c = v; break; }
+            run += v;
+        }
+    }
+    const unsigned long long m = __ballot(mine);
+    const int src = m ? __ffsll(static_cast<long long>(m)) - 1 : 0;
+    *digit = __shfl(d, src, 64); *rem = __shfl(r, src, 64); *cnt = __shfl(c, src, 64);
+}
+// population of a histogram (one wave)
+__device__ __forceinline__ int wave_hist_total(const int* hist, int bins) {
+    const int lane = threadIdx.x & 63;
+    int s = 0;
+    for (int i = lane; i < bins; i += 64) s += hist[i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+    return s;
+}
+
+__global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs a) {
+    __shared__ int hist[kFastSeg * 2048];
+    __shared__ int s_last;
+    const int tid = threadIdx.x;
+    const int j = blockIdx.x * kSelThreads + tid;
+    for (int i = tid; i < a.n_seg * 2048; i += kSelThreads) hist[i] = 0;
+    float sc = 0.f;
+    int sg = -1;
+    if (j < a.n_vis) {
+        if (a.colpart) {
+            float acc = 0.f;
+            for (int p = 0; p < a.n_parts; ++p) acc += a.colpart[static_cast<size_t>(p) * a.n_vis + j];
+            acc = acc / a.rows_total;
+            if (a.event_weight) {
+                int e = a.token_event[j];
+                e = e < 0 ? 0 : (e >= a.n_events ? a.n_events - 1 : e);
+                acc *= a.event_weight[e];
+            }
+            sc = acc;
+            a.scores[j] = sc;
+        } else {
+            sc = a.scores[j];
+        }
+        const int s = a.token_seg[j];
+        sg = (s >= 0 && s < a.n_seg) ? s : -1;
+    }
+    const uint32_t key = ordered_key(sc);
+    __syncthreads();
+    if (sg >= 0) atomicAdd(&hist[sg * 2048 + (key >> 21)], 1);
+    __syncthreads();
+    int32_t* ghist = &a.fs->hist[0][0];
+    for (int i = tid; i < a.n_seg * 2048; i += kSelThreads) {
+        const int v = hist[i];
+        if (v) atomicAdd(&ghist[i], v);
+    }
+    if (!arrive_and_check_last(&a.fs->arrive_a, &s_last)) return;
+    // last workgroup: the complete histograms come back into LDS, then one wave finds every class's bucket (no more barriers)
+    for (int i = tid; i < a.n_seg * 2048; i += kSelThreads) hist[i] = load_shared_between_workgroups(&ghist[i]);
+    __syncthreads();
+    if (tid >= 64) return;
+    for (int c = 0; c < a.n_seg; ++c) {
+        const int quota = a.quota[c];
+        const int pop = wave_hist_total(hist + c * 2048, 2048);
+        int digit = 0, rem = 0, cnt = 0;
+        const int mode = quota <= 0 ? kModeNone : (quota >= pop ? kModeAll : kModeSearch);
+        if (mode == kModeSearch) wave_find_bucket(hist + c * 2048, 2048, quota, &digit, &rem, &cnt);
+        if (tid == 0) { a.fs->state[c][0] = digit; a.fs->state[c][1] = rem; a.fs->state[c][2] = cnt; a.fs->state[c][3] = mode; }
+    }
+}
+
+constexpr int kCandRegs = 8;             // candidates a thread of the finishing workgroup keeps in registers
+
+__global__ __launch_bounds__(kSelThreads) void candidate_kernel(const FastArgs a) {
+    __shared__ int lhist[kFastSeg * 2048];
+    __shared__ int s_last, s_sure[kFastSeg], s_mode[kFastSeg], s_need[kFastSeg], s_cnt[kFastSeg];
+    __shared__ uint32_t s_tau[kFastSeg], s_keep_eq[kFastSeg], s_prefix[kFastSeg];
+    __shared__ int t_gt[kFastSeg][kFastTiles], t_eq[kFastSeg][kFastTiles];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int j = blockIdx.x * kSelThreads + tid;
+    if (tid < kFastSeg) s_sure[tid] = 0;
+    int sg = -1;
+    uint32_t key = 0u;
+    if (j < a.n_vis) {
+        key = ordered_key(a.scores[j]);
+        const int s = a.token_seg[j];
+        sg = (s >= 0 && s < a.n_seg) ? s : -1;
+    }
+    bool sure = false, cand = false;
+    if (sg >= 0) {
+        const int mode = a.fs->state[sg][3], digit = a.fs->state[sg][0];
+        const int d = static_cast<int>(key >> 21);
+        sure = mode == kModeAll || (mode == kModeSearch && d > digit);
+        cand = mode == kModeSearch && d == digit;
+    }
+    __syncthreads();
+    for (int c = 0; c < a.n_seg; ++c) {
+        const unsigned long long m = __ballot(sure && sg == c);
+        if (lane == 0 && m) atomicAdd(&s_sure[c], __popcll(m));
+    }
+    {   // candidates of a wave take consecutive slots of the list
+        const unsigned long long m = __ballot(cand);
+        if (m) {
+            const int leader = __ffsll(static_cast<long long>(m)) - 1;
+            uint32_t base = 0u;
+            if (lane == leader) base = atomicAdd(&a.fs->cand_total, static_cast<uint32_t>(__popcll(m)));
+            base = __shfl(base, leader, 64);
+            if (cand) {
+                const uint32_t pos = base + __popcll(m & ((1ull << lane) - 1ull));
+                if (pos < static_cast<uint32_t>(a.n_vis)) {
+                    store_shared_between_workgroups(&a.cand_key[pos], key);
+                    store_shared_between_workgroups(&a.cand_tok[pos], (static_cast<uint32_t>(sg) << 24) | static_cast<uint32_t>(j));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < a.n_seg) store_shared_between_workgroups(&a.fs->tile_sure[tid][blockIdx.x], s_sure[tid]);
+    if (!arrive_and_check_last(&a.fs->arrive_b, &s_last)) return;
+
+    // ---- last workgroup: every thread keeps up to eight candidates in registers; the searches of all classes run
+    //      side by side, one wave per class walking that class's histogram ----
+    const int n_tiles = gridDim.x;
+    int m = static_cast<int>(load_shared_between_workgroups(&a.fs->cand_total));
+    m = m < a.n_vis ? m : a.n_vis;
+    const bool in_regs = m <= kCandRegs * kSelThreads;
+    uint32_t ck[kCandRegs];
+    int cm[kCandRegs];                                              // class << 6 | tile, -1: no candidate
+#pragma unroll
+    for (int u = 0; u < kCandRegs; ++u) {
+        const int i = tid + u * kSelThreads;
+        ck[u] = 0u; cm[u] = -1;
+        if (in_regs && i < m) {
+            const uint32_t tok = load_shared_between_workgroups(&a.cand_tok[i]);
+            ck[u] = load_shared_between_workgroups(&a.cand_key[i]);
+            cm[u] = static_cast<int>(((tok >> 24) << 6) | (((tok & 0xffffffu) >> 10) & 63u));
+        }
+    }
+    // f(key, class, tile) for every candidate; a list too long for the registers is walked in memory
+    auto for_each_candidate = [&](auto&& f) {
+        if (in_regs) {
+#pragma unroll
+            for (int u = 0; u < kCandRegs; ++u)
+                if (cm[u] >= 0) f(ck[u], cm[u] >> 6, cm[u] & 63);
+        } else {
+            for (int i = tid; i < m; i += kSelThreads) {
+                const uint32_t tok = load_shared_between_workgroups(&a.cand_tok[i]);
+                f(load_shared_between_workgroups(&a.cand_key[i]), static_cast<int>(tok >> 24), static_cast<int>((tok & 0xffffffu) >> 10));
+            }
+        }
+    };
+    for (int i = tid; i < kFastSeg * kFastTiles; i += kSelThreads) {
+        const int c = i / kFastTiles, t = i % kFastTiles;
+        (&t_gt[0][0])[i] = (c < a.n_seg && t < n_tiles) ? load_shared_between_workgroups(&a.fs->tile_sure[c][t]) : 0;      // kept for sure
+        (&t_eq[0][0])[i] = 0;
+    }
+    if (tid < kFastSeg) {
+        const bool live = tid < a.n_seg;
+        s_mode[tid] = live ? a.fs->state[tid][3] : kModeNone;
+        s_prefix[tid] = live ? static_cast<uint32_t>(a.fs->state[tid][0]) << 21 : 0u;
+        s_need[tid] = live ? a.fs->state[tid][1] : 0;
+        s_cnt[tid] = live ? a.fs->state[tid][2] : 0;
+    }
+    __syncthreads();
+    // the remaining 21 key bits of every class's quota-th largest key, 11 then 10 bits
+    for (int top = 21; top > 0; top -= 11) {
+        const int bits = top < 11 ? top : 11, shift = top - bits, bins = 1 << bits;
+        const uint32_t hi_mask = 0xffffffffu << top, dmask = static_cast<uint32_t>(bins - 1);
+        for (int i = tid; i < kFastSeg * 2048; i += kSelThreads) lhist[i] = 0;
+        __syncthreads();
+        for_each_candidate([&](uint32_t k, int cls, int) {
+            if (s_mode[cls] == kModeSearch && (k & hi_mask) == s_prefix[cls]) atomicAdd(&lhist[cls * 2048 + ((k >> shift) & dmask)], 1);
+        });
+        __syncthreads();
+        const int w = tid >> 6;
+        if (w < a.n_seg && s_mode[w] == kModeSearch) {
+            int digit = 0, need = 0, cnt = 0;
+            wave_find_bucket(lhist + w * 2048, bins, s_need[w], &digit, &need, &cnt);
+            wave_sync();
+            if (lane == 0) { s_prefix[w] |= static_cast<uint32_t>(digit) << shift; s_need[w] = need; s_cnt[w] = cnt; }
+        }
+        __syncthreads();
+    }
+    if (tid < a.n_seg) {
+        const int mode = s_mode[tid];
+        uint32_t tau = 0u, keep_eq = kKeepAll;                      // kModeAll: every key is above or equal to 0
+        if (mode == kModeNone) { tau = 0xffffffffu; keep_eq = 0u; }
+        if (mode == kModeSearch) { tau = s_prefix[tid]; keep_eq = s_need[tid] >= s_cnt[tid] ? kKeepAll : static_cast<uint32_t>(s_need[tid]); }
+        s_tau[tid] = tau; s_keep_eq[tid] = keep_eq;
+        a.fs->sel_info[tid][0] = tau; a.fs->sel_info[tid][1] = keep_eq;
+    }
+    __syncthreads();
+    // per tile and class: candidates above / equal to the threshold (t_gt already holds the tokens kept for sure)
+    for_each_candidate([&](uint32_t k, int cls, int tile) {
+        if (cls < a.n_seg && tile < n_tiles) {
+            if (k > s_tau[cls]) atomicAdd(&t_gt[cls][tile], 1);
+            else if (k == s_tau[cls]) atomicAdd(&t_eq[cls][tile], 1);
+        }
+    });
+    __syncthreads();
+    if (tid >= 64) return;
+    // one lane per class: equal keys before every tile, kept tokens of every tile (in t_gt)
+    if (lane < a.n_seg) {
+        const int c = lane;
+        const uint32_t keep_eq = s_keep_eq[c];
+        int eqcum = 0;
+        for (int t = 0; t < n_tiles; ++t) {
+            const int eq = t_eq[c][t];
+            int room = keep_eq == kKeepAll ? eq : static_cast<int>(keep_eq) - eqcum;
+            room = room < 0 ? 0 : room;
+            a.fs->eq_before[c][t] = eqcum;
+            eqcum += eq;
+            t_gt[c][t] += eq < room ? eq : room;
+        }
+    }
+    wave_sync();
+    if (lane == 0) {
+        int running = 0;
+        for (int t = 0; t < n_tiles; ++t) {
+            a.fs->tile_off[t] = running;
+            for (int c = 0; c < a.n_seg; ++c) running += t_gt[c][t];
+        }
+    }
+}
+
 // Source row of every output row of the compacted sequence [prefix; kept visual rows; text rows].
 __global__ __launch_bounds__(256) void hidden_index_kernel(int32_t* __restrict__ src_row, int out_rows, int vis_start, int n_vis, int n_keep,
                                                            const int32_t* __restrict__ kept_idx) {
@@ -814,7 +1153,13 @@ static int select_tiles(int n_vis) { return (n_vis + kSelThreads - 1) / kSelThre
 static size_t select_count_bytes(int n_vis) {
     return round_up(static_cast<size_t>(METOK_MAX_SEGMENTS) * select_tiles(n_vis) * sizeof(int32_t), 256);
 }
-static size_t select_bytes(int n_vis) { return 2 * select_count_bytes(n_vis) + METOK_MAX_SEGMENTS * 2 * sizeof(uint32_t); }
+static size_t select_general_bytes(int n_vis) { return 2 * select_count_bytes(n_vis) + METOK_MAX_SEGMENTS * 2 * sizeof(uint32_t); }
+// then the fast path: its state block and the candidate list (key and token of at most min(n_vis, 40960) candidates)
+static size_t fast_state_bytes();
+static size_t select_bytes(int n_vis) {
+    const size_t cand = round_up(static_cast<size_t>(n_vis < kSelCache * kSelThreads ? n_vis : kSelCache * kSelThreads) * sizeof(uint32_t), 256);
+    return select_general_bytes(n_vis) + fast_state_bytes() + 2 * cand;
+}
 
 // In-place compaction (hidden_out == hidden): the source row of every output row as an index list, and the
 // progress flags of the row mover.  Rows of at most kInPlaceMaxRowBytes keep a row inside one workgroup
@@ -901,7 +1246,8 @@ static void launch_scores(const void* q, const void* k, const ScoreGeom& g, cons
     float* norm = reinterpret_cast<float*>(ws + p.off_norm);
     float* colpart = reinterpret_cast<float*>(ws + p.off_colpart);
     const int qslots = g.Hkv * g.rb_total * NCH * 64;
-    hipLaunchKernelGGL((pack_q_kernel<T, NCH>), dim3((qslots + 255) / 256), dim3(256), 0, st, static_cast<const T*>(q), g, qfrag);
+    hipLaunchKernelGGL((pack_q_kernel<T, NCH>), dim3((qslots + 255) / 256), dim3(256), 0, st, static_cast<const T*>(q), g, qfrag,
+                       reinterpret_cast<uint32_t*>(ws + p.off_sel + select_general_bytes(g.n_vis)), kFastClearWords);
     { TraceScope trace_scope(METOK_TRACE_ROW_STATS, st); hipLaunchKernelGGL((row_stats_kernel<T, NCH, RBW, SUBS>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
                        qfrag, static_cast<const T*>(k), g, p.per1, pstat); }
     const int total_rows = ny * g.rbw * 32;
@@ -976,6 +1322,10 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
     int rc;
     char* sel;
     char* inplace_ws;
+    const float* colpart = nullptr;
+    int n_parts = 0;
+    const int n_tiles = select_tiles(n_vis);
+    const bool fast = n_seg <= kFastSeg && n_tiles <= kFastTiles;       // else the general one-workgroup-per-class select
     if (q_text) {
         if (!k_all || !aligned16(q_text) || !aligned16(k_all)) return fail(METOK_ERR_INVALID_ARG, "q_text / k_all NULL or misaligned");
         if (Hq < 1 || Hkv < 1 || Hq % Hkv) return fail(METOK_ERR_INVALID_ARG, "Hq = %d must be a positive multiple of Hkv = %d", Hq, Hkv);
@@ -1009,31 +1359,61 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
         if ((rc = check_launch("attention scores"))) return rc;
         sel = ws + p.off_sel;
         inplace_ws = ws + p.off_inplace;
-        hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st,
-                           reinterpret_cast<const float*>(ws + p.off_colpart), g.Hkv * g.rs, n_vis,
-                           static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores);
-        if ((rc = check_launch("prepare"))) return rc;
+        colpart = reinterpret_cast<const float*>(ws + p.off_colpart);
+        n_parts = g.Hkv * g.rs;
+        if (!fast) {
+            hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st, colpart, n_parts, n_vis,
+                               static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores);
+            if ((rc = check_launch("prepare"))) return rc;
+        }
     } else {
         const size_t need = select_bytes(n_vis) + inplace_bytes(S);
         if (!workspace || workspace_bytes < need || !aligned16(workspace))
             return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
         sel = ws;
         inplace_ws = ws + select_bytes(n_vis);
+        if (fast) {      // no packing kernel runs on this path: clear the fast path's counters and histograms here
+            hipLaunchKernelGGL(clear_words_kernel, dim3(8), dim3(256), 0, st, reinterpret_cast<uint32_t*>(sel + select_general_bytes(n_vis)),
+                               kFastClearWords);
+            if ((rc = check_launch("clear"))) return rc;
+        }
     }
     int32_t* gt_count = reinterpret_cast<int32_t*>(sel);
     int32_t* eq_count = reinterpret_cast<int32_t*>(sel + select_count_bytes(n_vis));
     uint32_t* sel_info = reinterpret_cast<uint32_t*>(sel + 2 * select_count_bytes(n_vis));
-    const int n_tiles = select_tiles(n_vis);
-    if (n_vis <= kSelCache * kSelThreads)
-        { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                           gt_count, eq_count, sel_info); }
-    else
-        { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                           gt_count, eq_count, sel_info); }
-    if ((rc = check_launch("select"))) return rc;
+    const int32_t* tile_off = nullptr;
+    const int32_t* eq_before = nullptr;
+    if (fast) {
+        FastArgs fa;
+        fa.fs = reinterpret_cast<FastSel*>(sel + select_general_bytes(n_vis));
+        const size_t cand = round_up(static_cast<size_t>(n_vis) * sizeof(uint32_t), 256);
+        fa.cand_key = reinterpret_cast<uint32_t*>(sel + select_general_bytes(n_vis) + fast_state_bytes());
+        fa.cand_tok = reinterpret_cast<uint32_t*>(sel + select_general_bytes(n_vis) + fast_state_bytes() + cand);
+        fa.colpart = colpart; fa.n_parts = n_parts; fa.rows_total = static_cast<float>(static_cast<int64_t>(Hq) * Tq);
+        fa.token_event = token_event; fa.event_weight = event_weight; fa.n_events = n_events;
+        fa.scores = scores; fa.token_seg = token_seg; fa.n_vis = n_vis; fa.n_seg = n_seg;
+        for (int c = 0; c < kFastSeg; ++c) fa.quota[c] = c < n_seg ? quotas.q[c] : 0;
+        {
+            TraceScope trace_scope(METOK_TRACE_SELECT, st);          // both selection kernels
+            hipLaunchKernelGGL(score_hist_kernel, dim3(n_tiles), dim3(kSelThreads), 0, st, fa);
+            hipLaunchKernelGGL(candidate_kernel, dim3(n_tiles), dim3(kSelThreads), 0, st, fa);
+        }
+        if ((rc = check_launch("select"))) return rc;
+        sel_info = &fa.fs->sel_info[0][0];
+        tile_off = fa.fs->tile_off;
+        eq_before = &fa.fs->eq_before[0][0];
+    } else {
+        if (n_vis <= kSelCache * kSelThreads)
+            { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
+                               gt_count, eq_count, sel_info); }
+        else
+            { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
+                               gt_count, eq_count, sel_info); }
+        if ((rc = check_launch("select"))) return rc;
+    }
     { TraceScope trace_scope(METOK_TRACE_WRITE_INDEX, st); hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
                        n_tiles, static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out,
-                       token_event_out, orig_idx_out); }
+                       token_event_out, orig_idx_out, tile_off, eq_before); }
     if ((rc = check_launch("write index"))) return rc;
     if (in_place) {
         int32_t* src_row = reinterpret_cast<int32_t*>(inplace_ws);
