@@ -57,6 +57,7 @@ enum { METOK_EVENT_MEAN = 0, METOK_EVENT_MAX = 1 };/* event score: Sec. 3.2.1 te
 enum { METOK_POOL_FLOOR = 0, METOK_POOL_CEIL = 1 };/* output side floor(g/s) or ceil(g/s) */
 
 #define METOK_MAX_FRAMES 8192     /* T limit of the stage-1 calls */
+#define METOK_MAX_BATCH 64        /* videos per batched call */
 #define METOK_MAX_SEGMENTS 256    /* n_seg limit of metok_prefill_prune */
 #define METOK_MAX_LAYERS 128      /* L limit of metok_kv_compact */
 
@@ -287,6 +288,36 @@ METOK_API int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtyp
                         int n_seg, const int32_t* seg_quota,
                         const int32_t* orig_idx_in,
                         float* scores, int32_t* kept_idx, void* hidden_out,
+                        int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.2.2 for a batch of videos of one shape: the call of metok_prefill_prune on each of `batch` videos
+ * (1 <= batch <= METOK_MAX_BATCH), run as ONE sequence of launches whose grids span the whole batch, so that the
+ * per-kernel launch cost and the tail of every grid are paid once per level, not once per video.  Per video the
+ * results are those of metok_prefill_prune on that video: the same selection rule and the same row copies; the scores
+ * may differ in the last bits, because a video's keys are split over fewer workgroups and the partial sums are added
+ * in another order.
+ *   Inputs carry a leading batch dimension and are tightly packed: hidden [batch, S, D], q_text [batch, Hq, Tq, dh],
+ *   k_all [batch, Hkv, S, dh], token_seg / token_event / orig_idx_in / scores [batch, n_vis], event_weight
+ *   [batch, n_events]; seg_quota is host [batch, n_seg] (the kept count may differ between videos).
+ *   Outputs: kept_idx, token_seg_out, token_event_out, orig_idx_out are [batch, keep_stride] (keep_stride >= the largest
+ *   video's sum of quotas; entries past a video's own count are not written); hidden_out is [batch, out_row_stride, D]
+ *   (out_row_stride >= S - n_vis + that largest count; rows past a video's own count are not written).
+ *   hidden_out == hidden compacts every video in place (out_row_stride must be S).
+ *   workspace: metok_prefill_prune_batched_workspace_bytes(batch, ...) bytes.
+ */
+METOK_API size_t metok_prefill_prune_batched_workspace_bytes(int batch, int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype);
+
+METOK_API int metok_prefill_prune_batched(int batch, const void* hidden, int64_t S, int D, int dtype,
+                        const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                        int score_mode, int vis_start, int n_vis,
+                        const int32_t* token_seg, const int32_t* token_event,
+                        const float* event_weight, int n_events,
+                        int n_seg, const int32_t* seg_quota,
+                        const int32_t* orig_idx_in,
+                        float* scores, int32_t* kept_idx, int64_t keep_stride,
+                        void* hidden_out, int64_t out_row_stride,
                         int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
                         void* workspace, size_t workspace_bytes, void* stream);
 

@@ -29,6 +29,7 @@ EXPORTS = [
     "metok_segment_compress_workspace_bytes", "metok_segment_compress",
     "metok_retention_quotas", "metok_account",
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
+    "metok_prefill_prune_batched_workspace_bytes", "metok_prefill_prune_batched",
     "metok_kv_compact", "metok_kv_compact_paged", "metok_calib_copy",
     "metok_preset", "metok_compress_encoder_tokens_capacity_rows",
     "metok_static_scratch_bytes", "metok_prefill_prune_static",
@@ -93,6 +94,11 @@ def _load() -> ctypes.CDLL:
     lib.metok_prefill_prune.restype = i32
     lib.metok_prefill_prune.argtypes = [vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
                                         i32, c.POINTER(c.c_int32), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.metok_prefill_prune_batched_workspace_bytes.restype = sz
+    lib.metok_prefill_prune_batched_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, i32, i32, i32]
+    lib.metok_prefill_prune_batched.restype = i32
+    lib.metok_prefill_prune_batched.argtypes = [i32, vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
+                                                i32, c.POINTER(c.c_int32), vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, sz, vp]
     lib.metok_kv_compact.restype = i32
     lib.metok_kv_compact_workspace_bytes.restype = sz
     lib.metok_kv_compact_workspace_bytes.argtypes = [i32, i32, i32, i64, i32, i32]
@@ -392,6 +398,79 @@ def metok_prefill_prune(hidden: torch.Tensor, vis_start: int, n_vis: int, token_
         _check(_lib.metok_prefill_prune(*args, _dev(ws, "workspace"), ws.numel(), _stream()))
     res = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
                orig_idx_out=orig_idx_out)
+    if token_event_out is not None:
+        res["token_event_out"] = token_event_out
+    return res
+
+
+def metok_prefill_prune_batched(hidden: torch.Tensor, vis_start: int, n_vis: int, token_seg: torch.Tensor,
+                                seg_quota: Sequence[Sequence[int]],
+                                q_text: Optional[torch.Tensor] = None, k_all: Optional[torch.Tensor] = None,
+                                token_event: Optional[torch.Tensor] = None, event_weight: Optional[torch.Tensor] = None,
+                                orig_idx: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                                hidden_out: Optional[torch.Tensor] = None,
+                                workspace: Optional[torch.Tensor] = None,
+                                out: Optional[Dict[str, torch.Tensor]] = None,
+                                score_mode: int = 0, keep_stride: Optional[int] = None,
+                                out_row_stride: Optional[int] = None) -> Dict[str, torch.Tensor]:
+    """One pruning level of a batch of videos of one shape: every tensor of metok_prefill_prune with a leading batch
+    dimension, seg_quota one list per video.  Returns the per-video kept counts as `n_keep` (a Python list) beside the
+    padded outputs ([B, keep_stride] index lists, [B, out_row_stride, D] hidden states)."""
+    B, S, D = hidden.shape
+    dt = _dtype_code(hidden)
+    dev = hidden.device
+    if len(seg_quota) != B:
+        raise ValueError("seg_quota needs one list per video")
+    n_seg = len(seg_quota[0])
+    if any(len(q) != n_seg for q in seg_quota):
+        raise ValueError("every video needs the same number of retention classes")
+    n_keep = [int(sum(int(x) for x in q)) for q in seg_quota]
+    quota_arr = (ctypes.c_int32 * (B * n_seg))(*[int(x) for q in seg_quota for x in q])
+    if q_text is not None:
+        if k_all is None:
+            raise ValueError("k_all is required with q_text")
+        _, Hq, Tq, dh = q_text.shape
+        Hkv = k_all.shape[1]
+        if (q_text.shape[0] != B or k_all.shape[0] != B or k_all.shape[2] != S or k_all.shape[3] != dh
+                or _dtype_code(q_text) != dt or _dtype_code(k_all) != dt):
+            raise ValueError("q_text must be [B, Hq, Tq, dh] and k_all [B, Hkv, S, dh] with the dtype of hidden")
+        scores = _out(out, "scores", (B, n_vis), torch.float32, dev)
+    else:
+        if scores is None:
+            raise ValueError("either q_text/k_all or scores must be given")
+        Hq = Hkv = dh = Tq = 0
+    for name, t, shape in (("token_seg", token_seg, (B, n_vis)), ("token_event", token_event, (B, n_vis)),
+                           ("orig_idx", orig_idx, (B, n_vis)), ("scores", scores, (B, n_vis))):
+        if t is not None and tuple(t.shape) != shape:
+            raise ValueError(f"{name} must have the shape {shape}")
+    need = _lib.metok_prefill_prune_batched_workspace_bytes(B, S, Hq, Hkv, dh, Tq, n_vis, dt)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    in_place = hidden_out is hidden
+    keep_stride = max(n_keep) if keep_stride is None else int(keep_stride)
+    if out_row_stride is None:
+        out_row_stride = S if in_place else S - n_vis + max(n_keep)
+    kept_idx = _out(out, "kept_idx", (B, keep_stride), torch.int32, dev)
+    if hidden_out is None and out is not None:
+        hidden_out = out.get("hidden_out")
+    if hidden_out is None:
+        hidden_out = torch.empty((B, out_row_stride, D), dtype=hidden.dtype, device=dev)
+    elif tuple(hidden_out.shape) != (B, out_row_stride, D) or hidden_out.dtype != hidden.dtype:
+        raise ValueError(f"hidden_out must be {hidden.dtype} of shape {(B, out_row_stride, D)}")
+    token_seg_out = _out(out, "token_seg_out", (B, keep_stride), torch.int32, dev)
+    token_event_out = _out(out, "token_event_out", (B, keep_stride), torch.int32, dev) if token_event is not None else None
+    orig_idx_out = _out(out, "orig_idx_out", (B, keep_stride), torch.int32, dev)
+    n_events = int(event_weight.shape[1]) if event_weight is not None else 0
+    if event_weight is not None and event_weight.shape[0] != B:
+        raise ValueError("event_weight must be [B, n_events]")
+    _check(_lib.metok_prefill_prune_batched(
+        B, _dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
+        int(score_mode), int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
+        _dev(event_weight, "event_weight"), n_events, n_seg, quota_arr, _dev(orig_idx, "orig_idx"),
+        _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), keep_stride, _dev(hidden_out, "hidden_out"), out_row_stride,
+        _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
+        _dev(orig_idx_out, "orig_idx_out"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    res = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
+               orig_idx_out=orig_idx_out, n_keep=n_keep)
     if token_event_out is not None:
         res["token_event_out"] = token_event_out
     return res

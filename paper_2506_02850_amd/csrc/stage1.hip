@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     const float* __restrict__ part, int C, int T, int N, int k, int have_text, int sim_mode,
     float* __restrict__ sim, int32_t* __restrict__ event_start, int32_t* __restrict__ frame_event,
     float* __restrict__ frame_score, float* __restrict__ frame_norm2, float* __restrict__ pair_dot) {
-    __shared__ uint32_t key[METOK_MAX_FRAMES];      // ordered keys of S_i, later boundary flags
+    __shared__ __align__(16) uint32_t key[METOK_MAX_FRAMES + 8];      // ordered keys of S_i, padded with the largest key
     __shared__ int scan_scratch[17];
     const int tid = threadIdx.x;
 
@@ -201,6 +201,8 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
         sim[t] = s;
         key[t] = ordered_key(s);
     }
+    const int n_pairs = T - 1, n_quads = (n_pairs + 3) / 4;
+    if (tid < 4 && n_pairs + tid < n_quads * 4) key[n_pairs + tid] = 0xffffffffu;      // never below a real key, and at a higher index
     __syncthreads();
     // rank of S_i among the T-1 similarities under the order (value, index); the k-1 lowest are boundaries
     const int per = (T + kSegThreads - 1) / kSegThreads;      // frames per thread, consecutive
@@ -211,9 +213,15 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
             const int i = f - 1;
             const uint32_t ki = key[i];
             int rank = 0;
-            for (int m = 0; m < T - 1; ++m) {
-                const uint32_t km = key[m];
-                rank += (km < ki || (km == ki && m < i)) ? 1 : 0;
+            const uint4* key4 = reinterpret_cast<const uint4*>(key);          // four keys per LDS read, all lanes the same address
+#pragma unroll 4
+            for (int q = 0; q < n_quads; ++q) {
+                const uint4 km = key4[q];
+                const int m = 4 * q;
+                rank += (km.x < ki || (km.x == ki && m < i)) ? 1 : 0;
+                rank += (km.y < ki || (km.y == ki && m + 1 < i)) ? 1 : 0;
+                rank += (km.z < ki || (km.z == ki && m + 2 < i)) ? 1 : 0;
+                rank += (km.w < ki || (km.w == ki && m + 3 < i)) ? 1 : 0;
             }
             if (rank < k - 1) my_flags |= 1u << j;
         }

@@ -20,6 +20,7 @@
 #include <mutex>
 
 #include "common.h"
+#include <type_traits>
 
 namespace metok {
 
@@ -62,7 +63,22 @@ struct ScoreGeom {
     int vis_start, n_vis;
     int64_t key_begin, key_end;   // keys the softmax of pass 1 normalises over (before the causal mask)
     float scale_log2;   // log2(e) / sqrt(dh)
+    // a batch of videos runs as one launch, blockIdx.z = video: distances between consecutive videos
+    int64_t q_video, k_video;     // elements of q_text / k_all
+    int64_t ws_video;             // bytes of workspace
 };
+
+// Pointer of video blockIdx.z, `bytes` apart from its neighbours (NULL stays NULL).
+template <typename P> __device__ __forceinline__ P* of_video(P* p, int64_t bytes) {
+    using B = typename std::conditional<std::is_const<P>::value, const char, char>::type;
+    return p ? reinterpret_cast<P*>(reinterpret_cast<B*>(p) + static_cast<int64_t>(blockIdx.z) * bytes) : p;
+}
+template <typename P> __device__ __forceinline__ P* of_video_elems(P* p, int64_t elems) {
+    return p ? p + static_cast<int64_t>(blockIdx.z) * elems : p;
+}
+
+// Kept visual tokens of every video of a batch (the quotas of a video added up), passed by value.
+struct BatchKeep { int32_t n[METOK_MAX_BATCH]; };
 
 // ---------------------------------------------------------------------------------------------
 // Both MFMA passes are query-stationary: wave w of a workgroup keeps the fragments of its own row
@@ -115,6 +131,7 @@ template <typename T, int NCH>
 __global__ __launch_bounds__(256) void pack_q_kernel(const T* __restrict__ q_text, const ScoreGeom g, uint4* __restrict__ qfrag,
                                                      uint32_t* __restrict__ clear, int n_clear) {
     constexpr int CE = Mma<T>::kChunkElems;
+    q_text = of_video_elems(q_text, g.q_video); qfrag = of_video(qfrag, g.ws_video); clear = of_video(clear, g.ws_video);
     const int idx = blockIdx.x * 256 + threadIdx.x;
     for (int i = idx; i < n_clear; i += gridDim.x * 256) clear[i] = 0u;
     const int total = g.Hkv * g.rb_total * NCH * 64;
@@ -222,7 +239,8 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
     const int rb0 = split * g.rbw;
     const int nrb = min(g.rbw, g.rb_total - rb0);
     const int nrb_w = nrb > wave ? (nrb - wave + kScoreWaves - 1) / kScoreWaves : 0;     // row blocks of this wave
-    const T* k_head = k_all + static_cast<size_t>(kvh) * g.S * g.dh;
+    qfrag = of_video(qfrag, g.ws_video); pstat = of_video(pstat, g.ws_video);
+    const T* k_head = of_video_elems(k_all, g.k_video) + static_cast<size_t>(kvh) * g.S * g.dh;
 
     const int64_t kb = g.key_begin + static_cast<int64_t>(blockIdx.x) * sub_per_wg * 32;
     const int64_t ke = min(g.key_end, kb + static_cast<int64_t>(sub_per_wg) * 32);
@@ -366,6 +384,7 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(const float* __restric
                                                           float* __restrict__ norm) {
     const int rows_per_y = g.rbw * 32;
     const int total = g.Hkv * g.rs * rows_per_y;
+    pstat = of_video(pstat, g.ws_video); norm = of_video(norm, g.ws_video);
     const int i = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int p = threadIdx.x & 15;
     float mm = kNegBig, ll = 0.f;
@@ -411,7 +430,8 @@ __global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const uint4* __
     const int rb0 = split * g.rbw;
     const int nrb = min(g.rbw, g.rb_total - rb0);
     const int nrb_w = nrb > wave ? (nrb - wave + kScoreWaves - 1) / kScoreWaves : 0;
-    const T* k_head = k_all + static_cast<size_t>(kvh) * g.S * g.dh;
+    qfrag = of_video(qfrag, g.ws_video); norm = of_video(norm, g.ws_video); colpart = of_video(colpart, g.ws_video);
+    const T* k_head = of_video_elems(k_all, g.k_video) + static_cast<size_t>(kvh) * g.S * g.dh;
 
     const int vb = blockIdx.x * sub_per_wg * 32;                       // visual keys [vb, ve) of this workgroup
     const int ve = min(g.n_vis, vb + sub_per_wg * 32);
@@ -481,7 +501,9 @@ __global__ __launch_bounds__(kScoreThreads) void col_sums_kernel(const uint4* __
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prepare_kernel(const float* __restrict__ colpart, int n_parts, int n_vis, float rows_total,
                                                       const int32_t* __restrict__ token_event, const float* __restrict__ event_weight,
-                                                      int n_events, float* __restrict__ scores) {
+                                                      int n_events, float* __restrict__ scores, int64_t ws_video) {
+    colpart = of_video(colpart, ws_video); token_event = of_video_elems(token_event, n_vis);
+    event_weight = of_video_elems(event_weight, n_events); scores = of_video_elems(scores, n_vis);
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= n_vis) return;
     float a = 0.f;
@@ -692,12 +714,20 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
     int n_vis, int n_seg, int n_tiles, int total_keep, const int32_t* __restrict__ token_event,
     const int32_t* __restrict__ orig_idx_in, int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
     int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out,
-    const int32_t* __restrict__ given_tile_off, const int32_t* __restrict__ given_eq_before /*[class][kSelCache]*/) {
+    const int32_t* __restrict__ given_tile_off, const int32_t* __restrict__ given_eq_before /*[class][kSelCache]*/,
+    int64_t ws_video, int64_t keep_stride, const BatchKeep keeps) {
     __shared__ int scan_scratch[17];
     __shared__ uint32_t s_tau[METOK_MAX_SEGMENTS];
     __shared__ int s_rem[METOK_MAX_SEGMENTS], s_eq_before[METOK_MAX_SEGMENTS];
     __shared__ int tie_seg[kSelThreads];
     const int tile = blockIdx.x, tid = threadIdx.x;
+    total_keep = keeps.n[blockIdx.z];
+    scores = of_video_elems(scores, n_vis); token_seg = of_video_elems(token_seg, n_vis);
+    token_event = of_video_elems(token_event, n_vis); orig_idx_in = of_video_elems(orig_idx_in, n_vis);
+    sel_info = of_video(sel_info, ws_video); gt_count = of_video(gt_count, ws_video); eq_count = of_video(eq_count, ws_video);
+    given_tile_off = of_video(given_tile_off, ws_video); given_eq_before = of_video(given_eq_before, ws_video);
+    kept_idx = of_video_elems(kept_idx, keep_stride); token_seg_out = of_video_elems(token_seg_out, keep_stride);
+    token_event_out = of_video_elems(token_event_out, keep_stride); orig_idx_out = of_video_elems(orig_idx_out, keep_stride);
     // kept tokens in earlier tiles: given by the fast path, else thread s walks the tiles of class s
     int before = 0;
     if (given_tile_off != nullptr) {
@@ -830,8 +860,16 @@ struct FastArgs {
     float* scores;
     const int32_t* token_seg;
     int n_vis, n_seg;
-    int32_t quota[kFastSeg];
+    int64_t ws_video;                       // bytes between the workspaces of consecutive videos
+    int32_t quota[METOK_MAX_BATCH][kFastSeg];
 };
+// The arguments as video blockIdx.z sees them.
+__device__ __forceinline__ void to_video(FastArgs& a) {
+    a.fs = of_video(a.fs, a.ws_video); a.cand_key = of_video(a.cand_key, a.ws_video); a.cand_tok = of_video(a.cand_tok, a.ws_video);
+    a.colpart = of_video(a.colpart, a.ws_video);
+    a.token_event = of_video_elems(a.token_event, a.n_vis); a.event_weight = of_video_elems(a.event_weight, a.n_events);
+    a.scores = of_video_elems(a.scores, a.n_vis); a.token_seg = of_video_elems(a.token_seg, a.n_vis);
+}
 
 // Values handed from one workgroup to another inside a kernel travel through device-scope accesses (they pass the
 // caches that are not coherent between the chip's dies), so that no whole-cache write-back or invalidate is needed:
@@ -855,7 +893,8 @@ __device__ __forceinline__ bool arrive_and_check_last(uint32_t* counter, int* s_
     return *s_flag != 0;
 }
 
-__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t* __restrict__ words, int n) {
+__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t* __restrict__ words, int n, int64_t ws_video) {
+    words = of_video(words, ws_video);
     for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) words[i] = 0u;
 }
 
@@ -905,9 +944,11 @@ __device__ __forceinline__ int wave_hist_total(const int* hist, int bins) {
     return s;
 }
 
-__global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs a) {
+__global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs args) {
     __shared__ int hist[kFastSeg * 2048];
     __shared__ int s_last;
+    FastArgs a = args;
+    to_video(a);
     const int tid = threadIdx.x;
     const int j = blockIdx.x * kSelThreads + tid;
     for (int i = tid; i < a.n_seg * 2048; i += kSelThreads) hist[i] = 0;
@@ -946,7 +987,7 @@ __global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs 
     __syncthreads();
     if (tid >= 64) return;
     for (int c = 0; c < a.n_seg; ++c) {
-        const int quota = a.quota[c];
+        const int quota = a.quota[blockIdx.z][c];
         const int pop = wave_hist_total(hist + c * 2048, 2048);
         int digit = 0, rem = 0, cnt = 0;
         const int mode = quota <= 0 ? kModeNone : (quota >= pop ? kModeAll : kModeSearch);
@@ -957,13 +998,15 @@ __global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs 
 
 constexpr int kCandRegs = 8;             // candidates a thread of the finishing workgroup keeps in registers
 
-__global__ __launch_bounds__(kSelThreads) void candidate_kernel(const FastArgs a) {
+__global__ __launch_bounds__(kSelThreads) void candidate_kernel(const FastArgs args) {
     __shared__ int lhist[kFastSeg * 2048];
     __shared__ int s_last, s_sure[kFastSeg], s_mode[kFastSeg], s_need[kFastSeg], s_cnt[kFastSeg];
     __shared__ uint32_t s_tau[kFastSeg], s_keep_eq[kFastSeg], s_prefix[kFastSeg];
     __shared__ int t_gt[kFastSeg][kFastTiles], t_eq[kFastSeg][kFastTiles];
     const int tid = threadIdx.x, lane = tid & 63;
     const int j = blockIdx.x * kSelThreads + tid;
+    FastArgs a = args;
+    to_video(a);
     if (tid < kFastSeg) s_sure[tid] = 0;
     int sg = -1;
     uint32_t key = 0u;
@@ -1128,8 +1171,13 @@ constexpr int kGatherThreads = 256;
 
 // One 16-byte chunk per thread, non-temporal (the copy pattern that measured fastest on MI355X).
 __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst,
-                                                                     int64_t out_rows, int chunks_per_row, int vis_start,
-                                                                     int n_vis, int n_keep, const int32_t* __restrict__ kept_idx) {
+                                                                     int64_t S, int64_t out_row_stride, int chunks_per_row, int vis_start,
+                                                                     int n_vis, const int32_t* __restrict__ kept_idx, int64_t keep_stride,
+                                                                     const BatchKeep keeps) {
+    const int n_keep = keeps.n[blockIdx.z];
+    const int64_t out_rows = S - n_vis + n_keep;
+    src = of_video_elems(src, S * chunks_per_row); dst = of_video_elems(dst, out_row_stride * chunks_per_row);
+    kept_idx = of_video_elems(kept_idx, keep_stride);
     const int64_t gidx = static_cast<int64_t>(blockIdx.x) * kGatherThreads + threadIdx.x;
     const int64_t r = gidx / chunks_per_row;
     if (r >= out_rows) return;
@@ -1200,9 +1248,10 @@ struct ScorePlan {
 
 constexpr int kScoreSlots = 256;    // one 512-thread workgroup per CU
 
-static void plan_score(const ScoreGeom& g, int n_vis, int nch, ScorePlan* p) {
+static void plan_score(const ScoreGeom& g, int n_vis, int nch, int batch, ScorePlan* p) {
     const int ny = g.Hkv * g.rs;
-    const int nx0 = kScoreSlots / ny < 1 ? 1 : kScoreSlots / ny;
+    const int64_t rows_of_grid = static_cast<int64_t>(ny) * batch;          // the videos of a batch share the chip's slots
+    const int nx0 = kScoreSlots / rows_of_grid < 1 ? 1 : static_cast<int>(kScoreSlots / rows_of_grid);
     auto pick = [&](int64_t subtiles, int* per) {
         int64_t nx = nx0 < subtiles ? nx0 : subtiles;
         if (nx < 1) nx = 1;
@@ -1225,7 +1274,7 @@ static void plan_score(const ScoreGeom& g, int n_vis, int nch, ScorePlan* p) {
     p->off_colpart = off; off += round_up(static_cast<size_t>(ny) * n_vis * sizeof(float), 256);
     p->off_sel = off;     off += select_bytes(n_vis);
     p->off_inplace = off; off += inplace_bytes(g.S);
-    p->total = off;
+    p->total = round_up(off, 256);
 }
 
 static bool dh_supported(int dh, int dtype) {
@@ -1234,7 +1283,7 @@ static bool dh_supported(int dh, int dtype) {
 }
 
 template <typename T, int NCH>
-static void launch_scores(const void* q, const void* k, const ScoreGeom& g, const ScorePlan& p, char* ws, hipStream_t st) {
+static void launch_scores(const void* q, const void* k, const ScoreGeom& g, const ScorePlan& p, char* ws, int batch, hipStream_t st) {
     constexpr int RBW = NCH <= 8 ? 2 : 1;
     constexpr int SUBS = NCH <= 8 ? 2 : 1;
     using Stage = KeyStage<T, NCH, SUBS>;
@@ -1246,13 +1295,14 @@ static void launch_scores(const void* q, const void* k, const ScoreGeom& g, cons
     float* norm = reinterpret_cast<float*>(ws + p.off_norm);
     float* colpart = reinterpret_cast<float*>(ws + p.off_colpart);
     const int qslots = g.Hkv * g.rb_total * NCH * 64;
-    hipLaunchKernelGGL((pack_q_kernel<T, NCH>), dim3((qslots + 255) / 256), dim3(256), 0, st, static_cast<const T*>(q), g, qfrag,
+    const unsigned nb = static_cast<unsigned>(batch);
+    hipLaunchKernelGGL((pack_q_kernel<T, NCH>), dim3((qslots + 255) / 256, 1, nb), dim3(256), 0, st, static_cast<const T*>(q), g, qfrag,
                        reinterpret_cast<uint32_t*>(ws + p.off_sel + select_general_bytes(g.n_vis)), kFastClearWords);
-    { TraceScope trace_scope(METOK_TRACE_ROW_STATS, st); hipLaunchKernelGGL((row_stats_kernel<T, NCH, RBW, SUBS>), dim3(p.nx1, ny), dim3(kScoreThreads), lds1, st,
+    { TraceScope trace_scope(METOK_TRACE_ROW_STATS, st); hipLaunchKernelGGL((row_stats_kernel<T, NCH, RBW, SUBS>), dim3(p.nx1, ny, nb), dim3(kScoreThreads), lds1, st,
                        qfrag, static_cast<const T*>(k), g, p.per1, pstat); }
     const int total_rows = ny * g.rbw * 32;
-    hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 15) / 16), dim3(256), 0, st, pstat, g, p.nx1, norm);
-    { TraceScope trace_scope(METOK_TRACE_COL_SUMS, st); hipLaunchKernelGGL((col_sums_kernel<T, NCH, RBW, SUBS>), dim3(p.nx2, ny), dim3(kScoreThreads), lds2, st,
+    hipLaunchKernelGGL(merge_stats_kernel, dim3((total_rows + 15) / 16, 1, nb), dim3(256), 0, st, pstat, g, p.nx1, norm);
+    { TraceScope trace_scope(METOK_TRACE_COL_SUMS, st); hipLaunchKernelGGL((col_sums_kernel<T, NCH, RBW, SUBS>), dim3(p.nx2, ny, nb), dim3(kScoreThreads), lds2, st,
                        qfrag, static_cast<const T*>(k), g, p.per2, norm, colpart); }
 }
 
@@ -1260,30 +1310,43 @@ static void launch_scores(const void* q, const void* k, const ScoreGeom& g, cons
 
 using namespace metok;
 
-extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype) {
-    if (n_vis < 0 || S < 1) return 0;
+// Workspace of ONE video of a batch of `batch` videos (the batch's videos lie one after the other).
+static size_t video_workspace_bytes(int batch, int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype) {
+    if (n_vis < 0 || S < 1 || batch < 1) return 0;
     ScoreGeom g;
     ScorePlan p;
     if (Hq >= 1 && Hkv >= 1 && Tq >= 1 && Hq % Hkv == 0 && dh_supported(dh, dtype) &&
         make_geom(S, Hq, Hkv, dh, Tq, 0, n_vis, dtype, METOK_SCORE_CAUSAL_ALL, &g)) {
-        plan_score(g, n_vis, chunk_count(dh, dtype), &p);
+        plan_score(g, n_vis, chunk_count(dh, dtype), batch, &p);
         return p.total;
     }
-    return select_bytes(n_vis) + inplace_bytes(S);      // no attention pass (scores supplied by the caller)
+    return round_up(select_bytes(n_vis) + inplace_bytes(S), 256);      // no attention pass (scores supplied by the caller)
 }
 
-// Shared body of metok_prefill_prune and metok_prefill_prune_static: `workspace` is the caller's buffer or
-// the library's static scratch array; nothing below allocates.
-static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
+extern "C" size_t metok_prefill_prune_workspace_bytes(int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype) {
+    return video_workspace_bytes(1, S, Hq, Hkv, dh, Tq, n_vis, dtype);
+}
+
+extern "C" size_t metok_prefill_prune_batched_workspace_bytes(int batch, int64_t S, int Hq, int Hkv, int dh, int Tq, int n_vis, int dtype) {
+    if (batch < 1 || batch > METOK_MAX_BATCH) return 0;
+    return static_cast<size_t>(batch) * video_workspace_bytes(batch, S, Hq, Hkv, dh, Tq, n_vis, dtype);
+}
+
+// Shared body of metok_prefill_prune, metok_prefill_prune_batched and metok_prefill_prune_static: `workspace` is the
+// caller's buffer or the library's static scratch array; nothing below allocates.  Every array carries a leading
+// dimension of `batch` videos (tightly packed inputs; outputs keep_stride entries / out_row_stride rows apart); every
+// kernel takes the video from blockIdx.z.
+static int prune_impl(int batch, const void* hidden, int64_t S, int D, int dtype,
                       const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
                       int score_mode, int vis_start, int n_vis,
                       const int32_t* token_seg, const int32_t* token_event,
                       const float* event_weight, int n_events,
                       int n_seg, const int32_t* seg_quota,
                       const int32_t* orig_idx_in,
-                      float* scores, int32_t* kept_idx, void* hidden_out,
+                      float* scores, int32_t* kept_idx, int64_t keep_stride, void* hidden_out, int64_t out_row_stride,
                       int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
                       void* workspace, size_t workspace_bytes, void* stream) {
+    if (batch < 1 || batch > METOK_MAX_BATCH) return fail(METOK_ERR_INVALID_ARG, "batch must be in [1, %d]", METOK_MAX_BATCH);
     if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
     if (S < 1 || S > INT32_MAX || D < 1) return fail(METOK_ERR_INVALID_ARG, "S must be in [1, 2^31) and D positive");
     if (vis_start < 0 || n_vis < 1 || static_cast<int64_t>(vis_start) + n_vis > S)
@@ -1296,26 +1359,39 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
     if (n_seg < 1 || n_seg > METOK_MAX_SEGMENTS) return fail(METOK_ERR_INVALID_ARG, "n_seg must be in [1, %d]", METOK_MAX_SEGMENTS);
     if (!token_event && (event_weight || token_event_out)) return fail(METOK_ERR_INVALID_ARG, "token_event is NULL but needed");
     if (event_weight && n_events < 1) return fail(METOK_ERR_INVALID_ARG, "event_weight given with n_events < 1");
-    Quotas quotas;
-    int64_t total_keep = 0;
-    for (int s = 0; s < METOK_MAX_SEGMENTS; ++s) quotas.q[s] = 0;
-    for (int s = 0; s < n_seg; ++s) {
-        if (seg_quota[s] < 0 || seg_quota[s] > n_vis) return fail(METOK_ERR_INVALID_ARG, "seg_quota[%d] = %d outside [0, n_vis]", s, seg_quota[s]);
-        quotas.q[s] = seg_quota[s];
-        total_keep += seg_quota[s];
+    BatchKeep keeps;
+    int64_t max_keep = 0;
+    for (int b = 0; b < METOK_MAX_BATCH; ++b) keeps.n[b] = 0;
+    for (int b = 0; b < batch; ++b) {
+        int64_t total_keep = 0;
+        for (int s = 0; s < n_seg; ++s) {
+            const int32_t q = seg_quota[static_cast<size_t>(b) * n_seg + s];
+            if (q < 0 || q > n_vis) return fail(METOK_ERR_INVALID_ARG, "seg_quota[%d] = %d of video %d outside [0, n_vis]", s, q, b);
+            total_keep += q;
+        }
+        if (total_keep > n_vis) return fail(METOK_ERR_INVALID_ARG, "quotas of video %d add up to %lld > n_vis = %d", b, (long long)total_keep, n_vis);
+        keeps.n[b] = static_cast<int32_t>(total_keep);
+        max_keep = total_keep > max_keep ? total_keep : max_keep;
     }
-    if (total_keep > n_vis) return fail(METOK_ERR_INVALID_ARG, "quotas add up to %lld > n_vis = %d", (long long)total_keep, n_vis);
-    if (total_keep > 0 && !kept_idx) return fail(METOK_ERR_INVALID_ARG, "kept_idx is NULL");
-    const int64_t out_rows = S - n_vis + total_keep;
+    if (max_keep > 0 && !kept_idx) return fail(METOK_ERR_INVALID_ARG, "kept_idx is NULL");
+    const int64_t max_out_rows = S - n_vis + max_keep;
+    if (batch > 1 && (keep_stride < max_keep || out_row_stride < max_out_rows))
+        return fail(METOK_ERR_INVALID_ARG, "keep_stride = %lld / out_row_stride = %lld below the largest video's %lld kept tokens / %lld rows",
+                    (long long)keep_stride, (long long)out_row_stride, (long long)max_keep, (long long)max_out_rows);
+    if (batch == 1) { keep_stride = max_keep; out_row_stride = max_out_rows; }
     // hidden_out == hidden compacts in place (every kept row moves towards the front: source >= destination);
     // any other overlap is refused
     const bool in_place = hidden_out == hidden;
     if (!in_place) {
-        const char* a0 = static_cast<const char*>(hidden); const char* a1 = a0 + static_cast<size_t>(S) * row_bytes;
-        const char* b0 = static_cast<const char*>(hidden_out); const char* b1 = b0 + static_cast<size_t>(out_rows) * row_bytes;
+        const char* a0 = static_cast<const char*>(hidden); const char* a1 = a0 + static_cast<size_t>(batch) * S * row_bytes;
+        const char* b0 = static_cast<const char*>(hidden_out);
+        const char* b1 = b0 + (static_cast<size_t>(batch - 1) * out_row_stride + max_out_rows) * row_bytes;
         if (a0 < b1 && b0 < a1) return fail(METOK_ERR_INVALID_ARG, "hidden_out overlaps hidden without being the same buffer");
-    } else if (static_cast<int64_t>(row_bytes) > kInPlaceMaxRowBytes) {
-        return fail(METOK_ERR_UNSUPPORTED, "in-place compaction needs rows of at most %lld bytes, got %zu", (long long)kInPlaceMaxRowBytes, row_bytes);
+    } else {
+        if (static_cast<int64_t>(row_bytes) > kInPlaceMaxRowBytes)
+            return fail(METOK_ERR_UNSUPPORTED, "in-place compaction needs rows of at most %lld bytes, got %zu", (long long)kInPlaceMaxRowBytes, row_bytes);
+        if (batch > 1 && out_row_stride != S)
+            return fail(METOK_ERR_INVALID_ARG, "in-place compaction of a batch keeps every video where it is: out_row_stride must be S");
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
@@ -1324,6 +1400,9 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
     char* inplace_ws;
     const float* colpart = nullptr;
     int n_parts = 0;
+    const unsigned nb = static_cast<unsigned>(batch);
+    const int64_t ws_video = static_cast<int64_t>(video_workspace_bytes(batch, S, q_text ? Hq : 0, q_text ? Hkv : 0, q_text ? dh : 0,
+                                                                        q_text ? Tq : 0, n_vis, dtype));
     const int n_tiles = select_tiles(n_vis);
     const bool fast = n_seg <= kFastSeg && n_tiles <= kFastTiles;       // else the general one-workgroup-per-class select
     if (q_text) {
@@ -1338,22 +1417,24 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
         if (!make_geom(S, Hq, Hkv, dh, Tq, vis_start, n_vis, dtype, score_mode, &g)) return fail(METOK_ERR_UNSUPPORTED, "head dimension too large");
         if (static_cast<int64_t>(g.Hkv) * g.rs > 65535) return fail(METOK_ERR_UNSUPPORTED, "too many query rows");
         ScorePlan p;
-        plan_score(g, n_vis, chunk_count(dh, dtype), &p);
-        if (!workspace || workspace_bytes < p.total || !aligned16(workspace))
-            return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", p.total, workspace_bytes);
+        plan_score(g, n_vis, chunk_count(dh, dtype), batch, &p);
+        g.q_video = static_cast<int64_t>(Hq) * Tq * dh; g.k_video = static_cast<int64_t>(Hkv) * S * dh; g.ws_video = ws_video;
+        if (static_cast<int64_t>(p.total) != ws_video) return fail(METOK_ERR_DEVICE, "internal: workspace plan mismatch");
+        if (!workspace || workspace_bytes < p.total * batch || !aligned16(workspace))
+            return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", p.total * batch, workspace_bytes);
         const int nch = chunk_count(dh, dtype);
         if (dtype == METOK_BF16) {
             switch (nch) {
-                case 2: launch_scores<bf16_t, 2>(q_text, k_all, g, p, ws, st); break;
-                case 4: launch_scores<bf16_t, 4>(q_text, k_all, g, p, ws, st); break;
-                case 8: launch_scores<bf16_t, 8>(q_text, k_all, g, p, ws, st); break;
-                default: launch_scores<bf16_t, 16>(q_text, k_all, g, p, ws, st); break;
+                case 2: launch_scores<bf16_t, 2>(q_text, k_all, g, p, ws, batch, st); break;
+                case 4: launch_scores<bf16_t, 4>(q_text, k_all, g, p, ws, batch, st); break;
+                case 8: launch_scores<bf16_t, 8>(q_text, k_all, g, p, ws, batch, st); break;
+                default: launch_scores<bf16_t, 16>(q_text, k_all, g, p, ws, batch, st); break;
             }
         } else {
             switch (nch) {
-                case 4: launch_scores<float, 4>(q_text, k_all, g, p, ws, st); break;
-                case 8: launch_scores<float, 8>(q_text, k_all, g, p, ws, st); break;
-                default: launch_scores<float, 16>(q_text, k_all, g, p, ws, st); break;
+                case 4: launch_scores<float, 4>(q_text, k_all, g, p, ws, batch, st); break;
+                case 8: launch_scores<float, 8>(q_text, k_all, g, p, ws, batch, st); break;
+                default: launch_scores<float, 16>(q_text, k_all, g, p, ws, batch, st); break;
             }
         }
         if ((rc = check_launch("attention scores"))) return rc;
@@ -1362,19 +1443,19 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
         colpart = reinterpret_cast<const float*>(ws + p.off_colpart);
         n_parts = g.Hkv * g.rs;
         if (!fast) {
-            hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256), dim3(256), 0, st, colpart, n_parts, n_vis,
-                               static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores);
+            hipLaunchKernelGGL(prepare_kernel, dim3((n_vis + 255) / 256, 1, nb), dim3(256), 0, st, colpart, n_parts, n_vis,
+                               static_cast<float>(static_cast<int64_t>(Hq) * Tq), token_event, event_weight, n_events, scores, ws_video);
             if ((rc = check_launch("prepare"))) return rc;
         }
     } else {
-        const size_t need = select_bytes(n_vis) + inplace_bytes(S);
+        const size_t need = static_cast<size_t>(ws_video) * batch;
         if (!workspace || workspace_bytes < need || !aligned16(workspace))
             return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
         sel = ws;
         inplace_ws = ws + select_bytes(n_vis);
         if (fast) {      // no packing kernel runs on this path: clear the fast path's counters and histograms here
-            hipLaunchKernelGGL(clear_words_kernel, dim3(8), dim3(256), 0, st, reinterpret_cast<uint32_t*>(sel + select_general_bytes(n_vis)),
-                               kFastClearWords);
+            hipLaunchKernelGGL(clear_words_kernel, dim3(8, 1, nb), dim3(256), 0, st, reinterpret_cast<uint32_t*>(sel + select_general_bytes(n_vis)),
+                               kFastClearWords, ws_video);
             if ((rc = check_launch("clear"))) return rc;
         }
     }
@@ -1391,48 +1472,67 @@ static int prune_impl(const void* hidden, int64_t S, int D, int dtype,
         fa.cand_tok = reinterpret_cast<uint32_t*>(sel + select_general_bytes(n_vis) + fast_state_bytes() + cand);
         fa.colpart = colpart; fa.n_parts = n_parts; fa.rows_total = static_cast<float>(static_cast<int64_t>(Hq) * Tq);
         fa.token_event = token_event; fa.event_weight = event_weight; fa.n_events = n_events;
-        fa.scores = scores; fa.token_seg = token_seg; fa.n_vis = n_vis; fa.n_seg = n_seg;
-        for (int c = 0; c < kFastSeg; ++c) fa.quota[c] = c < n_seg ? quotas.q[c] : 0;
+        fa.scores = scores; fa.token_seg = token_seg; fa.n_vis = n_vis; fa.n_seg = n_seg; fa.ws_video = ws_video;
+        for (int b = 0; b < METOK_MAX_BATCH; ++b)
+            for (int c = 0; c < kFastSeg; ++c) fa.quota[b][c] = (b < batch && c < n_seg) ? seg_quota[static_cast<size_t>(b) * n_seg + c] : 0;
         {
             TraceScope trace_scope(METOK_TRACE_SELECT, st);          // both selection kernels
-            hipLaunchKernelGGL(score_hist_kernel, dim3(n_tiles), dim3(kSelThreads), 0, st, fa);
-            hipLaunchKernelGGL(candidate_kernel, dim3(n_tiles), dim3(kSelThreads), 0, st, fa);
+            hipLaunchKernelGGL(score_hist_kernel, dim3(n_tiles, 1, nb), dim3(kSelThreads), 0, st, fa);
+            hipLaunchKernelGGL(candidate_kernel, dim3(n_tiles, 1, nb), dim3(kSelThreads), 0, st, fa);
         }
         if ((rc = check_launch("select"))) return rc;
         sel_info = &fa.fs->sel_info[0][0];
         tile_off = fa.fs->tile_off;
         eq_before = &fa.fs->eq_before[0][0];
     } else {
-        if (n_vis <= kSelCache * kSelThreads)
-            { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                               gt_count, eq_count, sel_info); }
-        else
-            { TraceScope trace_scope(METOK_TRACE_SELECT, st); hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, scores, token_seg, n_vis, n_tiles, quotas,
-                               gt_count, eq_count, sel_info); }
+        // the general selection takes its quotas by value: one launch per video
+        TraceScope trace_scope(METOK_TRACE_SELECT, st);
+        for (int b = 0; b < batch; ++b) {
+            Quotas quotas;
+            for (int c = 0; c < METOK_MAX_SEGMENTS; ++c) quotas.q[c] = c < n_seg ? seg_quota[static_cast<size_t>(b) * n_seg + c] : 0;
+            const float* sc_b = scores + static_cast<size_t>(b) * n_vis;
+            const int32_t* seg_b = token_seg + static_cast<size_t>(b) * n_vis;
+            auto at = [&](auto* ptr) { return reinterpret_cast<decltype(ptr)>(reinterpret_cast<char*>(ptr) + static_cast<size_t>(b) * ws_video); };
+            if (n_vis <= kSelCache * kSelThreads)
+                hipLaunchKernelGGL(select_kernel<true>, dim3(n_seg), dim3(kSelThreads), 0, st, sc_b, seg_b, n_vis, n_tiles, quotas,
+                                   at(gt_count), at(eq_count), at(sel_info));
+            else
+                hipLaunchKernelGGL(select_kernel<false>, dim3(n_seg), dim3(kSelThreads), 0, st, sc_b, seg_b, n_vis, n_tiles, quotas,
+                                   at(gt_count), at(eq_count), at(sel_info));
+        }
         if ((rc = check_launch("select"))) return rc;
     }
-    { TraceScope trace_scope(METOK_TRACE_WRITE_INDEX, st); hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
-                       n_tiles, static_cast<int>(total_keep), token_event, orig_idx_in, kept_idx, token_seg_out,
-                       token_event_out, orig_idx_out, tile_off, eq_before); }
+    { TraceScope trace_scope(METOK_TRACE_WRITE_INDEX, st); hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles, 1, nb), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
+                       n_tiles, 0, token_event, orig_idx_in, kept_idx, token_seg_out,
+                       token_event_out, orig_idx_out, tile_off, eq_before, ws_video, keep_stride, keeps); }
     if ((rc = check_launch("write index"))) return rc;
     if (in_place) {
-        int32_t* src_row = reinterpret_cast<int32_t*>(inplace_ws);
-        hipLaunchKernelGGL(hidden_index_kernel, dim3(static_cast<unsigned>((out_rows + 255) / 256)), dim3(256), 0, st, src_row,
-                           static_cast<int>(out_rows), vis_start, n_vis, static_cast<int>(total_keep), kept_idx);
-        if ((rc = check_launch("hidden index"))) return rc;
-        RowMoveLayer layer;
-        layer.k = static_cast<char*>(hidden_out); layer.v = nullptr; layer.idx = src_row; layer.n_keep = static_cast<int32_t>(out_rows);
-        layer.first_item = 0; layer.tiles = 0; layer.flag_slot = 0; layer.layer_id = 0;
-        if (out_rows == 0) return METOK_OK;
-        return launch_row_moves(&layer, 1, 1, 1, 1, S, static_cast<int64_t>(row_bytes), nullptr, 0, 0, 0, nullptr, nullptr, 1,
-                                inplace_ws + inplace_index_bytes(S), inplace_bytes(S) - inplace_index_bytes(S), st, nullptr);
+        // the row mover takes one sequence per call here: the videos of a batch go one after the other
+        for (int b = 0; b < batch; ++b) {
+            const int64_t out_rows = S - n_vis + keeps.n[b];
+            if (out_rows == 0) continue;
+            char* ws_b = inplace_ws + static_cast<size_t>(b) * ws_video;
+            int32_t* src_row = reinterpret_cast<int32_t*>(ws_b);
+            hipLaunchKernelGGL(hidden_index_kernel, dim3(static_cast<unsigned>((out_rows + 255) / 256)), dim3(256), 0, st, src_row,
+                               static_cast<int>(out_rows), vis_start, n_vis, keeps.n[b], kept_idx + static_cast<size_t>(b) * keep_stride);
+            if ((rc = check_launch("hidden index"))) return rc;
+            RowMoveLayer layer;
+            layer.k = static_cast<char*>(hidden_out) + static_cast<size_t>(b) * S * row_bytes; layer.v = nullptr; layer.idx = src_row;
+            layer.n_keep = static_cast<int32_t>(out_rows);
+            layer.first_item = 0; layer.tiles = 0; layer.flag_slot = 0; layer.layer_id = 0;
+            rc = launch_row_moves(&layer, 1, 1, 1, 1, S, static_cast<int64_t>(row_bytes), nullptr, 0, 0, 0, nullptr, nullptr, 1,
+                                  ws_b + inplace_index_bytes(S), inplace_bytes(S) - inplace_index_bytes(S), st, nullptr);
+            if (rc) return rc;
+        }
+        return METOK_OK;
     }
     const int chunks_per_row = static_cast<int>(row_bytes / 16);
-    const int64_t blocks = (out_rows * chunks_per_row + kGatherThreads - 1) / kGatherThreads;
+    const int64_t blocks = (max_out_rows * chunks_per_row + kGatherThreads - 1) / kGatherThreads;
     if (blocks > 0x7fffffff) return fail(METOK_ERR_INVALID_ARG, "hidden_out too large for one launch");
-    { TraceScope trace_scope(METOK_TRACE_GATHER_ROWS, st); hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kGatherThreads), 0, st,
-                       static_cast<const u32x4_t*>(hidden), static_cast<u32x4_t*>(hidden_out), out_rows, chunks_per_row,
-                       vis_start, n_vis, static_cast<int>(total_keep), kept_idx); }
+    if (blocks == 0) return METOK_OK;
+    { TraceScope trace_scope(METOK_TRACE_GATHER_ROWS, st); hipLaunchKernelGGL(gather_rows_kernel, dim3(static_cast<unsigned>(blocks), 1, nb), dim3(kGatherThreads), 0, st,
+                       static_cast<const u32x4_t*>(hidden), static_cast<u32x4_t*>(hidden_out), S, out_row_stride, chunks_per_row,
+                       vis_start, n_vis, kept_idx, keep_stride, keeps); }
     return check_launch("gather");
 }
 
@@ -1447,9 +1547,26 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
                                    int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
                                    void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
-    return prune_impl(hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
-                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, hidden_out, token_seg_out,
+    return prune_impl(1, hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, 0, hidden_out, 0, token_seg_out,
                       token_event_out, orig_idx_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int metok_prefill_prune_batched(int batch, const void* hidden, int64_t S, int D, int dtype,
+                                           const void* q_text, const void* k_all, int Hq, int Hkv, int dh, int Tq,
+                                           int score_mode, int vis_start, int n_vis,
+                                           const int32_t* token_seg, const int32_t* token_event,
+                                           const float* event_weight, int n_events,
+                                           int n_seg, const int32_t* seg_quota,
+                                           const int32_t* orig_idx_in,
+                                           float* scores, int32_t* kept_idx, int64_t keep_stride,
+                                           void* hidden_out, int64_t out_row_stride,
+                                           int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    return prune_impl(batch, hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, keep_stride, hidden_out, out_row_stride,
+                      token_seg_out, token_event_out, orig_idx_out, workspace, workspace_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1505,7 +1622,7 @@ extern "C" int metok_prefill_prune_static(const void* hidden, int64_t S, int D, 
     void* ws = nullptr;
     int rc = static_scratch(&ws);
     if (rc) return rc;
-    return prune_impl(hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
-                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, hidden_out, token_seg_out,
+    return prune_impl(1, hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, 0, hidden_out, 0, token_seg_out,
                       token_event_out, orig_idx_out, ws, METOK_STATIC_SCRATCH_BYTES, stream);
 }
