@@ -199,6 +199,29 @@ METOK_API int metok_segment_compress(const void* feats, int dtype, int T, int gr
                            int32_t* frame_stride, float* event_score, float* frame_score,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Stage 1 in one call for a batch of videos of one shape (Sec. 3.2.1, Algorithm 1): metok_segment_compress on each of
+ * `batch` videos (1 <= batch <= METOK_MAX_BATCH) with the same settings.  In the one-pass case the batch runs as ONE
+ * sequence of four launches whose grids span all videos (the planning kernels, one workgroup per video, run side by
+ * side); otherwise the videos are processed one after the other.  Per video the results are those of
+ * metok_segment_compress, bit for bit.
+ *   Every array carries a leading batch dimension and is tightly packed: feats [batch, T, N, d], text_emb [batch, d],
+ *   sim [batch, T-1], event_start [batch, k+1], frame_event / frame_is_key / frame_stride / frame_score [batch, T],
+ *   out_tokens [batch, out_capacity_rows, d], token_event [batch, out_capacity_rows], frame_offsets [batch, T+1],
+ *   event_is_key / event_score [batch, k].  workspace: metok_segment_compress_batched_workspace_bytes(batch, ...).
+ */
+METOK_API size_t metok_segment_compress_batched_workspace_bytes(int batch, int T, int grid_h, int grid_w, int d, int dtype);
+
+METOK_API int metok_segment_compress_batched(int batch, const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                           const void* text_emb, int k, int sim_mode,
+                           double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
+                           float* sim, int32_t* event_start, int32_t* frame_event,
+                           void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                           int32_t* frame_offsets, int32_t* token_event,
+                           uint8_t* event_is_key, uint8_t* frame_is_key,
+                           int32_t* frame_stride, float* event_score, float* frame_score,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Stage 2 -- one level of hierarchical token pruning (Sec. 3.2.2).
  *

@@ -27,6 +27,7 @@ EXPORTS = [
     "metok_segment_events_workspace_bytes", "metok_segment_events",
     "metok_compress_encoder_tokens_workspace_bytes", "metok_compress_encoder_tokens",
     "metok_segment_compress_workspace_bytes", "metok_segment_compress",
+    "metok_segment_compress_batched_workspace_bytes", "metok_segment_compress_batched",
     "metok_retention_quotas", "metok_account",
     "metok_prefill_prune_workspace_bytes", "metok_prefill_prune",
     "metok_prefill_prune_batched_workspace_bytes", "metok_prefill_prune_batched",
@@ -82,6 +83,11 @@ def _load() -> ctypes.CDLL:
     lib.metok_segment_compress_workspace_bytes.restype = sz
     lib.metok_segment_compress_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.metok_segment_compress.restype = i32
+    lib.metok_segment_compress_batched_workspace_bytes.restype = sz
+    lib.metok_segment_compress_batched_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.metok_segment_compress_batched.restype = i32
+    lib.metok_segment_compress_batched.argtypes = [i32] + [vp, i32, i32, i32, i32, i32, vp, i32, i32, dbl, dbl, i32, i32, i32, i32,
+                                                            vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_segment_compress.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, i32, dbl, dbl, i32, i32, i32, i32,
                                            vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.metok_retention_quotas.restype = i32
@@ -308,6 +314,53 @@ def metok_segment_compress(feats: torch.Tensor, grid_h: int, grid_w: int, k: int
         float(alpha), float(beta), int(s1), int(s2), event_reduce, pool_edge,
         _dev(sim, "sim"), _dev(event_start, "event_start"), _dev(frame_event, "frame_event"),
         _dev(out_tokens, "out_tokens"), out_tokens.shape[0], _dtype_code(out_tokens),
+        _dev(frame_offsets, "frame_offsets"), _dev(token_event, "token_event"), _dev(event_is_key, "event_is_key"),
+        _dev(frame_is_key, "frame_is_key"), _dev(frame_stride, "frame_stride"), _dev(event_score, "event_score"),
+        _dev(frame_score, "frame_score"), _dev(ws, "workspace"), ws.numel(), _stream()))
+    return dict(sim=sim, event_start=event_start, frame_event=frame_event, out_tokens=out_tokens,
+                frame_offsets=frame_offsets, token_event=token_event, event_is_key=event_is_key,
+                frame_is_key=frame_is_key, frame_stride=frame_stride, event_score=event_score, frame_score=frame_score)
+
+
+def metok_segment_compress_batched(feats: torch.Tensor, grid_h: int, grid_w: int, k: int, text_emb: torch.Tensor,
+                                   alpha: float, beta: float, s1: int, s2: int,
+                                   sim_mode: int = SIM_FLAT, event_reduce: int = EVENT_MEAN, pool_edge: int = POOL_FLOOR,
+                                   out_dtype: Optional[torch.dtype] = None, workspace: Optional[torch.Tensor] = None,
+                                   out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """Stage 1 in one call for a batch of videos: feats [B, T, N, d], text_emb [B, d]; every output of
+    metok_segment_compress with a leading batch dimension."""
+    B, T, N, d = feats.shape
+    if N != grid_h * grid_w:
+        raise ValueError("feats.shape[2] must equal grid_h * grid_w")
+    if tuple(text_emb.shape) != (B, d):
+        raise ValueError("text_emb must be [B, d]")
+    dt = _dtype_code(feats)
+    dev = feats.device
+    odt = out_dtype if out_dtype is not None else feats.dtype
+    cap = metok_compress_encoder_tokens_capacity_rows(T, grid_h, grid_w, s1, s2, pool_edge)
+    out_tokens = out.get("out_tokens") if out is not None else None
+    if out_tokens is None:
+        out_tokens = torch.empty((B, cap, d), dtype=odt, device=dev)
+    elif out_tokens.dim() != 3 or out_tokens.shape[0] != B or out_tokens.shape[2] != d:
+        raise ValueError("out['out_tokens'] must be [B, capacity rows, d]")
+    rows = out_tokens.shape[1]
+    need = _lib.metok_segment_compress_batched_workspace_bytes(B, T, grid_h, grid_w, d, dt)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    sim = _out(out, "sim", (B, max(T - 1, 0)), torch.float32, dev)
+    event_start = _out(out, "event_start", (B, k + 1), torch.int32, dev)
+    frame_event = _out(out, "frame_event", (B, T), torch.int32, dev)
+    frame_offsets = _out(out, "frame_offsets", (B, T + 1), torch.int32, dev)
+    token_event = _out(out, "token_event", (B, rows), torch.int32, dev)
+    event_is_key = _out(out, "event_is_key", (B, k), torch.uint8, dev)
+    frame_is_key = _out(out, "frame_is_key", (B, T), torch.uint8, dev)
+    frame_stride = _out(out, "frame_stride", (B, T), torch.int32, dev)
+    event_score = _out(out, "event_score", (B, k), torch.float32, dev)
+    frame_score = _out(out, "frame_score", (B, T), torch.float32, dev)
+    _check(_lib.metok_segment_compress_batched(
+        B, _dev(feats, "feats"), dt, T, grid_h, grid_w, d, _dev(text_emb, "text_emb"), int(k), int(sim_mode),
+        float(alpha), float(beta), int(s1), int(s2), event_reduce, pool_edge,
+        _dev(sim, "sim"), _dev(event_start, "event_start"), _dev(frame_event, "frame_event"),
+        _dev(out_tokens, "out_tokens"), rows, _dtype_code(out_tokens),
         _dev(frame_offsets, "frame_offsets"), _dev(token_event, "token_event"), _dev(event_is_key, "event_is_key"),
         _dev(frame_is_key, "frame_is_key"), _dev(frame_stride, "frame_stride"), _dev(event_score, "event_score"),
         _dev(frame_score, "frame_score"), _dev(ws, "workspace"), ws.numel(), _stream()))

@@ -5,6 +5,7 @@
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <type_traits>
 
 #include "metok.h"
 
@@ -171,6 +172,16 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int G> __device__ __forceinline__ float group_sum(float v) {
     static_assert(G == 16 || G == 64, "token groups are one DPP row or one wave");
     return G == 16 ? row16_sum(v) : wave_sum(v);
+}
+
+// A batch of videos runs as one launch with blockIdx.z = video.  Pointer of that video, `bytes` (or `elems`
+// elements) apart from its neighbours; NULL stays NULL.  A launch without a batch has blockIdx.z = 0.
+template <typename P> __device__ __forceinline__ P* of_video(P* p, int64_t bytes) {
+    using B = typename std::conditional<std::is_const<P>::value, const char, char>::type;
+    return p ? reinterpret_cast<P*>(reinterpret_cast<B*>(p) + static_cast<int64_t>(blockIdx.z) * bytes) : p;
+}
+template <typename P> __device__ __forceinline__ P* of_video_elems(P* p, int64_t elems) {
+    return p ? p + static_cast<int64_t>(blockIdx.z) * elems : p;
 }
 
 // Exclusive prefix sum of one int per thread over a block of up to 1024 threads.

@@ -156,10 +156,13 @@ constexpr int kSegThreads = 1024;
 __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     const float* __restrict__ part, int C, int T, int N, int k, int have_text, int sim_mode,
     float* __restrict__ sim, int32_t* __restrict__ event_start, int32_t* __restrict__ frame_event,
-    float* __restrict__ frame_score, float* __restrict__ frame_norm2, float* __restrict__ pair_dot) {
+    float* __restrict__ frame_score, float* __restrict__ frame_norm2, float* __restrict__ pair_dot, int64_t ws_video) {
     __shared__ __align__(16) uint32_t key[METOK_MAX_FRAMES + 8];      // ordered keys of S_i, padded with the largest key
     __shared__ int scan_scratch[17];
     const int tid = threadIdx.x;
+    part = of_video(part, ws_video); frame_norm2 = of_video(frame_norm2, ws_video); pair_dot = of_video(pair_dot, ws_video);
+    sim = of_video_elems(sim, T - 1); event_start = of_video_elems(event_start, k + 1);
+    frame_event = of_video_elems(frame_event, T); frame_score = of_video_elems(frame_score, T);
 
     // per-frame totals: one wave per frame, lane c takes chunk partials c, c + 64, ...; the lane sums are
     // combined by a fixed butterfly, so the result does not depend on timing.  A wave takes eight frames at a
@@ -301,11 +304,16 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
     int grid_h, int grid_w, int event_reduce, int pool_edge,
     float* __restrict__ event_score, uint8_t* __restrict__ event_is_key, uint8_t* __restrict__ frame_is_key,
     int32_t* __restrict__ frame_stride, int32_t* __restrict__ frame_offsets, int32_t* __restrict__ frame_event_ws,
-    float* __restrict__ frame_score_out) {
+    float* __restrict__ frame_score_out, int64_t ws_video) {
     __shared__ uint32_t ekey[METOK_MAX_FRAMES];    // ordered keys of the event scores (k <= T)
     __shared__ uint8_t ev_key[METOK_MAX_FRAMES];
     __shared__ int scan_scratch[17];
     const int tid = threadIdx.x;
+    frame_score = of_video_elems(frame_score, T); event_start = of_video_elems(event_start, k + 1);
+    event_score = of_video_elems(event_score, k); event_is_key = of_video_elems(event_is_key, k);
+    frame_is_key = of_video_elems(frame_is_key, T); frame_stride = of_video_elems(frame_stride, T);
+    frame_offsets = of_video_elems(frame_offsets, T + 1); frame_event_ws = of_video(frame_event_ws, ws_video);
+    frame_score_out = of_video_elems(frame_score_out, T);
 
     // event score: mean (Sec. 3.2.1) or max (Algorithm 1) of the frame scores, frames in index order
     for (int e = tid; e < k; e += kSegThreads) {
@@ -479,10 +487,12 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
 template <typename T, int KL, typename TO>
 __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
     const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int grid_h, int grid_w, int d,
-    int frames_per_run, float* __restrict__ part, TO* __restrict__ pooled) {
+    int frames_per_run, float* __restrict__ part, TO* __restrict__ pooled, int64_t pooled_video, int64_t ws_video) {
     using E = Elem<T>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ow = grid_w / 2, n_win = (grid_h / 2) * ow, N = grid_h * grid_w;
+    feats = of_video_elems(feats, static_cast<int64_t>(T_frames) * N * d); text = of_video_elems(text, d);
+    part = of_video(part, ws_video); pooled = of_video_elems(pooled, pooled_video);
     const int w = blockIdx.x * kStatsWaves + wave;
     if (w >= n_win) return;                                          // there is no barrier below: a wave may leave on its own
     const int wy = w / ow, wx = w % ow;
@@ -574,7 +584,8 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
 
 // token_event of uniformly pooled frames: rows_per_frame consecutive rows carry their frame's event id.
 __global__ __launch_bounds__(256) void fill_token_event_kernel(const int32_t* __restrict__ frame_event, int T, int rows_per_frame,
-                                                               int32_t* __restrict__ token_event) {
+                                                               int32_t* __restrict__ token_event, int64_t rows_video) {
+    frame_event = of_video_elems(frame_event, T); token_event = of_video_elems(token_event, rows_video);
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < T * rows_per_frame) token_event[i] = frame_event[i / rows_per_frame];
 }
@@ -701,7 +712,7 @@ extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, 
         if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
         if ((rc = check_launch("frame_stats"))) return rc;
         { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, p.C, T, N, k, text_emb ? 1 : 0, sim_mode,
-                           sim, event_start, frame_event, frame_score, norm2, pair_dot); }
+                           sim, event_start, frame_event, frame_score, norm2, pair_dot, static_cast<int64_t>(0)); }
         return check_launch("segment");
     }
     // pooled reading: Eq. 5 (if wanted) from the tokens, Eq. 4 from the frames' mean tokens (a [T, 1, d] fp32 "video")
@@ -726,7 +737,7 @@ extern "C" int metok_segment_events(const void* feats, int dtype, int T, int N, 
         return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
     if ((rc = check_launch("frame_stats (means)"))) return rc;
     { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part_m, pm.C, T, 1, k, 0, METOK_SIM_FLAT,
-                       sim, event_start, frame_event, static_cast<float*>(nullptr), norm2, pair_dot); }
+                       sim, event_start, frame_event, static_cast<float*>(nullptr), norm2, pair_dot, static_cast<int64_t>(0)); }
     return check_launch("segment");
 }
 
@@ -824,7 +835,7 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
     { TraceScope trace_scope(METOK_TRACE_PLAN, st); hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, scores, event_start, T, k, n_key_events, beta,
                        s_key_kf, s_key_nf, s_non_kf, s_non_nf, grid_h, grid_w, event_reduce, pool_edge,
                        event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
-                       frame_score_out); }
+                       frame_score_out, static_cast<int64_t>(0)); }
     if ((rc = check_launch("plan"))) return rc;
 
     const int wg_per_frame = 36;      // 144 waves per frame; 18 to 72 workgroups measured within 3 % of each other
@@ -857,16 +868,16 @@ extern "C" size_t metok_segment_compress_workspace_bytes(int T, int grid_h, int 
     const size_t b = metok_compress_encoder_tokens_workspace_bytes(T, grid_h, grid_w, d, dtype);
     const size_t c = fused_part_bytes(T, grid_h, grid_w) + 3 * round_up(static_cast<size_t>(T) * sizeof(float), 256);
     const size_t ab = a > b ? a : b;
-    return ab > c ? ab : c;
+    return round_up(ab > c ? ab : c, 256);
 }
 
 template <typename T, typename TO>
 static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int grid_h, int grid_w, int d, int kl, int C, int fpr,
-                               int runs, float* part, void* pooled, hipStream_t st) {
+                               int runs, float* part, void* pooled, int batch, int64_t pooled_video, int64_t ws_video, hipStream_t st) {
 #define METOK_FUSED_CASE(KLV) \
     if (kl == KLV) { \
-        { TraceScope trace_scope(METOK_TRACE_FRAME_STATS_POOL2, st); hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs), dim3(kStatsThreads), 0, st, static_cast<const T*>(feats), \
-                           static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, static_cast<TO*>(pooled)); } \
+        { TraceScope trace_scope(METOK_TRACE_FRAME_STATS_POOL2, st); hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs, batch), dim3(kStatsThreads), 0, st, static_cast<const T*>(feats), \
+                           static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, static_cast<TO*>(pooled), pooled_video, ws_video); } \
         return true; \
     }
     METOK_FUSED_CASE(1) METOK_FUSED_CASE(2) METOK_FUSED_CASE(3) METOK_FUSED_CASE(4)
@@ -874,22 +885,25 @@ static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int 
     return false;
 }
 
-extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
-                                      const void* text_emb, int k, int sim_mode,
-                                      double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
-                                      float* sim, int32_t* event_start, int32_t* frame_event,
-                                      void* out_tokens, int64_t out_capacity_rows, int out_dtype,
-                                      int32_t* frame_offsets, int32_t* token_event,
-                                      uint8_t* event_is_key, uint8_t* frame_is_key,
-                                      int32_t* frame_stride, float* event_score, float* frame_score,
-                                      void* workspace, size_t workspace_bytes, void* stream) {
-    clear_error();
+// Shared body of metok_segment_compress (batch = 1) and metok_segment_compress_batched: every array carries a leading
+// dimension of `batch` videos, the workspace one slice per video; the one-pass kernels take the video from blockIdx.z.
+static int segment_compress_impl(int batch, const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                                 const void* text_emb, int k, int sim_mode,
+                                 double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
+                                 float* sim, int32_t* event_start, int32_t* frame_event,
+                                 void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                                 int32_t* frame_offsets, int32_t* token_event,
+                                 uint8_t* event_is_key, uint8_t* frame_is_key,
+                                 int32_t* frame_stride, float* event_score, float* frame_score,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (batch < 1 || batch > METOK_MAX_BATCH) return fail(METOK_ERR_INVALID_ARG, "batch must be in [1, %d]", METOK_MAX_BATCH);
     if (grid_h < 1 || grid_w < 1) return fail(METOK_ERR_INVALID_ARG, "grid sides must be positive");
     if (!text_emb || !frame_score) return fail(METOK_ERR_INVALID_ARG, "text_emb and frame_score are required (Eq. 5 drives the pooling plan)");
     const int N = grid_h * grid_w;
-    const size_t need = metok_segment_compress_workspace_bytes(T, grid_h, grid_w, d, dtype);
-    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace)))
-        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    const size_t need = metok_segment_compress_workspace_bytes(T, grid_h, grid_w, d, dtype);        // per video, a multiple of 256
+    if (need && (!workspace || workspace_bytes < need * batch || !aligned16(workspace)))
+        return fail(METOK_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need * batch, workspace_bytes);
+    const int64_t ws_video = static_cast<int64_t>(need);
 
     // can the pooled tokens be produced inside the statistics pass?
     bool fused = sim_mode == METOK_SIM_FLAT && grid_h % 2 == 0 && grid_w % 2 == 0 && alpha > 0.0 && alpha <= 1.0 && s1 >= 1 && s2 >= 1 &&
@@ -903,13 +917,26 @@ extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int g
     const int kl = (d > 0 && d % vec == 0) ? (d / vec + 63) / 64 : 0;
     if (kl < 1 || kl > 4) fused = false;
     if (!fused) {
-        int rc = metok_segment_events(feats, dtype, T, N, d, text_emb, k, sim_mode, sim, event_start, frame_event, frame_score,
-                                      workspace, workspace_bytes, stream);
-        if (rc) return rc;
-        return metok_compress_encoder_tokens(feats, dtype, T, grid_h, grid_w, d, nullptr, frame_score, event_start, k, alpha, beta, s1, s2,
-                                             event_reduce, pool_edge, out_tokens, out_capacity_rows, out_dtype, frame_offsets,
-                                             token_event, event_is_key, frame_is_key, frame_stride, event_score, nullptr,
-                                             workspace, workspace_bytes, stream);
+        // two passes per video (statistics, then pooling with the strides of Algorithm 1), one video after the other
+        const size_t in_es = dtype_size(dtype), out_es = dtype_size(out_dtype);
+        for (int b = 0; b < batch; ++b) {
+            auto at = [&](auto* ptr, int64_t elems) { return ptr ? ptr + static_cast<int64_t>(b) * elems : ptr; };
+            const char* f_b = static_cast<const char*>(feats) + static_cast<size_t>(b) * T * N * d * in_es;
+            const char* t_b = static_cast<const char*>(text_emb) + static_cast<size_t>(b) * d * in_es;
+            char* o_b = out_tokens ? static_cast<char*>(out_tokens) + static_cast<size_t>(b) * out_capacity_rows * d * out_es : nullptr;
+            char* ws_b = static_cast<char*>(workspace) + static_cast<size_t>(b) * ws_video;
+            int32_t* es_b = at(event_start, k + 1);
+            float* fs_b = at(frame_score, T);
+            int rc = metok_segment_events(f_b, dtype, T, N, d, t_b, k, sim_mode, at(sim, T - 1), es_b, at(frame_event, T), fs_b,
+                                          ws_b, need, stream);
+            if (rc) return rc;
+            rc = metok_compress_encoder_tokens(f_b, dtype, T, grid_h, grid_w, d, nullptr, fs_b, es_b, k, alpha, beta, s1, s2,
+                                               event_reduce, pool_edge, o_b, out_capacity_rows, out_dtype, at(frame_offsets, T + 1),
+                                               at(token_event, out_capacity_rows), at(event_is_key, k), at(frame_is_key, T),
+                                               at(frame_stride, T), at(event_score, k), nullptr, ws_b, need, stream);
+            if (rc) return rc;
+        }
+        return METOK_OK;
     }
     // ---- one pass over V ------------------------------------------------------------------------
     StatsPlan p;
@@ -950,25 +977,63 @@ extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int g
     float* pair_dot = reinterpret_cast<float*>(ws + part_bytes + tslot);
     int32_t* frame_event_ws = reinterpret_cast<int32_t*>(ws + part_bytes + 2 * tslot);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t pooled_video = out_capacity_rows * d;
+    const unsigned nb = static_cast<unsigned>(batch);
     bool ok;
     if (dtype == METOK_BF16)
-        ok = out_dtype == METOK_BF16 ? launch_stats_pool2<bf16_t, bf16_t>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st)
-                                     : launch_stats_pool2<bf16_t, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st);
+        ok = out_dtype == METOK_BF16 ? launch_stats_pool2<bf16_t, bf16_t>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, batch, pooled_video, ws_video, st)
+                                     : launch_stats_pool2<bf16_t, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, batch, pooled_video, ws_video, st);
     else
-        ok = out_dtype == METOK_BF16 ? launch_stats_pool2<float, bf16_t>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st)
-                                     : launch_stats_pool2<float, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, st);
+        ok = out_dtype == METOK_BF16 ? launch_stats_pool2<float, bf16_t>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, batch, pooled_video, ws_video, st)
+                                     : launch_stats_pool2<float, float>(feats, text_emb, T, grid_h, grid_w, d, kl, C, fpr, runs, part, out_tokens, batch, pooled_video, ws_video, st);
     if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no fused kernel for d = %d", d);
     if ((rc = check_launch("frame_stats_pool2"))) return rc;
-    { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(kSegThreads), 0, st, part, n_win, T, N, k, 1, METOK_SIM_FLAT,
-                       sim, event_start, frame_event, frame_score, norm2, pair_dot); }
+    { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1, 1, nb), dim3(kSegThreads), 0, st, part, n_win, T, N, k, 1, METOK_SIM_FLAT,
+                       sim, event_start, frame_event, frame_score, norm2, pair_dot, ws_video); }
     if ((rc = check_launch("segment"))) return rc;
     const int n_key_events = ceil_ratio(alpha * k) > k ? k : ceil_ratio(alpha * k);
-    { TraceScope trace_scope(METOK_TRACE_PLAN, st); hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kSegThreads), 0, st, frame_score, event_start, T, k, n_key_events, beta,
+    { TraceScope trace_scope(METOK_TRACE_PLAN, st); hipLaunchKernelGGL(plan_kernel, dim3(1, 1, nb), dim3(kSegThreads), 0, st, frame_score, event_start, T, k, n_key_events, beta,
                        2, 2, 2, 2, grid_h, grid_w, event_reduce, pool_edge,
                        event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
-                       static_cast<float*>(nullptr)); }
+                       static_cast<float*>(nullptr), ws_video); }
     if ((rc = check_launch("plan"))) return rc;
-    hipLaunchKernelGGL(fill_token_event_kernel, dim3(static_cast<unsigned>((rows + 255) / 256)), dim3(256), 0, st, frame_event, T, n_win,
-                       token_event);
+    hipLaunchKernelGGL(fill_token_event_kernel, dim3(static_cast<unsigned>((rows + 255) / 256), 1, nb), dim3(256), 0, st, frame_event, T, n_win,
+                       token_event, out_capacity_rows);
     return check_launch("token events");
+}
+
+extern "C" int metok_segment_compress(const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                                      const void* text_emb, int k, int sim_mode,
+                                      double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
+                                      float* sim, int32_t* event_start, int32_t* frame_event,
+                                      void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                                      int32_t* frame_offsets, int32_t* token_event,
+                                      uint8_t* event_is_key, uint8_t* frame_is_key,
+                                      int32_t* frame_stride, float* event_score, float* frame_score,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    return segment_compress_impl(1, feats, dtype, T, grid_h, grid_w, d, text_emb, k, sim_mode, alpha, beta, s1, s2, event_reduce, pool_edge,
+                                 sim, event_start, frame_event, out_tokens, out_capacity_rows, out_dtype, frame_offsets, token_event,
+                                 event_is_key, frame_is_key, frame_stride, event_score, frame_score, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t metok_segment_compress_batched_workspace_bytes(int batch, int T, int grid_h, int grid_w, int d, int dtype) {
+    if (batch < 1 || batch > METOK_MAX_BATCH) return 0;
+    return static_cast<size_t>(batch) * metok_segment_compress_workspace_bytes(T, grid_h, grid_w, d, dtype);
+}
+
+extern "C" int metok_segment_compress_batched(int batch, const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
+                                              const void* text_emb, int k, int sim_mode,
+                                              double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
+                                              float* sim, int32_t* event_start, int32_t* frame_event,
+                                              void* out_tokens, int64_t out_capacity_rows, int out_dtype,
+                                              int32_t* frame_offsets, int32_t* token_event,
+                                              uint8_t* event_is_key, uint8_t* frame_is_key,
+                                              int32_t* frame_stride, float* event_score, float* frame_score,
+                                              void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    return segment_compress_impl(batch, feats, dtype, T, grid_h, grid_w, d, text_emb, k, sim_mode, alpha, beta, s1, s2, event_reduce,
+                                 pool_edge, sim, event_start, frame_event, out_tokens, out_capacity_rows, out_dtype, frame_offsets,
+                                 token_event, event_is_key, frame_is_key, frame_stride, event_score, frame_score, workspace,
+                                 workspace_bytes, stream);
 }

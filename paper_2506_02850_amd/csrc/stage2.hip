@@ -20,7 +20,6 @@
 #include <mutex>
 
 #include "common.h"
-#include <type_traits>
 
 namespace metok {
 
@@ -68,14 +67,6 @@ struct ScoreGeom {
     int64_t ws_video;             // bytes of workspace
 };
 
-// Pointer of video blockIdx.z, `bytes` apart from its neighbours (NULL stays NULL).
-template <typename P> __device__ __forceinline__ P* of_video(P* p, int64_t bytes) {
-    using B = typename std::conditional<std::is_const<P>::value, const char, char>::type;
-    return p ? reinterpret_cast<P*>(reinterpret_cast<B*>(p) + static_cast<int64_t>(blockIdx.z) * bytes) : p;
-}
-template <typename P> __device__ __forceinline__ P* of_video_elems(P* p, int64_t elems) {
-    return p ? p + static_cast<int64_t>(blockIdx.z) * elems : p;
-}
 
 // Kept visual tokens of every video of a batch (the quotas of a video added up), passed by value.
 struct BatchKeep { int32_t n[METOK_MAX_BATCH]; };

@@ -140,3 +140,58 @@ def test_one_call_at_256_frames_and_errors():
     assert e.value.code == -4
     with pytest.raises(B.MetokError):
         B.metok_segment_compress(feats, 4, 4, 2, text, 1.0, 1.5, 2, 2)
+
+
+@pytest.mark.parametrize("T,grid,d,dtype,k,alpha,beta,s1,s2,out_dtype", [
+    (12, (6, 10), 512, "bf16", 3, 1.0, 1.0, 2, 2, "bf16"),     # one pass, ragged last workgroup
+    (40, (4, 6), 2048, "bf16", 7, 1.0, 0.5, 2, 2, "f32"),      # one pass, several frame runs
+    (10, (6, 6), 1024, "f32", 4, 1.0, 0.4, 2, 2, "f32"),       # one pass, fp32
+    (9, (6, 6), 64, "bf16", 3, 0.5, 0.45, 2, 3, "bf16"),       # adaptive strides: the videos run one after the other
+])
+def test_batched_one_call_equals_the_single_video_call(T, grid, d, dtype, k, alpha, beta, s1, s2, out_dtype):
+    """metok_segment_compress_batched: every video of the batch bit-identical to metok_segment_compress on that video
+    (which `check` above holds against the oracle), the segmentation of one video also directly against the oracle."""
+    B = mk()
+    videos = [synth.planted_video(900 + 17 * b + T, T, grid, d, k, 1, T, 0.15, dtype) for b in range(3)]
+    feats = synth.to_torch(np.stack([v.feats for v in videos]), dtype, "cuda")
+    text = synth.to_torch(np.stack([v.text_emb for v in videos]), dtype, "cuda")
+    odt = torch.bfloat16 if out_dtype == "bf16" else torch.float32
+    got = B.metok_segment_compress_batched(feats, grid[0], grid[1], k, text, alpha, beta, s1, s2, out_dtype=odt)
+    torch.cuda.synchronize()
+    for b, v in enumerate(videos):
+        one = B.metok_segment_compress(feats[b], grid[0], grid[1], k, text[b], alpha, beta, s1, s2, out_dtype=odt)
+        torch.cuda.synchronize()
+        M = int(one["frame_offsets"][-1])
+        for name, t in one.items():
+            rows = M if name in ("out_tokens", "token_event") else t.shape[0]
+            assert torch.equal(got[name][b][:rows], t[:rows]), f"video {b}: {name}"
+    es, fe = O.event_boundaries(O.adjacent_frame_cosine(videos[1].feats, 0), k)
+    np.testing.assert_array_equal(got["event_start"][1].cpu().numpy(), es)
+    np.testing.assert_array_equal(got["frame_event"][1].cpu().numpy(), fe)
+
+
+def test_batched_one_call_at_256_frames_against_the_oracle():
+    """Two 256-frame videos in one batched call: decisions and pooled tokens of the second video against the oracle."""
+    B = mk()
+    sh = synth.ENCODER_256
+    v0, v1 = synth.video_for(sh), synth.planted_video(4242, sh.T, sh.grid, sh.d, sh.n_events, 8, 64, 0.15, "bf16")
+    feats = synth.to_torch(np.stack([v0.feats, v1.feats]), "bf16", "cuda")
+    text = synth.to_torch(np.stack([v0.text_emb, v1.text_emb]), "bf16", "cuda")
+    got = B.metok_segment_compress_batched(feats, sh.grid[0], sh.grid[1], sh.n_events, text, 1.0, 1.0, 2, 2)
+    torch.cuda.synchronize()
+    g = {n: (t[1].float() if t.dtype == torch.bfloat16 else t[1]).cpu().numpy() for n, t in got.items()}
+    S = O.adjacent_frame_cosine(v1.feats, 0)
+    assert_rel(g["sim"], S, RTOL["bf16"], "sim", scale=np.abs(S).max())
+    es, fe = O.event_boundaries(S, sh.n_events)
+    np.testing.assert_array_equal(g["event_start"], es)
+    np.testing.assert_array_equal(g["frame_event"], fe)
+    assert_rel(g["frame_score"], O.frame_text_score(v1.feats, v1.text_emb), RTOL["bf16"], "frame_score")
+    ref = O.compress_encoder_tokens(v1.feats, sh.grid, None, es, 1.0, 1.0, 2, 2, 0, 0, frame_score=g["frame_score"].astype(np.float64))
+    for name in ("event_is_key", "frame_is_key", "frame_stride", "frame_offsets"):
+        np.testing.assert_array_equal(g[name], ref[name], err_msg=name)
+    np.testing.assert_array_equal(g["token_event"], ref["token_event"])
+    assert_pooled_bf16_strict(g["out_tokens"], ref["tokens"], "pooled tokens")
+    with pytest.raises(B.MetokError) as e:
+        B.metok_segment_compress_batched(feats[:, :4].contiguous(), sh.grid[0], sh.grid[1], 2, text, 1.0, 1.0, 2, 2,
+                                         workspace=torch.zeros(1024, dtype=torch.uint8, device="cuda"))
+    assert "workspace" in str(e.value)

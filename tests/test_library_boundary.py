@@ -33,7 +33,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert len(names) == 26 and len(set(names)) == len(names)
+    assert len(names) == 28 and len(set(names)) == len(names)
     for name in names:
         assert hasattr(lib, name), f"{name} is declared in metok.h but not exported"
     from paper_2506_02850_amd import binding
