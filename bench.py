@@ -3,15 +3,17 @@
 
 One step = one pass of stages 1-3 over a batch of synthetic, LongVA-7B-shaped 256-frame videos:
 
-  stage 1  per video: metok_segment_compress (segmentation, scores, plan and pooling in one call) on
-           CLIP-ViT-L/336-shaped features [256, 576, 1024] bf16 (16 planted events, uniform stride 2 ->
+  stage 1  the batch in one call: metok_segment_compress_batched (segmentation, scores, plan and pooling) on
+           CLIP-ViT-L/336-shaped features [8, 256, 576, 1024] bf16 (16 planted events per video, uniform stride 2 ->
            256 x 144 tokens, so the pooled tokens come out of the statistics pass: one read of the features);
-  stage 2  per video: three metok_prefill_prune levels (keep 0.5 / 0.5 / 0.5 of the current count) on
-           hidden states [36864 + 128, 3584] bf16 with 28 query / 4 kv heads of 128 and the last 64 text
-           positions as queries; keys carry a per-event mean shift and the queries lean towards one target
-           event; event ids come from stage 1, retained indices are carried level to level;
+  stage 2  the batch in one call per level: three metok_prefill_prune_batched levels (keep 0.5 / 0.5 / 0.5 of the
+           current count) on hidden states [8, 36864 + 128, 3584] bf16 with 28 query / 4 kv heads of 128 and the
+           last 64 text positions as queries; keys carry a per-event mean shift and the queries lean towards one
+           target event; event ids come from stage 1, retained indices are carried level to level;
   stage 3  the whole batch: metok_kv_compact of a 28-layer KV cache [8, 4, 36992, 128] bf16 (K and V) to
            the per-layer retained sets of stage 2 (levels start at layers 3, 10, 19) plus the text rows.
+
+--per-video runs stages 1-2 as one call per video on 8 streams instead (the same kernels with one video per launch).
 
 All inputs are resident in HBM before the timed region.  `value` is visual tokens entering stage 1 per
 second.  The JSON line also carries
@@ -110,8 +112,11 @@ class Workload:
         lib = binding.lib()
         i32, f32, u8 = torch.int32, torch.float32, torch.uint8
 
-        # ---- stage 1 inputs: planted events, unit centroid + N(0, 0.2^2) noise per entry
-        self.feats, self.text, planted_events = [], [], []
+        # ---- stage 1 inputs: planted events, unit centroid + N(0, 0.2^2) noise per entry.  Every tensor of the batch is one
+        # allocation with a leading video dimension (the batched calls take them whole); the per-video lists are views.
+        self.feats_b = torch.empty((batch, FRAMES, GRID * GRID, D_VIS), dtype=bf, device=device)
+        self.text_b = torch.empty((batch, D_VIS), dtype=bf, device=device)
+        planted_events = []
         for b in range(batch):
             lens = synth.event_lengths(rng, FRAMES, N_EVENTS, 4, 40)
             cent = torch.from_numpy(synth.unit_rows(rng, N_EVENTS, D_VIS)).to(device)
@@ -119,54 +124,62 @@ class Workload:
             planted_events.append(frame_event)
             f = torch.randn((FRAMES, GRID * GRID, D_VIS), generator=gen, device=device, dtype=torch.float32)
             f.mul_(0.2).add_(cent[frame_event][:, None, :])
-            self.feats.append(f.to(bf))
+            self.feats_b[b] = f.to(bf)
             w = torch.linspace(1.0, 0.2, N_EVENTS, device=device)[torch.randperm(N_EVENTS, generator=gen, device=device)]
             t = (w[:, None] * cent).sum(0)
-            self.text.append((t / t.norm()).to(bf))
+            self.text_b[b] = (t / t.norm()).to(bf)
             del f
+        self.feats = [self.feats_b[b] for b in range(batch)]
+        self.text = [self.text_b[b] for b in range(batch)]
         # ---- preallocated outputs and workspaces (nothing is allocated inside a step)
-        # Videos are independent until stage 3, so their stage-1/2 calls are spread over a few streams: the
-        # one-workgroup planning and selection kernels of one video then overlap with the streaming kernels
-        # of another.  One workspace per stream (calls on a stream are ordered, so they can share it).
         self.n_streams = max(1, min(n_streams, batch))
-        self.graph = None
+        self.mode, self.kv_overlap, self.graphs, self.step_no = "batched", False, [], 0
         self.streams = [torch.cuda.Stream(device=device) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        self.ws1_b = torch.empty(lib.metok_segment_compress_batched_workspace_bytes(batch, FRAMES, GRID, GRID, D_VIS, binding.BF16),
+                                 dtype=torch.uint8, device=device)
+        self.ws2_b = torch.empty(lib.metok_prefill_prune_batched_workspace_bytes(batch, S0, HQ, HKV, DH, TQ, N_VIS, binding.BF16),
+                                 dtype=torch.uint8, device=device)
+        # the per-video calls (one workspace per stream: calls on a stream are ordered, so they can share it)
         self.ws1 = [torch.empty(lib.metok_segment_compress_workspace_bytes(FRAMES, GRID, GRID, D_VIS, binding.BF16),
                                 dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
         self.ws2 = [torch.empty(lib.metok_prefill_prune_workspace_bytes(S0, HQ, HKV, DH, TQ, N_VIS, binding.BF16),
                                 dtype=torch.uint8, device=device) for _ in range(self.n_streams)]
 
-        def stage1_outputs():
-            return dict(sim=torch.empty(FRAMES - 1, dtype=f32, device=device),
-                        event_start=torch.empty(N_EVENTS + 1, dtype=i32, device=device),
-                        frame_event=torch.empty(FRAMES, dtype=i32, device=device),
-                        frame_score=torch.empty(FRAMES, dtype=f32, device=device),
-                        out_tokens=torch.empty((N_VIS, D_VIS), dtype=bf, device=device),
-                        frame_offsets=torch.empty(FRAMES + 1, dtype=i32, device=device),
-                        token_event=torch.empty(N_VIS, dtype=i32, device=device),
-                        event_is_key=torch.empty(N_EVENTS, dtype=u8, device=device),
-                        frame_is_key=torch.empty(FRAMES, dtype=u8, device=device),
-                        frame_stride=torch.empty(FRAMES, dtype=i32, device=device),
-                        event_score=torch.empty(N_EVENTS, dtype=f32, device=device))
-        self.s1_out = [stage1_outputs() for _ in range(batch)]
-        self.s1_adaptive_out = stage1_outputs()          # the two-pass adaptive setting is measured on one video at a time
+        def stage1_outputs(lead):
+            return dict(sim=torch.empty(lead + (FRAMES - 1,), dtype=f32, device=device),
+                        event_start=torch.empty(lead + (N_EVENTS + 1,), dtype=i32, device=device),
+                        frame_event=torch.empty(lead + (FRAMES,), dtype=i32, device=device),
+                        frame_score=torch.empty(lead + (FRAMES,), dtype=f32, device=device),
+                        out_tokens=torch.empty(lead + (N_VIS, D_VIS), dtype=bf, device=device),
+                        frame_offsets=torch.empty(lead + (FRAMES + 1,), dtype=i32, device=device),
+                        token_event=torch.empty(lead + (N_VIS,), dtype=i32, device=device),
+                        event_is_key=torch.empty(lead + (N_EVENTS,), dtype=u8, device=device),
+                        frame_is_key=torch.empty(lead + (FRAMES,), dtype=u8, device=device),
+                        frame_stride=torch.empty(lead + (FRAMES,), dtype=i32, device=device),
+                        event_score=torch.empty(lead + (N_EVENTS,), dtype=f32, device=device))
+        self.s1_out_b = stage1_outputs((batch,))
+        self.s1_out = [{k: v[b] for k, v in self.s1_out_b.items()} for b in range(batch)]
+        self.s1_adaptive_out = stage1_outputs(())        # the two-pass adaptive setting is measured on one video at a time
 
-        # ---- stage 3: KV cache and per-level index lists [B, kept + text]; the text part is fixed
+        # ---- stage 3: KV cache and per-level index lists [B, kept + text]; the text part is fixed.  Two sets of lists:
+        # the KV compaction of one step reads one set while the next step's pruning already fills the other.
         self.k_layers = [torch.empty((batch, HKV, S0, DH), dtype=bf, device=device).normal_(generator=gen)
                          for _ in range(N_LAYERS)]
         self.v_layers = [torch.empty((batch, HKV, S0, DH), dtype=bf, device=device).normal_(generator=gen)
                          for _ in range(N_LAYERS)]
         text_rows = torch.arange(N_VIS, S0, dtype=torch.int32, device=device)
-        self.idx_level = []
-        for c in counts:
-            t = torch.empty((batch, c + N_TEXT), dtype=torch.int32, device=device)
-            t[:, c:] = text_rows
-            t[:, :c] = torch.arange(c, dtype=torch.int32, device=device)      # overwritten by stage 2
-            self.idx_level.append(t)
-        self.idx_layers = []
-        for l in range(N_LAYERS):
-            level = sum(1 for b in L_H if l >= b)
-            self.idx_layers.append(None if level == 0 else self.idx_level[level - 1])
+        self.idx_level_sets, self.idx_layers_sets = [], []
+        for _ in range(2):
+            levels = []
+            for c in counts:
+                t = torch.empty((batch, c + N_TEXT), dtype=torch.int32, device=device)
+                t[:, c:] = text_rows
+                t[:, :c] = torch.arange(c, dtype=torch.int32, device=device)      # overwritten by stage 2
+                levels.append(t)
+            self.idx_level_sets.append(levels)
+            self.idx_layers_sets.append([None if sum(1 for b in L_H if l >= b) == 0 else levels[sum(1 for b in L_H if l >= b) - 1]
+                                         for l in range(N_LAYERS)])
+        self.idx_level, self.idx_layers = self.idx_level_sets[0], self.idx_layers_sets[0]
         self.new_len = torch.empty(N_LAYERS, dtype=torch.int32, device=device)
         self.kv_ws = torch.empty(binding.metok_kv_compact_workspace_bytes(N_LAYERS, batch, HKV, S0, DH, binding.BF16),
                                  dtype=torch.uint8, device=device)
@@ -175,15 +188,25 @@ class Workload:
         # event share a mean shift, the text queries lean towards one target event, hidden rows carry a per-event
         # shift.  The keys of level 2 and 3 belong to the survivors of the level before, so the levels are run
         # once here, in order, to learn which tokens those are (the timed steps repeat exactly these selections).
-        self.seg0 = torch.zeros(N_VIS, dtype=torch.int32, device=device)
-        self.hidden_out = [[torch.empty((c + N_TEXT, D_HID), dtype=bf, device=device) for c in counts] for _ in range(batch)]
-        self.prune_out = [[dict(scores=torch.empty(n, dtype=f32, device=device),
-                                kept_idx=torch.empty(c, dtype=i32, device=device),
-                                token_seg_out=torch.empty(c, dtype=i32, device=device),
-                                token_event_out=torch.empty(c, dtype=i32, device=device),
-                                orig_idx_out=self.idx_level[lv][b, :c])
-                           for lv, (n, c) in enumerate(zip(self.n_in, counts))] for b in range(batch)]
-        self.hidden0, self.K, self.Q, self.weight = [], [], [], []
+        self.seg0_b = torch.zeros((batch, N_VIS), dtype=torch.int32, device=device)
+        self.seg0 = self.seg0_b[0]
+        self.hidden_out_b = [torch.empty((batch, c + N_TEXT, D_HID), dtype=bf, device=device) for c in counts]
+        self.hidden_out = [[self.hidden_out_b[lv][b] for lv in range(len(counts))] for b in range(batch)]
+        shared = [dict(scores=torch.empty((batch, n), dtype=f32, device=device),
+                       kept_idx=torch.empty((batch, c), dtype=i32, device=device),
+                       token_seg_out=torch.empty((batch, c), dtype=i32, device=device),
+                       token_event_out=torch.empty((batch, c), dtype=i32, device=device))
+                  for n, c in zip(self.n_in, counts)]
+        # orig_idx_out of a level is the leading block of that level's KV index lists (its own stride: kept + text)
+        self.prune_out_b_sets = [[dict(shared[lv], orig_idx_out=self.idx_level_sets[p][lv]) for lv in range(len(counts))]
+                                 for p in range(2)]
+        self.prune_out = [[dict({k: v[b] for k, v in shared[lv].items()}, orig_idx_out=self.idx_level[lv][b, :c])
+                           for lv, c in enumerate(counts)] for b in range(batch)]
+        self.hidden0_b = torch.empty((batch, S0, D_HID), dtype=bf, device=device)
+        self.weight_b = torch.rand((batch, N_EVENTS), generator=gen, device=device) + 0.5
+        self.Q_b = [torch.empty((batch, HQ, TQ, DH), dtype=bf, device=device) for _ in self.n_in]
+        self.K_b = [torch.empty((batch, HKV, n + N_TEXT, DH), dtype=bf, device=device) for n in self.n_in]
+        mus = []
         for b in range(batch):
             mu = torch.randn((N_EVENTS, DH), generator=gen, device=device)
             target = int(torch.randint(0, N_EVENTS, (1,), generator=gen, device=device))
@@ -191,19 +214,24 @@ class Workload:
             tev = planted_events[b].repeat_interleave(TOK_PER_FRAME)            # event of every pooled token
             h = torch.randn((S0, D_HID), generator=gen, device=device, dtype=torch.float32)
             h[:N_VIS] += shift[tev][:, None]
-            self.hidden0.append(h.to(bf))
+            self.hidden0_b[b] = h.to(bf)
             del h
-            self.weight.append(torch.rand(N_EVENTS, generator=gen, device=device) + 0.5)
-            self.K.append([])
-            self.Q.append([(torch.randn((HQ, TQ, DH), generator=gen, device=device) + 0.5 * mu[target]).to(bf) for _ in self.n_in])
-            tev = tev.to(torch.int32)
-            for lv, n in enumerate(self.n_in):
+            for lv in range(len(self.n_in)):
+                self.Q_b[lv][b] = (torch.randn((HQ, TQ, DH), generator=gen, device=device) + 0.5 * mu[target]).to(bf)
+            mus.append(mu)
+        self.hidden0 = [self.hidden0_b[b] for b in range(batch)]
+        self.weight = [self.weight_b[b] for b in range(batch)]
+        self.Q = [[self.Q_b[lv][b] for lv in range(len(self.n_in))] for b in range(batch)]
+        self.K = [[self.K_b[lv][b] for lv in range(len(self.n_in))] for b in range(batch)]
+        tev_b = torch.stack([planted_events[b].repeat_interleave(TOK_PER_FRAME) for b in range(batch)]).to(torch.int32)
+        for lv, n in enumerate(self.n_in):
+            for b in range(batch):
                 k = torch.randn((HKV, n + N_TEXT, DH), generator=gen, device=device)
-                k[:, :n] += 0.5 * mu[tev.long()][None]
-                self.K[b].append(k.to(bf))
+                k[:, :n] += 0.5 * mus[b][tev_b[b].long()][None]
+                self.K_b[lv][b] = k.to(bf)
                 del k
-                if lv + 1 < len(self.n_in):
-                    tev = self.prune_level(b, lv, tev)["token_event_out"].clone()
+            if lv + 1 < len(self.n_in):
+                tev_b = self.prune_level_batched(lv, tev_b, 0)["token_event_out"].clone()
         torch.cuda.synchronize()
 
     # ---- algorithmic bytes / flops (what the method itself must move or compute)
@@ -251,16 +279,38 @@ class Workload:
                                           event_weight=self.weight[b], orig_idx=orig, hidden_out=self.hidden_out[b][lv],
                                           workspace=self.ws2[b % self.n_streams], out=self.prune_out[b][lv])
 
+    def stage1_batched(self):
+        return self.B.metok_segment_compress_batched(self.feats_b, GRID, GRID, N_EVENTS, self.text_b, 1.0, 1.0, 2, 2,
+                                                     workspace=self.ws1_b, out=self.s1_out_b)
+
+    def prune_level_batched(self, lv, token_event, p):
+        """Level lv of the whole batch in one call; p selects the set of KV index lists that receives the retained indices."""
+        n, c = self.n_in[lv], self.counts[lv]
+        prev = self.prune_out_b_sets[p][lv - 1] if lv > 0 else None
+        h = self.hidden0_b if lv == 0 else self.hidden_out_b[lv - 1]
+        tseg = self.seg0_b if lv == 0 else prev["token_seg_out"]
+        orig = None if lv == 0 else prev["orig_idx_out"]
+        return self.B.metok_prefill_prune_batched(h, 0, n, tseg, [[c]] * self.batch, q_text=self.Q_b[lv], k_all=self.K_b[lv],
+                                                  token_event=token_event, event_weight=self.weight_b, orig_idx=orig,
+                                                  hidden_out=self.hidden_out_b[lv], workspace=self.ws2_b,
+                                                  out=self.prune_out_b_sets[p][lv])
+
+    def stage2_batched(self, token_event, p=0):
+        tev = token_event
+        for lv in range(len(self.n_in)):
+            tev = self.prune_level_batched(lv, tev, p)["token_event_out"]
+
     def stage2(self, b, token_event):
         tev = token_event
         for lv in range(len(self.n_in)):
             tev = self.prune_level(b, lv, tev)["token_event_out"]
 
-    def stage3(self):
-        self.B.metok_kv_compact(self.k_layers, self.v_layers, self.idx_layers, new_len=self.new_len, workspace=self.kv_ws)
+    def stage3(self, p=0):
+        self.B.metok_kv_compact(self.k_layers, self.v_layers, self.idx_layers_sets[p], new_len=self.new_len, workspace=self.kv_ws)
 
-    def stages_1_2(self):
-        """Stage 1 and the three pruning levels of every video, spread over the streams, joined on the current stream."""
+    def stages_1_2_per_video(self):
+        """Stage 1 and the three pruning levels of every video as calls of their own, spread over the streams and joined
+        on the current stream."""
         torch = self.torch
         if self.streams:
             main = torch.cuda.current_stream()
@@ -277,30 +327,66 @@ class Workload:
                 cmp = self.stage1(b)
                 self.stage2(b, cmp["token_event"])
 
-    def capture(self):
-        """Records the stage-1/2 launches of one step (about 270 kernels on 8 streams) into a HIP graph.  The
-        library calls only launch kernels on the stream they are given (no allocation, copy, memset or
-        synchronisation), so they can be captured as they are; the KV compaction stays an ordinary launch so
-        that the library can bracket its kernel with events."""
+    def stages_1_2(self, p=0):
+        """Stage 1 and the three pruning levels of the batch; the retained indices go to set p of the KV index lists."""
+        if self.mode == "per-video":
+            return self.stages_1_2_per_video()
+        cmp = self.stage1_batched()
+        self.stage2_batched(cmp["token_event"], p)
+
+    def configure(self, mode="batched", kv_overlap=False, use_graph=True):
+        """mode: "batched" (one call per stage and level for the whole batch: 28 launches per step) or "per-video" (one
+        call per video, 8 streams: about 230 launches).  kv_overlap: the KV compaction of a step runs on a stream of its
+        own, beside the next step's stages 1-2 (which fill the other set of index lists).  use_graph: the stage-1/2 launches
+        are replayed from a HIP graph.  The library calls only launch kernels on the stream they are given (no allocation,
+        copy, memset or synchronisation), so they can be captured as they are; the KV compaction stays an ordinary launch
+        so that the library can bracket its kernel with events."""
         torch = self.torch
-        self.graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(self.graph, stream=side):
-                self.stages_1_2()
-        torch.cuda.current_stream().wait_stream(side)
+        self.mode = mode
+        self.kv_overlap = bool(kv_overlap) and mode == "batched"
+        self.step_no = 0
+        self.kv_stream = torch.cuda.Stream(device=self.dev) if self.kv_overlap else None
+        self.filled = [torch.cuda.Event() for _ in range(2)]        # stages 1-2 have filled set p
+        self.consumed = [torch.cuda.Event() for _ in range(2)]      # the KV compaction has read set p
+        self.graphs = []
+        if use_graph:
+            for p in range(2 if self.kv_overlap else 1):
+                g = torch.cuda.CUDAGraph()
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(g, stream=side):
+                        self.stages_1_2(p)
+                torch.cuda.current_stream().wait_stream(side)
+                self.graphs.append(g)
 
     def step(self, kv_events=None):
-        if self.graph is not None:
-            self.graph.replay()
+        torch = self.torch
+        p = self.step_no % 2 if self.kv_overlap else 0
+        main = torch.cuda.current_stream()
+        if self.kv_overlap and self.step_no >= 2:
+            main.wait_event(self.consumed[p])                       # the KV pass of two steps ago has finished with set p
+        if self.graphs:
+            self.graphs[p].replay()
         else:
-            self.stages_1_2()
-        if kv_events is not None:
-            self.B.lib().metok_trace_kernel(TRACE["move_rows"], kv_events[0], kv_events[1])
-        self.stage3()
-        if kv_events is not None:
-            self.B.lib().metok_trace_kernel(0, None, None)
+            self.stages_1_2(p)
+
+        def kv():
+            if kv_events is not None:
+                self.B.lib().metok_trace_kernel(TRACE["move_rows"], kv_events[0], kv_events[1])
+            self.stage3(p)
+            if kv_events is not None:
+                self.B.lib().metok_trace_kernel(0, None, None)
+
+        if self.kv_overlap:
+            self.filled[p].record(main)
+            with torch.cuda.stream(self.kv_stream):
+                self.kv_stream.wait_event(self.filled[p])
+                kv()
+                self.consumed[p].record(self.kv_stream)
+        else:
+            kv()
+        self.step_no += 1
 
 
 def stats_us(ms_list):
@@ -331,10 +417,16 @@ def time_kernels(w: Workload, hev: HipEvents, reps: int):
 
     out = {}
     videos = list(range(w.batch))
+    # in the batched mode one launch covers the whole batch: bytes and flops per launch scale with it
+    batched = w.mode == "batched"
+    nb = w.batch if batched else 1
+    units = [None] * w.batch if batched else videos
     # stage 1, one pass (uniform stride 2)
-    ms = [traced("frame_stats_pool2", lambda v=v: w.stage1(v))[0] for _ in range(reps) for v in videos]
-    e = hbm_entry(ms, w.stage1_fused_bytes(), "frame_stats_pool2_kernel")
-    e["workload"] = "[256, 576, 1024] bf16, every frame pooled 2 x 2: statistics and pooled tokens from one read"
+    s1 = (lambda v: w.stage1_batched()) if batched else w.stage1
+    ms = [traced("frame_stats_pool2", lambda v=v: s1(v))[0] for _ in range(reps) for v in units]
+    e = hbm_entry(ms, nb * w.stage1_fused_bytes(), "frame_stats_pool2_kernel")
+    e["videos_per_launch"] = nb
+    e["workload"] = "[256, 576, 1024] bf16 per video, every frame pooled 2 x 2: statistics and pooled tokens from one read"
     out["stage1_one_pass"] = e
     # stage 1, the paper's adaptive strides: statistics pass, then pooling pass
     ms_stats, ms_pool, rows = [], [], []
@@ -356,19 +448,24 @@ def time_kernels(w: Workload, hev: HipEvents, reps: int):
     # stage 2 per level
     toks = [w.s1_out[v]["token_event"] for v in videos]
     for lv in range(len(w.n_in)):
-        tev = [toks[v] if lv == 0 else w.prune_out[v][lv - 1]["token_event_out"] for v in videos]
-        entry = dict(visual_tokens_in=w.n_in[lv], kept=w.counts[lv])
+        if batched:
+            tev_b = w.s1_out_b["token_event"] if lv == 0 else w.prune_out_b_sets[0][lv - 1]["token_event_out"]
+            level = lambda v, lv=lv, tev_b=tev_b: w.prune_level_batched(lv, tev_b, 0)
+        else:
+            tev = [toks[v] if lv == 0 else w.prune_out[v][lv - 1]["token_event_out"] for v in videos]
+            level = lambda v, lv=lv, tev=tev: w.prune_level(v, lv, tev[v])
+        entry = dict(visual_tokens_in=w.n_in[lv], kept=w.counts[lv], videos_per_launch=nb)
         for kernel in ("row_stats", "col_sums"):
-            ms = [traced(kernel, lambda v=v: w.prune_level(v, lv, tev[v]))[0] for _ in range(reps) for v in videos]
-            k = dict(kernel=kernel + "_kernel", **stats_us(ms), flops=w.score_flops(lv))
+            ms = [traced(kernel, lambda v=v: level(v))[0] for _ in range(reps) for v in units]
+            k = dict(kernel=kernel + "_kernel", **stats_us(ms), flops=nb * w.score_flops(lv))
             k["TFLOPs"] = round(k["flops"] / (k["us_median"] * 1e-6) / 1e12, 1)
             k["frac_of_bf16_mfma_peak"] = round(k["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
             entry[kernel] = k
         for kernel in ("select", "write_index"):
-            ms = [traced(kernel, lambda v=v: w.prune_level(v, lv, tev[v]))[0] for _ in range(reps) for v in videos]
-            entry[kernel] = dict(kernel=kernel + "_kernel", **stats_us(ms))
-        ms = [traced("gather_rows", lambda v=v: w.prune_level(v, lv, tev[v]))[0] for _ in range(reps) for v in videos]
-        entry["gather_rows"] = hbm_entry(ms, w.gather_bytes(lv), "gather_rows_kernel")
+            ms = [traced(kernel, lambda v=v: level(v))[0] for _ in range(reps) for v in units]
+            entry[kernel] = dict(kernel=("score_hist_kernel + candidate_kernel" if kernel == "select" else kernel + "_kernel"), **stats_us(ms))
+        ms = [traced("gather_rows", lambda v=v: level(v))[0] for _ in range(reps) for v in units]
+        entry["gather_rows"] = hbm_entry(ms, nb * w.gather_bytes(lv), "gather_rows_kernel")
         out[f"stage2_level{lv + 1}"] = entry
     torch.cuda.synchronize()
     return out
@@ -381,10 +478,15 @@ def time_stages(w: Workload, reps: int):
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
     for r in range(reps):
         ev[r][0].record()
-        toks = [w.stage1(b)["token_event"] for b in range(w.batch)]
-        ev[r][1].record()
-        for b in range(w.batch):
-            w.stage2(b, toks[b])
+        if w.mode == "batched":
+            tok_b = w.stage1_batched()["token_event"]
+            ev[r][1].record()
+            w.stage2_batched(tok_b, 0)
+        else:
+            toks = [w.stage1(b)["token_event"] for b in range(w.batch)]
+            ev[r][1].record()
+            for b in range(w.batch):
+                w.stage2(b, toks[b])
         ev[r][2].record()
         w.stage3()
         ev[r][3].record()
@@ -435,6 +537,9 @@ def time_configs(w: Workload, reps: int):
     e = timed(lambda: w.stage2(0, w.s1_out[0]["token_event"]))
     e["tokens_in_per_s"] = round(N_VIS / (e["ms_median"] * 1e-3), 1)
     out["hierarchical_36864_three_levels"] = e
+    e = timed(lambda: w.stage2_batched(w.s1_out_b["token_event"], 0))
+    e["tokens_in_per_s"] = round(w.batch * N_VIS / (e["ms_median"] * 1e-3), 1)
+    out["hierarchical_36864_three_levels_batch8_one_call_per_level"] = e
     # decoding configuration: the batch's KV cache
     e = timed(w.stage3)
     e["tokens_in_per_s"] = round(w.batch * N_VIS / (e["ms_median"] * 1e-3), 1)
@@ -509,7 +614,7 @@ def cpu_baseline(n_videos: int):
                 t_stage[i] += t
     total = sum(t_stage)
     return dict(value=n_videos * FRAMES * GRID * GRID / total, unit="tokens/s", cores=1, kind="oracle",
-                sample=f"{n_videos} whole videos (one step has 8): stage 1 on 256 frames, three pruning levels, KV compaction of "
+                sample=f"{n_videos} whole videos (one step has 8; every video has its own seed): stage 1 on 256 frames, three pruning levels, KV compaction of "
                        "25 layers x 4 heads x (K, V); oracle calls only, one thread",
                 seconds_by_stage=[round(t, 3) for t in t_stage], seconds=round(total, 3))
 
@@ -558,8 +663,12 @@ def main():
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--streams", type=int, default=8, help="streams that share the per-video stage-1/2 work")
     ap.add_argument("--no-graph", action="store_true", help="launch the stage-1/2 kernels one by one instead of replaying a HIP graph")
+    ap.add_argument("--per-video", action="store_true", help="one library call per video and stage on 8 streams instead of the batched calls")
+    ap.add_argument("--kv-overlap", action="store_true",
+                    help="run the KV compaction of a step on a stream of its own, beside the next step's stages 1-2 (higher whole-job rate, "
+                         "but the two HBM-bound parts then share the memory system and the KV kernel's own duration grows by half)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-videos", type=int, default=4, help="videos of the single-thread oracle leg (the all-cores leg takes 8)")
+    ap.add_argument("--cpu-videos", type=int, default=12, help="videos of the single-thread oracle leg (the all-cores leg takes 8)")
     ap.add_argument("--kernel-reps", type=int, default=3, help="repetitions (x 8 videos) of the per-kernel measurements")
     ap.add_argument("--only", choices=["all", "kv", "copy", "prune", "stage1", "stage1_adaptive"], default="all",
                     help="run only one part (for profiler runs): the KV compaction, the calibration copy, the stage-2 calls, "
@@ -603,16 +712,24 @@ def main():
         print(json.dumps({"kv_bytes_per_launch": w.kv_bytes()}))
         return
     if args.only == "prune":
-        toks = [w.stage1(b)["token_event"] for b in range(args.batch)]
-        for _ in range(args.warmup + args.steps):
-            for b in range(args.batch):
-                w.stage2(b, toks[b])
+        if args.per_video:
+            toks = [w.stage1(b)["token_event"] for b in range(args.batch)]
+            for _ in range(args.warmup + args.steps):
+                for b in range(args.batch):
+                    w.stage2(b, toks[b])
+        else:
+            tok_b = w.stage1_batched()["token_event"]
+            for _ in range(args.warmup + args.steps):
+                w.stage2_batched(tok_b, 0)
         torch.cuda.synchronize()
         print(json.dumps({"score_flops_per_step": sum(2 * w.score_flops(lv) for lv in range(3)) * args.batch}))
         return
     if args.only in ("stage1", "stage1_adaptive"):
         call = w.stage1 if args.only == "stage1" else w.stage1_adaptive
         for _ in range(args.warmup + args.steps):
+            if args.only == "stage1" and not args.per_video:
+                w.stage1_batched()
+                continue
             for b in range(args.batch):
                 call(b)
         torch.cuda.synchronize()
@@ -620,10 +737,10 @@ def main():
         return
 
     hev = HipEvents()
+    w.mode = "per-video" if args.per_video else "batched"
     w.step()                                             # eager once: loads code objects before any capture
     torch.cuda.synchronize()
-    if not args.no_graph:
-        w.capture()
+    w.configure(w.mode, kv_overlap=args.kv_overlap, use_graph=not args.no_graph)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -639,6 +756,7 @@ def main():
 
     kv_all = [hev.elapsed_ms(a, b) for a, b in kv_ev]
     kv_ms = float(np.mean(kv_all))
+    # step boundaries on the main stream; with the KV compaction on its own stream a step's KV pass ends inside the next step
     step_ms = [step_ev[s].elapsed_time(step_ev[s + 1]) for s in range(args.steps)]
     err_word = int(w.kv_ws[:4].view(torch.int32)[0])
     if err_word != 0:
@@ -666,7 +784,10 @@ def main():
                    "tokens_per_frame_pooled": TOK_PER_FRAME, "prune_levels": level_counts(), "text_tokens": N_TEXT,
                    "text_queries": TQ, "kv_layers": N_LAYERS, "L_H": list(L_H), "streams": w.n_streams,
                    "stage2_inputs": "keys 0.5 mu_event + N(0,1), queries N(0,1) + 0.5 mu_target, hidden N(0,1) + event shift",
-                   "launch": "eager" if w.graph is None else "stages 1-2 replayed from one HIP graph, KV compaction launched directly"},
+                   "calls": "one call per stage and level for the whole batch" if w.mode == "batched" else "one call per video, stage and level",
+                   "launch": ("eager" if not w.graphs else "stages 1-2 replayed from a HIP graph, KV compaction launched directly")
+                             + ("; the KV compaction of a step runs on its own stream beside the next step's stages 1-2 (two sets of index lists)"
+                                if w.kv_overlap else "; one stream")},
         "value_in_pooled_tokens_per_s": args.batch * N_VIS / (elapsed / args.steps),
         "roofline": {"kernel": "move_rows_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_file,

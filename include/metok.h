@@ -322,11 +322,14 @@ METOK_API int metok_prefill_prune(const void* hidden, int64_t S, int D, int dtyp
  * may differ in the last bits, because a video's keys are split over fewer workgroups and the partial sums are added
  * in another order.
  *   Inputs carry a leading batch dimension and are tightly packed: hidden [batch, S, D], q_text [batch, Hq, Tq, dh],
- *   k_all [batch, Hkv, S, dh], token_seg / token_event / orig_idx_in / scores [batch, n_vis], event_weight
- *   [batch, n_events]; seg_quota is host [batch, n_seg] (the kept count may differ between videos).
- *   Outputs: kept_idx, token_seg_out, token_event_out, orig_idx_out are [batch, keep_stride] (keep_stride >= the largest
- *   video's sum of quotas; entries past a video's own count are not written); hidden_out is [batch, out_row_stride, D]
- *   (out_row_stride >= S - n_vis + that largest count; rows past a video's own count are not written).
+ *   k_all [batch, Hkv, S, dh], token_seg / token_event / scores [batch, n_vis], event_weight [batch, n_events];
+ *   orig_idx_in is [batch, orig_idx_in_stride] (>= n_vis; its own stride, like orig_idx_out below);
+ *   seg_quota is host [batch, n_seg] (the kept count may differ between videos).
+ *   Outputs: kept_idx, token_seg_out, token_event_out are [batch, keep_stride] (keep_stride >= the largest video's sum
+ *   of quotas; entries past a video's own count are not written); orig_idx_out is [batch, orig_idx_stride] with the
+ *   same rule (its own stride, so that it can be the leading columns of stage 3's index lists [batch, kept + text]);
+ *   hidden_out is [batch, out_row_stride, D] (out_row_stride >= S - n_vis + that largest count; rows past a video's own
+ *   count are not written).
  *   hidden_out == hidden compacts every video in place (out_row_stride must be S).
  *   workspace: metok_prefill_prune_batched_workspace_bytes(batch, ...) bytes.
  */
@@ -338,10 +341,11 @@ METOK_API int metok_prefill_prune_batched(int batch, const void* hidden, int64_t
                         const int32_t* token_seg, const int32_t* token_event,
                         const float* event_weight, int n_events,
                         int n_seg, const int32_t* seg_quota,
-                        const int32_t* orig_idx_in,
+                        const int32_t* orig_idx_in, int64_t orig_idx_in_stride,
                         float* scores, int32_t* kept_idx, int64_t keep_stride,
                         void* hidden_out, int64_t out_row_stride,
-                        int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                        int32_t* token_seg_out, int32_t* token_event_out,
+                        int32_t* orig_idx_out, int64_t orig_idx_stride,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*

@@ -104,7 +104,7 @@ def _load() -> ctypes.CDLL:
     lib.metok_prefill_prune_batched_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, i32, i32, i32]
     lib.metok_prefill_prune_batched.restype = i32
     lib.metok_prefill_prune_batched.argtypes = [i32, vp, i64, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32,
-                                                i32, c.POINTER(c.c_int32), vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, sz, vp]
+                                                i32, c.POINTER(c.c_int32), vp, i64, vp, vp, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp]
     lib.metok_kv_compact.restype = i32
     lib.metok_kv_compact_workspace_bytes.restype = sz
     lib.metok_kv_compact_workspace_bytes.argtypes = [i32, i32, i32, i64, i32, i32]
@@ -492,8 +492,10 @@ def metok_prefill_prune_batched(hidden: torch.Tensor, vis_start: int, n_vis: int
         if scores is None:
             raise ValueError("either q_text/k_all or scores must be given")
         Hq = Hkv = dh = Tq = 0
+    if orig_idx is not None and (orig_idx.dim() != 2 or orig_idx.shape[0] != B or orig_idx.shape[1] < n_vis):
+        raise ValueError("orig_idx must be int32 [B, stride >= n_vis]")
     for name, t, shape in (("token_seg", token_seg, (B, n_vis)), ("token_event", token_event, (B, n_vis)),
-                           ("orig_idx", orig_idx, (B, n_vis)), ("scores", scores, (B, n_vis))):
+                           ("scores", scores, (B, n_vis))):
         if t is not None and tuple(t.shape) != shape:
             raise ValueError(f"{name} must have the shape {shape}")
     need = _lib.metok_prefill_prune_batched_workspace_bytes(B, S, Hq, Hkv, dh, Tq, n_vis, dt)
@@ -511,7 +513,12 @@ def metok_prefill_prune_batched(hidden: torch.Tensor, vis_start: int, n_vis: int
         raise ValueError(f"hidden_out must be {hidden.dtype} of shape {(B, out_row_stride, D)}")
     token_seg_out = _out(out, "token_seg_out", (B, keep_stride), torch.int32, dev)
     token_event_out = _out(out, "token_event_out", (B, keep_stride), torch.int32, dev) if token_event is not None else None
-    orig_idx_out = _out(out, "orig_idx_out", (B, keep_stride), torch.int32, dev)
+    # orig_idx_out may be wider than the other lists (the leading columns of stage 3's [B, kept + text] index lists)
+    orig_idx_out = out.get("orig_idx_out") if out is not None else None
+    if orig_idx_out is None:
+        orig_idx_out = torch.empty((B, keep_stride), dtype=torch.int32, device=dev)
+    elif orig_idx_out.dtype != torch.int32 or orig_idx_out.dim() != 2 or orig_idx_out.shape[0] != B:
+        raise ValueError("out['orig_idx_out'] must be int32 [B, stride]")
     n_events = int(event_weight.shape[1]) if event_weight is not None else 0
     if event_weight is not None and event_weight.shape[0] != B:
         raise ValueError("event_weight must be [B, n_events]")
@@ -519,9 +526,10 @@ def metok_prefill_prune_batched(hidden: torch.Tensor, vis_start: int, n_vis: int
         B, _dev(hidden, "hidden"), S, D, dt, _dev(q_text, "q_text"), _dev(k_all, "k_all"), Hq, Hkv, dh, Tq,
         int(score_mode), int(vis_start), int(n_vis), _dev(token_seg, "token_seg"), _dev(token_event, "token_event"),
         _dev(event_weight, "event_weight"), n_events, n_seg, quota_arr, _dev(orig_idx, "orig_idx"),
+        orig_idx.shape[1] if orig_idx is not None else 0,
         _dev(scores, "scores"), _dev(kept_idx, "kept_idx"), keep_stride, _dev(hidden_out, "hidden_out"), out_row_stride,
         _dev(token_seg_out, "token_seg_out"), _dev(token_event_out, "token_event_out"),
-        _dev(orig_idx_out, "orig_idx_out"), _dev(ws, "workspace"), ws.numel(), _stream()))
+        _dev(orig_idx_out, "orig_idx_out"), orig_idx_out.shape[1], _dev(ws, "workspace"), ws.numel(), _stream()))
     res = dict(scores=scores, kept_idx=kept_idx, hidden_out=hidden_out, token_seg_out=token_seg_out,
                orig_idx_out=orig_idx_out, n_keep=n_keep)
     if token_event_out is not None:

@@ -706,7 +706,7 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
     const int32_t* __restrict__ orig_idx_in, int32_t* __restrict__ kept_idx, int32_t* __restrict__ token_seg_out,
     int32_t* __restrict__ token_event_out, int32_t* __restrict__ orig_idx_out,
     const int32_t* __restrict__ given_tile_off, const int32_t* __restrict__ given_eq_before /*[class][kSelCache]*/,
-    int64_t ws_video, int64_t keep_stride, const BatchKeep keeps) {
+    int64_t ws_video, int64_t keep_stride, int64_t orig_idx_in_stride, int64_t orig_idx_stride, const BatchKeep keeps) {
     __shared__ int scan_scratch[17];
     __shared__ uint32_t s_tau[METOK_MAX_SEGMENTS];
     __shared__ int s_rem[METOK_MAX_SEGMENTS], s_eq_before[METOK_MAX_SEGMENTS];
@@ -714,11 +714,11 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
     const int tile = blockIdx.x, tid = threadIdx.x;
     total_keep = keeps.n[blockIdx.z];
     scores = of_video_elems(scores, n_vis); token_seg = of_video_elems(token_seg, n_vis);
-    token_event = of_video_elems(token_event, n_vis); orig_idx_in = of_video_elems(orig_idx_in, n_vis);
+    token_event = of_video_elems(token_event, n_vis); orig_idx_in = of_video_elems(orig_idx_in, orig_idx_in_stride);
     sel_info = of_video(sel_info, ws_video); gt_count = of_video(gt_count, ws_video); eq_count = of_video(eq_count, ws_video);
     given_tile_off = of_video(given_tile_off, ws_video); given_eq_before = of_video(given_eq_before, ws_video);
     kept_idx = of_video_elems(kept_idx, keep_stride); token_seg_out = of_video_elems(token_seg_out, keep_stride);
-    token_event_out = of_video_elems(token_event_out, keep_stride); orig_idx_out = of_video_elems(orig_idx_out, keep_stride);
+    token_event_out = of_video_elems(token_event_out, keep_stride); orig_idx_out = of_video_elems(orig_idx_out, orig_idx_stride);
     // kept tokens in earlier tiles: given by the fast path, else thread s walks the tiles of class s
     int before = 0;
     if (given_tile_off != nullptr) {
@@ -854,12 +854,30 @@ struct FastArgs {
     int64_t ws_video;                       // bytes between the workspaces of consecutive videos
     int32_t quota[METOK_MAX_BATCH][kFastSeg];
 };
-// The arguments as video blockIdx.z sees them.
-__device__ __forceinline__ void to_video(FastArgs& a) {
-    a.fs = of_video(a.fs, a.ws_video); a.cand_key = of_video(a.cand_key, a.ws_video); a.cand_tok = of_video(a.cand_tok, a.ws_video);
-    a.colpart = of_video(a.colpart, a.ws_video);
-    a.token_event = of_video_elems(a.token_event, a.n_vis); a.event_weight = of_video_elems(a.event_weight, a.n_events);
-    a.scores = of_video_elems(a.scores, a.n_vis); a.token_seg = of_video_elems(a.token_seg, a.n_vis);
+// The arguments as video blockIdx.z sees them: its pointers and the scalars; the quota table stays in the kernel
+// arguments (a private copy of it would live in scratch memory).
+struct FastView {
+    FastSel* fs;
+    uint32_t* cand_key;
+    uint32_t* cand_tok;
+    const float* colpart;
+    int n_parts;
+    float rows_total;
+    const int32_t* token_event;
+    const float* event_weight;
+    int n_events;
+    float* scores;
+    const int32_t* token_seg;
+    int n_vis, n_seg;
+};
+__device__ __forceinline__ FastView to_video(const FastArgs& a) {
+    FastView v;
+    v.fs = of_video(a.fs, a.ws_video); v.cand_key = of_video(a.cand_key, a.ws_video); v.cand_tok = of_video(a.cand_tok, a.ws_video);
+    v.colpart = of_video(a.colpart, a.ws_video);
+    v.n_parts = a.n_parts; v.rows_total = a.rows_total; v.n_events = a.n_events; v.n_vis = a.n_vis; v.n_seg = a.n_seg;
+    v.token_event = of_video_elems(a.token_event, a.n_vis); v.event_weight = of_video_elems(a.event_weight, a.n_events);
+    v.scores = of_video_elems(a.scores, a.n_vis); v.token_seg = of_video_elems(a.token_seg, a.n_vis);
+    return v;
 }
 
 // Values handed from one workgroup to another inside a kernel travel through device-scope accesses (they pass the
@@ -938,8 +956,7 @@ __device__ __forceinline__ int wave_hist_total(const int* hist, int bins) {
 __global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs args) {
     __shared__ int hist[kFastSeg * 2048];
     __shared__ int s_last;
-    FastArgs a = args;
-    to_video(a);
+    const FastView a = to_video(args);
     const int tid = threadIdx.x;
     const int j = blockIdx.x * kSelThreads + tid;
     for (int i = tid; i < a.n_seg * 2048; i += kSelThreads) hist[i] = 0;
@@ -978,7 +995,7 @@ __global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs 
     __syncthreads();
     if (tid >= 64) return;
     for (int c = 0; c < a.n_seg; ++c) {
-        const int quota = a.quota[blockIdx.z][c];
+        const int quota = args.quota[blockIdx.z][c];
         const int pop = wave_hist_total(hist + c * 2048, 2048);
         int digit = 0, rem = 0, cnt = 0;
         const int mode = quota <= 0 ? kModeNone : (quota >= pop ? kModeAll : kModeSearch);
@@ -996,8 +1013,7 @@ __global__ __launch_bounds__(kSelThreads) void candidate_kernel(const FastArgs a
     __shared__ int t_gt[kFastSeg][kFastTiles], t_eq[kFastSeg][kFastTiles];
     const int tid = threadIdx.x, lane = tid & 63;
     const int j = blockIdx.x * kSelThreads + tid;
-    FastArgs a = args;
-    to_video(a);
+    const FastView a = to_video(args);
     if (tid < kFastSeg) s_sure[tid] = 0;
     int sg = -1;
     uint32_t key = 0u;
@@ -1333,9 +1349,9 @@ static int prune_impl(int batch, const void* hidden, int64_t S, int D, int dtype
                       const int32_t* token_seg, const int32_t* token_event,
                       const float* event_weight, int n_events,
                       int n_seg, const int32_t* seg_quota,
-                      const int32_t* orig_idx_in,
+                      const int32_t* orig_idx_in, int64_t orig_idx_in_stride,
                       float* scores, int32_t* kept_idx, int64_t keep_stride, void* hidden_out, int64_t out_row_stride,
-                      int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                      int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out, int64_t orig_idx_stride,
                       void* workspace, size_t workspace_bytes, void* stream) {
     if (batch < 1 || batch > METOK_MAX_BATCH) return fail(METOK_ERR_INVALID_ARG, "batch must be in [1, %d]", METOK_MAX_BATCH);
     if (dtype != METOK_F32 && dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown dtype %d", dtype);
@@ -1369,7 +1385,11 @@ static int prune_impl(int batch, const void* hidden, int64_t S, int D, int dtype
     if (batch > 1 && (keep_stride < max_keep || out_row_stride < max_out_rows))
         return fail(METOK_ERR_INVALID_ARG, "keep_stride = %lld / out_row_stride = %lld below the largest video's %lld kept tokens / %lld rows",
                     (long long)keep_stride, (long long)out_row_stride, (long long)max_keep, (long long)max_out_rows);
-    if (batch == 1) { keep_stride = max_keep; out_row_stride = max_out_rows; }
+    if (batch > 1 && orig_idx_out && orig_idx_stride < max_keep)
+        return fail(METOK_ERR_INVALID_ARG, "orig_idx_stride = %lld below the largest video's %lld kept tokens", (long long)orig_idx_stride, (long long)max_keep);
+    if (batch > 1 && orig_idx_in && orig_idx_in_stride < n_vis)
+        return fail(METOK_ERR_INVALID_ARG, "orig_idx_in_stride = %lld below n_vis = %d", (long long)orig_idx_in_stride, n_vis);
+    if (batch == 1) { keep_stride = max_keep; out_row_stride = max_out_rows; orig_idx_stride = max_keep; orig_idx_in_stride = n_vis; }
     // hidden_out == hidden compacts in place (every kept row moves towards the front: source >= destination);
     // any other overlap is refused
     const bool in_place = hidden_out == hidden;
@@ -1495,7 +1515,7 @@ static int prune_impl(int batch, const void* hidden, int64_t S, int D, int dtype
     }
     { TraceScope trace_scope(METOK_TRACE_WRITE_INDEX, st); hipLaunchKernelGGL(write_index_kernel, dim3(n_tiles, 1, nb), dim3(kIdxThreads), 0, st, scores, sel_info, gt_count, eq_count, token_seg, n_vis, n_seg,
                        n_tiles, 0, token_event, orig_idx_in, kept_idx, token_seg_out,
-                       token_event_out, orig_idx_out, tile_off, eq_before, ws_video, keep_stride, keeps); }
+                       token_event_out, orig_idx_out, tile_off, eq_before, ws_video, keep_stride, orig_idx_in_stride, orig_idx_stride, keeps); }
     if ((rc = check_launch("write index"))) return rc;
     if (in_place) {
         // the row mover takes one sequence per call here: the videos of a batch go one after the other
@@ -1539,8 +1559,8 @@ extern "C" int metok_prefill_prune(const void* hidden, int64_t S, int D, int dty
                                    void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
     return prune_impl(1, hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
-                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, 0, hidden_out, 0, token_seg_out,
-                      token_event_out, orig_idx_out, workspace, workspace_bytes, stream);
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, 0, scores, kept_idx, 0, hidden_out, 0, token_seg_out,
+                      token_event_out, orig_idx_out, 0, workspace, workspace_bytes, stream);
 }
 
 extern "C" int metok_prefill_prune_batched(int batch, const void* hidden, int64_t S, int D, int dtype,
@@ -1549,15 +1569,16 @@ extern "C" int metok_prefill_prune_batched(int batch, const void* hidden, int64_
                                            const int32_t* token_seg, const int32_t* token_event,
                                            const float* event_weight, int n_events,
                                            int n_seg, const int32_t* seg_quota,
-                                           const int32_t* orig_idx_in,
+                                           const int32_t* orig_idx_in, int64_t orig_idx_in_stride,
                                            float* scores, int32_t* kept_idx, int64_t keep_stride,
                                            void* hidden_out, int64_t out_row_stride,
-                                           int32_t* token_seg_out, int32_t* token_event_out, int32_t* orig_idx_out,
+                                           int32_t* token_seg_out, int32_t* token_event_out,
+                                           int32_t* orig_idx_out, int64_t orig_idx_stride,
                                            void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
     return prune_impl(batch, hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
-                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, keep_stride, hidden_out, out_row_stride,
-                      token_seg_out, token_event_out, orig_idx_out, workspace, workspace_bytes, stream);
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, orig_idx_in_stride, scores, kept_idx, keep_stride, hidden_out, out_row_stride,
+                      token_seg_out, token_event_out, orig_idx_out, orig_idx_stride, workspace, workspace_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1614,6 +1635,6 @@ extern "C" int metok_prefill_prune_static(const void* hidden, int64_t S, int D, 
     int rc = static_scratch(&ws);
     if (rc) return rc;
     return prune_impl(1, hidden, S, D, dtype, q_text, k_all, Hq, Hkv, dh, Tq, score_mode, vis_start, n_vis, token_seg, token_event,
-                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, scores, kept_idx, 0, hidden_out, 0, token_seg_out,
-                      token_event_out, orig_idx_out, ws, METOK_STATIC_SCRATCH_BYTES, stream);
+                      event_weight, n_events, n_seg, seg_quota, orig_idx_in, 0, scores, kept_idx, 0, hidden_out, 0, token_seg_out,
+                      token_event_out, orig_idx_out, 0, ws, METOK_STATIC_SCRATCH_BYTES, stream);
 }

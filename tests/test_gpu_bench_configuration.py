@@ -1,7 +1,8 @@
 """One step of bench.py's workload, launched the way bench.py times it -- 8 LongVA-7B-shaped 256-frame videos,
-stage 1 and the three pruning levels of every video spread over 8 streams and replayed from one HIP graph, then
-one in-place KV compaction of the 28-layer cache -- checked against the CPU oracle: whole outputs where the
-oracle finishes in seconds (stage 1 of a video, the scores of a level), sampled rows for the bulk tensors."""
+stage 1 and the three pruning levels as batched calls (28 launches) replayed from one HIP graph, then one in-place
+KV compaction of the 28-layer cache -- checked against the CPU oracle: whole outputs where the oracle finishes in
+seconds (stage 1 of a video, the scores of a level), sampled rows for the bulk tensors.  The same for bench.py's
+--per-video launch (one call per video on 8 streams, one graph) and for the KV pass on its own stream."""
 import numpy as np
 import pytest
 import torch
@@ -16,9 +17,11 @@ def f64(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
-def test_one_bench_step_matches_the_oracle():
+@pytest.mark.parametrize("mode,kv_overlap", [("batched", False), ("per-video", False), ("batched", True)])
+def test_one_bench_step_matches_the_oracle(mode, kv_overlap):
     import bench
     w = bench.Workload(8, "cuda:0", 8)
+    w.mode = mode
     n_text, counts, n_in = bench.N_TEXT, w.counts, w.n_in
     S = bench.N_VIS + n_text
 
@@ -28,8 +31,8 @@ def test_one_bench_step_matches_the_oracle():
 
     w.stages_1_2()                       # eager once, so that every code object is loaded before the capture
     torch.cuda.synchronize()
-    w.capture()
-    w.step()                             # graph replay of stages 1-2 on 8 streams + KV compaction
+    w.configure(mode, kv_overlap=kv_overlap, use_graph=True)
+    w.step()                             # graph replay of stages 1-2 + KV compaction (index lists of set 0)
     torch.cuda.synchronize()
 
     grid = (bench.GRID, bench.GRID)

@@ -34,13 +34,15 @@ def run_batched(layers, segs, quotas, use_weight=True, orig=None, Tq=None, score
     hidden = synth.to_torch(stack(layers, "hidden"), dt, "cuda")
     out = {name: torch.full((B, keep_stride), SENTINEL, dtype=torch.int32, device="cuda")
            for name in ("kept_idx", "token_seg_out", "token_event_out", "orig_idx_out")}
+    out["orig_idx_out"] = torch.full((B, keep_stride + 5), SENTINEL, dtype=torch.int32, device="cuda")     # its own stride
     hidden_out = hidden if in_place else torch.full((B, out_stride, l0.hidden.shape[1]), float(SENTINEL), dtype=hidden.dtype, device="cuda")
     res = Bm.metok_prefill_prune_batched(
         hidden, l0.vis_start, l0.n_vis, i32(np.stack(segs)), quotas,
         q_text=synth.to_torch(np.stack(qs), dt, "cuda"), k_all=synth.to_torch(stack(layers, "k_all"), dt, "cuda"),
         token_event=i32(stack(layers, "token_event")),
         event_weight=torch.from_numpy(stack(layers, "event_weight", np.float32)).cuda() if use_weight else None,
-        orig_idx=None if orig is None else i32(np.stack(orig)), score_mode=score_mode,
+        orig_idx=None if orig is None else i32(np.pad(np.stack(orig), ((0, 0), (0, 4)), constant_values=-1)),     # its own stride
+        score_mode=score_mode,
         hidden_out=hidden_out, out=out, keep_stride=keep_stride, out_row_stride=out_stride)
     torch.cuda.synchronize()
     assert res["n_keep"] == n_keep
