@@ -152,6 +152,7 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
 // segment_kernel: one workgroup of 1024 threads.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSegThreads = 1024;
+constexpr int kRankLoopFrames = 2048;      // up to here every thread ranks its frames against all others
 
 __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     const float* __restrict__ part, int C, int T, int N, int k, int have_text, int sim_mode,
@@ -207,9 +208,60 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     const int n_pairs = T - 1, n_quads = (n_pairs + 3) / 4;
     if (tid < 4 && n_pairs + tid < n_quads * 4) key[n_pairs + tid] = 0xffffffffu;      // never below a real key, and at a higher index
     __syncthreads();
-    // rank of S_i among the T-1 similarities under the order (value, index); the k-1 lowest are boundaries
+    // the k-1 lowest similarities under the order (value, index) are boundaries
     const int per = (T + kSegThreads - 1) / kSegThreads;      // frames per thread, consecutive
     uint32_t my_flags = 0;                                    // bit j: frame tid*per + j opens an event (per <= 8)
+    if (T > kRankLoopFrames) {
+        // Long videos: the (k-1)-th lowest key by a radix select over the keys in LDS (four 8-bit digits), then
+        // "below it, or equal to it and among the first equal keys by index" -- the same set as the rank rule
+        // below, in O(T) instead of O(T^2 / threads) compares.
+        __shared__ int hist[256];
+        __shared__ uint32_t s_prefix;
+        __shared__ int s_need;
+        if (tid == 0) { s_prefix = 0u; s_need = k - 1; }
+        for (int shift = 24; shift >= 0 && k > 1; shift -= 8) {
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix, himask = shift == 24 ? 0u : 0xffffffffu << (shift + 8);
+            for (int i = tid; i < n_pairs; i += kSegThreads)
+                if ((key[i] & himask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+            __syncthreads();
+            if (tid < 64) {                                   // one wave: four bins per lane, ascending
+                const int need = s_need;
+                int c[4], mine = 0;
+                for (int u = 0; u < 4; ++u) { c[u] = hist[4 * tid + u]; mine += c[u]; }
+                int incl = mine;
+                for (int off = 1; off < 64; off <<= 1) { const int up = __shfl_up(incl, off, 64); if (tid >= off) incl += up; }
+                int run = incl - mine;
+                if (run < need && incl >= need) {             // exactly one lane: the digit holding the need-th lowest key
+                    for (int u = 0; u < 4; ++u) {
+                        if (run + c[u] >= need) { s_prefix = prefix | (static_cast<uint32_t>(4 * tid + u) << shift); s_need = need - run; break; }
+                        run += c[u];
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        const uint32_t tau = s_prefix;
+        const int take_equal = s_need;                        // equal keys that still are boundaries, lowest index first
+        int n_eq = 0;
+        for (int j = 0; j < per; ++j) {
+            const int f = tid * per + j;
+            if (k > 1 && f >= 1 && f < T) {
+                if (key[f - 1] < tau) my_flags |= 1u << j;
+                n_eq += key[f - 1] == tau ? 1 : 0;
+            }
+        }
+        int total_eq = 0;
+        int eq_rank = block_exclusive_scan(n_eq, scan_scratch, &total_eq);
+        for (int j = 0; j < per; ++j) {
+            const int f = tid * per + j;
+            if (k > 1 && f >= 1 && f < T && key[f - 1] == tau) {
+                if (eq_rank < take_equal) my_flags |= 1u << j;
+                ++eq_rank;
+            }
+        }
+    } else
     for (int j = 0; j < per; ++j) {
         const int f = tid * per + j;                          // frame f opens an event if pair f-1 is a boundary
         if (f >= 1 && f < T) {

@@ -216,6 +216,28 @@ def test_maximum_frame_count():
         B.metok_segment_events(torch.zeros((T + 1, 4, 8), dtype=torch.float32, device="cuda"), 2)
 
 
+@pytest.mark.parametrize("T,k", [(4096, 37), (3000, 2999), (2049, 2), (5000, 1)])
+def test_long_videos_with_tied_similarities(T, k):
+    """Above 2048 frames the boundaries come from a radix select of the (k-1)-th lowest similarity; equal similarities
+    are taken lowest index first.  Frames drawn from four distinct vectors make most adjacent pairs tie exactly (the
+    same two vectors give the same fp32 cosine wherever they meet), at the threshold too."""
+    B = mk()
+    rng = np.random.default_rng(T + k)
+    basis = rng.standard_normal((4, 2, 16)).astype(np.float32)
+    pick = rng.integers(0, 4, size=T)
+    feats_np = basis[pick]
+    out = B.metok_segment_events(torch.from_numpy(feats_np).cuda(), k)
+    torch.cuda.synchronize()
+    sim_gpu = out["sim"].cpu().numpy()
+    assert len(np.unique(sim_gpu)) <= 10                             # 4 + 6 unordered pairs of vectors
+    S = O.adjacent_frame_cosine(feats_np.astype(np.float64))
+    assert_rel(sim_gpu, S, RTOL["f32"], "sim", scale=np.abs(S).max())
+    # the decision is checked on the GPU's own fp32 similarities (ties are exact there), bit for bit
+    es, fe = O.event_boundaries(sim_gpu, k)
+    np.testing.assert_array_equal(out["event_start"].cpu().numpy(), es)
+    np.testing.assert_array_equal(out["frame_event"].cpu().numpy(), fe)
+
+
 def test_argument_errors_are_reported():
     B = mk()
     feats = torch.zeros((4, 4, 64), dtype=torch.float32, device="cuda")
