@@ -649,7 +649,8 @@ def read_traffic():
         with open(path) as fh:
             for line in fh:
                 if line.startswith("traffic_bytes_per_launch"):
-                    return float(line.split()[1]), os.path.relpath(path, ROOT)
+                    return float(line.split()[1]), (os.path.relpath(path, ROOT) + ": rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --only kv`, "
+                                                    "scaled by the same counters on a plain copy; a separate run, not measured in this one")
     except OSError:
         pass
     return None, None

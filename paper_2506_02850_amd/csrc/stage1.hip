@@ -7,6 +7,11 @@
 //   segment_kernel       one workgroup: T-1 cosines, the k-1 lowest become boundaries
 //   plan_kernel          one workgroup: event scores, key events, key frames, strides, row offsets
 //   pool_kernel          second streaming pass: s x s mean pooling of every frame, packed output
+//   frame_stats_pool2_kernel   statistics and 2 x 2 pooling from ONE pass, when every frame's stride is 2
+//   frame_mean_kernel, frame_score_kernel, fill_token_event_kernel   small helpers of the other readings / paths
+//
+// In the one-pass call a batch of videos of one shape runs as one launch of every kernel: blockIdx.z is the
+// video, every pointer advances by that video's stride.
 #include "common.h"
 
 namespace metok {

@@ -6,12 +6,20 @@
 //   merge_stats_kernel   merges the per-workgroup (max, sum) pairs into one normaliser per row
 //   col_sums_kernel      MFMA pass 2 over the visual keys: recomputes the logits and adds up the
 //                        probabilities of every visual key over the rows of a workgroup
-//   prepare_kernel       score_j = w_e(j) * mean probability
-//   select_kernel        one workgroup per retention class: radix select of the quota-th largest
-//                        score -> class threshold, number of equal scores still kept, per-tile counts
+//   score_hist_kernel    score_j = w_e(j) * mean probability; per 1024-token tile a histogram of the leading key
+//                        bits per retention class; the workgroup that arrives last finds each class's bucket
+//   candidate_kernel     per tile: tokens above the bucket counted, tokens inside it listed; the workgroup that
+//                        arrives last finishes the radix select on the list -> class threshold, number of equal
+//                        scores still kept, output offset of every tile
+//   prepare_kernel, select_kernel   the same two steps for more than four classes or more than 40 tiles: one
+//                        workgroup per class walks all keys
 //   write_index_kernel   one workgroup per 1024-token tile: keep rule (lowest index first among equal
 //                        scores), prefix sums -> ascending kept index list and carried metadata
-//   gather_rows_kernel   compaction of the hidden states
+//   gather_rows_kernel   compaction of the hidden states (hidden_index_kernel + the row mover of stage 3 when
+//                        the output is the input buffer)
+//
+// A batch of videos of one shape runs as one launch of every kernel: blockIdx.z is the video, every pointer
+// advances by that video's stride, and the per-video workspaces lie one after the other.
 //
 // Both MFMA passes are query-stationary: a wave keeps the fragments of its own 32-row blocks of queries in
 // registers and the workgroup streams its range of keys through LDS.  The contraction index may be
