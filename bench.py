@@ -545,6 +545,31 @@ def time_configs(w: Workload, reps: int):
     e["tokens_in_per_s"] = round(w.batch * N_VIS / (e["ms_median"] * 1e-3), 1)
     e["GBs"] = round(w.kv_bytes() / (e["ms_median"] * 1e-3) / 1e9, 1)
     out["kv_28_layers_batch8"] = e
+    # the same cache as page pools (pages of 16 rows; the dense cache's memory reinterpreted, contents do not matter for the
+    # timing): rows moved through the page table against tables rewritten.  Runs last: it scrambles the cache.
+    ps = 16
+    S0 = N_VIS + N_TEXT
+    pages_per_seq, n_pages = S0 // ps, w.batch * (S0 // ps)
+    kp = [k.view(n_pages, HKV, ps, DH) for k in w.k_layers]
+    vp = [v.view(n_pages, HKV, ps, DH) for v in w.v_layers]
+    table = torch.randperm(n_pages, device=w.dev).to(torch.int32).view(w.batch, pages_per_seq)
+    level_of = [sum(1 for b in L_H if l >= b) for l in range(N_LAYERS)]
+    text_rows = torch.arange(N_VIS, S0, dtype=torch.int32, device=w.dev).repeat(w.batch, 1)
+    keep_pages = torch.sort(torch.randperm(N_VIS // ps, device=w.dev)[: N_VIS // ps // 2]).values.to(torch.int32)
+    block_rows = (keep_pages[:, None] * ps + torch.arange(ps, dtype=torch.int32, device=w.dev)[None, :]).reshape(-1)
+    block_idx = torch.cat([block_rows, text_rows[0]]).repeat(w.batch, 1).contiguous()
+    cases = {"paper_rule_text_rows_only_from_l1": [None if lv == 0 else text_rows for lv in level_of],
+             "whole_pages_dropped_half_of_the_visual_pages": [None if lv == 0 else block_idx for lv in level_of],
+             "stage2_retained_sets": w.idx_layers}
+    for name, idx in cases.items():
+        res = B.metok_kv_relink_paged(kp, vp, table, idx)
+        e = timed(lambda: B.metok_kv_relink_paged(kp, vp, table, idx, workspace=res["workspace"]))
+        e["rows_copied_per_layer_and_video_max"] = int(res["rows_copied"].max())
+        e["pages_released"] = int(res["n_free"].sum())
+        out["kv_paged_relink_" + name] = e
+    e = timed(lambda: B.metok_kv_compact_paged(kp, vp, table, w.idx_layers))
+    e["GBs"] = round(w.kv_bytes() / (e["ms_median"] * 1e-3) / 1e9, 1)
+    out["kv_paged_move_rows_stage2_retained_sets"] = e
     return out
 
 

@@ -61,6 +61,7 @@ struct RelinkTables {
     int64_t table_in_layer_stride;   // 0: one input table shared by the layers
     const int32_t* table_out;        // [L, B, pages_per_seq]
     const int32_t* home_page;        // [L, B, pages_per_seq]
+    const int32_t* relinked;         // [L, B, pages_per_seq]: 1 where the new page is an old page as it stands
 };
 
 struct RowMoveGeom { int parts, lanes_per_row, rows_per_step, rows_per_tile; };

@@ -68,6 +68,7 @@ struct MoveArgs {
     int64_t table_in_layer_stride;
     const int32_t* table_out;    // [L, B, pages_per_seq]
     const int32_t* home_page;    // [L, B, pages_per_seq]
+    const int32_t* relinked;     // [L, B, pages_per_seq]
 };
 
 enum { kMoveDense = 0, kMovePaged = 1, kMoveRelink = 2 };
@@ -146,6 +147,21 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
         return pool + prow * args.row_bytes;
     };
 
+    if (MODE == kMoveRelink) {
+        // A tile whose new pages are all old pages as they stand has nothing to move (block-aligned drops, kept prefixes):
+        // it raises its flag, so that no later tile waits for it, and leaves.
+        __shared__ int s_work;
+        if (threadIdx.x == 0) s_work = 0;
+        __syncthreads();
+        const int last = min(r0 + R, rows) - 1;
+        for (int D = r0 / args.page_size + static_cast<int>(threadIdx.x); D <= last / args.page_size; D += kMoveThreads)
+            if (args.relinked[lb + D] == 0) s_work = 1;
+        __syncthreads();
+        if (s_work == 0) {
+            if (threadIdx.x == 0) __hip_atomic_store(&flags[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+    }
     u32x4_t v[U];
     char* dst[U];                                                 // nullptr: this piece does not move
 #pragma unroll
@@ -298,6 +314,7 @@ int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_w
         args.table_in_layer_stride = relink ? relink->table_in_layer_stride : 0;
         args.table_out = relink ? relink->table_out : nullptr;
         args.home_page = relink ? relink->home_page : nullptr;
+        args.relinked = relink ? relink->relinked : nullptr;
         if (items == 0) continue;
         if (relink)
             { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<kMoveRelink>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
@@ -625,7 +642,7 @@ extern "C" int metok_kv_relink_paged(void* const* k_pools, void* const* v_pools,
         layers[i].first_item = 0; layers[i].tiles = 0; layers[i].flag_slot = 0; layers[i].layer_id = l;
     }
     RelinkTables tables;
-    tables.table_in_layer_stride = table_in_layer_stride; tables.table_out = page_table_out; tables.home_page = plan.home;
+    tables.table_in_layer_stride = table_in_layer_stride; tables.table_out = page_table_out; tables.home_page = plan.home; tables.relinked = plan.relinked;
     return launch_row_moves(layers, n_active, B, Hkv, 2, S_cap, row_bytes, page_table_in, page_size, pages_per_seq, n_pages_pool,
                             new_len, host_len, L, workspace, move_bytes, st, &tables);
 }
