@@ -88,14 +88,13 @@ struct bf16_t { uint16_t bits; };           // storage type of a bf16 element
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs).
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
-    uint32_t u = __float_as_uint(x);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+// Two fp32 values -> packed bf16 pair, round to nearest even: gfx950 converts a pair with one instruction.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    const bf16x2v_t r = __builtin_convertvector(v, bf16x2v_t);
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 // Streaming 16-byte load / store (non-temporal): on MI355X a read-once pass over a few hundred MB runs

@@ -571,41 +571,53 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
     }
     const float tnorm = sqrtf(wave_sum(tn2));
 
+    // Loads are branch-free -- lanes past the last chunk read the row's last chunk again, the step behind the last frame
+    // reads the last frame again -- so that the compiler can count the loads in flight and wait for exactly the
+    // older ones; what such a lane loaded is masked where it is used.
+    bool valid[KL];
+    int chc[KL];
+#pragma unroll
+    for (int k = 0; k < KL; ++k) {
+        const int ch = lane + 64 * k;
+        valid[k] = ch < nchunks;
+        chc[k] = valid[k] ? ch : nchunks - 1;
+    }
     auto load_rows = [&](int t, uint4 (&dst)[4][KL]) {
-        const uint4* frame = reinterpret_cast<const uint4*>(feats) + static_cast<size_t>(t) * N * nchunks;
+        const int tc = t < T_frames ? t : T_frames - 1;
+        const uint4* frame = reinterpret_cast<const uint4*>(feats) + static_cast<size_t>(tc) * N * nchunks;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint4* row = frame + static_cast<size_t>(tok[c]) * nchunks;
 #pragma unroll
-            for (int k = 0; k < KL; ++k) {
-                const int ch = lane + 64 * k;
-                dst[c][k] = ch < nchunks ? load_stream(row + ch) : zero;
-            }
+            for (int k = 0; k < KL; ++k) dst[c][k] = load_stream(row + chc[k]);
         }
     };
-    // X holds frame t; Y receives frame t + 1 while X is worked on
+    // X holds frame t; Y receives frame t + 1 while X is worked on.  Order inside a step: request Y, all arithmetic
+    // on X alone, then <X, Y> (the first use of Y: the only wait of the step), then the stores -- a store issued
+    // earlier would be waited for together with Y.
     auto step = [&](int t, uint4 (&X)[4][KL], uint4 (&Y)[4][KL]) {
         const bool has_next = t + 1 < T_frames;
-        if (has_next) load_rows(t + 1, Y);
+        load_rows(t + 1, Y);
         float p[4], q[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             p[c] = 0.f; q[c] = 0.f;
 #pragma unroll
-            for (int k = 0; k < KL; ++k) { p[c] = E::dot(X[c][k], X[c][k], p[c]); q[c] = E::dot(X[c][k], txt[k], q[c]); }
+            for (int k = 0; k < KL; ++k) {
+                const float pk = E::dot(X[c][k], X[c][k], 0.f);
+                p[c] += valid[k] ? pk : 0.f;
+                q[c] = E::dot(X[c][k], txt[k], q[c]);               // txt is zero past the last chunk
+            }
         }
-        TO* out_row = pooled + (static_cast<size_t>(t) * n_win + w) * d;
+        float pooled_acc[KL][8];
 #pragma unroll
         for (int k = 0; k < KL; ++k) {
-            const int ch = lane + 64 * k;
-            if (ch < nchunks) {
-                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int c = 0; c < 4; ++c) E::accumulate(X[c][k], acc);
+            for (int i = 0; i < 8; ++i) pooled_acc[k][i] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = acc[i] / 4.f;
-                Store<TO>::put(out_row, ch, E::kVec, acc);
-            }
+            for (int c = 0; c < 4; ++c) E::accumulate(X[c][k], pooled_acc[k]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pooled_acc[k][i] = pooled_acc[k][i] / 4.f;
         }
         // after the two halving steps rows 0 / 1 hold |v|^2 of the tokens (0, 2) / (1, 3) in (u0, u1), rows 2 / 3 their text products
         const float s0 = swap32_add(p[0], q[0]), s1 = swap32_add(p[1], q[1]), s2 = swap32_add(p[2], q[2]), s3 = swap32_add(p[3], q[3]);
@@ -617,22 +629,31 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_pool2_kernel(
         const float da = sqrtf(pa) * tnorm, db = sqrtf(pb) * tnorm;
         const float cosv = (!(da < kZeroNorm) ? qa / da : 0.f) + (!(db < kZeroNorm) ? qb / db : 0.f);
         const float tot = swap16_add(cosv, pa + pb);                  // row 0: the four cosines added; row 1: the four |v|^2 added
+        __builtin_amdgcn_sched_barrier(0);
         float cd = 0.f;
-        if (has_next) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
+        for (int c = 0; c < 4; ++c)
 #pragma unroll
-                for (int k = 0; k < KL; ++k) cd = E::dot(X[c][k], Y[c][k], cd);
-        }
+            for (int k = 0; k < KL; ++k) {
+                const float ck = E::dot(X[c][k], Y[c][k], 0.f);
+                cd += (valid[k] && has_next) ? ck : 0.f;
+            }
         cd = row16_sum(cd);
         cd = swap32_add(cd, cd);
         cd = swap16_add(cd, cd);                                      // row 0: all four rows
+        __builtin_amdgcn_sched_barrier(0);
+        TO* out_row = pooled + (static_cast<size_t>(t) * n_win + w) * d;
+#pragma unroll
+        for (int k = 0; k < KL; ++k)
+            if (valid[k]) Store<TO>::put(out_row, lane + 64 * k, E::kVec, pooled_acc[k]);
         float* dst = part + (static_cast<size_t>(t) * n_win + w) * 3;
         if (lane == 0) { dst[1] = cd; dst[2] = tot; }
         if (lane == 16) dst[0] = tot;
     };
     uint4 A[4][KL], B[4][KL];
     load_rows(t0, A);
+    // the first frame has landed before the loop: inside it the only wait is the one for the frame requested in the same step
+    __builtin_amdgcn_s_waitcnt(0);
     for (int t = t0; t < t1; t += 2) {
         step(t, A, B);
         if (t + 1 < t1) step(t + 1, B, A);
@@ -928,12 +949,24 @@ extern "C" size_t metok_segment_compress_workspace_bytes(int T, int grid_h, int 
     return round_up(ab > c ? ab : c, 256);
 }
 
+// Streaming kernels here run fastest with FEW waves per CU: each wave keeps a whole frame step of loads in flight, and
+// more resident waves only queue more requests at the memory system (measured for the one-pass kernel, 8 videos:
+// 636 us with 8 workgroups per CU, 612 us with 2, 580 us with 1).  The launch therefore asks for more than half of a
+// CU's 160 KB of LDS, which the kernel never touches: one workgroup per CU.
+constexpr unsigned kOneWorkgroupPerCuLds = 96 * 1024;
+
 template <typename T, typename TO>
 static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int grid_h, int grid_w, int d, int kl, int C, int fpr,
                                int runs, float* part, void* pooled, int batch, int64_t pooled_video, int64_t ws_video, hipStream_t st) {
 #define METOK_FUSED_CASE(KLV) \
     if (kl == KLV) { \
-        { TraceScope trace_scope(METOK_TRACE_FRAME_STATS_POOL2, st); hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs, batch), dim3(kStatsThreads), 0, st, static_cast<const T*>(feats), \
+        static bool lds_allowed = false; \
+        if (!lds_allowed) { \
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&frame_stats_pool2_kernel<T, KLV, TO>), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kOneWorkgroupPerCuLds) != hipSuccess) return false; \
+            lds_allowed = true; \
+        } \
+        { TraceScope trace_scope(METOK_TRACE_FRAME_STATS_POOL2, st); hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs, batch), dim3(kStatsThreads), kOneWorkgroupPerCuLds, st, static_cast<const T*>(feats), \
                            static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, static_cast<TO*>(pooled), pooled_video, ws_video); } \
         return true; \
     }
