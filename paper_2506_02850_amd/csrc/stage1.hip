@@ -79,32 +79,61 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
     }
     const float tnorm = sqrtf(group_sum<G>(tn2));
 
+    // Loads are branch-free (a lane past the last chunk or token reads a valid address again and its data is masked
+    // where it is used), so that the compiler can count the loads in flight and wait for exactly the older ones.
+    bool valid[KL];
+    int chc[KL];
+#pragma unroll
+    for (int k = 0; k < KL; ++k) {
+        const int c = sub + k * G;
+        valid[k] = tok_ok && c < nchunks;
+        chc[k] = c < nchunks ? c : nchunks - 1;
+    }
     auto load_row = [&](int t, uint4 (&dst)[KL]) {
         const uint4* row = reinterpret_cast<const uint4*>(feats) + (static_cast<size_t>(t) * N + (tok_ok ? n : 0)) * row_chunks;
 #pragma unroll
-        for (int k = 0; k < KL; ++k) {
-            const int c = sub + k * G;
-            dst[k] = (tok_ok && c < nchunks) ? load_stream(row + c) : zero;
-        }
+        for (int k = 0; k < KL; ++k) dst[k] = load_stream(row + chc[k]);
     };
 
     const int t_last = (do_pair && t1 < T_frames) ? t1 : t1 - 1;      // last frame that is loaded
     float p_prev = 0.f;
-    // X holds frame t, W frame t - 1; after the pair product W receives frame t + 1
-    auto step = [&](int t, uint4 (&W)[KL], uint4 (&X)[KL]) {
+    // the partial sums of a step are stored at the start of the next one, after that step's wait: a store issued just
+    // before a wait for loads would be waited for as well
+    float st_cd = 0.f, st_p = 0.f, st_c = 0.f;
+    int st_t = -1;                                                    // frame whose sums are pending (-1: none)
+    bool st_own = false;
+    auto flush = [&]() {
+        if (st_t < 0) return;
+        if (lane == 0) {
+            if (st_t > t0) part[(static_cast<size_t>(st_t - 1) * C + cw) * 3 + 1] = st_cd;
+            if (st_own) part[(static_cast<size_t>(st_t) * C + cw) * 3 + 0] = st_p;
+        }
+        if (G == 16 ? lane == 32 : lane == 0) {
+            if (st_own) part[(static_cast<size_t>(st_t) * C + cw) * 3 + 2] = st_c;
+        }
+    };
+    // X holds frame t, W frame t - 1; after the pair product W receives frame t + 1 (LOAD: there is such a frame)
+    auto step = [&](int t, uint4 (&W)[KL], uint4 (&X)[KL], auto load_tag) {
+        constexpr bool LOAD = decltype(load_tag)::value;
         const bool own = t < t1;                                      // frame t belongs to this run
         float p = 0.f, q = 0.f, cd = 0.f;
-        if (do_pair && t > t0) {
+        const bool pair = do_pair && t > t0;
 #pragma unroll
-            for (int k = 0; k < KL; ++k) cd = E::dot(W[k], X[k], cd);
+        for (int k = 0; k < KL; ++k) {                                // the first use of X: the only wait of the step
+            const float ck = E::dot(W[k], X[k], 0.f);
+            cd += (pair && valid[k]) ? ck : 0.f;
         }
-        if (t + 1 <= t_last) load_row(t + 1, W);
+        __builtin_amdgcn_sched_barrier(0);
+        flush();
+        if (LOAD) load_row(t + 1, W);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int k = 0; k < KL; ++k) p = E::dot(X[k], X[k], p);
-        if (own) {
-#pragma unroll
-            for (int k = 0; k < KL; ++k) q = E::dot(X[k], txt[k], q);
+        for (int k = 0; k < KL; ++k) {
+            const float pk = E::dot(X[k], X[k], 0.f);
+            p += valid[k] ? pk : 0.f;
+            q = E::dot(X[k], txt[k], q);                              // txt is zero past the last chunk
         }
+        if (!own) q = 0.f;
         // per token (one 16-lane row, or the whole wave): every lane of the group gets the token's sums
         p = row16_sum(p); q = row16_sum(q); cd = row16_sum(cd);
         if (G == 64) {
@@ -133,22 +162,26 @@ __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
             cd = swap16_add(cd, cd);
         }
         // slot 1 of frame t-1 holds <v_{t-1}, v_t>; slots 0 and 2 belong to frame t
-        if (lane == 0) {
-            if (t > t0) part[(static_cast<size_t>(t - 1) * C + cw) * 3 + 1] = cd;
-            if (own) part[(static_cast<size_t>(t) * C + cw) * 3 + 0] = p;
-        }
-        if (G == 16 ? lane == 32 : lane == 0) {
-            if (own) part[(static_cast<size_t>(t) * C + cw) * 3 + 2] = G == 16 ? p : cosv;
-        }
+        st_t = t; st_own = own; st_cd = cd; st_p = p; st_c = G == 16 ? p : cosv;
     };
+    const std::integral_constant<bool, true> with_load;
+    const std::integral_constant<bool, false> without_load;
     uint4 A[KL], B[KL];
 #pragma unroll
     for (int k = 0; k < KL; ++k) B[k] = zero;
     load_row(t0, A);
-    for (int t = t0; t <= t_last; t += 2) {
-        step(t, B, A);
-        if (t + 1 <= t_last) step(t + 1, A, B);
+    int t = t0;
+    for (; t + 2 <= t_last; t += 2) {                                 // straight-line pairs of steps, each requesting a frame
+        step(t, B, A, with_load);
+        step(t + 1, A, B, with_load);
     }
+    if (t + 1 <= t_last) {
+        step(t, B, A, with_load);
+        step(t + 1, A, B, without_load);
+    } else if (t <= t_last) {
+        step(t, B, A, without_load);
+    }
+    flush();
     // the pair slot of the very last frame is never read; define it
     if (lane == 0 && t1 == T_frames) part[(static_cast<size_t>(T_frames - 1) * C + cw) * 3 + 1] = 0.f;
 }
