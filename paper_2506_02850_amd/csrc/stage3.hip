@@ -138,15 +138,6 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
     const bool active = r_in < rps;                               // threads beyond the last whole row idle
     const uint32_t s_cap = static_cast<uint32_t>(args.S_cap);
 
-    // address of logical row r of this (video, head) through a page table; nullptr if its page id is not a page of the pool
-    auto row_ptr = [&](const int32_t* __restrict__ tab, uint32_t r) -> char* {
-        if (!PAGED) return base + static_cast<int64_t>(r) * args.row_bytes;
-        const int page = tab[r / static_cast<uint32_t>(args.page_size)];
-        if (page < 0 || page >= args.n_pages_pool) return nullptr;
-        const int64_t prow = (static_cast<int64_t>(page) * args.Hkv + head) * args.page_size + r % static_cast<uint32_t>(args.page_size);
-        return pool + prow * args.row_bytes;
-    };
-
     if (MODE == kMoveRelink) {
         // A tile whose new pages are all old pages as they stand has nothing to move (block-aligned drops, kept prefixes):
         // it raises its flag, so that no later tile waits for it, and leaves.
@@ -162,25 +153,58 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
             return;
         }
     }
-    u32x4_t v[U];
-    char* dst[U];                                                 // nullptr: this piece does not move
+    // The loads of a tile are requested in batches without any branch between them -- first the U index entries, then
+    // (paged) the 2 U page-table entries, then the U row pieces -- so that all pieces of a thread are in flight
+    // together.  (With a branch around each load the compiler has to wait for every earlier load before the next
+    // one, and the eight pieces of a thread went to memory one after the other.)  A piece that does not move reads
+    // the first 16 bytes of the pool instead, a valid address, and is never stored.
+    uint32_t src_row[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int i = r0 + u * rps + r_in;
-        dst[u] = nullptr;
-        if (active && i < rows) {
-            const uint32_t s = static_cast<uint32_t>(idx[i]);
-            // rows that stay where they are need no copy; positions outside (i, S_cap) are skipped.  With relinked
-            // tables "where they are" is about the physical row: a row of a relinked page never moves, a row with
-            // s == i moves if its page changed.
-            if ((MODE == kMoveRelink ? s >= static_cast<uint32_t>(i) : s > static_cast<uint32_t>(i)) && s < s_cap) {
-                const char* src = row_ptr(table, s);
-                char* d = row_ptr(table_dst, static_cast<uint32_t>(i));
-                if (src != nullptr && d != nullptr && src != d) {
-                    dst[u] = d + col;
-                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + col));
-                }
-            }
+        src_row[u] = static_cast<uint32_t>(idx[i < rows ? i : rows - 1]);
+    }
+    u32x4_t v[U];
+    char* dst[U];                                                 // nullptr: this piece does not move
+    if (!PAGED) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = r0 + u * rps + r_in;
+            const uint32_t sr = src_row[u];
+            // rows that stay where they are need no copy; positions outside (i, S_cap) are skipped
+            const bool moves = active && i < rows && sr > static_cast<uint32_t>(i) && sr < s_cap;
+            const char* src = moves ? base + static_cast<int64_t>(sr) * args.row_bytes + col : pool;
+            dst[u] = moves ? base + static_cast<int64_t>(i) * args.row_bytes + col : nullptr;
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src));
+        }
+    } else {
+        // logical row r of this (video, head) lives in page table[r / page_size], slot r % page_size; a page id that
+        // is not a page of the pool makes the piece stay.  With relinked tables "stays where it is" is about the
+        // physical row: a row of a relinked page never moves, a row with the same logical position moves if its page
+        // changed.
+        const uint32_t ps = static_cast<uint32_t>(args.page_size);
+        const uint32_t last_page = static_cast<uint32_t>(args.pages_per_seq - 1);
+        int page_s[U], page_d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = r0 + u * rps + r_in;
+            const uint32_t ps_idx = src_row[u] / ps, pd_idx = static_cast<uint32_t>(i < rows ? i : rows - 1) / ps;
+            page_s[u] = table[ps_idx < last_page ? ps_idx : last_page];
+            page_d[u] = table_dst[pd_idx < last_page ? pd_idx : last_page];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = r0 + u * rps + r_in;
+            const uint32_t sr = src_row[u];
+            const bool in_range = active && i < rows && sr < s_cap &&
+                                  (MODE == kMoveRelink ? sr >= static_cast<uint32_t>(i) : sr > static_cast<uint32_t>(i));
+            const bool pages_ok = page_s[u] >= 0 && page_s[u] < args.n_pages_pool && page_d[u] >= 0 && page_d[u] < args.n_pages_pool;
+            const int64_t prow_s = (static_cast<int64_t>(page_s[u]) * args.Hkv + head) * args.page_size + sr % ps;
+            const int64_t prow_d = (static_cast<int64_t>(page_d[u]) * args.Hkv + head) * args.page_size + static_cast<uint32_t>(i) % ps;
+            const bool moves = in_range && pages_ok && prow_s != prow_d;
+            const char* src = moves ? pool + prow_s * args.row_bytes + col : pool;
+            dst[u] = moves ? pool + prow_d * args.row_bytes + col : nullptr;
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src));
         }
     }
     // Destination rows [lo, hi) of earlier tiles take their sources from the rows this tile overwrites: its own
