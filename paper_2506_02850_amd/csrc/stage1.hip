@@ -203,29 +203,47 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     sim = of_video_elems(sim, T - 1); event_start = of_video_elems(event_start, k + 1);
     frame_event = of_video_elems(frame_event, T); frame_score = of_video_elems(frame_score, T);
 
-    // per-frame totals: one wave per frame, lane c takes chunk partials c, c + 64, ...; the lane sums are
-    // combined by a fixed butterfly, so the result does not depend on timing.  A wave takes eight frames at a
-    // time so that their loads are in flight together.
+    // per-frame totals: the 3 C partial sums of a frame are contiguous (|v|^2, pair product, cosine sum, repeated C
+    // times).  A wave takes four frames at a time; a lane reads the floats lane, lane + 64, ... of each and adds every
+    // value to the total of its component; the lane totals are combined by a fixed butterfly, so the result does not
+    // depend on timing.  The 16 loads of a step are requested together, without a branch between them (a position past
+    // the end reads the last one again and is not added).
     {
-        constexpr int kWaves = kSegThreads / 64, kBatch = 8;
+        constexpr int kWaves = kSegThreads / 64, kBatch = 4, kRounds = 4;
         const int lane = tid & 63, wave = tid >> 6;
+        const int n = 3 * C;
         for (int tb = wave; tb < T; tb += kWaves * kBatch) {
-            float n2[kBatch], dot[kBatch], fs[kBatch];
+            float acc[kBatch][3];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int t = tb + u * kWaves;
-                n2[u] = 0.f; dot[u] = 0.f; fs[u] = 0.f;
-                if (t < T) {
-                    for (int c = lane; c < C; c += 64) {
-                        const float* src = part + (static_cast<size_t>(t) * C + c) * 3;
-                        n2[u] += src[0]; dot[u] += src[1]; fs[u] += src[2];
+            for (int u = 0; u < kBatch; ++u) { acc[u][0] = 0.f; acc[u][1] = 0.f; acc[u][2] = 0.f; }
+            for (int e0 = 0; e0 < n; e0 += 64 * kRounds) {
+                float v[kBatch][kRounds];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const int t = tb + u * kWaves < T ? tb + u * kWaves : T - 1;
+                    const float* src = part + static_cast<size_t>(t) * n;
+#pragma unroll
+                    for (int r = 0; r < kRounds; ++r) {
+                        const int e = e0 + 64 * r + lane;
+                        v[u][r] = src[e < n ? e : n - 1];
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < kRounds; ++r) {
+                    const int e = e0 + 64 * r + lane;
+                    const int comp = e < n ? e % 3 : 3;
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        acc[u][0] += comp == 0 ? v[u][r] : 0.f;
+                        acc[u][1] += comp == 1 ? v[u][r] : 0.f;
+                        acc[u][2] += comp == 2 ? v[u][r] : 0.f;
                     }
                 }
             }
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const int t = tb + u * kWaves;
-                const float a = wave_sum(n2[u]), b = wave_sum(dot[u]), c3 = wave_sum(fs[u]);
+                const float a = wave_sum(acc[u][0]), b = wave_sum(acc[u][1]), c3 = wave_sum(acc[u][2]);
                 if (lane == 0 && t < T) {
                     frame_norm2[t] = a;
                     pair_dot[t] = b;

@@ -972,8 +972,19 @@ __global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs 
     int sg = -1;
     if (j < a.n_vis) {
         if (a.colpart) {
+            // the partial sums of the workgroup rows, added in order; four loads are requested together (a part past the
+            // last one reads the last one again and is not added)
             float acc = 0.f;
-            for (int p = 0; p < a.n_parts; ++p) acc += a.colpart[static_cast<size_t>(p) * a.n_vis + j];
+            for (int p0 = 0; p0 < a.n_parts; p0 += 4) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int p = p0 + u < a.n_parts ? p0 + u : a.n_parts - 1;
+                    v[u] = a.colpart[static_cast<size_t>(p) * a.n_vis + j];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc += p0 + u < a.n_parts ? v[u] : 0.f;
+            }
             acc = acc / a.rows_total;
             if (a.event_weight) {
                 int e = a.token_event[j];
@@ -999,7 +1010,14 @@ __global__ __launch_bounds__(kSelThreads) void score_hist_kernel(const FastArgs 
     }
     if (!arrive_and_check_last(&a.fs->arrive_a, &s_last)) return;
     // last workgroup: the complete histograms come back into LDS, then one wave finds every class's bucket (no more barriers)
-    for (int i = tid; i < a.n_seg * 2048; i += kSelThreads) hist[i] = load_shared_between_workgroups(&ghist[i]);
+    {
+        constexpr int kPer = kFastSeg * 2048 / kSelThreads;
+        int32_t h[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) h[u] = load_shared_between_workgroups(&ghist[tid + u * kSelThreads]);      // the block holds kFastSeg rows
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) hist[tid + u * kSelThreads] = h[u];
+    }
     __syncthreads();
     if (tid >= 64) return;
     for (int c = 0; c < a.n_seg; ++c) {
@@ -1070,14 +1088,24 @@ __global__ __launch_bounds__(kSelThreads) void candidate_kernel(const FastArgs a
     const bool in_regs = m <= kCandRegs * kSelThreads;
     uint32_t ck[kCandRegs];
     int cm[kCandRegs];                                              // class << 6 | tile, -1: no candidate
+    {
+        // all loads are requested before the first is used: no branch between them (a slot past the list reads the
+        // list's last entry again and is dropped)
+        uint32_t tok[kCandRegs];
+        const int last = m > 0 ? m - 1 : 0;
 #pragma unroll
-    for (int u = 0; u < kCandRegs; ++u) {
-        const int i = tid + u * kSelThreads;
-        ck[u] = 0u; cm[u] = -1;
-        if (in_regs && i < m) {
-            const uint32_t tok = load_shared_between_workgroups(&a.cand_tok[i]);
-            ck[u] = load_shared_between_workgroups(&a.cand_key[i]);
-            cm[u] = static_cast<int>(((tok >> 24) << 6) | (((tok & 0xffffffu) >> 10) & 63u));
+        for (int u = 0; u < kCandRegs; ++u) {
+            const int i = tid + u * kSelThreads;
+            const int ic = i < last ? i : last;
+            tok[u] = load_shared_between_workgroups(&a.cand_tok[ic]);
+            ck[u] = load_shared_between_workgroups(&a.cand_key[ic]);
+        }
+#pragma unroll
+        for (int u = 0; u < kCandRegs; ++u) {
+            const int i = tid + u * kSelThreads;
+            const bool have = in_regs && i < m;
+            cm[u] = have ? static_cast<int>(((tok[u] >> 24) << 6) | (((tok[u] & 0xffffffu) >> 10) & 63u)) : -1;
+            ck[u] = have ? ck[u] : 0u;
         }
     }
     // f(key, class, tile) for every candidate; a list too long for the registers is walked in memory
