@@ -133,7 +133,7 @@ class Workload:
         self.text = [self.text_b[b] for b in range(batch)]
         # ---- preallocated outputs and workspaces (nothing is allocated inside a step)
         self.n_streams = max(1, min(n_streams, batch))
-        self.mode, self.kv_overlap, self.graphs, self.step_no = "batched", False, [], 0
+        self.mode, self.kv_overlap, self.graphs, self.step_no, self.split = "batched", False, [], 0, 1
         self.streams = [torch.cuda.Stream(device=device) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         self.ws1_b = torch.empty(lib.metok_segment_compress_batched_workspace_bytes(batch, FRAMES, GRID, GRID, D_VIS, binding.BF16),
                                  dtype=torch.uint8, device=device)
@@ -279,26 +279,32 @@ class Workload:
                                           event_weight=self.weight[b], orig_idx=orig, hidden_out=self.hidden_out[b][lv],
                                           workspace=self.ws2[b % self.n_streams], out=self.prune_out[b][lv])
 
-    def stage1_batched(self):
-        return self.B.metok_segment_compress_batched(self.feats_b, GRID, GRID, N_EVENTS, self.text_b, 1.0, 1.0, 2, 2,
-                                                     workspace=self.ws1_b, out=self.s1_out_b)
+    def stage1_batched(self, part=None):
+        """Stage 1 of the whole batch in one call (part = (first video, end, workspace): of a share of the batch)."""
+        b0, b1, ws = part if part is not None else (0, self.batch, self.ws1_b)
+        return self.B.metok_segment_compress_batched(self.feats_b[b0:b1], GRID, GRID, N_EVENTS, self.text_b[b0:b1], 1.0, 1.0, 2, 2,
+                                                     workspace=ws, out={k: v[b0:b1] for k, v in self.s1_out_b.items()})
 
-    def prune_level_batched(self, lv, token_event, p):
-        """Level lv of the whole batch in one call; p selects the set of KV index lists that receives the retained indices."""
+    def prune_level_batched(self, lv, token_event, p, part=None):
+        """Level lv of the whole batch (or of a share of it) in one call; p selects the set of KV index lists that receives
+        the retained indices."""
+        b0, b1, ws = part if part is not None else (0, self.batch, self.ws2_b)
         n, c = self.n_in[lv], self.counts[lv]
-        prev = self.prune_out_b_sets[p][lv - 1] if lv > 0 else None
+        cut = lambda d: {k: v[b0:b1] for k, v in d.items()}
+        prev = cut(self.prune_out_b_sets[p][lv - 1]) if lv > 0 else None
         h = self.hidden0_b if lv == 0 else self.hidden_out_b[lv - 1]
-        tseg = self.seg0_b if lv == 0 else prev["token_seg_out"]
+        tseg = self.seg0_b[b0:b1] if lv == 0 else prev["token_seg_out"]
         orig = None if lv == 0 else prev["orig_idx_out"]
-        return self.B.metok_prefill_prune_batched(h, 0, n, tseg, [[c]] * self.batch, q_text=self.Q_b[lv], k_all=self.K_b[lv],
-                                                  token_event=token_event, event_weight=self.weight_b, orig_idx=orig,
-                                                  hidden_out=self.hidden_out_b[lv], workspace=self.ws2_b,
-                                                  out=self.prune_out_b_sets[p][lv])
+        return self.B.metok_prefill_prune_batched(h[b0:b1], 0, n, tseg, [[c]] * (b1 - b0), q_text=self.Q_b[lv][b0:b1],
+                                                  k_all=self.K_b[lv][b0:b1], token_event=token_event,
+                                                  event_weight=self.weight_b[b0:b1], orig_idx=orig,
+                                                  hidden_out=self.hidden_out_b[lv][b0:b1], workspace=ws,
+                                                  out=cut(self.prune_out_b_sets[p][lv]))
 
-    def stage2_batched(self, token_event, p=0):
+    def stage2_batched(self, token_event, p=0, part=None):
         tev = token_event
         for lv in range(len(self.n_in)):
-            tev = self.prune_level_batched(lv, tev, p)["token_event_out"]
+            tev = self.prune_level_batched(lv, tev, p, part)["token_event_out"]
 
     def stage2(self, b, token_event):
         tev = token_event
@@ -331,10 +337,28 @@ class Workload:
         """Stage 1 and the three pruning levels of the batch; the retained indices go to set p of the KV index lists."""
         if self.mode == "per-video":
             return self.stages_1_2_per_video()
-        cmp = self.stage1_batched()
-        self.stage2_batched(cmp["token_event"], p)
+        if self.split <= 1:
+            cmp = self.stage1_batched()
+            self.stage2_batched(cmp["token_event"], p)
+            return
+        # the batch in `split` shares, each on a stream of its own: the ALU-bound score passes of one share can then run
+        # beside the HBM-bound kernels of another
+        torch = self.torch
+        main = torch.cuda.current_stream()
+        per = (self.batch + self.split - 1) // self.split
+        for i in range(self.split):
+            b0, b1 = i * per, min(self.batch, (i + 1) * per)
+            if b0 >= b1:
+                continue
+            st = self.streams[i]
+            st.wait_stream(main)
+            with torch.cuda.stream(st):
+                cmp = self.stage1_batched((b0, b1, self.ws1_parts[i]))
+                self.stage2_batched(cmp["token_event"], p, (b0, b1, self.ws2_parts[i]))
+        for i in range(self.split):
+            main.wait_stream(self.streams[i])
 
-    def configure(self, mode="batched", kv_overlap=False, use_graph=True):
+    def configure(self, mode="batched", kv_overlap=False, use_graph=True, split=1):
         """mode: "batched" (one call per stage and level for the whole batch: 28 launches per step) or "per-video" (one
         call per video, 8 streams: about 230 launches).  kv_overlap: the KV compaction of a step runs on a stream of its
         own, beside the next step's stages 1-2 (which fill the other set of index lists).  use_graph: the stage-1/2 launches
@@ -343,6 +367,14 @@ class Workload:
         so that the library can bracket its kernel with events."""
         torch = self.torch
         self.mode = mode
+        self.split = max(1, min(int(split), len(self.streams) if self.streams else 1)) if mode == "batched" else 1
+        if self.split > 1:
+            lib, S0 = self.B.lib(), N_VIS + N_TEXT
+            per = (self.batch + self.split - 1) // self.split
+            self.ws1_parts = [torch.empty(lib.metok_segment_compress_batched_workspace_bytes(per, FRAMES, GRID, GRID, D_VIS, self.B.BF16),
+                                          dtype=torch.uint8, device=self.dev) for _ in range(self.split)]
+            self.ws2_parts = [torch.empty(lib.metok_prefill_prune_batched_workspace_bytes(per, S0, HQ, HKV, DH, TQ, N_VIS, self.B.BF16),
+                                          dtype=torch.uint8, device=self.dev) for _ in range(self.split)]
         self.kv_overlap = bool(kv_overlap) and mode == "batched"
         self.step_no = 0
         self.kv_stream = torch.cuda.Stream(device=self.dev) if self.kv_overlap else None
@@ -690,6 +722,7 @@ def main():
     ap.add_argument("--streams", type=int, default=8, help="streams that share the per-video stage-1/2 work")
     ap.add_argument("--no-graph", action="store_true", help="launch the stage-1/2 kernels one by one instead of replaying a HIP graph")
     ap.add_argument("--per-video", action="store_true", help="one library call per video and stage on 8 streams instead of the batched calls")
+    ap.add_argument("--split", type=int, default=1, help="run stages 1-2 on this many shares of the batch, each on its own stream")
     ap.add_argument("--kv-overlap", action="store_true",
                     help="run the KV compaction of a step on a stream of its own, beside the next step's stages 1-2 (higher whole-job rate, "
                          "but the two HBM-bound parts then share the memory system and the KV kernel's own duration grows by half)")
@@ -766,7 +799,7 @@ def main():
     w.mode = "per-video" if args.per_video else "batched"
     w.step()                                             # eager once: loads code objects before any capture
     torch.cuda.synchronize()
-    w.configure(w.mode, kv_overlap=args.kv_overlap, use_graph=not args.no_graph)
+    w.configure(w.mode, kv_overlap=args.kv_overlap, use_graph=not args.no_graph, split=args.split)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()

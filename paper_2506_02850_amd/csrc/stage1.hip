@@ -1011,11 +1011,13 @@ static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int 
                                int runs, float* part, void* pooled, int batch, int64_t pooled_video, int64_t ws_video, hipStream_t st) {
 #define METOK_FUSED_CASE(KLV) \
     if (kl == KLV) { \
-        static bool lds_allowed = false; \
-        if (!lds_allowed) { \
+        static bool lds_allowed[64] = {false};        /* per device: the attribute belongs to the device's copy of the kernel */ \
+        int dev = 0; \
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false; \
+        if (!lds_allowed[dev]) { \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&frame_stats_pool2_kernel<T, KLV, TO>), \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kOneWorkgroupPerCuLds) != hipSuccess) return false; \
-            lds_allowed = true; \
+            lds_allowed[dev] = true; \
         } \
         { TraceScope trace_scope(METOK_TRACE_FRAME_STATS_POOL2, st); hipLaunchKernelGGL((frame_stats_pool2_kernel<T, KLV, TO>), dim3(C, runs, batch), dim3(kStatsThreads), kOneWorkgroupPerCuLds, st, static_cast<const T*>(feats), \
                            static_cast<const T*>(text), Tf, grid_h, grid_w, d, fpr, part, static_cast<TO*>(pooled), pooled_video, ws_video); } \
