@@ -816,7 +816,7 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
 // workgroup; here the token-parallel parts run on one workgroup per tile and only the short serial parts run
 // on the workgroup that arrives last at an atomic counter (it is the one that knows every other workgroup's
 // results are complete; nobody waits for anybody):
-//   score_hist_kernel   per tile: scores (the former prepare_kernel), histogram of the top 11 key bits per class
+//   score_hist_kernel   per tile: scores (what prepare_kernel does on the general path), histogram of the top 11 key bits per class
 //                       -> global histogram.  Last workgroup: per class the histogram bucket that holds the
 //                       quota-th largest key, how many keys of that bucket are still needed, or keep all / none.
 //   candidate_kernel    per tile: tokens above the bucket are kept for sure (counted per tile), tokens inside it are
