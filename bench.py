@@ -577,6 +577,14 @@ def time_configs(w: Workload, reps: int):
     e["tokens_in_per_s"] = round(w.batch * N_VIS / (e["ms_median"] * 1e-3), 1)
     e["GBs"] = round(w.kv_bytes() / (e["ms_median"] * 1e-3) / 1e9, 1)
     out["kv_28_layers_batch8"] = e
+    # the paper's LongVA setting of stage 1 (strides 2 / 3 / 4 / 6 per frame: two passes over the features) for the whole batch;
+    # overwrites the stage-1 outputs, so it comes after the configurations that read them
+    e = timed(lambda: B.metok_segment_compress_batched(w.feats_b, GRID, GRID, N_EVENTS, w.text_b, a["alpha"], a["beta"], a["s1"], a["s2"],
+                                                       workspace=w.ws1_b, out=w.s1_out_b))
+    e["tokens_in_per_s"] = round(w.batch * FRAMES * GRID * GRID / (e["ms_median"] * 1e-3), 1)
+    e["GBs"] = round(w.batch * (2 * FRAMES * GRID * GRID * D_VIS * 2 + int(w.s1_out_b["frame_offsets"][:, -1].float().mean()) * D_VIS * 2)
+                     / (e["ms_median"] * 1e-3) / 1e9, 1)
+    out["encoder_256_frames_adaptive_batch8"] = e
     # the same cache as page pools (pages of 16 rows; the dense cache's memory reinterpreted, contents do not matter for the
     # timing): rows moved through the page table against tables rewritten.  Runs last: it scrambles the cache.
     ps = 16

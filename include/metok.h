@@ -201,10 +201,10 @@ METOK_API int metok_segment_compress(const void* feats, int dtype, int T, int gr
 
 /*
  * Stage 1 in one call for a batch of videos of one shape (Sec. 3.2.1, Algorithm 1): metok_segment_compress on each of
- * `batch` videos (1 <= batch <= METOK_MAX_BATCH) with the same settings.  In the one-pass case the batch runs as ONE
- * sequence of four launches whose grids span all videos (the planning kernels, one workgroup per video, run side by
- * side); otherwise the videos are processed one after the other.  Per video the results are those of
- * metok_segment_compress, bit for bit.
+ * `batch` videos (1 <= batch <= METOK_MAX_BATCH) with the same settings.  Every kernel is launched once for the whole
+ * batch (four launches in the one-pass case, four in the two-pass case: statistics, segmentation, plan, pooling; the
+ * planning kernels, one workgroup per video, run side by side); only with METOK_SIM_POOLED the videos are processed
+ * one after the other.  Per video the results are those of metok_segment_compress, bit for bit.
  *   Every array carries a leading batch dimension and is tightly packed: feats [batch, T, N, d], text_emb [batch, d],
  *   sim [batch, T-1], event_start [batch, k+1], frame_event / frame_is_key / frame_stride / frame_score [batch, T],
  *   out_tokens [batch, out_capacity_rows, d], token_event [batch, out_capacity_rows], frame_offsets [batch, T+1],

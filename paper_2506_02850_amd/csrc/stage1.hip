@@ -51,9 +51,11 @@ __device__ __forceinline__ float swap16_add(float a, float b) {
 template <typename T, int G, int KL>
 __global__ __launch_bounds__(kStatsThreads) void frame_stats_kernel(
     const T* __restrict__ feats, const T* __restrict__ text, int T_frames, int N, int d,
-    int frames_per_run, int do_pair, int sim_mode, float* __restrict__ part, int C) {
+    int frames_per_run, int do_pair, int sim_mode, float* __restrict__ part, int C, int64_t ws_video) {
     using E = Elem<T>;
     static_assert(G == 16 || G == 64, "token groups are one DPP row or one wave");
+    feats = of_video_elems(feats, static_cast<int64_t>(T_frames) * N * d); text = of_video_elems(text, d);
+    part = of_video(part, ws_video);
     constexpr int TPW = 64 / G;                 // tokens per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % G, tw = lane / G;
@@ -526,8 +528,12 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
     const TI* __restrict__ feats, int grid_h, int grid_w, int d,
     const int32_t* __restrict__ frame_stride, const int32_t* __restrict__ frame_offsets,
     const int32_t* __restrict__ frame_event, int pool_edge, int64_t capacity_rows,
-    TO* __restrict__ out, int32_t* __restrict__ token_event) {
+    TO* __restrict__ out, int32_t* __restrict__ token_event, int T_frames, int64_t ws_video) {
     using E = Elem<TI>;
+    feats = of_video_elems(feats, static_cast<int64_t>(T_frames) * grid_h * grid_w * d);
+    frame_stride = of_video_elems(frame_stride, T_frames); frame_offsets = of_video_elems(frame_offsets, T_frames + 1);
+    frame_event = of_video(frame_event, ws_video);
+    out = of_video_elems(out, capacity_rows * d); token_event = of_video_elems(token_event, capacity_rows);
     const int f = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = frame_stride[f];
@@ -758,17 +764,17 @@ static bool plan_stats(int T, int N, int d, int dtype, StatsPlan* p) {
 
 template <typename T, int G, int KL>
 static void launch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
-                         int sim_mode, float* part, hipStream_t st) {
-    { TraceScope trace_scope(METOK_TRACE_FRAME_STATS, st); hipLaunchKernelGGL((frame_stats_kernel<T, G, KL>), dim3((p.C + kStatsWaves - 1) / kStatsWaves, p.runs), dim3(kStatsThreads), 0, st,
+                         int sim_mode, float* part, hipStream_t st, int batch, int64_t ws_video) {
+    { TraceScope trace_scope(METOK_TRACE_FRAME_STATS, st); hipLaunchKernelGGL((frame_stats_kernel<T, G, KL>), dim3((p.C + kStatsWaves - 1) / kStatsWaves, p.runs, batch), dim3(kStatsThreads), 0, st,
                        static_cast<const T*>(feats), static_cast<const T*>(text), Tf, N, d, p.frames_per_run, do_pair,
-                       sim_mode, part, p.C); }
+                       sim_mode, part, p.C, ws_video); }
 }
 
 template <typename T>
 static bool dispatch_stats(const void* feats, const void* text, int Tf, int N, int d, const StatsPlan& p, int do_pair,
-                           int sim_mode, float* part, hipStream_t st) {
+                           int sim_mode, float* part, hipStream_t st, int batch = 1, int64_t ws_video = 0) {
 #define METOK_STATS_CASE(g, kl) \
-    if (p.G == g && p.KL == kl) { launch_stats<T, g, kl>(feats, text, Tf, N, d, p, do_pair, sim_mode, part, st); return true; }
+    if (p.G == g && p.KL == kl) { launch_stats<T, g, kl>(feats, text, Tf, N, d, p, do_pair, sim_mode, part, st, batch, ws_video); return true; }
     METOK_STATS_CASE(16, 1) METOK_STATS_CASE(16, 2) METOK_STATS_CASE(16, 4) METOK_STATS_CASE(16, 8)
     METOK_STATS_CASE(64, 1) METOK_STATS_CASE(64, 2) METOK_STATS_CASE(64, 4) METOK_STATS_CASE(64, 8) METOK_STATS_CASE(64, 16)
 #undef METOK_STATS_CASE
@@ -972,7 +978,8 @@ extern "C" int metok_compress_encoder_tokens(const void* feats, int dtype, int T
 #define METOK_POOL_CASE(TI, TO) \
     { TraceScope trace_scope(METOK_TRACE_POOL, st); \
       hipLaunchKernelGGL((pool_kernel<TI, TO>), grid, dim3(kPoolThreads), 0, st, static_cast<const TI*>(feats), grid_h, grid_w, d, \
-                         frame_stride, frame_offsets, frame_event_ws, pool_edge, out_capacity_rows, static_cast<TO*>(out_tokens), token_event); }
+                         frame_stride, frame_offsets, frame_event_ws, pool_edge, out_capacity_rows, static_cast<TO*>(out_tokens), token_event, \
+                         T, static_cast<int64_t>(0)); }
     if (dtype == METOK_BF16 && out_dtype == METOK_BF16) METOK_POOL_CASE(bf16_t, bf16_t)
     else if (dtype == METOK_BF16 && out_dtype == METOK_F32) METOK_POOL_CASE(bf16_t, float)
     else if (dtype == METOK_F32 && out_dtype == METOK_BF16) METOK_POOL_CASE(float, bf16_t)
@@ -1059,6 +1066,67 @@ static int segment_compress_impl(int batch, const void* feats, int dtype, int T,
     const int vec = dtype == METOK_BF16 ? 8 : 4;
     const int kl = (d > 0 && d % vec == 0) ? (d / vec + 63) / 64 : 0;
     if (kl < 1 || kl > 4) fused = false;
+    if (!fused && batch > 1 && (sim_mode == METOK_SIM_FLAT || sim_mode == METOK_SIM_TOKEN_MEAN)) {
+        // two passes (statistics, then pooling with the strides of Algorithm 1), each kernel once for the whole batch
+        StatsPlan p;
+        int rc = check_feats(feats, dtype, T, N, d, &p);
+        if (rc) return rc;
+        if (out_dtype != METOK_F32 && out_dtype != METOK_BF16) return fail(METOK_ERR_INVALID_ARG, "unknown out_dtype %d", out_dtype);
+        if (k < 1 || k > T) return fail(METOK_ERR_INVALID_ARG, "k must be in [1, T] (k=%d, T=%d)", k, T);
+        if (!(alpha > 0.0 && alpha <= 1.0) || !(beta > 0.0 && beta <= 1.0))
+            return fail(METOK_ERR_INVALID_ARG, "need 0 < alpha, beta <= 1 (alpha=%g beta=%g)", alpha, beta);
+        if (s1 < 1 || s2 < 1) return fail(METOK_ERR_INVALID_ARG, "strides must be >= 1 (s1=%d s2=%d)", s1, s2);
+        if (event_reduce != METOK_EVENT_MEAN && event_reduce != METOK_EVENT_MAX)
+            return fail(METOK_ERR_INVALID_ARG, "unknown event_reduce %d", event_reduce);
+        if (pool_edge != METOK_POOL_FLOOR && pool_edge != METOK_POOL_CEIL)
+            return fail(METOK_ERR_INVALID_ARG, "unknown pool_edge %d", pool_edge);
+        if (!event_start || !frame_event || (T > 1 && !sim) || !out_tokens || !frame_offsets || !token_event || !event_is_key ||
+            !frame_is_key || !frame_stride || !event_score)
+            return fail(METOK_ERR_INVALID_ARG, "NULL pointer argument");
+        if (!aligned16(text_emb) || !aligned16(out_tokens)) return fail(METOK_ERR_INVALID_ARG, "text_emb / out_tokens not 16-byte aligned");
+        if ((static_cast<size_t>(d) * dtype_size(dtype)) % 16 || (static_cast<size_t>(d) * dtype_size(out_dtype)) % 16)
+            return fail(METOK_ERR_INVALID_ARG, "d * sizeof(dtype) must be a multiple of 16 for the features and the pooled tokens");
+        if (static_cast<int64_t>(grid_h) * grid_w > (1 << 24)) return fail(METOK_ERR_INVALID_ARG, "bad patch grid %d x %d", grid_h, grid_w);
+        const int gmax = grid_h > grid_w ? grid_h : grid_w;
+        auto clamp_stride = [&](double v) { int c = ceil_ratio(v); return c < 1 ? 1 : (c > gmax ? gmax : c); };
+        const int64_t worst = worst_case_rows(T, grid_h, grid_w, s1, s2, pool_edge);
+        if (out_capacity_rows < worst)
+            return fail(METOK_ERR_CAPACITY, "out_capacity_rows = %lld, worst case needs %lld", (long long)out_capacity_rows, (long long)worst);
+        if (worst > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "pooled row count must fit int32");
+        char* ws = static_cast<char*>(workspace);
+        const size_t tslot = round_up(static_cast<size_t>(T) * sizeof(float), 256);
+        float* part = reinterpret_cast<float*>(ws);
+        float* norm2 = reinterpret_cast<float*>(ws + stats_part_bytes(T, p));
+        float* pair_dot = reinterpret_cast<float*>(ws + stats_part_bytes(T, p) + tslot);
+        int32_t* frame_event_ws = reinterpret_cast<int32_t*>(ws + stats_part_bytes(T, p) + 2 * tslot);
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const unsigned nb = static_cast<unsigned>(batch);
+        const bool ok = dtype == METOK_BF16 ? dispatch_stats<bf16_t>(feats, text_emb, T, N, d, p, 1, sim_mode, part, st, batch, ws_video)
+                                            : dispatch_stats<float>(feats, text_emb, T, N, d, p, 1, sim_mode, part, st, batch, ws_video);
+        if (!ok) return fail(METOK_ERR_UNSUPPORTED, "no frame-statistics kernel for d = %d", d);
+        if ((rc = check_launch("frame_stats"))) return rc;
+        { TraceScope trace_scope(METOK_TRACE_SEGMENT, st); hipLaunchKernelGGL(segment_kernel, dim3(1, 1, nb), dim3(kSegThreads), 0, st, part, p.C, T, N, k, 1, sim_mode,
+                           sim, event_start, frame_event, frame_score, norm2, pair_dot, ws_video); }
+        if ((rc = check_launch("segment"))) return rc;
+        const int n_key_events = ceil_ratio(alpha * k) > k ? k : ceil_ratio(alpha * k);
+        { TraceScope trace_scope(METOK_TRACE_PLAN, st); hipLaunchKernelGGL(plan_kernel, dim3(1, 1, nb), dim3(kSegThreads), 0, st, frame_score, event_start, T, k, n_key_events, beta,
+                           clamp_stride(s1), clamp_stride(s2), clamp_stride(s1 / alpha), clamp_stride(s2 / alpha), grid_h, grid_w, event_reduce, pool_edge,
+                           event_score, event_is_key, frame_is_key, frame_stride, frame_offsets, frame_event_ws,
+                           static_cast<float*>(nullptr), ws_video); }
+        if ((rc = check_launch("plan"))) return rc;
+        dim3 grid(36, T, nb);
+#define METOK_POOL_CASE(TI, TO) \
+        { TraceScope trace_scope(METOK_TRACE_POOL, st); \
+          hipLaunchKernelGGL((pool_kernel<TI, TO>), grid, dim3(kPoolThreads), 0, st, static_cast<const TI*>(feats), grid_h, grid_w, d, \
+                             frame_stride, frame_offsets, frame_event_ws, pool_edge, out_capacity_rows, static_cast<TO*>(out_tokens), token_event, \
+                             T, ws_video); }
+        if (dtype == METOK_BF16 && out_dtype == METOK_BF16) METOK_POOL_CASE(bf16_t, bf16_t)
+        else if (dtype == METOK_BF16 && out_dtype == METOK_F32) METOK_POOL_CASE(bf16_t, float)
+        else if (dtype == METOK_F32 && out_dtype == METOK_BF16) METOK_POOL_CASE(float, bf16_t)
+        else METOK_POOL_CASE(float, float)
+#undef METOK_POOL_CASE
+        return check_launch("pool");
+    }
     if (!fused) {
         // two passes per video (statistics, then pooling with the strides of Algorithm 1), one video after the other
         const size_t in_es = dtype_size(dtype), out_es = dtype_size(out_dtype);

@@ -146,7 +146,9 @@ def test_one_call_at_256_frames_and_errors():
     (12, (6, 10), 512, "bf16", 3, 1.0, 1.0, 2, 2, "bf16"),     # one pass, ragged last workgroup
     (40, (4, 6), 2048, "bf16", 7, 1.0, 0.5, 2, 2, "f32"),      # one pass, several frame runs
     (10, (6, 6), 1024, "f32", 4, 1.0, 0.4, 2, 2, "f32"),       # one pass, fp32
-    (9, (6, 6), 64, "bf16", 3, 0.5, 0.45, 2, 3, "bf16"),       # adaptive strides: the videos run one after the other
+    (9, (6, 6), 64, "bf16", 3, 0.5, 0.45, 2, 3, "bf16"),       # adaptive strides: two passes, each kernel once for the batch
+    (21, (27, 27), 1152, "bf16", 5, 0.5, 0.4, 2, 3, "f32"),    # SigLIP grid, the OneVision setting, fp32 output
+    (13, (5, 7), 24, "f32", 4, 0.3, 0.5, 1, 2, "f32"),         # odd grid, fp32, s / alpha rounds up
 ])
 def test_batched_one_call_equals_the_single_video_call(T, grid, d, dtype, k, alpha, beta, s1, s2, out_dtype):
     """metok_segment_compress_batched: every video of the batch bit-identical to metok_segment_compress on that video
