@@ -585,6 +585,10 @@ def time_configs(w: Workload, reps: int):
     e["GBs"] = round(w.batch * (2 * FRAMES * GRID * GRID * D_VIS * 2 + int(w.s1_out_b["frame_offsets"][:, -1].float().mean()) * D_VIS * 2)
                      / (e["ms_median"] * 1e-3) / 1e9, 1)
     out["encoder_256_frames_adaptive_batch8"] = e
+    e = timed(lambda: B.metok_segment_compress(w.feats[0], GRID, GRID, N_EVENTS, w.text[0], a["alpha"], a["beta"], a["s1"], a["s2"],
+                                               workspace=w.ws1[0], out=w.s1_out[0]))
+    e["tokens_in_per_s"] = round(FRAMES * GRID * GRID / (e["ms_median"] * 1e-3), 1)
+    out["encoder_256_frames_adaptive_one_video"] = e
     # the same cache as page pools (pages of 16 rows; the dense cache's memory reinterpreted, contents do not matter for the
     # timing): rows moved through the page table against tables rewritten.  Runs last: it scrambles the cache.
     ps = 16
