@@ -577,6 +577,13 @@ def time_configs(w: Workload, reps: int):
     e["tokens_in_per_s"] = round(w.batch * N_VIS / (e["ms_median"] * 1e-3), 1)
     e["GBs"] = round(w.kv_bytes() / (e["ms_median"] * 1e-3) / 1e9, 1)
     out["kv_28_layers_batch8"] = e
+    # the paper's own stage-3 rule on the same cache: every visual row leaves from layer l1 on, only the 128 text rows move
+    # (a latency case: 25 layers x 8 videos x 4 heads x (K, V) x 128 rows of 256 bytes = 52 MB each way)
+    text_only = torch.arange(N_VIS, N_VIS + N_TEXT, dtype=torch.int32, device=w.dev).repeat(w.batch, 1)
+    paper_idx = [None if l < L_H[0] else text_only for l in range(N_LAYERS)]
+    paper_len = torch.empty_like(w.new_len)
+    e = timed(lambda: B.metok_kv_compact(w.k_layers, w.v_layers, paper_idx, new_len=paper_len, workspace=w.kv_ws))
+    out["kv_28_layers_batch8_paper_rule_text_rows_only_from_l1"] = e
     # the paper's LongVA setting of stage 1 (strides 2 / 3 / 4 / 6 per frame: two passes over the features) for the whole batch;
     # overwrites the stage-1 outputs, so it comes after the configurations that read them
     e = timed(lambda: B.metok_segment_compress_batched(w.feats_b, GRID, GRID, N_EVENTS, w.text_b, a["alpha"], a["beta"], a["s1"], a["s2"],

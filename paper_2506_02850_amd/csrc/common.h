@@ -57,11 +57,12 @@ struct RowMoveLayer {
     int32_t layer_id;    // index of the layer in per-layer tables (relink variant)
 };
 
+struct PlanArgs;                     // arguments of the planning kernel of the relink variant
 struct RelinkTables {
     int64_t table_in_layer_stride;   // 0: one input table shared by the layers
     const int32_t* table_out;        // [L, B, pages_per_seq]
     const int32_t* home_page;        // [L, B, pages_per_seq]
-    const int32_t* relinked;         // [L, B, pages_per_seq]: 1 where the new page is an old page as it stands
+    PlanArgs* plan;                  // launch_row_moves fills in the mover's geometry and launches the planning kernel
 };
 
 struct RowMoveGeom { int parts, lanes_per_row, rows_per_step, rows_per_tile; };

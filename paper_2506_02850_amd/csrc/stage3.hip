@@ -33,6 +33,11 @@
 // page table[b][p / page_size], slot p % page_size, of a per-layer pool [n_pages, Hkv, page_size, dh].
 // The ordering argument is about logical rows; it carries over because distinct logical rows of a video
 // are distinct physical rows as long as no page appears twice in the table.
+//
+// With relinked page tables (metok_kv_relink_paged) the planning kernel decides which tiles copy anything at
+// all: it raises the flags of the others itself and writes the tiles with work, ascending inside a (layer,
+// video), to a list; only the first (length of the list) x (slabs per video) workgroups of the mover take a
+// ticket, and the ticket order is the order of the list, so the argument about the waits is unchanged.
 #include "common.h"
 
 namespace metok {
@@ -68,7 +73,10 @@ struct MoveArgs {
     int64_t table_in_layer_stride;
     const int32_t* table_out;    // [L, B, pages_per_seq]
     const int32_t* home_page;    // [L, B, pages_per_seq]
-    const int32_t* relinked;     // [L, B, pages_per_seq]
+    // (video, tile) groups of this launch that have rows to copy, written by the planning kernel: group ids
+    // first_item / n_sub + video * tiles + tile, ascending within a (layer, video); *n_work of them
+    const int32_t* worklist;
+    const uint32_t* n_work;
 };
 
 enum { kMoveDense = 0, kMovePaged = 1, kMoveRelink = 2 };
@@ -100,15 +108,23 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
     constexpr bool PAGED = MODE != kMoveDense;
     constexpr int U = kMoveInFlight;
     __shared__ int s_item, s_lo, s_hi;
+    const int n_sub = args.Hkv * args.n_which * args.parts;
+    // With relinked tables only the tiles on the work list run: the first n_work * n_sub workgroups take one ticket
+    // each, the others leave before they touch the counter.
+    const int64_t n_items = MODE == kMoveRelink ? static_cast<int64_t>(*args.n_work) * n_sub : args.total_items;
+    if (MODE == kMoveRelink && static_cast<int64_t>(blockIdx.x) >= n_items) return;
     if (threadIdx.x == 0) s_item = static_cast<int>(atomicAdd(args.ticket, 1u));
     __syncthreads();
-    const int item = s_item;
-    if (item >= args.total_items) return;
+    int item = s_item;
+    if (item >= n_items) return;
+    if (MODE == kMoveRelink) {
+        const int k = item / n_sub;
+        item = args.worklist[k] * n_sub + (item - k * n_sub);
+    }
     int slot = 0;
     while (slot + 1 < args.n_layers && args.layer[slot + 1].first_item <= item) ++slot;
     const RowMoveLayer& L = args.layer[slot];
     // item -> (video, tile, sub-slab): the sub-slabs of one video share its index list and advance together
-    const int n_sub = args.Hkv * args.n_which * args.parts;
     const int local = item - L.first_item;
     const int b = local / (n_sub * L.tiles);
     int rem = local - b * n_sub * L.tiles;
@@ -138,21 +154,6 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(const MoveArgs 
     const bool active = r_in < rps;                               // threads beyond the last whole row idle
     const uint32_t s_cap = static_cast<uint32_t>(args.S_cap);
 
-    if (MODE == kMoveRelink) {
-        // A tile whose new pages are all old pages as they stand has nothing to move (block-aligned drops, kept prefixes):
-        // it raises its flag, so that no later tile waits for it, and leaves.
-        __shared__ int s_work;
-        if (threadIdx.x == 0) s_work = 0;
-        __syncthreads();
-        const int last = min(r0 + R, rows) - 1;
-        for (int D = r0 / args.page_size + static_cast<int>(threadIdx.x); D <= last / args.page_size; D += kMoveThreads)
-            if (args.relinked[lb + D] == 0) s_work = 1;
-        __syncthreads();
-        if (s_work == 0) {
-            if (threadIdx.x == 0) __hip_atomic_store(&flags[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return;
-        }
-    }
     // The loads of a tile are requested in batches without any branch between them -- first the U index entries, then
     // (paged) the 2 U page-table entries, then the U row pieces -- so that all pieces of a thread are in flight
     // together.  (With a branch around each load the compiler has to wait for every earlier load before the next
@@ -265,6 +266,173 @@ __global__ __launch_bounds__(256) void move_init_kernel(uint32_t* __restrict__ w
     if (new_len != nullptr && blockIdx.x == 0 && static_cast<int>(threadIdx.x) < lengths.n) new_len[threadIdx.x] = lengths.len[threadIdx.x];
 }
 
+// ---------------------------------------------------------------------------------------------
+// Page relinking (Sec. 3.3 on a paged cache): instead of moving every kept row, a new page table is
+// written per layer and video.  A new logical page whose rows are exactly one whole old page (all kept,
+// in order, aligned) simply takes over that page's physical page; the other new pages are filled by row
+// copies into physical pages the sequence already owns, and the pages left over are reported as free.
+//
+// Plan, one workgroup per (layer, video):
+//   1. new page D is "relinked" to old page P iff idx[D ps + t] = P ps + t for all its rows;
+//   2. the old pages that are not taken over this way are "free", in ascending order;
+//   3. the k-th new page that is not relinked takes the k-th free old page as its home.  Among the old pages
+//      0..D at most D - k are taken over by relinks, so that home is at most D: a copied page never lands
+//      behind its own logical position, and the rows it overwrites were read by new pages at or before it.
+//      This is what lets the row mover order its tiles exactly as in the plain compaction.
+//   4. table_out[D] = table_in[home[D]]; the free old pages beyond the ones used as homes are released.
+// ---------------------------------------------------------------------------------------------
+
+struct PlanLayer {
+    const int32_t* idx; int32_t n_keep; int32_t len_in;
+    // the layer's place in the row mover's launches (filled by launch_row_moves; launch < 0: the mover skips the layer)
+    int32_t group_base;      // first_item / n_sub
+    int16_t flag_slot, launch;
+};
+struct PlanArgs {
+    PlanLayer layer[METOK_MAX_LAYERS];
+    // row mover geometry and work lists (filled by launch_row_moves)
+    int rows_per_tile, n_sub, tiles_max;
+    uint32_t* flags;         // the mover's progress flags
+    uint32_t* n_work;        // [launches] counters, zero before this kernel
+    int32_t* worklist;       // [L, B, tiles_max]; the list of launch k starts at entry k * kMaxLayersPerLaunch * B * tiles_max
+    int B, page_size, pages_per_seq;
+    int64_t S_cap, table_in_layer_stride;
+    const int32_t* table_in;
+    int32_t* table_out;      // [L, B, pps]
+    int32_t* free_pages;     // [L, B, pps]
+    int32_t* n_free;         // [L, B]
+    int32_t* rows_copied;    // [L, B]
+    int32_t* home;           // [L, B, pps]  scratch kept for the row mover
+    int32_t* used;           // [L, B, pps]  scratch
+    int32_t* free_by_rank;   // [L, B, pps]  scratch
+    int32_t* relinked;       // [L, B, pps]  scratch
+};
+
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void relink_plan_kernel(const PlanArgs a) {
+    __shared__ int scan_scratch[17];
+    __shared__ int s_count, s_base;
+    const int l = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+    const int pps = a.pages_per_seq, ps = a.page_size;
+    const int64_t lb = (static_cast<int64_t>(l) * a.B + b) * pps;
+    const int32_t* __restrict__ tin = a.table_in + l * a.table_in_layer_stride + static_cast<int64_t>(b) * pps;
+    int32_t* tout = a.table_out + lb;
+    int32_t* freed = a.free_pages + lb;
+    int32_t* home = a.home + lb;
+    int32_t* used = a.used + lb;
+    int32_t* fbr = a.free_by_rank + lb;
+    int32_t* rel = a.relinked + lb;
+    const PlanLayer& L = a.layer[l];
+    if (L.idx == nullptr) {                      // untouched layer: the table is carried over
+        for (int D = tid; D < pps; D += kPlanThreads) { tout[D] = tin[D]; home[D] = D; freed[D] = -1; }
+        if (tid == 0) { a.n_free[static_cast<int64_t>(l) * a.B + b] = 0; a.rows_copied[static_cast<int64_t>(l) * a.B + b] = 0; }
+        return;
+    }
+    const int n = L.n_keep;
+    const int32_t* __restrict__ idx = L.idx + static_cast<int64_t>(b) * n;
+    const int np_old = (L.len_in + ps - 1) / ps, nd = (n + ps - 1) / ps;
+    for (int j = tid; j < pps; j += kPlanThreads) { used[j] = 0; freed[j] = -1; }
+    __syncthreads();
+    // 1. which new pages are whole old pages
+    for (int D = tid; D < nd; D += kPlanThreads) {
+        const int rows_d = min(ps, n - D * ps);
+        const int s0 = idx[D * ps];
+        bool ok = s0 >= 0 && s0 % ps == 0 && static_cast<int64_t>(s0) + rows_d <= L.len_in;
+        for (int t = 1; ok && t < rows_d; ++t) ok = idx[D * ps + t] == s0 + t;
+        rel[D] = ok ? 1 : 0;
+        home[D] = ok ? s0 / ps : -1;
+        if (ok) used[s0 / ps] = 1;
+    }
+    __syncthreads();
+    // 1b. the row mover's work list: a tile of destination rows whose new pages are all old pages as they stand has
+    // nothing to copy (block-aligned drops, kept prefixes); its progress flags go up here so that no tile waits for
+    // it, and it gets no workgroup.  The other tiles of this (layer, video) are appended in ascending order to the
+    // list of the layer's launch, in a range reserved with one atomic.
+    if (L.launch >= 0) {
+        const int R = a.rows_per_tile, tiles = (n + R - 1) / R;
+        auto has_work = [&](int t) {
+            const int64_t end = min(static_cast<int64_t>(t + 1) * R, static_cast<int64_t>(n));
+            const int d1 = static_cast<int>((end - 1) / ps);
+            for (int D = static_cast<int>(static_cast<int64_t>(t) * R / ps); D <= d1; ++D)
+                if (rel[D] == 0) return 1;
+            return 0;
+        };
+        int n_mine = 0;
+        for (int base = 0; base < tiles; base += kPlanThreads) {
+            const int t = base + tid;
+            n_mine += __syncthreads_count(t < tiles && has_work(t));
+        }
+        if (tid == 0) s_base = n_mine ? static_cast<int>(atomicAdd(a.n_work + L.launch, static_cast<uint32_t>(n_mine))) : 0;
+        __syncthreads();
+        int32_t* list = a.worklist + static_cast<int64_t>(L.launch) * kMaxLayersPerLaunch * a.B * a.tiles_max + s_base;
+        uint32_t* flags = a.flags + (static_cast<size_t>(L.flag_slot) * a.B + b) * a.n_sub * a.tiles_max;
+        int done = 0;
+        for (int base = 0; base < tiles; base += kPlanThreads) {
+            const int t = base + tid;
+            const int f = (t < tiles) ? has_work(t) : 0;
+            int tot = 0;
+            const int ex = block_exclusive_scan(f, scan_scratch, &tot);
+            if (f) list[done + ex] = L.group_base + b * tiles + t;
+            else if (t < tiles)
+                for (int sub = 0; sub < a.n_sub; ++sub) flags[static_cast<size_t>(sub) * a.tiles_max + t] = 1u;
+            done += tot;
+        }
+    }
+    // 2. free old pages in ascending order
+    int carry = 0;
+    for (int base = 0; base < np_old; base += kPlanThreads) {
+        const int j = base + tid;
+        const int f = (j < np_old && used[j] == 0) ? 1 : 0;
+        int tot = 0;
+        const int ex = block_exclusive_scan(f, scan_scratch, &tot);
+        if (f) fbr[carry + ex] = j;
+        carry += tot;
+    }
+    const int total_free = carry;
+    __syncthreads();
+    // 3. homes of the new pages that are filled by copies
+    carry = 0;
+    for (int base = 0; base < nd; base += kPlanThreads) {
+        const int D = base + tid;
+        const int f = (D < nd && rel[D] == 0) ? 1 : 0;
+        int tot = 0;
+        const int ex = block_exclusive_scan(f, scan_scratch, &tot);
+        if (f) home[D] = carry + ex < total_free ? fbr[carry + ex] : D;      // the bound only fails for n_keep > len_in, refused by the host
+        carry += tot;
+    }
+    const int n_copied_pages = carry;
+    __syncthreads();
+    // 4. the new table and the released pages
+    for (int D = tid; D < pps; D += kPlanThreads) {
+        int page = -1;
+        if (D < nd) { const int h = home[D]; page = (h >= 0 && h < pps) ? tin[h] : -1; }
+        tout[D] = page;
+    }
+    for (int r = n_copied_pages + tid; r < total_free; r += kPlanThreads) freed[r - n_copied_pages] = tin[fbr[r]];
+    // rows that change their physical place
+    int mine = 0;
+    for (int d = tid; d < n; d += kPlanThreads) {
+        const int s = idx[d];
+        if (s >= d && s < a.S_cap && static_cast<int64_t>(home[d / ps]) * ps + d % ps != s) ++mine;
+    }
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    if (mine) atomicAdd(&s_count, mine);
+    __syncthreads();
+    if (tid == 0) {
+        a.n_free[static_cast<int64_t>(l) * a.B + b] = total_free > n_copied_pages ? total_free - n_copied_pages : 0;
+        a.rows_copied[static_cast<int64_t>(l) * a.B + b] = s_count;
+    }
+}
+
+// four [L, B, pages_per_seq] tables and the mover's work lists [L, B, tiles_max]
+static size_t relink_scratch_bytes(int L, int B, int pages_per_seq, int64_t tiles_max) {
+    return 4 * round_up(static_cast<size_t>(L) * B * pages_per_seq * sizeof(int32_t), 256) +
+           round_up(static_cast<size_t>(L) * B * static_cast<size_t>(tiles_max) * sizeof(int32_t), 256);
+}
+
+
 RowMoveGeom row_move_geom(int64_t row_bytes) {
     RowMoveGeom g;
     const int chunks = static_cast<int>(row_bytes / 16);
@@ -278,8 +446,10 @@ RowMoveGeom row_move_geom(int64_t row_bytes) {
     return g;
 }
 
-// words: [0] error, [1 .. 1 + launches) tickets, then padding to 64 words, then the flags
-static size_t move_header_words(int L) { return round_up(1 + (static_cast<size_t>(L) + kMaxLayersPerLaunch - 1) / kMaxLayersPerLaunch, 64); }
+// words: [0] error, [1 .. 1 + launches) tickets, [1 + launches .. 1 + 2 launches) work-list lengths (relinked tables),
+// then padding to 64 words, then the flags
+static int move_launches(int L) { return (L + kMaxLayersPerLaunch - 1) / kMaxLayersPerLaunch; }
+static size_t move_header_words(int L) { return round_up(1 + 2 * static_cast<size_t>(move_launches(L)), 64); }
 
 size_t row_move_workspace_bytes(int L, int B, int Hkv, int n_which, int64_t S_cap, int64_t row_bytes) {
     const RowMoveGeom g = row_move_geom(row_bytes);
@@ -315,20 +485,46 @@ int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_w
     int rc = check_launch("row move init");
     if (rc) return rc;
 
+    // the place of every layer in the launches
+    const int n_launches = move_launches(L_total);
+    int64_t launch_items[(METOK_MAX_LAYERS + kMaxLayersPerLaunch - 1) / kMaxLayersPerLaunch] = {};
     for (int first = 0, launch = 0; first < n_active; first += kMaxLayersPerLaunch, ++launch) {
-        MoveArgs args;
-        args.n_layers = (n_active - first < kMaxLayersPerLaunch) ? n_active - first : kMaxLayersPerLaunch;
+        const int n_here = (n_active - first < kMaxLayersPerLaunch) ? n_active - first : kMaxLayersPerLaunch;
         int64_t items = 0;
-        for (int i = 0; i < args.n_layers; ++i) {
+        for (int i = 0; i < n_here; ++i) {
             RowMoveLayer& Lr = layers[first + i];
             Lr.tiles = (Lr.n_keep + g.rows_per_tile - 1) / g.rows_per_tile;
             if (items > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "too many tiles for one launch");
             Lr.first_item = static_cast<int32_t>(items);
             Lr.flag_slot = first + i;
             items += static_cast<int64_t>(Lr.tiles) * B * n_sub;
-            args.layer[i] = Lr;
         }
         if (items > INT32_MAX) return fail(METOK_ERR_INVALID_ARG, "too many tiles for one launch");
+        launch_items[launch] = items;
+    }
+    if (relink) {
+        // the planning kernel runs between the clearing of the flags and the moves: it raises the flags of the tiles
+        // that have nothing to copy and lists the others
+        PlanArgs& plan = *relink->plan;
+        for (int l = 0; l < METOK_MAX_LAYERS; ++l) { plan.layer[l].group_base = 0; plan.layer[l].flag_slot = 0; plan.layer[l].launch = -1; }
+        for (int i = 0; i < n_active; ++i) {
+            PlanLayer& pl = plan.layer[layers[i].layer_id];
+            pl.group_base = layers[i].first_item / n_sub;
+            pl.flag_slot = static_cast<int16_t>(layers[i].flag_slot);
+            pl.launch = static_cast<int16_t>(i / kMaxLayersPerLaunch);
+        }
+        plan.rows_per_tile = g.rows_per_tile; plan.n_sub = n_sub; plan.tiles_max = tiles_max;
+        plan.flags = words + header; plan.n_work = words + 1 + n_launches;
+        hipLaunchKernelGGL(relink_plan_kernel, dim3(B, L_total), dim3(kPlanThreads), 0, st, plan);
+        rc = check_launch("relink plan");
+        if (rc) return rc;
+    }
+
+    for (int first = 0, launch = 0; first < n_active; first += kMaxLayersPerLaunch, ++launch) {
+        MoveArgs args;
+        args.n_layers = (n_active - first < kMaxLayersPerLaunch) ? n_active - first : kMaxLayersPerLaunch;
+        for (int i = 0; i < args.n_layers; ++i) args.layer[i] = layers[first + i];
+        const int64_t items = launch_items[launch];
         args.B = B; args.Hkv = Hkv; args.n_which = n_which; args.parts = g.parts; args.lanes_per_row = g.lanes_per_row;
         args.rows_per_step = g.rows_per_step; args.tiles_max = tiles_max; args.total_items = static_cast<int>(items);
         args.spin_limit = g_spin_limit;
@@ -338,7 +534,8 @@ int launch_row_moves(RowMoveLayer* layers, int n_active, int B, int Hkv, int n_w
         args.table_in_layer_stride = relink ? relink->table_in_layer_stride : 0;
         args.table_out = relink ? relink->table_out : nullptr;
         args.home_page = relink ? relink->home_page : nullptr;
-        args.relinked = relink ? relink->relinked : nullptr;
+        args.worklist = relink ? relink->plan->worklist + static_cast<int64_t>(launch) * kMaxLayersPerLaunch * B * tiles_max : nullptr;
+        args.n_work = relink ? words + 1 + n_launches + launch : nullptr;
         if (items == 0) continue;
         if (relink)
             { TraceScope trace_scope(METOK_TRACE_MOVE_ROWS, st); hipLaunchKernelGGL(move_rows_kernel<kMoveRelink>, dim3(static_cast<unsigned>(items)), dim3(kMoveThreads), 0, st, args); }
@@ -447,128 +644,6 @@ extern "C" int metok_debug_set_move_spin_limit(int polls) {
     return METOK_OK;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Page relinking (Sec. 3.3 on a paged cache): instead of moving every kept row, a new page table is
-// written per layer and video.  A new logical page whose rows are exactly one whole old page (all kept,
-// in order, aligned) simply takes over that page's physical page; the other new pages are filled by row
-// copies into physical pages the sequence already owns, and the pages left over are reported as free.
-//
-// Plan, one workgroup per (layer, video):
-//   1. new page D is "relinked" to old page P iff idx[D ps + t] = P ps + t for all its rows;
-//   2. the old pages that are not taken over this way are "free", in ascending order;
-//   3. the k-th new page that is not relinked takes the k-th free old page as its home.  Among the old pages
-//      0..D at most D - k are taken over by relinks, so that home is at most D: a copied page never lands
-//      behind its own logical position, and the rows it overwrites were read by new pages at or before it.
-//      This is what lets the row mover order its tiles exactly as in the plain compaction.
-//   4. table_out[D] = table_in[home[D]]; the free old pages beyond the ones used as homes are released.
-// ---------------------------------------------------------------------------------------------
-namespace metok {
-
-struct PlanLayer { const int32_t* idx; int32_t n_keep; int32_t len_in; };
-struct PlanArgs {
-    PlanLayer layer[METOK_MAX_LAYERS];
-    int B, page_size, pages_per_seq;
-    int64_t S_cap, table_in_layer_stride;
-    const int32_t* table_in;
-    int32_t* table_out;      // [L, B, pps]
-    int32_t* free_pages;     // [L, B, pps]
-    int32_t* n_free;         // [L, B]
-    int32_t* rows_copied;    // [L, B]
-    int32_t* home;           // [L, B, pps]  scratch kept for the row mover
-    int32_t* used;           // [L, B, pps]  scratch
-    int32_t* free_by_rank;   // [L, B, pps]  scratch
-    int32_t* relinked;       // [L, B, pps]  scratch
-};
-
-constexpr int kPlanThreads = 1024;
-
-__global__ __launch_bounds__(kPlanThreads) void relink_plan_kernel(const PlanArgs a) {
-    __shared__ int scan_scratch[17];
-    __shared__ int s_count;
-    const int l = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
-    const int pps = a.pages_per_seq, ps = a.page_size;
-    const int64_t lb = (static_cast<int64_t>(l) * a.B + b) * pps;
-    const int32_t* __restrict__ tin = a.table_in + l * a.table_in_layer_stride + static_cast<int64_t>(b) * pps;
-    int32_t* tout = a.table_out + lb;
-    int32_t* freed = a.free_pages + lb;
-    int32_t* home = a.home + lb;
-    int32_t* used = a.used + lb;
-    int32_t* fbr = a.free_by_rank + lb;
-    int32_t* rel = a.relinked + lb;
-    const PlanLayer& L = a.layer[l];
-    if (L.idx == nullptr) {                      // untouched layer: the table is carried over
-        for (int D = tid; D < pps; D += kPlanThreads) { tout[D] = tin[D]; home[D] = D; freed[D] = -1; }
-        if (tid == 0) { a.n_free[static_cast<int64_t>(l) * a.B + b] = 0; a.rows_copied[static_cast<int64_t>(l) * a.B + b] = 0; }
-        return;
-    }
-    const int n = L.n_keep;
-    const int32_t* __restrict__ idx = L.idx + static_cast<int64_t>(b) * n;
-    const int np_old = (L.len_in + ps - 1) / ps, nd = (n + ps - 1) / ps;
-    for (int j = tid; j < pps; j += kPlanThreads) { used[j] = 0; freed[j] = -1; }
-    __syncthreads();
-    // 1. which new pages are whole old pages
-    for (int D = tid; D < nd; D += kPlanThreads) {
-        const int rows_d = min(ps, n - D * ps);
-        const int s0 = idx[D * ps];
-        bool ok = s0 >= 0 && s0 % ps == 0 && static_cast<int64_t>(s0) + rows_d <= L.len_in;
-        for (int t = 1; ok && t < rows_d; ++t) ok = idx[D * ps + t] == s0 + t;
-        rel[D] = ok ? 1 : 0;
-        home[D] = ok ? s0 / ps : -1;
-        if (ok) used[s0 / ps] = 1;
-    }
-    __syncthreads();
-    // 2. free old pages in ascending order
-    int carry = 0;
-    for (int base = 0; base < np_old; base += kPlanThreads) {
-        const int j = base + tid;
-        const int f = (j < np_old && used[j] == 0) ? 1 : 0;
-        int tot = 0;
-        const int ex = block_exclusive_scan(f, scan_scratch, &tot);
-        if (f) fbr[carry + ex] = j;
-        carry += tot;
-    }
-    const int total_free = carry;
-    __syncthreads();
-    // 3. homes of the new pages that are filled by copies
-    carry = 0;
-    for (int base = 0; base < nd; base += kPlanThreads) {
-        const int D = base + tid;
-        const int f = (D < nd && rel[D] == 0) ? 1 : 0;
-        int tot = 0;
-        const int ex = block_exclusive_scan(f, scan_scratch, &tot);
-        if (f) home[D] = carry + ex < total_free ? fbr[carry + ex] : D;      // the bound only fails for n_keep > len_in, refused by the host
-        carry += tot;
-    }
-    const int n_copied_pages = carry;
-    __syncthreads();
-    // 4. the new table and the released pages
-    for (int D = tid; D < pps; D += kPlanThreads) {
-        int page = -1;
-        if (D < nd) { const int h = home[D]; page = (h >= 0 && h < pps) ? tin[h] : -1; }
-        tout[D] = page;
-    }
-    for (int r = n_copied_pages + tid; r < total_free; r += kPlanThreads) freed[r - n_copied_pages] = tin[fbr[r]];
-    // rows that change their physical place
-    int mine = 0;
-    for (int d = tid; d < n; d += kPlanThreads) {
-        const int s = idx[d];
-        if (s >= d && s < a.S_cap && static_cast<int64_t>(home[d / ps]) * ps + d % ps != s) ++mine;
-    }
-    if (tid == 0) s_count = 0;
-    __syncthreads();
-    if (mine) atomicAdd(&s_count, mine);
-    __syncthreads();
-    if (tid == 0) {
-        a.n_free[static_cast<int64_t>(l) * a.B + b] = total_free > n_copied_pages ? total_free - n_copied_pages : 0;
-        a.rows_copied[static_cast<int64_t>(l) * a.B + b] = s_count;
-    }
-}
-
-static size_t relink_scratch_bytes(int L, int B, int pages_per_seq) {
-    return 4 * round_up(static_cast<size_t>(L) * B * pages_per_seq * sizeof(int32_t), 256);
-}
-
-}  // namespace metok
 
 extern "C" size_t metok_kv_relink_paged_workspace_bytes(int L, int B, int Hkv, int page_size, int pages_per_seq, int dh, int dtype) {
     if (L < 1 || L > METOK_MAX_LAYERS || B < 1 || Hkv < 1 || page_size < 1 || pages_per_seq < 1 || dh < 1 ||
@@ -577,7 +652,9 @@ extern "C" size_t metok_kv_relink_paged_workspace_bytes(int L, int B, int Hkv, i
     const int64_t S_cap = static_cast<int64_t>(pages_per_seq) * page_size;
     const int64_t row_bytes = static_cast<int64_t>(dh) * static_cast<int64_t>(dtype_size(dtype));
     if (S_cap > INT32_MAX || row_bytes % 16 != 0 || row_bytes / 16 > kMoveThreads * 64) return 0;
-    return row_move_workspace_bytes(L, B, Hkv, 2, S_cap, row_bytes) + relink_scratch_bytes(L, B, pages_per_seq);
+    const RowMoveGeom g = row_move_geom(row_bytes);
+    return row_move_workspace_bytes(L, B, Hkv, 2, S_cap, row_bytes) +
+           relink_scratch_bytes(L, B, pages_per_seq, (S_cap + g.rows_per_tile - 1) / g.rows_per_tile);
 }
 
 extern "C" int metok_kv_relink_paged(void* const* k_pools, void* const* v_pools, int L, int B, int Hkv,
@@ -651,10 +728,8 @@ extern "C" int metok_kv_relink_paged(void* const* k_pools, void* const* v_pools,
     plan.used = reinterpret_cast<int32_t*>(ws + move_bytes + slot);
     plan.free_by_rank = reinterpret_cast<int32_t*>(ws + move_bytes + 2 * slot);
     plan.relinked = reinterpret_cast<int32_t*>(ws + move_bytes + 3 * slot);
+    plan.worklist = reinterpret_cast<int32_t*>(ws + move_bytes + 4 * slot);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(relink_plan_kernel, dim3(B, L), dim3(kPlanThreads), 0, st, plan);
-    int rc = check_launch("relink plan");
-    if (rc) return rc;
 
     RowMoveLayer layers[METOK_MAX_LAYERS];
     for (int i = 0; i < n_active; ++i) {
@@ -666,7 +741,7 @@ extern "C" int metok_kv_relink_paged(void* const* k_pools, void* const* v_pools,
         layers[i].first_item = 0; layers[i].tiles = 0; layers[i].flag_slot = 0; layers[i].layer_id = l;
     }
     RelinkTables tables;
-    tables.table_in_layer_stride = table_in_layer_stride; tables.table_out = page_table_out; tables.home_page = plan.home; tables.relinked = plan.relinked;
+    tables.table_in_layer_stride = table_in_layer_stride; tables.table_out = page_table_out; tables.home_page = plan.home; tables.plan = &plan;
     return launch_row_moves(layers, n_active, B, Hkv, 2, S_cap, row_bytes, page_table_in, page_size, pages_per_seq, n_pages_pool,
                             new_len, host_len, L, workspace, move_bytes, st, &tables);
 }

@@ -58,6 +58,8 @@ def run_relink(L, B, H, pages_per_seq, page_size, dh16, dtype, idx_lists, seed=0
             np.testing.assert_array_equal(freed[l, b, :n_free[l, b]], ref["free_pages"], err_msg=f"layer {l} video {b}: released pages")
             assert copied[l, b] == ref["rows_copied"]
             total_copied += int(copied[l, b])
+            if n_new == 0:                                   # a layer that keeps nothing: every page was released
+                continue
             for dense, before, pool, name in pools:
                 # relinked pages were not written at all
                 for D, whole in enumerate(ref["relinked"]):
@@ -110,6 +112,40 @@ def test_unaligned_text_rows_and_block_aligned_drops():
     copied = out["rows_copied"].cpu().numpy()
     assert (copied[0] == 50).all() and (copied[1] == 0).all()
     assert (out["n_free"].cpu().numpy()[1] == pages - 17).all()
+
+
+def test_tiles_without_copies_among_tiles_with_copies_over_two_launches():
+    """Only the tiles that copy rows get a workgroup.  45 layers (two launches of the row mover), pages of 24 rows
+    that straddle the 512-row tiles, and per layer a different mix: a kept prefix, whole pages dropped at random
+    (tiles with nothing to copy), scattered rows (tiles that copy), whole pages again behind them (their homes
+    depend on the copies before them), untouched and empty layers in between."""
+    rng = np.random.default_rng(77)
+    L, B, H, ps, pages = 45, 2, 2, 24, 130
+    S = pages * ps
+    lists = []
+    for l in range(L):
+        if l % 11 == 5:
+            lists.append(None)
+            continue
+        if l == 7:
+            lists.append(np.zeros((B, 0), dtype=np.int32))
+            continue
+        per_video = []
+        n_keep = None
+        for b in range(B):
+            prefix = int(rng.integers(0, 30))
+            mid_end = int(rng.integers(60, 90))
+            whole = np.sort(rng.choice(np.arange(prefix, mid_end), size=(mid_end - prefix) // 2, replace=False))
+            tail_pages = np.sort(rng.choice(np.arange(mid_end + 20, pages), size=6, replace=False))
+            rows = np.concatenate([np.arange(prefix * ps),
+                                   (whole[:, None] * ps + np.arange(ps)[None, :]).reshape(-1),
+                                   np.sort(rng.choice(np.arange(mid_end * ps, (mid_end + 20) * ps), size=200 + 24 * (l % 3), replace=False)),
+                                   (tail_pages[:, None] * ps + np.arange(ps)[None, :]).reshape(-1)]).astype(np.int32)
+            n_keep = len(rows) if n_keep is None else min(n_keep, len(rows))
+            per_video.append(rows)
+        lists.append(np.stack([r[:n_keep] for r in per_video]))
+    out, copied = run_relink(L, B, H, pages, ps, 128, "bf16", lists, seed=8)
+    assert copied > 0
 
 
 def test_relinking_twice_with_per_layer_tables_and_shorter_layers():
