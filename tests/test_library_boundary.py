@@ -261,3 +261,12 @@ def test_product_path_does_not_touch_the_oracle():
     # and the oracle does not import the package's binding or library
     text = open(os.path.join(ROOT, "oracle", "metok_oracle.py")).read()
     assert "binding" not in text and "libmetok" not in text and "ctypes" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The measurement is one GPU's: bench.py says so and exits instead of timing anything at --gpus 2."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
