@@ -829,6 +829,7 @@ __global__ __launch_bounds__(kIdxThreads) void write_index_kernel(
 // ---------------------------------------------------------------------------------------------
 constexpr int kFastSeg = 4;
 constexpr int kFastTiles = kSelCache;
+static_assert(kFastTiles <= 64, "the finishing workgroup scans the tiles with one wave, a lane per tile");
 constexpr uint32_t kKeepAll = 0x7fffffffu;
 
 struct FastSel {
@@ -1171,28 +1172,34 @@ __global__ __launch_bounds__(kSelThreads) void candidate_kernel(const FastArgs a
     });
     __syncthreads();
     if (tid >= 64) return;
-    // one lane per class: equal keys before every tile, kept tokens of every tile (in t_gt)
-    if (lane < a.n_seg) {
-        const int c = lane;
+    // one wave, lane = tile (at most kFastTiles <= 64): per class the equal keys before every tile and the equal keys a
+    // tile still keeps (the first keep_eq by index), then the output offset of every tile
+    const bool live = lane < n_tiles;
+    int kept = 0;
+    for (int c = 0; c < a.n_seg; ++c) {
+        const int eq = live ? t_eq[c][lane] : 0;
+        int incl = eq;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        const int before = incl - eq;
         const uint32_t keep_eq = s_keep_eq[c];
-        int eqcum = 0;
-        for (int t = 0; t < n_tiles; ++t) {
-            const int eq = t_eq[c][t];
-            int room = keep_eq == kKeepAll ? eq : static_cast<int>(keep_eq) - eqcum;
-            room = room < 0 ? 0 : room;
-            a.fs->eq_before[c][t] = eqcum;
-            eqcum += eq;
-            t_gt[c][t] += eq < room ? eq : room;
+        int room = keep_eq == kKeepAll ? eq : static_cast<int>(keep_eq) - before;
+        room = room < 0 ? 0 : room;
+        if (live) {
+            a.fs->eq_before[c][lane] = before;
+            kept += t_gt[c][lane] + (eq < room ? eq : room);
         }
     }
-    wave_sync();
-    if (lane == 0) {
-        int running = 0;
-        for (int t = 0; t < n_tiles; ++t) {
-            a.fs->tile_off[t] = running;
-            for (int c = 0; c < a.n_seg; ++c) running += t_gt[c][t];
-        }
+    int incl = kept;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
     }
+    if (live) a.fs->tile_off[lane] = incl - kept;
 }
 
 // Source row of every output row of the compacted sequence [prefix; kept visual rows; text rows].
