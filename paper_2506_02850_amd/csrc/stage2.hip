@@ -183,6 +183,10 @@ __device__ __forceinline__ void softmax_step_full(const f32x16_t& acc, float sca
     m = m_new;
 }
 
+// Keeps the MFMA chain that produces `acc` inside the scheduling region in which it was written: the value counts as
+// used (and changed) here, so the chain cannot sink towards its first real use in a later region.
+__device__ __forceinline__ void pin_accumulators(f32x16_t& acc) { asm volatile("" : "+v"(acc)); }
+
 // Asks the scheduler to place `valu` vector instructions after each of the next `mfmas` MFMAs of the
 // region, so that the softmax arithmetic of one block runs while the matrix pipe works on the next block.
 template <int MFMAS, int VALU>
@@ -303,6 +307,7 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
                 B = mma_chain<T, NCH>(kf0, q[1]);
                 softmax_step_full(A, g.scale_log2, m[0], l[0]);
                 interleave_mfma_valu<kMfmas, kValu>();
+                pin_accumulators(B);
                 __builtin_amdgcn_sched_barrier(0);
                 {   // subtile 0 of the next stage: published before the previous barrier
                     const uint4* knext = stage_buf(s + 1);
@@ -313,16 +318,20 @@ __global__ __launch_bounds__(kScoreThreads) void row_stats_kernel(const uint4* _
                 A = mma_chain<T, NCH>(kf1, q[0]);
                 softmax_step_full(B, g.scale_log2, m[1], l[1]);
                 interleave_mfma_valu<kMfmas, kValu>();
+                pin_accumulators(A);
                 __builtin_amdgcn_sched_barrier(0);
                 B = mma_chain<T, NCH>(kf1, q[1]);
                 softmax_step_full(A, g.scale_log2, m[0], l[0]);
                 interleave_mfma_valu<kMfmas, kValu>();
+                pin_accumulators(B);
                 __builtin_amdgcn_sched_barrier(0);
                 Stage::template store<true>(kv, stage_buf(s + 2));
                 __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
                 A = mma_chain<T, NCH>(kf0, q[0]);
                 softmax_step_full(B, g.scale_log2, m[1], l[1]);
                 interleave_mfma_valu<kMfmas, kValu>();
+                pin_accumulators(A);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
