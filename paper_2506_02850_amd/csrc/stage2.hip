@@ -104,7 +104,9 @@ struct KeyStage {
             const int jl = id % kKeys, p = id / kKeys;
             int64_t j = j0 + jl;
             j = j < S ? j : S - 1;                                  // stages may overhang the sequence; masked later
-            v[u] = *reinterpret_cast<const u32x4_t*>(k_head + static_cast<size_t>(j) * dh + (p / NCH) * (dh / 2) + (p % NCH) * CE);
+            // S < 2^31: one 32 x 32 -> 64 bit multiply instead of a 64-bit one in every stage
+            const size_t row = static_cast<size_t>(static_cast<uint32_t>(j)) * static_cast<uint32_t>(dh);
+            v[u] = *reinterpret_cast<const u32x4_t*>(k_head + row + (p / NCH) * (dh / 2) + (p % NCH) * CE);
         }
     }
     // UNCHECKED_ROUNDS: rounds in which every thread of the workgroup owns a piece skip the bounds check,
