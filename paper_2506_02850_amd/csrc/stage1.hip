@@ -1036,7 +1036,7 @@ static bool launch_stats_pool2(const void* feats, const void* text, int Tf, int 
 }
 
 // Shared body of metok_segment_compress (batch = 1) and metok_segment_compress_batched: every array carries a leading
-// dimension of `batch` videos, the workspace one slice per video; the one-pass kernels take the video from blockIdx.z.
+// dimension of `batch` videos, the workspace one slice per video; every kernel takes the video from blockIdx.z.
 static int segment_compress_impl(int batch, const void* feats, int dtype, int T, int grid_h, int grid_w, int d,
                                  const void* text_emb, int k, int sim_mode,
                                  double alpha, double beta, int s1, int s2, int event_reduce, int pool_edge,
@@ -1128,7 +1128,8 @@ static int segment_compress_impl(int batch, const void* feats, int dtype, int T,
         return check_launch("pool");
     }
     if (!fused) {
-        // two passes per video (statistics, then pooling with the strides of Algorithm 1), one video after the other
+        // a single video, or the reading of Eq. 4 that needs the extra pass over token means: the two stage-1 calls
+        // (statistics, then pooling with the strides of Algorithm 1), one video after the other
         const size_t in_es = dtype_size(dtype), out_es = dtype_size(out_dtype);
         for (int b = 0; b < batch; ++b) {
             auto at = [&](auto* ptr, int64_t elems) { return ptr ? ptr + static_cast<int64_t>(b) * elems : ptr; };
