@@ -492,6 +492,10 @@ def time_kernels(w: Workload, hev: HipEvents, reps: int):
             k = dict(kernel=kernel + "_kernel", **stats_us(ms), flops=nb * w.score_flops(lv))
             k["TFLOPs"] = round(k["flops"] / (k["us_median"] * 1e-6) / 1e12, 1)
             k["frac_of_bf16_mfma_peak"] = round(k["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
+            # the keys of the level are streamed once per pass: pass 1 reads all S keys, pass 2 the visual ones
+            key_rows = w.n_in[lv] + (N_TEXT if kernel == "row_stats" else 0)
+            k["key_stream_bytes"] = nb * HKV * key_rows * DH * 2
+            k["key_stream_GBs"] = round(k["key_stream_bytes"] / (k["us_median"] * 1e-6) / 1e9, 1)
             entry[kernel] = k
         for kernel in ("select", "write_index"):
             ms = [traced(kernel, lambda v=v: level(v))[0] for _ in range(reps) for v in units]
@@ -847,6 +851,16 @@ def main():
     stages["stage3"]["GBs"] = round(w.kv_bytes() / (stages["stage3"]["ms_per_step_alone"] * 1e-3) / 1e9, 1)
     stages.update(time_kernels(w, hev, args.kernel_reps))
     stages["stage3_kv_compaction"] = hbm_entry(kv_all, w.kv_bytes(), "move_rows_kernel")
+    # every streaming kernel's fraction of the HBM peak and every score pass's fraction of the bf16 MFMA peak, side by side
+    fractions = {"hbm": {}, "mfma_bf16": {}}
+    for name, e in stages.items():
+        if isinstance(e, dict) and "frac_of_hbm_peak" in e:
+            fractions["hbm"][e.get("kernel", name) + " (" + name + ")"] = e["frac_of_hbm_peak"]
+        for sub, k in (e.items() if isinstance(e, dict) else ()):
+            if isinstance(k, dict) and "frac_of_hbm_peak" in k:
+                fractions["hbm"][k["kernel"] + " (" + name + ")"] = k["frac_of_hbm_peak"]
+            if isinstance(k, dict) and "frac_of_bf16_mfma_peak" in k:
+                fractions["mfma_bf16"][k["kernel"] + " (" + name + ")"] = k["frac_of_bf16_mfma_peak"]
     out = {
         "metric": "visual tokens processed/sec through stages 1-3",
         "value": tokens_per_step / (elapsed / args.steps),
@@ -871,6 +885,7 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_file,
                      "algorithmic_bytes_per_launch": w.kv_bytes(), "ms_per_launch": kv_ms,
                      "ms_per_launch_min": round(float(np.min(kv_all)), 4), "ms_per_launch_median": round(float(np.median(kv_all)), 4)},
+        "kernel_fractions_of_peak": fractions,
         "stages": stages,
         "configs": time_configs(w, 10),
     }
