@@ -477,6 +477,22 @@ def time_kernels(w: Workload, hev: HipEvents, reps: int):
     e["pooled_rows_per_video_mean"] = float(np.mean(rows))
     e["workload"] = "[256, 576, 1024] bf16, (s1, s2) = (2, 3), alpha = 0.5, beta = 0.45: strides 2 / 3 / 4 / 6 per frame"
     out["stage1_adaptive_pooling"] = e
+    if batched:
+        # the same two kernels with the whole batch per launch (metok_segment_compress_batched), outputs of their own
+        ad = ADAPTIVE
+        call = lambda o=None: w.B.metok_segment_compress_batched(w.feats_b, GRID, GRID, N_EVENTS, w.text_b, ad["alpha"], ad["beta"],
+                                                                 ad["s1"], ad["s2"], workspace=w.ws1_b, out=o)
+        bufs = call()
+        ms_stats = [traced("frame_stats", lambda: call(bufs))[0] for _ in range(reps * 4)]
+        ms_pool = [traced("pool", lambda: call(bufs))[0] for _ in range(reps * 4)]
+        rows_b = int(bufs["frame_offsets"][:, -1].sum())
+        e = hbm_entry(ms_stats, nb * v_bytes, "frame_stats_kernel")
+        e["videos_per_launch"] = nb
+        out["stage1_adaptive_statistics_batched"] = e
+        e = hbm_entry(ms_pool, nb * v_bytes + rows_b * D_VIS * 2, "pool_kernel")
+        e["videos_per_launch"] = nb
+        out["stage1_adaptive_pooling_batched"] = e
+        del bufs
     # stage 2 per level
     toks = [w.s1_out[v]["token_event"] for v in videos]
     for lv in range(len(w.n_in)):
