@@ -415,7 +415,7 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
     float* __restrict__ event_score, uint8_t* __restrict__ event_is_key, uint8_t* __restrict__ frame_is_key,
     int32_t* __restrict__ frame_stride, int32_t* __restrict__ frame_offsets, int32_t* __restrict__ frame_event_ws,
     float* __restrict__ frame_score_out, int64_t ws_video) {
-    __shared__ uint32_t ekey[METOK_MAX_FRAMES];    // ordered keys of the event scores (k <= T)
+    __shared__ __align__(16) uint32_t ekey[METOK_MAX_FRAMES];    // ordered keys of the event scores (k <= T), then of the frame scores
     __shared__ uint8_t ev_key[METOK_MAX_FRAMES];
     __shared__ int scan_scratch[17];
     const int tid = threadIdx.x;
@@ -446,6 +446,10 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
         event_is_key[e] = is_key;
     }
     __syncthreads();
+    // the frame scores as ordered keys in LDS (the event keys are no longer needed): the ranking below reads every key
+    // of a frame's event, four per 16-byte read
+    for (int f = tid; f < T; f += kSegThreads) ekey[f] = ordered_key(frame_score[f]);
+    __syncthreads();
     // per frame: event id (binary search), rank inside the event, stride, pooled row count
     const int per = (T + kSegThreads - 1) / kSegThreads;
     int counts[8];
@@ -462,12 +466,16 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
             const int e = lo;
             int a = event_start[e], b = event_start[e + 1];
             a = max(0, min(a, T)); b = max(a, min(b, T));
-            const uint32_t kf = ordered_key(frame_score[f]);
+            const uint32_t kf = ekey[f];
             int rank = 0;
-            for (int m = a; m < b; ++m) {
-                const uint32_t km = ordered_key(frame_score[m]);
-                rank += (km > kf || (km == kf && m < f)) ? 1 : 0;
+            auto count = [&](uint32_t km, int m) { rank += (km > kf || (km == kf && m < f)) ? 1 : 0; };
+            int m = a;
+            for (; m < b && (m & 3); ++m) count(ekey[m], m);
+            for (; m + 4 <= b; m += 4) {
+                const uint4 q = *reinterpret_cast<const uint4*>(&ekey[m]);
+                count(q.x, m); count(q.y, m + 1); count(q.z, m + 2); count(q.w, m + 3);
             }
+            for (; m < b; ++m) count(ekey[m], m);
             const int len = b - a;
             int n_kf = static_cast<int>(ceil(beta * static_cast<double>(len) - 1e-9));
             n_kf = min(len, n_kf);

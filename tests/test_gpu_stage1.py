@@ -238,6 +238,33 @@ def test_long_videos_with_tied_similarities(T, k):
     np.testing.assert_array_equal(out["frame_event"].cpu().numpy(), fe)
 
 
+@pytest.mark.parametrize("T,starts", [(5000, [0, 5000]), (4099, [0, 1, 4098, 4099]), (3001, [0, 7, 1501, 3001])])
+def test_key_frames_of_long_events_with_tied_scores(T, starts):
+    """Algorithm 1's key frames inside events of thousands of frames: every frame is ranked against all frames of its
+    event (keys read from LDS four at a time, so event starts that are not multiples of four matter), equal scores
+    lowest index first.  Frames drawn from four vectors tie exactly in their frame-text score."""
+    B = mk()
+    rng = np.random.default_rng(T)
+    basis = rng.standard_normal((4, 4, 16)).astype(np.float32)
+    feats_np = basis[rng.integers(0, 4, size=T)]
+    text_np = rng.standard_normal(16).astype(np.float32)
+    es = np.asarray(starts, dtype=np.int32)
+    out = B.metok_compress_encoder_tokens(torch.from_numpy(feats_np).cuda(), 2, 2, torch.from_numpy(es).cuda(), 0.5, 0.45, 1, 2,
+                                          text_emb=torch.from_numpy(text_np).cuda(), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    fs = out["frame_score"].cpu().numpy()
+    assert len(np.unique(fs)) <= 4
+    ref = O.compress_encoder_tokens(feats_np.astype(np.float64), (2, 2), text_np.astype(np.float64), es, 0.5, 0.45, 1, 2,
+                                    O.EVENT_REDUCE_MEAN, O.POOL_FLOOR, frame_score=fs.astype(np.float64))
+    np.testing.assert_array_equal(out["frame_is_key"].cpu().numpy(), ref["frame_is_key"])
+    np.testing.assert_array_equal(out["event_is_key"].cpu().numpy(), ref["event_is_key"])
+    np.testing.assert_array_equal(out["frame_stride"].cpu().numpy(), ref["frame_stride"])
+    np.testing.assert_array_equal(out["frame_offsets"].cpu().numpy(), ref["frame_offsets"])
+    # ceil(0.45 len) key frames in every event
+    for a, b in zip(starts[:-1], starts[1:]):
+        assert int(out["frame_is_key"][a:b].sum()) == int(np.ceil(0.45 * (b - a) - 1e-9))
+
+
 def test_argument_errors_are_reported():
     B = mk()
     feats = torch.zeros((4, 4, 64), dtype=torch.float32, device="cuda")
