@@ -450,8 +450,58 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
     // of a frame's event, four per 16-byte read
     for (int f = tid; f < T; f += kSegThreads) ekey[f] = ordered_key(frame_score[f]);
     __syncthreads();
+    const int per = (T + kSegThreads - 1) / kSegThreads;      // thread tid owns frames tid * per .. tid * per + per - 1
+    // Events longer than kLongEvent frames (at most 7 of them) do not rank frame against frame: the workgroup finds the
+    // event's n-th largest key bit by bit (32 counting rounds), then keeps the keys above it and, of the keys equal
+    // to it, the first ones by index (their order comes from an exclusive scan over the threads' contiguous frames).
+    constexpr int kLongEvent = 1024;
+    __shared__ int long_list[8];
+    __shared__ int n_long_s;
+    if (tid == 0) n_long_s = 0;
+    __syncthreads();
+    for (int e = tid; e < k; e += kSegThreads) {
+        int a = event_start[e], b = event_start[e + 1];
+        a = max(0, min(a, T)); b = max(a, min(b, T));
+        if (b - a > kLongEvent) { const int p = atomicAdd(&n_long_s, 1); if (p < 8) long_list[p] = e; }
+    }
+    __syncthreads();
+    const int n_long = min(n_long_s, 8);
+    uint32_t long_flags = 0u;                                  // bit j: frame tid * per + j is a key frame of a long event
+    for (int li = 0; li < n_long; ++li) {
+        const int e = long_list[li];
+        int a = event_start[e], b = event_start[e + 1];
+        a = max(0, min(a, T)); b = max(a, min(b, T));
+        const int len = b - a;
+        const int n_kf = min(len, static_cast<int>(ceil(beta * static_cast<double>(len) - 1e-9)));
+        uint32_t tau = 0u;
+        int total = 0;
+        for (int bit = 31; bit >= 0 && n_kf > 0; --bit) {
+            const uint32_t cand = tau | (1u << bit);
+            int c = 0;
+            for (int m = a + tid; m < b; m += kSegThreads) c += ekey[m] >= cand ? 1 : 0;
+            block_exclusive_scan(c, scan_scratch, &total);
+            if (total >= n_kf) tau = cand;
+        }
+        int c_gt = 0;
+        for (int m = a + tid; m < b; m += kSegThreads) c_gt += ekey[m] > tau ? 1 : 0;
+        block_exclusive_scan(c_gt, scan_scratch, &total);
+        const int need = n_kf - total;                         // equal keys still kept
+        int eq_mine = 0;
+        for (int j = 0; j < per; ++j) {
+            const int f = tid * per + j;
+            eq_mine += (f >= a && f < b && ekey[f] == tau) ? 1 : 0;
+        }
+        int eq_run = block_exclusive_scan(eq_mine, scan_scratch, &total);
+        for (int j = 0; j < per; ++j) {
+            const int f = tid * per + j;
+            if (f >= a && f < b) {
+                const uint32_t kf = ekey[f];
+                if (n_kf > 0 && (kf > tau || (kf == tau && eq_run < need))) long_flags |= 1u << j;
+                eq_run += kf == tau ? 1 : 0;
+            }
+        }
+    }
     // per frame: event id (binary search), rank inside the event, stride, pooled row count
-    const int per = (T + kSegThreads - 1) / kSegThreads;
     int counts[8];
     int mine = 0;
     for (int j = 0; j < per; ++j) {
@@ -467,19 +517,24 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
             int a = event_start[e], b = event_start[e + 1];
             a = max(0, min(a, T)); b = max(a, min(b, T));
             const uint32_t kf = ekey[f];
-            int rank = 0;
-            auto count = [&](uint32_t km, int m) { rank += (km > kf || (km == kf && m < f)) ? 1 : 0; };
-            int m = a;
-            for (; m < b && (m & 3); ++m) count(ekey[m], m);
-            for (; m + 4 <= b; m += 4) {
-                const uint4 q = *reinterpret_cast<const uint4*>(&ekey[m]);
-                count(q.x, m); count(q.y, m + 1); count(q.z, m + 2); count(q.w, m + 3);
-            }
-            for (; m < b; ++m) count(ekey[m], m);
             const int len = b - a;
             int n_kf = static_cast<int>(ceil(beta * static_cast<double>(len) - 1e-9));
             n_kf = min(len, n_kf);
-            const bool kf_flag = rank < n_kf;
+            bool kf_flag;
+            if (len > kLongEvent) {
+                kf_flag = (long_flags >> j & 1u) != 0u;
+            } else {
+                int rank = 0;
+                auto count = [&](uint32_t km, int m) { rank += (km > kf || (km == kf && m < f)) ? 1 : 0; };
+                int m = a;
+                for (; m < b && (m & 3); ++m) count(ekey[m], m);
+                for (; m + 4 <= b; m += 4) {
+                    const uint4 q = *reinterpret_cast<const uint4*>(&ekey[m]);
+                    count(q.x, m); count(q.y, m + 1); count(q.z, m + 2); count(q.w, m + 3);
+                }
+                for (; m < b; ++m) count(ekey[m], m);
+                kf_flag = rank < n_kf;
+            }
             const bool ek_flag = ev_key[e] != 0;
             int s = ek_flag ? (kf_flag ? s_key_kf : s_key_nf) : (kf_flag ? s_non_kf : s_non_nf);
             frame_is_key[f] = kf_flag ? 1 : 0;
