@@ -408,6 +408,46 @@ __device__ __forceinline__ int pooled_side(int g, int s, int edge) {
     return edge == METOK_POOL_FLOOR ? max(1, g / s) : (g + s - 1) / s;
 }
 
+// The n largest of keys[a, b) under (key descending, index ascending), found by the whole workgroup without comparing
+// item against item: the n-th largest key bit by bit (32 counting rounds), then the keys above it and, of the keys
+// equal to it, the first ones by index (an exclusive scan over the threads in index order).  The calling thread owns the
+// contiguous items first_owned .. first_owned + per - 1 (per <= 32); bit j of the result says whether item
+// first_owned + j is among the n.  Every thread of the workgroup must call it with the same a, b, n.
+__device__ __forceinline__ uint32_t block_top_n_flags(const uint32_t* keys, int a, int b, int n, int first_owned, int per,
+                                                      int* scan_scratch) {
+    const int tid = threadIdx.x;
+    if (n <= 0) return 0u;
+    uint32_t tau = 0u;
+    int total = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = tau | (1u << bit);
+        int c = 0;
+        for (int m = a + tid; m < b; m += static_cast<int>(blockDim.x)) c += keys[m] >= cand ? 1 : 0;
+        block_exclusive_scan(c, scan_scratch, &total);
+        if (total >= n) tau = cand;
+    }
+    int c_gt = 0;
+    for (int m = a + tid; m < b; m += static_cast<int>(blockDim.x)) c_gt += keys[m] > tau ? 1 : 0;
+    block_exclusive_scan(c_gt, scan_scratch, &total);
+    const int need = n - total;                                // equal keys still kept
+    int eq_mine = 0;
+    for (int j = 0; j < per; ++j) {
+        const int f = first_owned + j;
+        eq_mine += (f >= a && f < b && keys[f] == tau) ? 1 : 0;
+    }
+    int eq_run = block_exclusive_scan(eq_mine, scan_scratch, &total);
+    uint32_t flags = 0u;
+    for (int j = 0; j < per; ++j) {
+        const int f = first_owned + j;
+        if (f >= a && f < b) {
+            const uint32_t kf = keys[f];
+            if (kf > tau || (kf == tau && eq_run < need)) flags |= 1u << j;
+            eq_run += kf == tau ? 1 : 0;
+        }
+    }
+    return flags;
+}
+
 __global__ __launch_bounds__(kSegThreads) void plan_kernel(
     const float* __restrict__ frame_score, const int32_t* __restrict__ event_start, int T, int k,
     int n_key_events, double beta, int s_key_kf, int s_key_nf, int s_non_kf, int s_non_nf,
@@ -436,14 +476,24 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
         ekey[e] = ordered_key(acc);
     }
     __syncthreads();
-    // key events: rank under (score descending, index ascending)
-    for (int e = tid; e < k; e += kSegThreads) {
-        const uint32_t ke = ekey[e];
-        int rank = 0;
-        for (int m = 0; m < k; ++m) rank += (ekey[m] > ke || (ekey[m] == ke && m < e)) ? 1 : 0;
-        const uint8_t is_key = rank < n_key_events ? 1 : 0;
-        ev_key[e] = is_key;
-        event_is_key[e] = is_key;
+    // key events: rank under (score descending, index ascending); beyond kLongEvent events without the all-pairs ranking
+    constexpr int kLongEvent = 1024;
+    if (k <= kLongEvent) {
+        for (int e = tid; e < k; e += kSegThreads) {
+            const uint32_t ke = ekey[e];
+            int rank = 0;
+            for (int m = 0; m < k; ++m) rank += (ekey[m] > ke || (ekey[m] == ke && m < e)) ? 1 : 0;
+            const uint8_t is_key = rank < n_key_events ? 1 : 0;
+            ev_key[e] = is_key;
+            event_is_key[e] = is_key;
+        }
+    } else {
+        const int per_e = (k + kSegThreads - 1) / kSegThreads;
+        const uint32_t flags = block_top_n_flags(ekey, 0, k, min(n_key_events, k), tid * per_e, per_e, scan_scratch);
+        for (int j = 0; j < per_e; ++j) {
+            const int e = tid * per_e + j;
+            if (e < k) { const uint8_t is_key = (flags >> j & 1u) ? 1 : 0; ev_key[e] = is_key; event_is_key[e] = is_key; }
+        }
     }
     __syncthreads();
     // the frame scores as ordered keys in LDS (the event keys are no longer needed): the ranking below reads every key
@@ -451,10 +501,7 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
     for (int f = tid; f < T; f += kSegThreads) ekey[f] = ordered_key(frame_score[f]);
     __syncthreads();
     const int per = (T + kSegThreads - 1) / kSegThreads;      // thread tid owns frames tid * per .. tid * per + per - 1
-    // Events longer than kLongEvent frames (at most 7 of them) do not rank frame against frame: the workgroup finds the
-    // event's n-th largest key bit by bit (32 counting rounds), then keeps the keys above it and, of the keys equal
-    // to it, the first ones by index (their order comes from an exclusive scan over the threads' contiguous frames).
-    constexpr int kLongEvent = 1024;
+    // Events longer than kLongEvent frames (at most 7 of them) do not rank frame against frame either.
     __shared__ int long_list[8];
     __shared__ int n_long_s;
     if (tid == 0) n_long_s = 0;
@@ -473,33 +520,7 @@ __global__ __launch_bounds__(kSegThreads) void plan_kernel(
         a = max(0, min(a, T)); b = max(a, min(b, T));
         const int len = b - a;
         const int n_kf = min(len, static_cast<int>(ceil(beta * static_cast<double>(len) - 1e-9)));
-        uint32_t tau = 0u;
-        int total = 0;
-        for (int bit = 31; bit >= 0 && n_kf > 0; --bit) {
-            const uint32_t cand = tau | (1u << bit);
-            int c = 0;
-            for (int m = a + tid; m < b; m += kSegThreads) c += ekey[m] >= cand ? 1 : 0;
-            block_exclusive_scan(c, scan_scratch, &total);
-            if (total >= n_kf) tau = cand;
-        }
-        int c_gt = 0;
-        for (int m = a + tid; m < b; m += kSegThreads) c_gt += ekey[m] > tau ? 1 : 0;
-        block_exclusive_scan(c_gt, scan_scratch, &total);
-        const int need = n_kf - total;                         // equal keys still kept
-        int eq_mine = 0;
-        for (int j = 0; j < per; ++j) {
-            const int f = tid * per + j;
-            eq_mine += (f >= a && f < b && ekey[f] == tau) ? 1 : 0;
-        }
-        int eq_run = block_exclusive_scan(eq_mine, scan_scratch, &total);
-        for (int j = 0; j < per; ++j) {
-            const int f = tid * per + j;
-            if (f >= a && f < b) {
-                const uint32_t kf = ekey[f];
-                if (n_kf > 0 && (kf > tau || (kf == tau && eq_run < need))) long_flags |= 1u << j;
-                eq_run += kf == tau ? 1 : 0;
-            }
-        }
+        long_flags |= block_top_n_flags(ekey, a, b, n_kf, tid * per, per, scan_scratch);
     }
     // per frame: event id (binary search), rank inside the event, stride, pooled row count
     int counts[8];

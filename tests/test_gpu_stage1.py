@@ -238,11 +238,13 @@ def test_long_videos_with_tied_similarities(T, k):
     np.testing.assert_array_equal(out["frame_event"].cpu().numpy(), fe)
 
 
-@pytest.mark.parametrize("T,starts", [(5000, [0, 5000]), (4099, [0, 1, 4098, 4099]), (3001, [0, 7, 1501, 3001])])
+@pytest.mark.parametrize("T,starts", [(5000, [0, 5000]), (4099, [0, 1, 4098, 4099]), (3001, [0, 7, 1501, 3001]),
+                                      (3000, list(range(3001))), (4100, [0] + list(range(1100, 4101)))])
 def test_key_frames_of_long_events_with_tied_scores(T, starts):
-    """Algorithm 1's key frames inside events of thousands of frames: every frame is ranked against all frames of its
-    event (keys read from LDS four at a time, so event starts that are not multiples of four matter), equal scores
-    lowest index first.  Frames drawn from four vectors tie exactly in their frame-text score."""
+    """Algorithm 1's key frames inside events of thousands of frames, and key events among thousands of events: up to
+    1024 items every item is ranked against all others (keys read from LDS four at a time, so event starts that are
+    not multiples of four matter), beyond that the n-th largest key is found bit by bit; equal scores lowest index
+    first either way.  Frames drawn from four vectors tie exactly in their frame-text score."""
     B = mk()
     rng = np.random.default_rng(T)
     basis = rng.standard_normal((4, 4, 16)).astype(np.float32)
