@@ -18,6 +18,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue
  *     work on that stream; they never synchronise.  Results are deterministic: the same inputs
  *     give bit-identical outputs (no floating-point atomics anywhere).
+ *   - Calls may be captured into a HIP graph (they only launch kernels: no memsets, no copies).  Make one
+ *     ordinary call of each entry point on a device before capturing it there: the first call loads the
+ *     code objects and, for metok_segment_compress, sets a launch attribute of one kernel once per device.
  *   - Return value: METOK_OK or a negative METOK_ERR_* code.  On error nothing has been
  *     enqueued (argument errors) or the launch failed (METOK_ERR_DEVICE); metok_last_error()
  *     returns a thread-local description.
