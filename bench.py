@@ -19,6 +19,8 @@ All inputs are resident in HBM before the timed region.  `value` is visual token
 second.  The JSON line also carries
   roofline      the dominant kernel (the in-place row mover of the KV compaction, HBM bound), its duration taken
                 from events the library records around that kernel inside the timed region;
+  kernel_fractions_of_peak   every streaming kernel's fraction of the HBM peak and every score pass's fraction of the
+                bf16 MFMA peak, side by side (the figures of `stages`);
   stages        per kernel family, measured in the same run right after the timed region with the same event
                 hook: duration (min / median), algorithmic GB/s or TFLOP/s and the fraction of the peak; per
                 stage the tokens entering it per second;
